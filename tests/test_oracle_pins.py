@@ -1,0 +1,351 @@
+"""Pins for the CPU oracle: each test ties one part of oracle/otas_oracle.py to something other
+than itself — an independent library routine, a closed form, an invariant of the method, or a
+brute-force enumeration — so that a dropped term, a wrong sign or index, or a transposed operand
+fails at least one of them.  CPU only."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import otas_synth as synth
+from oracle import otas_oracle as orc
+
+
+def _rand_layers(rng, L, D, F, scale=0.2):
+    out = []
+    for _ in range(L):
+        out.append({
+            "ln1_g": 1 + 0.1 * rng.standard_normal(D), "ln1_b": 0.1 * rng.standard_normal(D),
+            "w_qkv": scale * rng.standard_normal((3 * D, D)), "b_qkv": scale * rng.standard_normal(3 * D),
+            "w_proj": scale * rng.standard_normal((D, D)), "b_proj": scale * rng.standard_normal(D),
+            "ln2_g": 1 + 0.1 * rng.standard_normal(D), "ln2_b": 0.1 * rng.standard_normal(D),
+            "w_fc1": scale * rng.standard_normal((F, D)), "b_fc1": scale * rng.standard_normal(F),
+            "w_fc2": scale * rng.standard_normal((D, F)), "b_fc2": scale * rng.standard_normal(D),
+        })
+    return out
+
+
+# ------------------------------------------------------------------ gamma = 0 is the plain encoder
+def _torch_encoder(layers, D, H, F, eps):
+    mods = []
+    for w in layers:
+        m = torch.nn.TransformerEncoderLayer(D, H, F, dropout=0.0, activation="gelu",
+                                             layer_norm_eps=eps, batch_first=True, norm_first=True,
+                                             dtype=torch.float64)
+        sd = {
+            "self_attn.in_proj_weight": w["w_qkv"], "self_attn.in_proj_bias": w["b_qkv"],
+            "self_attn.out_proj.weight": w["w_proj"], "self_attn.out_proj.bias": w["b_proj"],
+            "linear1.weight": w["w_fc1"], "linear1.bias": w["b_fc1"],
+            "linear2.weight": w["w_fc2"], "linear2.bias": w["b_fc2"],
+            "norm1.weight": w["ln1_g"], "norm1.bias": w["ln1_b"],
+            "norm2.weight": w["ln2_g"], "norm2.bias": w["ln2_b"],
+        }
+        m.load_state_dict({k: torch.from_numpy(np.asarray(v, dtype=np.float64)) for k, v in sd.items()})
+        mods.append(m.eval())
+    return mods
+
+
+@pytest.mark.parametrize("n,D,H,F,L", [(7, 16, 2, 32, 2), (33, 48, 3, 96, 3)])
+def test_gamma_zero_equals_library_prenorm_encoder(n, D, H, F, L):
+    """Sec. III-D: gamma = 0 is the unmodified transformer.  The independent implementation is
+    torch.nn.TransformerEncoderLayer (norm_first, exact GELU) in float64."""
+    rng = np.random.default_rng(5)
+    layers = _rand_layers(rng, L, D, F)
+    x0 = rng.standard_normal((n, D))
+    got = orc.encoder_forward_query(x0, layers, 0, H=H, ln_eps=1e-6, n_lead=1)
+    # the fused fast path of the torch layer is inference-only and needs no_grad; both paths agree
+    with torch.no_grad():
+        t = torch.from_numpy(x0)[None]
+        for m in _torch_encoder(layers, D, H, F, 1e-6):
+            t = m(t)
+    ref = t[0].numpy()
+    assert got["x"].shape == (n, D)
+    assert np.max(np.abs(got["x"] - ref)) <= 1e-11 * max(1.0, np.max(np.abs(ref)))
+    assert got["sizes"].tolist() == [1] * n
+    assert all(s.size == 0 for s, _ in got["trace"])
+
+
+def test_attention_matches_library_sdpa_and_rows_sum_to_one():
+    rng = np.random.default_rng(1)
+    n, H, dh = 19, 4, 8
+    qkv = rng.standard_normal((n, 3 * H * dh))
+    got = orc.attention_heads(qkv, H)
+    t = torch.from_numpy(qkv)
+    q, k, v = (t[:, i * H * dh:(i + 1) * H * dh].reshape(n, H, dh).transpose(0, 1) for i in range(3))
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v).transpose(0, 1).reshape(n, H * dh)
+    assert np.allclose(got, ref.numpy(), rtol=0, atol=1e-12)
+    z = rng.standard_normal((5, 11)) * 30
+    assert np.allclose(orc.softmax_rows(z).sum(axis=1), 1.0, atol=1e-14)
+
+
+def test_layer_norm_and_gelu_match_library_and_closed_form():
+    rng = np.random.default_rng(2)
+    x = rng.standard_normal((6, 40)) * 3 + 1
+    g, b = rng.standard_normal(40), rng.standard_normal(40)
+    ref = torch.nn.functional.layer_norm(torch.from_numpy(x), (40,), torch.from_numpy(g), torch.from_numpy(b), 1e-6)
+    assert np.allclose(orc.layer_norm(x, g, b, 1e-6), ref.numpy(), atol=1e-12)
+    v = np.linspace(-6, 6, 101)
+    closed = np.array([0.5 * t * (1 + math.erf(t / math.sqrt(2))) for t in v])
+    assert np.allclose(orc.gelu(v), closed, atol=1e-15)
+    assert orc.gelu(np.array([0.0]))[0] == 0.0
+    assert abs(orc.gelu(np.array([1.0]))[0] - 0.8413447460685429) < 1e-15   # Phi(1)
+
+
+def test_bf16_rounding_matches_library_cast():
+    rng = np.random.default_rng(3)
+    a = np.concatenate([rng.standard_normal(5000) * 10.0 ** rng.integers(-6, 6, 5000),
+                        np.array([1.00390625, 1.01171875, 0.0, -0.0, 65280.0])])  # exact ties: to even
+    ref = torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(orc.round_storage(a, "bf16"), ref)
+    assert np.array_equal(synth.round_to_bf16(a.astype(np.float32)).astype(np.float64), ref)
+    assert orc.round_storage(np.array([1.00390625]), "bf16")[0] == 1.0          # tie -> even mantissa
+    assert orc.round_storage(np.array([1.01171875]), "bf16")[0] == 1.015625
+
+
+# ------------------------------------------------------------------ shape laws / schedule
+def test_length_schedule_closed_forms():
+    """Sec. III-B: n_i + gamma after prompting, n_i - |gamma| after each merging module."""
+    assert orc.length_schedule(197, 4, 8, 1, 2) == [201, 193, 185]
+    assert orc.length_schedule(197, 0, 0, 1, 12) == [197] * 13
+    assert orc.length_schedule(197, 0, 16, 1, 12) == [197 - 16 * i for i in range(12)] + [11]
+    assert orc.length_schedule(197, 10, 8, 1, 12) == [207 - 8 * i for i in range(13)]
+    # r = 24 collapses to the floor of two tokens (class token + one)
+    s = orc.length_schedule(197, 0, 24, 1, 24)
+    assert s[:14] == [197, 173, 149, 125, 101, 77, 53, 29, 15, 8, 5, 3, 2, 2] and set(s[14:]) == {2}
+    # no protected token: floor is one token
+    assert orc.length_schedule(8, 0, 100, 0, 5) == [8, 4, 2, 1, 1, 1]
+    for n, r, nl in itertools.product(range(1, 40), range(0, 30), (0, 1)):
+        if n < nl + 1:
+            continue
+        k = orc.removal_count(n, r, nl)
+        assert 0 <= k <= r and n - k >= nl + (1 if n > nl else 0)
+        assert k <= n // 2                       # never more edges than set B has tokens
+
+
+def test_prompt_prepend_layout_and_identity():
+    rng = np.random.default_rng(0)
+    tok = rng.standard_normal((6, 4))
+    pr = rng.standard_normal((3, 4))
+    x, s = orc.prompt_prepend(tok, pr, 1)
+    assert x.shape == (9, 4) and s.tolist() == [1] * 9
+    assert np.array_equal(x[0], tok[0]) and np.array_equal(x[1:4], pr) and np.array_equal(x[4:], tok[1:])
+    x0, _ = orc.prompt_prepend(tok, pr, 0)
+    assert np.array_equal(x0[:3], pr) and np.array_equal(x0[3:], tok)
+    xi, _ = orc.prompt_prepend(tok, np.zeros((0, 4)), 1)
+    assert np.array_equal(xi, tok)
+
+
+# ------------------------------------------------------------------ merge selection
+def _brute_force_edges(metric, r_eff, n_lead):
+    """Independent statement of Sec. II-C steps 1-2 with explicit Python loops and a full sort of
+    explicit edge records (no argmax / argsort on matrices)."""
+    n = metric.shape[0]
+    unit = []
+    for i in range(n):
+        nrm = math.sqrt(sum(float(v) * float(v) for v in metric[i]))
+        unit.append([float(v) / max(nrm, 1e-12) for v in metric[i]])
+    picks = []
+    for a in range(0, n, 2):
+        if a < n_lead:
+            continue
+        edges = []
+        for b in range(1, n, 2):
+            edges.append((-sum(p * q for p, q in zip(unit[a], unit[b])), b))
+        edges.sort()
+        picks.append((edges[0][0], a, edges[0][1]))      # (-similarity, a, b)
+    picks.sort()
+    return [(a, b) for _, a, b in picks[:r_eff]]
+
+
+@pytest.mark.parametrize("n_lead", [0, 1])
+def test_merge_selection_matches_brute_force(n_lead):
+    rng = np.random.default_rng(11)
+    for n in range(2, 13):
+        for trial in range(6):
+            metric = rng.standard_normal((n, 5))
+            if trial % 2:                               # signed one-hot rows: cosines are exactly
+                metric = np.zeros((n, 5))               # -1, 0 or 1 on both sides -> many exact ties
+                metric[np.arange(n), rng.integers(0, 3, n)] = rng.choice([-1.0, 1.0, 2.0, 4.0], n)
+            for r in range(0, n):
+                r_eff = orc.removal_count(n, r, n_lead)
+                src, dst, _ = orc.merge_plan(metric, r_eff, n_lead)
+                want = _brute_force_edges(metric, r_eff, n_lead)
+                assert list(zip(src.tolist(), dst.tolist())) == want, (n, r, n_lead, trial)
+                orc.validate_decision(n, r_eff, n_lead, src, dst)
+
+
+def test_tie_rules_closed_form():
+    """All tokens identical: every similarity is equal, so every A token picks the first B token
+    (position 1) and the merged set is the r lowest unprotected even positions, in order."""
+    x = np.tile(np.array([[0.5, -1.0, 2.0, 0.25]]), (11, 1))
+    src, dst, _ = orc.merge_plan(x, 3, 1)
+    assert src.tolist() == [2, 4, 6] and dst.tolist() == [1, 1, 1]
+    src, dst, _ = orc.merge_plan(x, 3, 0)
+    assert src.tolist() == [0, 2, 4] and dst.tolist() == [1, 1, 1]
+    x2, s2, *_ = orc.token_merge(x, x, None, 3, 1)
+    assert x2.shape[0] == 8 and s2.tolist() == [1, 4, 1, 1, 1, 1, 1, 1]
+    assert np.allclose(x2, x[:8], atol=1e-15)
+
+
+def test_planted_duplicate_pairs_are_the_merged_edges():
+    rng = np.random.default_rng(4)
+    n, d, r = 41, 16, 5
+    x = rng.standard_normal((n, d))
+    ks = [1, 4, 7, 12, 19]
+    for k in ks:
+        x[2 * k + 1] = x[2 * k] * 1.0                   # exact duplicates: cosine is exactly the row max
+    x2, s2, src, dst, _ = orc.token_merge(x, x, None, r, 1)
+    assert sorted(zip(src.tolist(), dst.tolist())) == [(2 * k, 2 * k + 1) for k in ks]
+    assert x2.shape[0] == n - r
+    kept = [i for i in range(n) if i not in {2 * k for k in ks}]
+    for j, i in enumerate(kept):
+        if i in {2 * k + 1 for k in ks}:
+            assert s2[j] == 2 and np.allclose(x2[j], x[i], atol=1e-15)
+        else:
+            assert s2[j] == 1 and np.array_equal(x2[j], x[i])
+
+
+def test_scaled_metric_rows_do_not_change_the_decision():
+    """Cosine similarity: rescaling any token's metric vector by a positive factor changes nothing."""
+    rng = np.random.default_rng(8)
+    m = rng.standard_normal((30, 12))
+    a = orc.merge_plan(m, 7, 1)
+    b = orc.merge_plan(m * rng.uniform(0.1, 9.0, size=(30, 1)), 7, 1)
+    assert a[0].tolist() == b[0].tolist() and a[1].tolist() == b[1].tolist()
+
+
+# ------------------------------------------------------------------ merge arithmetic
+@pytest.mark.parametrize("seed", range(4))
+def test_weighted_merge_conserves_sizes_and_weighted_sum(seed):
+    rng = np.random.default_rng(seed)
+    n, d = 57, 9
+    x = rng.standard_normal((n, d))
+    sizes = rng.integers(1, 6, n)
+    order_tag = np.arange(n, dtype=np.float64)
+    total, wsum = int(sizes.sum()), (sizes[:, None] * x).sum(axis=0)
+    for r in (0, 1, 5, 28, 200):
+        x2, s2, src, dst, _ = orc.token_merge(x, rng.standard_normal((n, 6)), sizes, r, 1)
+        r_eff = orc.removal_count(n, r, 1)
+        assert x2.shape == (n - r_eff, d) and s2.shape == (n - r_eff,)
+        assert int(s2.sum()) == total and s2.min() >= 1
+        assert np.allclose((s2[:, None] * x2).sum(axis=0), wsum, rtol=1e-12, atol=1e-12)
+        assert np.array_equal(x2[0], x[0])              # the protected lead token is untouched
+        # survivors keep their relative order: un-merged survivors carry their tag unchanged
+        t2, _ = orc.merge_apply(order_tag[:, None], np.ones(n, dtype=np.int64), [], [])
+        assert np.array_equal(t2[:, 0], order_tag)
+        tags, _ = orc.merge_apply(np.where(np.isin(np.arange(n), dst), np.nan, order_tag)[:, None],
+                                  sizes, src, dst)
+        surv = tags[~np.isnan(tags[:, 0]), 0]
+        assert np.all(np.diff(surv) > 0)
+
+
+def test_merge_apply_hand_example():
+    """Three tokens into one, by hand: sizes 2,1,3 and values 1,4,10 -> (2*1+1*4+3*10)/6 = 6."""
+    x = np.array([[9.0], [4.0], [1.0], [7.0], [10.0]])
+    s = np.array([1, 1, 2, 1, 3])
+    x2, s2 = orc.merge_apply(x, s, [2, 4], [1, 1])
+    assert x2[:, 0].tolist() == [9.0, 6.0, 7.0] and s2.tolist() == [1, 6, 1]
+
+
+def test_identity_cases():
+    rng = np.random.default_rng(6)
+    x = rng.standard_normal((10, 4))
+    x2, s2, src, dst, _ = orc.token_merge(x, x, None, 0, 1)
+    assert np.array_equal(x2, x) and s2.tolist() == [1] * 10 and src.size == 0
+    # size bias with all sizes 1 changes nothing (ln 1 = 0)
+    qkv = rng.standard_normal((10, 24))
+    assert np.array_equal(orc.attention_heads(qkv, 2), orc.attention_heads(qkv, 2, np.ones(10), True))
+    # and with real sizes it equals attention over the token list with every key repeated size times
+    sizes = np.array([1, 3, 1, 2, 1, 1, 4, 1, 1, 2])
+    rep = np.repeat(np.arange(10), sizes)
+    D = 8
+    big = qkv[rep]
+    ref = orc.attention_heads(big, 2)                   # duplicated keys/values == + ln(size) bias
+    got = orc.attention_heads(qkv, 2, sizes, True)
+    first = np.concatenate([[0], np.cumsum(sizes)[:-1]])
+    assert np.allclose(got, ref[first], atol=1e-12)
+    assert D == qkv.shape[1] // 3
+
+
+# ------------------------------------------------------------------ whole encoder with adaptation
+def test_encoder_invariants_on_tiny_config():
+    cfg = synth.config("tiny")
+    layers = synth.all_weights(cfg)
+    toks, prm, P, R = synth.batch(cfg)
+    outs = []
+    for q in range(cfg.B):
+        x0, _ = orc.prompt_prepend(toks[q], prm[q], cfg.n_lead)
+        o = orc.encoder_forward_query(x0, layers, R[q], H=cfg.H, ln_eps=cfg.ln_eps, n_lead=cfg.n_lead)
+        outs.append(o)
+        assert o["lengths"] == orc.length_schedule(cfg.n0, P[q], R[q], cfg.n_lead, cfg.L) == [201, 193, 185]
+        assert int(o["sizes"].sum()) == cfg.n0 + P[q] and o["sizes"].min() >= 1
+        for (src, dst), n in zip(o["trace"], o["lengths"]):
+            orc.validate_decision(n, 8, 1, src, dst)
+        assert o["sizes"][0] == 1                       # class token never merged
+        assert min(m["rank_margin"] for m in o["margins"]) > 1e-6
+        assert min(m["argmax_margin"] for m in o["margins"]) > 1e-6
+    # query independence: the batch routine is the per-query routine
+    x0s = [orc.prompt_prepend(t, p, 1)[0] for t, p in zip(toks, prm)]
+    both = orc.encoder_forward(x0s, layers, R, H=cfg.H, ln_eps=cfg.ln_eps, n_lead=1)
+    for a, b in zip(outs, both):
+        assert np.array_equal(a["x"], b["x"])
+
+
+def test_lockstep_adoption_counts_disagreements_and_applies_given_decision():
+    rng = np.random.default_rng(9)
+    D, H, F, n = 16, 2, 32, 21
+    layers = _rand_layers(rng, 2, D, F)
+    x0 = rng.standard_normal((n, D))
+    own = orc.encoder_forward_query(x0, layers, 3, H=H, ln_eps=1e-6, n_lead=1)
+    same = orc.encoder_forward_query(x0, layers, 3, H=H, ln_eps=1e-6, n_lead=1, adopt=own["trace"])
+    assert same["disagree"] == [0, 0] and np.array_equal(same["x"], own["x"])
+    src, dst = own["trace"][0]
+    other_a = next(a for a in range(2, n, 2) if a not in set(src.tolist()))
+    forced = [(np.concatenate([src[:-1], [other_a]]), np.concatenate([dst[:-1], [1]])), None]
+    first = orc.encoder_forward_query(x0, layers[:1], 3, H=H, ln_eps=1e-6, n_lead=1, adopt=forced[:1])
+    assert first["disagree"] == [1]
+    assert not np.array_equal(first["x"], orc.encoder_forward_query(x0, layers[:1], 3, H=H, ln_eps=1e-6, n_lead=1)["x"])
+    with pytest.raises(ValueError):
+        orc.validate_decision(n, 3, 1, [0, 2, 4], [1, 1, 1])      # protected token as a source
+    with pytest.raises(ValueError):
+        orc.validate_decision(n, 3, 1, [2, 2, 4], [1, 1, 1])      # a token merged twice
+
+
+def test_storage_modes_round_where_stated():
+    rng = np.random.default_rng(10)
+    D, H, F, n = 32, 2, 64, 15
+    layers = [{k: synth.round_to_bf16(v.astype(np.float32)) for k, v in w.items()} for w in _rand_layers(rng, 2, D, F, 0.1)]
+    x0 = synth.round_to_bf16(rng.standard_normal((n, D)).astype(np.float32))
+    f64 = orc.encoder_forward_query(x0, layers, 2, H=H, ln_eps=1e-6, n_lead=1)
+    b16 = orc.encoder_forward_query(x0, layers, 2, H=H, ln_eps=1e-6, n_lead=1, storage="bf16")
+    assert np.array_equal(b16["x"], orc.round_storage(b16["x"], "bf16"))     # output is bf16-representable
+    err = np.max(np.abs(b16["x"] - f64["x"])) / np.max(np.abs(f64["x"]))
+    assert 0 < err < 3e-2
+    f32 = orc.encoder_forward_query(x0, layers, 2, H=H, ln_eps=1e-6, n_lead=1, storage="f32")
+    assert np.max(np.abs(f32["x"] - f64["x"])) / np.max(np.abs(f64["x"])) < 1e-5
+
+
+# ------------------------------------------------------------------ planted mistakes are caught
+def test_pins_catch_planted_mistakes(monkeypatch):
+    """Mutate the oracle on the CPU and check that a pin notices: guards against vacuous pins."""
+    rng = np.random.default_rng(12)
+    m = rng.standard_normal((12, 5))
+    want = _brute_force_edges(m, 4, 1)
+    # (a) swapped sets (odd -> A)
+    bad = orc.merge_plan(m[::-1].copy(), 4, 1)
+    assert list(zip(bad[0].tolist(), bad[1].tolist())) != want
+    # (b) unweighted average breaks the conserved weighted sum
+    x = rng.standard_normal((9, 3)); s = np.array([1, 2, 3, 1, 1, 2, 1, 1, 5])
+    x2, s2 = orc.merge_apply(x, s, [2, 6], [3, 3])
+    assert np.allclose((s2[:, None] * x2).sum(0), (s[:, None] * x).sum(0))
+    naive = (x[3] + x[2] + x[6]) / 3
+    assert not np.allclose(naive, x2[2])
+    # (c) missing 1/sqrt(d_k): the library SDPA comparison would fail
+    monkeypatch.setattr(orc.math, "sqrt", lambda v: 1.0)
+    qkv = rng.standard_normal((7, 3 * 8))
+    t = torch.from_numpy(qkv)
+    q, k, v = (t[:, i * 8:(i + 1) * 8].reshape(7, 2, 4).transpose(0, 1) for i in range(3))
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v).transpose(0, 1).reshape(7, 8).numpy()
+    assert not np.allclose(orc.attention_heads(qkv, 2), ref, atol=1e-6)
