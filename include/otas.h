@@ -1,0 +1,199 @@
+/*
+ * otas.h -- C ABI of the token-adapted transformer encoder for AMD MI355X (gfx950).
+ *
+ * The operations are those of the OTAS paper (arXiv 2401.05031): a pre-norm transformer encoder
+ * (Sec. II-A) with a prompting module that prepends trained prompt tokens (Sec. II-B, Sec. III-B)
+ * and a merging module that, in every layer between attention and the MLP, removes the r most
+ * redundant tokens by bipartite similarity matching and a weighted average (Sec. II-C,
+ * Sec. III-B).  The paper's one signed number gamma per batch is split here into two
+ * non-negative per-query numbers: P prompt tokens added once, r tokens removed per layer.
+ *
+ * General conventions
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are ordinary host memory.
+ *   - Token tensors are packed row-major [T, D]: query q owns rows offsets[q] .. offsets[q+1]-1.
+ *     Element type is the model's dtype (float or bf16, 2 bytes, upper half of an IEEE float)
+ *     unless a parameter says "float": inside the encoder the residual stream is always float
+ *     (bf16 is used for the GEMM and attention operands), and the encoder returns it as float.
+ *   - The caller owns every buffer.  The library allocates device memory only in otas_create
+ *     (a small plan buffer) and frees it in otas_destroy.
+ *   - All device work is enqueued on the HIP stream given to otas_create and the calls return
+ *     without waiting for it.  Host outputs (offsets_out) are complete on return, because every
+ *     sequence length is a function of (n, r, layer) alone and is computed on the host.
+ *   - Host arrays are read during the call and never retained.
+ *   - Every argument check happens on the host before any launch; a failed call enqueues
+ *     nothing.  Errors are returned as otas_status, never thrown or aborted.
+ *   - Calls on one context must not overlap in time from different host threads.
+ */
+#ifndef OTAS_H_
+#define OTAS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { OTAS_F32 = 0, OTAS_BF16 = 1 } otas_dtype;
+
+typedef enum {
+  OTAS_OK = 0,
+  OTAS_EINVAL = 1,       /* NULL pointer, negative count, malformed offsets               */
+  OTAS_ESHAPE = 2,       /* shapes that contradict the model description                  */
+  OTAS_ENOMEM = 3,       /* workspace or plan buffer too small                            */
+  OTAS_EDEVICE = 4,      /* a HIP runtime call failed                                     */
+  OTAS_EUNSUPPORTED = 5  /* a size outside what the kernels are built for (see limits)    */
+} otas_status;
+
+enum {
+  OTAS_FLAG_SIZE_BIAS = 1u << 0, /* add ln(size_j) to the attention logits of key j.  Not part of
+                                    the paper's definition of attention (Sec. II-A); off by default. */
+  OTAS_FLAG_TRACE = 1u << 1      /* write every layer's merge edges to trace_src / trace_dst */
+};
+
+/* Limits of this build: D % H == 0, head width d_h in {64, 80, 96, 128} for bf16 and any
+ * multiple of 4 up to 128 for f32, D % 8 == 0, F % 8 == 0, sequence length per query <= 1024,
+ * n_lead in {0, 1}. */
+#define OTAS_MAX_SEQ 1024
+
+typedef struct {
+  int32_t L;        /* encoder blocks                                                     */
+  int32_t D;        /* model width                                                        */
+  int32_t H;        /* attention heads (Sec. II-A)                                        */
+  int32_t F;        /* MLP hidden width                                                   */
+  int32_t dtype;    /* otas_dtype: type of tokens, weights and all arithmetic inputs      */
+  float ln_eps;     /* LayerNorm epsilon                                                  */
+  int32_t n_lead;   /* leading tokens that are never merged away (1 = class token, or 0)  */
+} otas_model_desc;
+
+/* Device pointers to one block's parameters, all of the model's dtype.  Linear weights are
+ * [out, in] row-major (y = x W^T + b).  w_qkv is [3D, D] with rows ordered Q | K | V and the H
+ * heads contiguous inside each third (Sec. II-A per-head projections).  The pointers are kept,
+ * not copied: the memory must stay valid until otas_destroy. */
+typedef struct {
+  const void *ln1_g, *ln1_b;   /* [D]            */
+  const void *w_qkv, *b_qkv;   /* [3D, D], [3D]  */
+  const void *w_proj, *b_proj; /* [D, D], [D]    */
+  const void *ln2_g, *ln2_b;   /* [D]            */
+  const void *w_fc1, *b_fc1;   /* [F, D], [F]    */
+  const void *w_fc2, *b_fc2;   /* [D, F], [D]    */
+} otas_layer_weights;
+
+typedef struct otas_ctx otas_ctx;
+
+/* Create a context for one model.  layers: host array of L structs holding dev pointers.
+ * hip_stream: a hipStream_t (NULL = the default stream).  The device current at the time of the
+ * call is the one the context works on.  Returns EINVAL/ESHAPE/EUNSUPPORTED on bad descriptions,
+ * EDEVICE if the plan buffer cannot be allocated. */
+otas_status otas_create(otas_ctx **ctx, const otas_model_desc *desc,
+                        const otas_layer_weights *layers, void *hip_stream);
+otas_status otas_destroy(otas_ctx *ctx);
+
+/* Length schedule of one query (pure host; Sec. III-B shape laws).  n0 tokens, P prompts added
+ * once, then in each of the L layers r_eff = min(r, floor((n - n_lead) / 2)) tokens removed.
+ * len_out[L+1]: length entering layer 0..L-1, then the output length. */
+otas_status otas_schedule(int32_t n0, int32_t P, int32_t r, int32_t n_lead, int32_t L,
+                          int32_t *len_out);
+
+/* Bytes of device workspace otas_encoder_forward needs for B queries with T0 packed tokens in
+ * total (pure host).  Returns 0 on invalid arguments. */
+size_t otas_workspace_bytes(const otas_ctx *ctx, int32_t B, int64_t T0);
+/* Same for otas_token_merge (plan arrays only). */
+size_t otas_merge_workspace_bytes(int32_t B, int64_t T);
+
+/* Prompting module (Sec. II-B, Sec. III-B): for every query, put its P_q prompt rows in front of
+ * its input tokens, after the n_lead leading tokens:  [lead | prompts | remaining tokens].
+ *   tokens  dev [T_in, D], tok_offsets host [B+1]
+ *   prompts dev [sum P, D] (may be NULL if sum P == 0), prompt_offsets host [B+1]
+ *   out     dev [T_in + sum P, D]; must not alias the inputs
+ *   out_offsets host [B+1], filled on return.
+ * A query shorter than n_lead tokens is EINVAL. */
+otas_status otas_prompt_prepend(otas_ctx *ctx, const void *tokens, const int32_t *tok_offsets,
+                                const void *prompts, const int32_t *prompt_offsets, int32_t B,
+                                void *out, int32_t *out_offsets);
+
+/* Merging module (Sec. II-C) applied once to every query of a packed batch.
+ * Tokens at even positions of a query form set A, odd positions set B.  Every A token picks the
+ * B token whose metric vector has the highest cosine similarity (ties: lowest position); the
+ * r_eff = min(r_q, floor((n_q - n_lead)/2)) A tokens with the highest such similarity (ties:
+ * lower position first) are merged into their picks by an average weighted with the token
+ * sizes; sizes add; the surviving rows keep their order.
+ *   x       dev [T, D]      tokens
+ *   metric  dev [T, dm]     vectors the similarity is taken on (model dtype), dm % 4 == 0, dm <= 128
+ *   sizes   dev [T] int32   tokens each row stands for; NULL = all 1
+ *   offsets host [B+1], r host [B]
+ *   workspace dev, >= otas_merge_workspace_bytes(B, T) bytes, 256-byte aligned
+ *   x_out   dev [T', D], sizes_out dev [T'] with T' = sum (n_q - r_eff_q); no aliasing of inputs
+ *   offsets_out host [B+1], filled on return
+ *   trace_src / trace_dst dev [sum r_eff] int32 or both NULL: per query (in batch order) the
+ *     merged edges in rank order, as positions inside the query's input sequence. */
+otas_status otas_token_merge(otas_ctx *ctx, const void *x, const void *metric, int32_t dm,
+                             const int32_t *sizes, const int32_t *offsets, const int32_t *r,
+                             int32_t B, void *workspace, size_t workspace_bytes, void *x_out,
+                             int32_t *sizes_out, int32_t *offsets_out, int32_t *trace_src,
+                             int32_t *trace_dst);
+
+/* Token-adapted encoder forward (Sec. III-B unified model; the ServeModel.forward of Sec. IV
+ * without the task heads).  Per layer and query:
+ *   x += Proj(Attention(LN1(x)));  merge r_eff tokens using the cosine similarity of the
+ *   head-averaged attention keys;  x += FC2(GELU(FC1(LN2(x)))).
+ *   x0      dev [T0, D]  tokens with prompts already prepended (otas_prompt_prepend)
+ *   offsets host [B+1], r host [B] removal count per layer for each query
+ *   flags   OTAS_FLAG_*
+ *   workspace dev, >= otas_workspace_bytes(ctx, B, T0) bytes, 256-byte aligned
+ *   x_out   dev float [T_L, D] (the residual stream after the last block, for every dtype),
+ *           sizes_out dev [T_L] int32, offsets_out host [B+1] (filled on return)
+ *   trace_src / trace_dst dev int32 [sum over layers and queries of r_eff], required with
+ *     OTAS_FLAG_TRACE, ignored otherwise.  Layout: layer-major, then query, then rank order;
+ *     values are positions inside the query's sequence as it enters that layer's merge.
+ * x_out must not alias x0 or the workspace. */
+otas_status otas_encoder_forward(otas_ctx *ctx, const void *x0, const int32_t *offsets,
+                                 const int32_t *r, int32_t B, uint32_t flags, void *workspace,
+                                 size_t workspace_bytes, void *x_out, int32_t *sizes_out,
+                                 int32_t *offsets_out, int32_t *trace_src, int32_t *trace_dst);
+
+/* The same for a contiguous range of blocks [layer_begin, layer_end) starting from a given state:
+ * x0 is the residual stream entering block layer_begin, dev float [T0, D] for every dtype (what a
+ * previous stage returned in x_out), and sizes_in (dev int32 [T0], NULL = all 1) the number of
+ * original tokens each row stands for.  otas_encoder_forward is
+ * otas_encoder_layers(0, L, sizes_in = NULL).  The trace covers the blocks of the range only.
+ * Use: running the encoder in stages, and per-layer parity checks. */
+otas_status otas_encoder_layers(otas_ctx *ctx, int32_t layer_begin, int32_t layer_end,
+                                const void *x0, const int32_t *sizes_in, const int32_t *offsets,
+                                const int32_t *r, int32_t B, uint32_t flags, void *workspace,
+                                size_t workspace_bytes, void *x_out, int32_t *sizes_out,
+                                int32_t *offsets_out, int32_t *trace_src, int32_t *trace_dst);
+
+/* Individual steps of the path, exposed for parity tests and profiling.  All pointers dev,
+ * model dtype, enqueued on the context's stream.
+ *   otas_layer_norm: y[T,D] = LN(x[T,D]) with biased variance and the context's eps.
+ *   otas_linear:     y[T,N] = epilogue(x[T,K] W[N,K]^T + b[N]);  epilogue 0 = none, 1 = exact
+ *                    GELU, 2 = add residual res[T,N]; with epilogue 2, res and y are float (the
+ *                    residual stream) and res may equal y.
+ *   otas_attention:  o[T,D] = concat_h softmax(Q_h K_h^T / sqrt(d_h) [+ ln size_j]) V_h from
+ *                    qkv[T,3D]; sizes dev int32 [T] or NULL; offsets host [B+1]. */
+otas_status otas_layer_norm(otas_ctx *ctx, const void *x, const void *g, const void *b,
+                            int64_t T, void *y);
+otas_status otas_linear(otas_ctx *ctx, const void *x, const void *w, const void *b,
+                        const void *res, int64_t T, int32_t N, int32_t K, int32_t epilogue,
+                        void *y);
+otas_status otas_attention(otas_ctx *ctx, const void *qkv, const int32_t *sizes,
+                           const int32_t *offsets, int32_t B, uint32_t flags, void *o);
+
+/* Per-launch timing for benchmarks (callers that want the time of each kernel kind measured with
+ * HIP events on the context's stream).  otas_timing_enable(ctx, 1) waits for the stream, then makes
+ * every later launch of this context record an event before and after itself;
+ * otas_timing_read waits for the stream, returns for each kind 0 .. otas_timing_kinds()-1 the summed
+ * milliseconds and the number of launches since the last read, and clears the records.
+ * total_ms / launches: host arrays of otas_timing_kinds() entries.  Off by default. */
+otas_status otas_timing_enable(otas_ctx *ctx, int32_t on);
+int32_t otas_timing_kinds(void);
+const char *otas_timing_kind_name(int32_t kind);
+otas_status otas_timing_read(otas_ctx *ctx, double *total_ms, int64_t *launches);
+
+const char *otas_strerror(otas_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OTAS_H_ */

@@ -41,9 +41,11 @@ identity cases.  The paper prints no worked numeric example for this path, so no
 pinned to a paper-printed value.
 
 Storage modes.  storage="f64" computes everything in float64.  storage="bf16" keeps float64
-arithmetic but rounds (float64 -> float32 -> bf16, ties to even) at the points where the HIP path
-stores a 16-bit tensor: LayerNorm output, QKV, attention output, residual stream, MLP hidden,
-merged tokens.  storage="f32" rounds to float32 at the same points.
+arithmetic but rounds at the points where the HIP path of a bf16 model stores a tensor: to bf16
+(float64 -> float32 -> bf16, ties to even) for the GEMM / attention operands -- LayerNorm output,
+QKV, attention output, MLP hidden -- and to float32 for the residual stream (after each residual
+add and after merging), which the HIP path keeps in float.  storage="f32" rounds to float32 at all
+of these points.
 """
 from __future__ import annotations
 
@@ -154,7 +156,7 @@ def merge_plan(metric: np.ndarray, r_eff: int, n_lead: int):
     src[k], dst[k] = positions (in the current sequence) of the k-th best kept edge, A token and
     its B token, in rank order; info carries the decision margins."""
     n = metric.shape[0]
-    info = {"argmax_margin": math.inf, "rank_margin": math.inf}
+    info = {"argmax_margin": math.inf, "rank_margin": math.inf, "sim": None, "best": None, "kth": math.inf}
     if r_eff <= 0:
         return np.zeros(0, dtype=np.int64), np.zeros(0, dtype=np.int64), info
     norm = np.sqrt((metric * metric).sum(axis=1, keepdims=True))
@@ -167,7 +169,8 @@ def merge_plan(metric: np.ndarray, r_eff: int, n_lead: int):
     best = sim[np.arange(a_pos.size), best_col]
     order = np.argsort(-best, kind="stable")        # descending, equal values: lower A first (R5)
     chosen = order[:r_eff]
-    # decision margins, for the tests' robustness print-out
+    # decision margins, for the tests' robustness print-out and near-tie attribution
+    info.update(sim=sim, best=best, kth=float(best[order[r_eff - 1]]))
     if sim.shape[1] > 1:
         part = np.sort(sim[chosen], axis=1)
         info["argmax_margin"] = float(np.min(part[:, -1] - part[:, -2]))
@@ -176,6 +179,13 @@ def merge_plan(metric: np.ndarray, r_eff: int, n_lead: int):
         if np.isfinite(nxt):
             info["rank_margin"] = float(best[order[r_eff - 1]] - nxt)
     return a_pos[chosen], b_pos[best_col[chosen]], info
+
+
+def edge_deficit(info: dict, a: int, b: int) -> float:
+    """How far (in similarity) the edge (a, b) is from being one the oracle itself would keep:
+    max(best[a] - sim[a,b], kth best - sim[a,b], 0).  0 for the oracle's own edges."""
+    s = info["sim"][a // 2, b // 2]
+    return float(max(info["best"][a // 2] - s, info["kth"] - s, 0.0))
 
 
 def merge_apply(x: np.ndarray, sizes: np.ndarray, src: Sequence[int], dst: Sequence[int]):
@@ -232,25 +242,31 @@ def validate_decision(n: int, r_eff: int, n_lead: int, src, dst) -> None:
 def encoder_forward_query(x0: np.ndarray, layers: Sequence[Dict[str, np.ndarray]], r: int, *,
                           H: int, ln_eps: float, n_lead: int, storage: str = "f64",
                           size_bias: bool = False, adopt: Optional[Sequence] = None,
-                          taps: Optional[dict] = None):
+                          taps: Optional[dict] = None, sizes0: Optional[np.ndarray] = None):
     """Token-adapted encoder for ONE query (prompts already prepended).
 
     adopt: optional per-layer (src, dst) decisions to apply instead of the oracle's own
     (lock-step comparison); the oracle still computes its own decision and reports how many edges
-    differ.  Returns dict(x, sizes, trace=[(src,dst) per layer], disagree=[per layer],
-    margins=[per layer], lengths)."""
+    differ and, for every adopted edge the oracle would not have kept, its similarity deficit
+    (edge_deficit).  sizes0: sizes entering the first given layer (default all 1); taps: dict that
+    receives per-layer intermediate states.  Returns dict(x, sizes, trace=[(src,dst) per layer],
+    disagree=[per layer], margins=[per layer], lengths, deficits)."""
     st = storage
-    x = round_storage(np.asarray(x0, dtype=np.float64), st)
+    rs = "f32" if storage == "bf16" else storage          # storage of the residual stream
+    x = round_storage(np.asarray(x0, dtype=np.float64), rs)
     n = x.shape[0]
-    sizes = np.ones(n, dtype=np.int64)
-    trace, disagree, margins, lengths = [], [], [], [n]
+    sizes = np.ones(n, dtype=np.int64) if sizes0 is None else np.array(sizes0, dtype=np.int64)
+    trace, disagree, margins, lengths, deficits = [], [], [], [n], []
     for l, w in enumerate(layers):
         W = {k: np.asarray(v, dtype=np.float64) for k, v in w.items()}
+        if taps is not None:
+            taps.setdefault("x_in", []).append(x.copy())
+            taps.setdefault("sizes_in", []).append(sizes.copy())
         # normalisation -> multi-head attention -> residual
         h = round_storage(layer_norm(x, W["ln1_g"], W["ln1_b"], ln_eps), st)
         qkv = round_storage(qkv_project(h, W["w_qkv"], W["b_qkv"]), st)
         o = round_storage(attention_heads(qkv, H, sizes, size_bias), st)
-        x = round_storage(x + o @ W["w_proj"].T + W["b_proj"], st)
+        x = round_storage(x + o @ W["w_proj"].T + W["b_proj"], rs)
         if taps is not None:
             taps.setdefault("x_attn", []).append(x.copy())
             taps.setdefault("qkv", []).append(qkv.copy())
@@ -265,22 +281,23 @@ def encoder_forward_query(x0: np.ndarray, layers: Sequence[Dict[str, np.ndarray]
             mine = set(zip(src.tolist(), dst.tolist()))
             theirs = set(zip(g_src.tolist(), g_dst.tolist()))
             n_dis = len(mine ^ theirs) // 2 + len(mine ^ theirs) % 2
+            deficits.extend(edge_deficit(info, a, b) for a, b in theirs - mine)
             src, dst = g_src, g_dst
         if r_eff > 0:
             x, sizes = merge_apply(x, sizes, src, dst)
-            x = round_storage(x, st)
+            x = round_storage(x, rs)
         trace.append((np.asarray(src), np.asarray(dst)))
         disagree.append(n_dis)
-        margins.append(info)
+        margins.append({k: info[k] for k in ("argmax_margin", "rank_margin")})
         # normalisation -> MLP -> residual
         h2 = round_storage(layer_norm(x, W["ln2_g"], W["ln2_b"], ln_eps), st)
         hid = round_storage(gelu(h2 @ W["w_fc1"].T + W["b_fc1"]), st)
-        x = round_storage(x + hid @ W["w_fc2"].T + W["b_fc2"], st)
+        x = round_storage(x + hid @ W["w_fc2"].T + W["b_fc2"], rs)
         lengths.append(x.shape[0])
         if taps is not None:
             taps.setdefault("x_out", []).append(x.copy())
     return {"x": x, "sizes": sizes, "trace": trace, "disagree": disagree,
-            "margins": margins, "lengths": lengths}
+            "margins": margins, "lengths": lengths, "deficits": deficits}
 
 
 def encoder_forward(x0_list: Sequence[np.ndarray], layers, r_list: Sequence[int], *, H: int,

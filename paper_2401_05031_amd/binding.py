@@ -1,0 +1,248 @@
+"""ctypes binding of libotas.so.
+
+The functions mirror the C ABI one to one (same names, same argument order) and only marshal
+arguments: torch tensors become device pointers, Python lists become host int32 arrays.  There is
+no fallback: if the library is missing or fails to load, importing a symbol raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+OTAS_F32, OTAS_BF16 = 0, 1
+OTAS_FLAG_SIZE_BIAS, OTAS_FLAG_TRACE = 1, 2
+_WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
+                  "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+
+
+class OtasError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {otas_strerror(status)} (status {status})")
+
+
+class _ModelDesc(C.Structure):
+    _fields_ = [("L", C.c_int32), ("D", C.c_int32), ("H", C.c_int32), ("F", C.c_int32),
+                ("dtype", C.c_int32), ("ln_eps", C.c_float), ("n_lead", C.c_int32)]
+
+
+class _LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _WEIGHT_FIELDS]
+
+
+_I32P = C.POINTER(C.c_int32)
+_LIB = None
+
+
+def lib_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libotas.so")
+
+
+def load_library():
+    """Load libotas.so (built in-tree by paper_2401_05031_amd/build.py).  Raises if absent."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is not built: run `python -m paper_2401_05031_amd.build` "
+                          "(there is no CPU fallback)")
+    # torch ships its own copy of the HIP runtime under the same soname as the system one; load
+    # torch first so that the library, torch's allocator and torch's streams share ONE runtime.
+    import torch  # noqa: F401
+    lib = C.CDLL(path)
+    vp, i32, i64, u32, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_uint32, C.c_size_t
+    sigs = {
+        "otas_create": (i32, [C.POINTER(vp), C.POINTER(_ModelDesc), C.POINTER(_LayerWeights), vp]),
+        "otas_destroy": (i32, [vp]),
+        "otas_schedule": (i32, [i32, i32, i32, i32, i32, _I32P]),
+        "otas_workspace_bytes": (sz, [vp, i32, i64]),
+        "otas_merge_workspace_bytes": (sz, [i32, i64]),
+        "otas_prompt_prepend": (i32, [vp, vp, _I32P, vp, _I32P, i32, vp, _I32P]),
+        "otas_token_merge": (i32, [vp, vp, vp, i32, vp, _I32P, _I32P, i32, vp, sz, vp, vp, _I32P, vp, vp]),
+        "otas_encoder_forward": (i32, [vp, vp, _I32P, _I32P, i32, u32, vp, sz, vp, vp, _I32P, vp, vp]),
+        "otas_encoder_layers": (i32, [vp, i32, i32, vp, vp, _I32P, _I32P, i32, u32, vp, sz, vp, vp, _I32P, vp, vp]),
+        "otas_layer_norm": (i32, [vp, vp, vp, vp, i64, vp]),
+        "otas_linear": (i32, [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]),
+        "otas_attention": (i32, [vp, vp, vp, _I32P, i32, u32, vp]),
+        "otas_strerror": (C.c_char_p, [i32]),
+        "otas_timing_enable": (i32, [vp, i32]),
+        "otas_timing_kinds": (i32, []),
+        "otas_timing_kind_name": (C.c_char_p, [i32]),
+        "otas_timing_read": (i32, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)          # AttributeError if a declared symbol is not exported
+        fn.restype, fn.argtypes = res, args
+    _LIB = lib
+    return lib
+
+
+EXPORTED = ("otas_create", "otas_destroy", "otas_schedule", "otas_workspace_bytes",
+            "otas_merge_workspace_bytes", "otas_prompt_prepend", "otas_token_merge",
+            "otas_encoder_forward", "otas_encoder_layers", "otas_layer_norm", "otas_linear", "otas_attention", "otas_strerror",
+            "otas_timing_enable", "otas_timing_kinds", "otas_timing_kind_name", "otas_timing_read")
+
+
+def otas_strerror(status: int) -> str:
+    return load_library().otas_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise OtasError(status, where)
+
+
+def _i32(values: Sequence[int]):
+    a = np.ascontiguousarray(np.asarray(values, dtype=np.int32))
+    return a, a.ctypes.data_as(_I32P)
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def otas_schedule(n0: int, P: int, r: int, n_lead: int, L: int) -> List[int]:
+    out = (C.c_int32 * (L + 1))()
+    _check(load_library().otas_schedule(n0, P, r, n_lead, L, out), "otas_schedule")
+    return list(out)
+
+
+class Context:
+    """Owns an otas_ctx.  Methods carry the C entry points' names and argument meaning; tensors
+    must be contiguous torch tensors on the GPU, of the model's dtype unless noted."""
+
+    def __init__(self, L: int, D: int, H: int, F: int, dtype: int, ln_eps: float, n_lead: int,
+                 layers: Sequence[dict], stream: Optional[int] = None):
+        import torch
+        self._lib = load_library()
+        self.L, self.D, self.H, self.F, self.dtype, self.n_lead = L, D, H, F, dtype, n_lead
+        self.torch_dtype = torch.float32 if dtype == OTAS_F32 else torch.bfloat16
+        self._keep = [dict(w) for w in layers]           # the library keeps pointers, not copies
+        arr = (_LayerWeights * L)()
+        for l, w in enumerate(self._keep):
+            for f in _WEIGHT_FIELDS:
+                t = w[f]
+                assert t.is_cuda and t.is_contiguous() and t.dtype == self.torch_dtype, f
+                setattr(arr[l], f, t.data_ptr())
+        desc = _ModelDesc(L, D, H, F, dtype, ln_eps, n_lead)
+        self._h = C.c_void_p()
+        if stream is None:
+            stream = torch.cuda.current_stream().cuda_stream
+        self.stream = stream
+        _check(self._lib.otas_create(C.byref(self._h), C.byref(desc), arr, C.c_void_p(stream)), "otas_create")
+
+    @classmethod
+    def from_host_weights(cls, L, D, H, F, dtype, ln_eps, n_lead, layers_host, stream=None) -> "Context":
+        """Upload per-layer dicts of host (NumPy float32) arrays to the GPU in the model's dtype and
+        create the context on them."""
+        import torch
+        tdt = torch.float32 if dtype == OTAS_F32 else torch.bfloat16
+        dev = [{k: torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to("cuda").to(tdt).contiguous()
+                for k, v in w.items()} for w in layers_host]
+        return cls(L, D, H, F, dtype, ln_eps, n_lead, dev, stream)
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            self._lib.otas_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- pure host helpers
+    def otas_workspace_bytes(self, B: int, T0: int) -> int:
+        return int(self._lib.otas_workspace_bytes(self._h, B, T0))
+
+    def otas_merge_workspace_bytes(self, B: int, T: int) -> int:
+        return int(self._lib.otas_merge_workspace_bytes(B, T))
+
+    # -- device entry points
+    def otas_prompt_prepend(self, tokens, tok_offsets, prompts, prompt_offsets, out) -> np.ndarray:
+        B = len(tok_offsets) - 1
+        ta, tp = _i32(tok_offsets)
+        pa, pp = _i32(prompt_offsets)
+        oo = np.zeros(B + 1, dtype=np.int32)
+        _check(self._lib.otas_prompt_prepend(self._h, _ptr(tokens), tp, _ptr(prompts), pp, B, _ptr(out),
+                                             oo.ctypes.data_as(_I32P)), "otas_prompt_prepend")
+        return oo
+
+    def otas_token_merge(self, x, metric, dm, sizes, offsets, r, workspace, x_out, sizes_out,
+                         trace_src=None, trace_dst=None) -> np.ndarray:
+        B = len(offsets) - 1
+        oa, op = _i32(offsets)
+        ra, rp = _i32(r)
+        oo = np.zeros(B + 1, dtype=np.int32)
+        _check(self._lib.otas_token_merge(self._h, _ptr(x), _ptr(metric), dm, _ptr(sizes), op, rp, B,
+                                          _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                          _ptr(x_out), _ptr(sizes_out), oo.ctypes.data_as(_I32P),
+                                          _ptr(trace_src), _ptr(trace_dst)), "otas_token_merge")
+        return oo
+
+    def otas_encoder_forward(self, x0, offsets, r, flags, workspace, x_out, sizes_out,
+                             trace_src=None, trace_dst=None) -> np.ndarray:
+        B = len(offsets) - 1
+        oa, op = _i32(offsets)
+        ra, rp = _i32(r)
+        oo = np.zeros(B + 1, dtype=np.int32)
+        _check(self._lib.otas_encoder_forward(self._h, _ptr(x0), op, rp, B, flags, _ptr(workspace),
+                                              workspace.numel() * workspace.element_size(), _ptr(x_out),
+                                              _ptr(sizes_out), oo.ctypes.data_as(_I32P), _ptr(trace_src),
+                                              _ptr(trace_dst)), "otas_encoder_forward")
+        return oo
+
+    def otas_encoder_layers(self, layer_begin, layer_end, x0, sizes_in, offsets, r, flags, workspace, x_out,
+                            sizes_out, trace_src=None, trace_dst=None) -> np.ndarray:
+        B = len(offsets) - 1
+        oa, op = _i32(offsets)
+        ra, rp = _i32(r)
+        oo = np.zeros(B + 1, dtype=np.int32)
+        _check(self._lib.otas_encoder_layers(self._h, layer_begin, layer_end, _ptr(x0), _ptr(sizes_in), op, rp, B,
+                                             flags, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                             _ptr(x_out), _ptr(sizes_out), oo.ctypes.data_as(_I32P),
+                                             _ptr(trace_src), _ptr(trace_dst)), "otas_encoder_layers")
+        return oo
+
+    def otas_layer_norm(self, x, g, b, T, y) -> None:
+        _check(self._lib.otas_layer_norm(self._h, _ptr(x), _ptr(g), _ptr(b), T, _ptr(y)), "otas_layer_norm")
+
+    def otas_linear(self, x, w, b, res, T, N, K, epilogue, y) -> None:
+        _check(self._lib.otas_linear(self._h, _ptr(x), _ptr(w), _ptr(b), _ptr(res), T, N, K, epilogue, _ptr(y)),
+               "otas_linear")
+
+    def otas_attention(self, qkv, sizes, offsets, flags, o) -> None:
+        B = len(offsets) - 1
+        oa, op = _i32(offsets)
+        _check(self._lib.otas_attention(self._h, _ptr(qkv), _ptr(sizes), op, B, flags, _ptr(o)), "otas_attention")
+
+    def otas_timing_enable(self, on: bool) -> None:
+        _check(self._lib.otas_timing_enable(self._h, 1 if on else 0), "otas_timing_enable")
+
+    def otas_timing_read(self) -> dict:
+        """{kind name: (total ms, launches)} since the last read."""
+        k = self._lib.otas_timing_kinds()
+        ms = (C.c_double * k)()
+        cnt = (C.c_int64 * k)()
+        _check(self._lib.otas_timing_read(self._h, ms, cnt), "otas_timing_read")
+        return {self._lib.otas_timing_kind_name(i).decode(): (ms[i], int(cnt[i])) for i in range(k)}
+
+    # -- plan arithmetic shared with callers (host only)
+    def trace_layout(self, lengths0: Sequence[int], r: Sequence[int],
+                     n_layers: Optional[int] = None) -> Tuple[np.ndarray, np.ndarray]:
+        """(r_eff[n_layers][B], trace_offset[n_layers][B]) of the trace buffers of
+        otas_encoder_forward / otas_encoder_layers, from the library's own schedule function."""
+        B = len(lengths0)
+        nl = self.L if n_layers is None else n_layers
+        reff = np.zeros((nl, B), dtype=np.int64)
+        for q in range(B):
+            s = otas_schedule(int(lengths0[q]), 0, int(r[q]), self.n_lead, nl)
+            reff[:, q] = -np.diff(np.asarray(s))
+        flat = reff.reshape(-1)
+        troff = np.concatenate([[0], np.cumsum(flat)[:-1]]).reshape(nl, B)
+        return reff, troff

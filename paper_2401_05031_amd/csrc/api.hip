@@ -1,0 +1,522 @@
+// C ABI of the library (include/otas.h): argument validation, the host-side length schedule, the
+// per-call plan upload, and the launch sequence of the token-adapted encoder block (Sec. III-B:
+// normalisation -> attention -> [merge] -> normalisation -> MLP, prompting in front).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/otas.h"
+#include "kernels.h"
+
+using namespace otas;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int64_t kRowPad = 256;              // activation buffers are padded to this many rows
+constexpr size_t kPlanInts = (size_t)1 << 20;  // capacity of the device plan buffer (int32 entries)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int removal_count(int n, int r, int n_lead) { return std::max(0, std::min(r, (n - n_lead) / 2)); }
+
+}  // namespace
+
+struct otas_ctx {
+  otas_model_desc desc;
+  std::vector<otas_layer_weights> layers;
+  hipStream_t stream;
+  int device;
+  int32_t* d_plan;        // device plan buffer [kPlanInts]
+  int32_t* h_plan[2];     // pinned host staging, double buffered
+  hipEvent_t h_done[2];   // staging buffer i may be overwritten once h_done[i] has completed
+  bool h_used[2];
+  int h_next;
+  // optional per-launch timing (otas_timing_enable): one event pair per launch, summed per kind
+  bool timing;
+  std::vector<hipEvent_t> ev_pool;
+  std::vector<int> ev_kind;   // kind of the launch bracketed by ev_pool[2i], ev_pool[2i+1]
+};
+
+namespace {
+
+size_t elem_size(int dtype) { return dtype == OTAS_F32 ? 4 : 2; }
+
+bool offsets_ok(const int32_t* off, int B) {
+  if (off[0] != 0) return false;
+  for (int q = 0; q < B; ++q)
+    if (off[q + 1] < off[q]) return false;
+  return true;
+}
+
+// Copies `count` ints to the device plan buffer at entry `at` through pinned staging.
+otas_status upload_plan(otas_ctx* c, const std::vector<int32_t>& host) {
+  if (host.size() > kPlanInts) return OTAS_ENOMEM;
+  const int i = c->h_next;
+  c->h_next ^= 1;
+  if (c->h_used[i] && hipEventSynchronize(c->h_done[i]) != hipSuccess) return OTAS_EDEVICE;
+  std::memcpy(c->h_plan[i], host.data(), host.size() * sizeof(int32_t));
+  if (hipMemcpyAsync(c->d_plan, c->h_plan[i], host.size() * sizeof(int32_t), hipMemcpyHostToDevice, c->stream) !=
+      hipSuccess)
+    return OTAS_EDEVICE;
+  if (hipEventRecord(c->h_done[i], c->stream) != hipSuccess) return OTAS_EDEVICE;
+  c->h_used[i] = true;
+  return OTAS_OK;
+}
+
+struct WorkspaceLayout {
+  size_t xa, xb, h, qkv, hid, mhat, sizes_a, sizes_b, src_list, row_ptr, total;
+};
+
+WorkspaceLayout forward_layout(const otas_model_desc& d, int64_t T0) {
+  const size_t es = elem_size(d.dtype);
+  const size_t rows = (size_t)((T0 + kRowPad - 1) / kRowPad * kRowPad);
+  WorkspaceLayout w;
+  size_t p = 0;
+  auto take = [&](size_t bytes) { size_t at = p; p = align_up(p + bytes, kAlign); return at; };
+  w.xa = take(rows * d.D * sizeof(float));   // the residual stream is float for every dtype
+  w.xb = take(rows * d.D * sizeof(float));
+  w.h = take(rows * d.D * es);
+  w.qkv = take(rows * 3 * d.D * es);
+  w.hid = take(rows * d.F * es);
+  w.mhat = take(rows * (size_t)(d.D / d.H) * sizeof(float));
+  w.sizes_a = take(rows * sizeof(int32_t));
+  w.sizes_b = take(rows * sizeof(int32_t));
+  w.src_list = take(rows * sizeof(int32_t));
+  w.row_ptr = take((rows + 1) * sizeof(int32_t));
+  w.total = p;
+  return w;
+}
+
+#define OTAS_HIP(expr)                         \
+  do {                                         \
+    if ((expr) != hipSuccess) return OTAS_EDEVICE; \
+  } while (0)
+
+enum Kind { K_PREPEND = 0, K_LN, K_QKV, K_ATTN, K_PROJ, K_METRIC, K_PLAN, K_APPLY, K_FC1, K_FC2, K_MISC, K_COUNT };
+const char* const kKindNames[K_COUNT] = {"prompt_prepend", "layer_norm", "gemm_qkv", "attention", "gemm_proj",
+                                         "merge_metric", "merge_plan", "merge_apply", "gemm_fc1", "gemm_fc2", "misc"};
+
+// Brackets one launch with an event pair when timing is on.
+struct LaunchTimer {
+  otas_ctx* c;
+  bool on;
+  LaunchTimer(otas_ctx* ctx, int kind) : c(ctx), on(ctx->timing) {
+    if (!on) return;
+    const size_t i = c->ev_kind.size();
+    while (c->ev_pool.size() < 2 * (i + 1)) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) { on = false; return; }
+      c->ev_pool.push_back(e);
+    }
+    c->ev_kind.push_back(kind);
+    (void)hipEventRecord(c->ev_pool[2 * i], c->stream);
+  }
+  ~LaunchTimer() {
+    if (on) (void)hipEventRecord(c->ev_pool[2 * (c->ev_kind.size() - 1) + 1], c->stream);
+  }
+};
+#define OTAS_LAUNCH(kind, expr)   \
+  do {                            \
+    LaunchTimer _t(c, kind);      \
+    OTAS_HIP(expr);               \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+const char* otas_strerror(otas_status s) {
+  switch (s) {
+    case OTAS_OK: return "ok";
+    case OTAS_EINVAL: return "invalid argument";
+    case OTAS_ESHAPE: return "shape does not match the model description";
+    case OTAS_ENOMEM: return "workspace or plan buffer too small";
+    case OTAS_EDEVICE: return "HIP runtime error";
+    case OTAS_EUNSUPPORTED: return "size outside the supported range";
+  }
+  return "unknown status";
+}
+
+otas_status otas_schedule(int32_t n0, int32_t P, int32_t r, int32_t n_lead, int32_t L, int32_t* len_out) {
+  if (!len_out || n0 < 0 || P < 0 || r < 0 || L < 0 || n_lead < 0 || n_lead > 1) return OTAS_EINVAL;
+  if (n0 < n_lead) return OTAS_EINVAL;
+  int n = n0 + P;
+  len_out[0] = n;
+  for (int l = 0; l < L; ++l) {
+    n -= removal_count(n, r, n_lead);
+    len_out[l + 1] = n;
+  }
+  return OTAS_OK;
+}
+
+otas_status otas_create(otas_ctx** out, const otas_model_desc* desc, const otas_layer_weights* layers,
+                        void* hip_stream) {
+  if (!out || !desc || !layers) return OTAS_EINVAL;
+  *out = nullptr;
+  const otas_model_desc& d = *desc;
+  if (d.L <= 0 || d.D <= 0 || d.H <= 0 || d.F <= 0 || !(d.ln_eps >= 0.f)) return OTAS_EINVAL;
+  if (d.dtype != OTAS_F32 && d.dtype != OTAS_BF16) return OTAS_EINVAL;
+  if (d.n_lead < 0 || d.n_lead > 1) return OTAS_EUNSUPPORTED;
+  if (d.D % d.H != 0) return OTAS_ESHAPE;
+  const int dh = d.D / d.H;
+  if (d.D % 8 != 0 || d.F % 8 != 0 || dh % 4 != 0 || dh > 128) return OTAS_EUNSUPPORTED;
+  if (d.D > 8 * 64 * (d.dtype == OTAS_F32 ? 4 : 8)) return OTAS_EUNSUPPORTED;
+  for (int l = 0; l < d.L; ++l) {
+    const void* const* p = reinterpret_cast<const void* const*>(&layers[l]);
+    for (size_t i = 0; i < sizeof(otas_layer_weights) / sizeof(void*); ++i)
+      if (!p[i]) return OTAS_EINVAL;
+  }
+  otas_ctx* c = new (std::nothrow) otas_ctx();
+  if (!c) return OTAS_ENOMEM;
+  c->desc = d;
+  c->layers.assign(layers, layers + d.L);
+  c->stream = (hipStream_t)hip_stream;
+  c->d_plan = nullptr;
+  c->h_plan[0] = c->h_plan[1] = nullptr;
+  c->h_done[0] = c->h_done[1] = nullptr;
+  c->h_used[0] = c->h_used[1] = false;
+  c->h_next = 0;
+  c->timing = false;
+  bool ok = hipGetDevice(&c->device) == hipSuccess;
+  ok = ok && hipMalloc((void**)&c->d_plan, kPlanInts * sizeof(int32_t)) == hipSuccess;
+  for (int i = 0; i < 2 && ok; ++i) {
+    ok = hipHostMalloc((void**)&c->h_plan[i], kPlanInts * sizeof(int32_t), hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&c->h_done[i], hipEventDisableTiming) == hipSuccess;
+  }
+  if (!ok) {
+    otas_destroy(c);
+    return OTAS_EDEVICE;
+  }
+  *out = c;
+  return OTAS_OK;
+}
+
+otas_status otas_destroy(otas_ctx* c) {
+  if (!c) return OTAS_OK;
+  if (c->stream || c->d_plan) (void)hipStreamSynchronize(c->stream);
+  for (int i = 0; i < 2; ++i) {
+    if (c->h_done[i]) (void)hipEventDestroy(c->h_done[i]);
+    if (c->h_plan[i]) (void)hipHostFree(c->h_plan[i]);
+  }
+  for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+  if (c->d_plan) (void)hipFree(c->d_plan);
+  delete c;
+  return OTAS_OK;
+}
+
+size_t otas_workspace_bytes(const otas_ctx* c, int32_t B, int64_t T0) {
+  if (!c || B <= 0 || T0 <= 0) return 0;
+  return forward_layout(c->desc, T0).total;
+}
+
+size_t otas_merge_workspace_bytes(int32_t B, int64_t T) {
+  if (B <= 0 || T <= 0) return 0;
+  // mhat [T,128] float (worst case), src_list [T], row_ptr [T+1]
+  return align_up((size_t)T * 128 * sizeof(float), kAlign) + align_up((size_t)T * 4, kAlign) +
+         align_up((size_t)(T + 1) * 4, kAlign);
+}
+
+otas_status otas_prompt_prepend(otas_ctx* c, const void* tokens, const int32_t* tok_off, const void* prompts,
+                                const int32_t* prm_off, int32_t B, void* out, int32_t* out_off) {
+  if (!c || !tokens || !tok_off || !prm_off || !out || !out_off || B <= 0) return OTAS_EINVAL;
+  if (!offsets_ok(tok_off, B) || !offsets_ok(prm_off, B)) return OTAS_EINVAL;
+  if (prm_off[B] > 0 && !prompts) return OTAS_EINVAL;
+  if (out == tokens || (prompts && out == prompts)) return OTAS_EINVAL;
+  int max_n = 0;
+  std::vector<int32_t> plan(3 * (size_t)(B + 1));
+  out_off[0] = 0;
+  for (int q = 0; q < B; ++q) {
+    const int n = tok_off[q + 1] - tok_off[q], P = prm_off[q + 1] - prm_off[q];
+    if (n < c->desc.n_lead) return OTAS_EINVAL;
+    out_off[q + 1] = out_off[q] + n + P;
+    max_n = std::max(max_n, n + P);
+  }
+  std::memcpy(&plan[0], tok_off, (B + 1) * sizeof(int32_t));
+  std::memcpy(&plan[B + 1], prm_off, (B + 1) * sizeof(int32_t));
+  std::memcpy(&plan[2 * (B + 1)], out_off, (B + 1) * sizeof(int32_t));
+  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
+  otas_status st = upload_plan(c, plan);
+  if (st != OTAS_OK) return st;
+  OTAS_LAUNCH(K_PREPEND, launch_prepend(c->desc.dtype, tokens, prompts, out, c->d_plan, c->d_plan + (B + 1),
+                          c->d_plan + 2 * (B + 1), B, max_n, c->desc.D, c->desc.n_lead, c->stream));
+  return OTAS_OK;
+}
+
+otas_status otas_token_merge(otas_ctx* c, const void* x, const void* metric, int32_t dm, const int32_t* sizes,
+                             const int32_t* offsets, const int32_t* r, int32_t B, void* workspace,
+                             size_t workspace_bytes, void* x_out, int32_t* sizes_out, int32_t* offsets_out,
+                             int32_t* trace_src, int32_t* trace_dst) {
+  if (!c || !x || !metric || !offsets || !r || !workspace || !x_out || !sizes_out || !offsets_out || B <= 0)
+    return OTAS_EINVAL;
+  if ((trace_src == nullptr) != (trace_dst == nullptr)) return OTAS_EINVAL;
+  if (dm <= 0 || dm % 4 != 0 || dm > 128) return OTAS_EUNSUPPORTED;
+  if (!offsets_ok(offsets, B)) return OTAS_EINVAL;
+  if (x_out == x || (const void*)sizes_out == (const void*)sizes) return OTAS_EINVAL;
+  if (((uintptr_t)workspace) % kAlign != 0) return OTAS_EINVAL;
+  const int64_t T = offsets[B];
+  if (T <= 0) return OTAS_EINVAL;
+  if (workspace_bytes < otas_merge_workspace_bytes(B, T)) return OTAS_ENOMEM;
+  const int n_lead = c->desc.n_lead;
+  // plan: in_off [B+1] | out_off [B+1] | r_eff [B] | trace_off [B]
+  std::vector<int32_t> plan(4 * (size_t)B + 2);
+  int32_t* in_off = &plan[0];
+  int32_t* out_off = &plan[B + 1];
+  int32_t* reff = &plan[2 * (B + 1)];
+  int32_t* troff = &plan[2 * (B + 1) + B];
+  int max_n = 0, tr = 0;
+  out_off[0] = 0;
+  for (int q = 0; q < B; ++q) {
+    const int n = offsets[q + 1] - offsets[q];
+    if (r[q] < 0) return OTAS_EINVAL;
+    if (n > 0 && n < n_lead) return OTAS_EINVAL;
+    if (n > OTAS_MAX_SEQ) return OTAS_EUNSUPPORTED;
+    in_off[q] = offsets[q];
+    reff[q] = removal_count(n, r[q], n_lead);
+    troff[q] = tr;
+    tr += reff[q];
+    out_off[q + 1] = out_off[q] + n - reff[q];
+    max_n = std::max(max_n, n);
+  }
+  in_off[B] = offsets[B];
+  if (merge_plan_lds_bytes(max_n, dm) > 160 * 1024) return OTAS_EUNSUPPORTED;
+  std::memcpy(offsets_out, out_off, (B + 1) * sizeof(int32_t));
+  const int64_t T_out = out_off[B];
+  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
+  otas_status st = upload_plan(c, plan);
+  if (st != OTAS_OK) return st;
+  char* ws = (char*)workspace;
+  float* mhat = (float*)ws;
+  int32_t* src_list = (int32_t*)(ws + align_up((size_t)T * 128 * sizeof(float), kAlign));
+  int32_t* row_ptr = (int32_t*)((char*)src_list + align_up((size_t)T * 4, kAlign));
+  const int32_t* dp = c->d_plan;
+  OTAS_LAUNCH(K_METRIC, launch_metric(c->desc.dtype, metric, dm, 0, 1, dm, T, mhat, c->stream));
+  OTAS_LAUNCH(K_PLAN, launch_merge_plan(mhat, dm, dp, dp + (B + 1), dp + 2 * (B + 1), dp + 2 * (B + 1) + B, B, max_n, n_lead,
+                             src_list, row_ptr, trace_src, trace_dst, c->stream));
+  OTAS_LAUNCH(K_APPLY, launch_merge_apply(c->desc.dtype, x, sizes, src_list, row_ptr, T, T_out, c->desc.D, x_out, sizes_out,
+                              c->stream));
+  return OTAS_OK;
+}
+
+namespace {
+otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, const void* x0, bool x0_is_float,
+                       const int32_t* sizes_in, const int32_t* offsets, const int32_t* r, int32_t B, uint32_t flags,
+                       void* workspace, size_t workspace_bytes, void* x_out, int32_t* sizes_out,
+                       int32_t* offsets_out, int32_t* trace_src, int32_t* trace_dst);
+}
+
+otas_status otas_encoder_forward(otas_ctx* c, const void* x0, const int32_t* offsets, const int32_t* r, int32_t B,
+                                 uint32_t flags, void* workspace, size_t workspace_bytes, void* x_out,
+                                 int32_t* sizes_out, int32_t* offsets_out, int32_t* trace_src, int32_t* trace_dst) {
+  if (!c) return OTAS_EINVAL;
+  return run_layers(c, 0, c->desc.L, x0, c->desc.dtype == OTAS_F32, nullptr, offsets, r, B, flags, workspace,
+                    workspace_bytes, x_out, sizes_out, offsets_out, trace_src, trace_dst);
+}
+
+otas_status otas_encoder_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, const void* x0,
+                                const int32_t* sizes_in, const int32_t* offsets, const int32_t* r, int32_t B,
+                                uint32_t flags, void* workspace, size_t workspace_bytes, void* x_out,
+                                int32_t* sizes_out, int32_t* offsets_out, int32_t* trace_src, int32_t* trace_dst) {
+  if (!c) return OTAS_EINVAL;
+  return run_layers(c, layer_begin, layer_end, x0, true, sizes_in, offsets, r, B, flags, workspace, workspace_bytes,
+                    x_out, sizes_out, offsets_out, trace_src, trace_dst);
+}
+
+}  // extern "C"
+
+namespace {
+otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, const void* x0, bool x0_is_float,
+                       const int32_t* sizes_in, const int32_t* offsets, const int32_t* r, int32_t B, uint32_t flags,
+                       void* workspace, size_t workspace_bytes, void* x_out, int32_t* sizes_out,
+                       int32_t* offsets_out, int32_t* trace_src, int32_t* trace_dst) {
+  if (!c || !x0 || !offsets || !r || !workspace || !x_out || !sizes_out || !offsets_out || B <= 0)
+    return OTAS_EINVAL;
+  if (layer_begin < 0 || layer_end > c->desc.L || layer_begin >= layer_end) return OTAS_EINVAL;
+  if ((const void*)sizes_in == (const void*)sizes_out) return OTAS_EINVAL;
+  if (flags & ~(uint32_t)(OTAS_FLAG_SIZE_BIAS | OTAS_FLAG_TRACE)) return OTAS_EINVAL;
+  const bool trace = flags & OTAS_FLAG_TRACE;
+  if (trace && (!trace_src || !trace_dst)) return OTAS_EINVAL;
+  if (!offsets_ok(offsets, B)) return OTAS_EINVAL;
+  if (x_out == x0 || ((uintptr_t)workspace) % kAlign != 0) return OTAS_EINVAL;
+  const otas_model_desc& d = c->desc;
+  const int L = layer_end - layer_begin, D = d.D, H = d.H, F = d.F, dh = D / H, n_lead = d.n_lead;
+  const int64_t T0 = offsets[B];
+  if (T0 <= 0) return OTAS_EINVAL;
+  const WorkspaceLayout w = forward_layout(d, T0);
+  if (workspace_bytes < w.total) return OTAS_ENOMEM;
+  {
+    const char* ws = (const char*)workspace;
+    const char* xo = (const char*)x_out;
+    if (xo >= ws && xo < ws + w.total) return OTAS_EINVAL;
+  }
+
+  // Host plan.  Layout (int32): off[l][B+1] for l = 0..L | r_eff[l][B] | trace_off[l][B].
+  const size_t o_off = 0, o_reff = (size_t)(L + 1) * (B + 1), o_tr = o_reff + (size_t)L * B;
+  std::vector<int32_t> plan(o_tr + (size_t)L * B);
+  std::vector<int> max_n(L + 1, 0);
+  std::vector<char> any_merge(L, 0);
+  std::vector<int> len(B);
+  plan[0] = 0;
+  for (int q = 0; q < B; ++q) {
+    len[q] = offsets[q + 1] - offsets[q];
+    if (r[q] < 0 || len[q] <= 0 || len[q] < n_lead) return OTAS_EINVAL;
+    if (len[q] > OTAS_MAX_SEQ) return OTAS_EUNSUPPORTED;
+    plan[o_off + q + 1] = offsets[q + 1];
+    max_n[0] = std::max(max_n[0], len[q]);
+  }
+  int tr = 0;
+  for (int l = 0; l < L; ++l) {
+    int32_t* off_next = &plan[o_off + (size_t)(l + 1) * (B + 1)];
+    off_next[0] = 0;
+    for (int q = 0; q < B; ++q) {
+      const int k = removal_count(len[q], r[q], n_lead);
+      plan[o_reff + (size_t)l * B + q] = k;
+      plan[o_tr + (size_t)l * B + q] = tr;
+      tr += k;
+      if (k > 0) any_merge[l] = 1;
+      len[q] -= k;
+      off_next[q + 1] = off_next[q] + len[q];
+      max_n[l + 1] = std::max(max_n[l + 1], len[q]);
+    }
+    if (any_merge[l] && merge_plan_lds_bytes(max_n[l], dh) > 160 * 1024) return OTAS_EUNSUPPORTED;
+  }
+  std::memcpy(offsets_out, &plan[o_off + (size_t)L * (B + 1)], (B + 1) * sizeof(int32_t));
+
+  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
+  otas_status st = upload_plan(c, plan);
+  if (st != OTAS_OK) return st;
+
+  char* ws = (char*)workspace;
+  void* xa = ws + w.xa;
+  void* xb = ws + w.xb;
+  void* hbuf = ws + w.h;
+  void* qkv = ws + w.qkv;
+  void* hid = ws + w.hid;
+  float* mhat = (float*)(ws + w.mhat);
+  int32_t* sizes_cur = (int32_t*)(ws + w.sizes_a);
+  int32_t* sizes_alt = (int32_t*)(ws + w.sizes_b);
+  int32_t* src_list = (int32_t*)(ws + w.src_list);
+  int32_t* row_ptr = (int32_t*)(ws + w.row_ptr);
+  const int32_t* dp = c->d_plan;
+  hipStream_t s = c->stream;
+  const int dt = d.dtype;
+  const bool size_bias = flags & OTAS_FLAG_SIZE_BIAS;
+
+  if (sizes_in) OTAS_LAUNCH(K_MISC, launch_copy_i32(sizes_in, sizes_cur, T0, s));
+  else OTAS_LAUNCH(K_MISC, launch_fill_i32(sizes_cur, 1, T0, s));
+  void* x_free[2] = {xa, xb};
+  const void* x_cur = x0;   // residual stream entering the block (float)
+  bool x_owned = false;     // x_cur is one of the workspace buffers, so it may be updated in place
+  if (!x0_is_float) {       // 16-bit tokens: widen once into the workspace
+    OTAS_LAUNCH(K_MISC, launch_widen(x0, (float*)xa, T0 * D, s));
+    x_cur = xa;
+    x_owned = true;
+  }
+  for (int l = 0; l < L; ++l) {
+    const otas_layer_weights& wl = c->layers[layer_begin + l];
+    const int32_t* off_l = dp + o_off + (size_t)l * (B + 1);
+    const int32_t* off_n = dp + o_off + (size_t)(l + 1) * (B + 1);
+    const int64_t T = plan[o_off + (size_t)l * (B + 1) + B];
+    const int64_t Tn = plan[o_off + (size_t)(l + 1) * (B + 1) + B];
+    // normalisation -> QKV -> attention -> projection + residual
+    OTAS_LAUNCH(K_LN, launch_layer_norm(dt, true, x_cur, wl.ln1_g, wl.ln1_b, hbuf, T, D, d.ln_eps, s));
+    OTAS_LAUNCH(K_QKV, launch_linear(dt, hbuf, wl.w_qkv, wl.b_qkv, nullptr, qkv, T, 3 * D, D, EPI_NONE, s));
+    OTAS_LAUNCH(K_ATTN, launch_attention(dt, qkv, sizes_cur, off_l, B, max_n[l], D, H, size_bias, hbuf, s));
+    // in-place residual is safe (each element is read then written by the same thread); the
+    // caller's x0 is never written, so layer 0 writes into the workspace.
+    void* x_attn = x_owned ? const_cast<void*>(x_cur) : x_free[0];
+    OTAS_LAUNCH(K_PROJ, launch_linear(dt, hbuf, wl.w_proj, wl.b_proj, (const float*)x_cur, x_attn, T, D, D,
+                                      EPI_RESIDUAL, s));
+    void* x_mlp = x_attn;
+    // merging module
+    if (any_merge[l]) {
+      void* x_other = (x_attn == x_free[0]) ? x_free[1] : x_free[0];
+      OTAS_LAUNCH(K_METRIC, launch_metric(dt, qkv, 3 * (int64_t)D, D, H, dh, T, mhat, s));
+      OTAS_LAUNCH(K_PLAN, launch_merge_plan(mhat, dh, off_l, off_n, dp + o_reff + (size_t)l * B, dp + o_tr + (size_t)l * B, B,
+                                 max_n[l], n_lead, src_list, row_ptr, trace ? trace_src : nullptr,
+                                 trace ? trace_dst : nullptr, s));
+      OTAS_LAUNCH(K_APPLY, launch_merge_apply(OTAS_F32, x_attn, sizes_cur, src_list, row_ptr, T, Tn, D, x_other, sizes_alt, s));
+      std::swap(sizes_cur, sizes_alt);
+      x_mlp = x_other;
+    }
+    // normalisation -> MLP + residual
+    OTAS_LAUNCH(K_LN, launch_layer_norm(dt, true, x_mlp, wl.ln2_g, wl.ln2_b, hbuf, Tn, D, d.ln_eps, s));
+    OTAS_LAUNCH(K_FC1, launch_linear(dt, hbuf, wl.w_fc1, wl.b_fc1, nullptr, hid, Tn, F, D, EPI_GELU, s));
+    void* x_next = (l == L - 1) ? x_out : x_mlp;
+    OTAS_LAUNCH(K_FC2, launch_linear(dt, hid, wl.w_fc2, wl.b_fc2, (const float*)x_mlp, x_next, Tn, D, F,
+                                     EPI_RESIDUAL, s));
+    x_cur = x_next;
+    x_owned = true;
+  }
+  OTAS_LAUNCH(K_MISC, launch_copy_i32(sizes_cur, sizes_out, plan[o_off + (size_t)L * (B + 1) + B], s));
+  return OTAS_OK;
+}
+}  // namespace
+
+extern "C" {
+
+otas_status otas_layer_norm(otas_ctx* c, const void* x, const void* g, const void* b, int64_t T, void* y) {
+  if (!c || !x || !g || !b || !y || T < 0) return OTAS_EINVAL;
+  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
+  OTAS_LAUNCH(K_LN, launch_layer_norm(c->desc.dtype, c->desc.dtype == OTAS_F32, x, g, b, y, T, c->desc.D, c->desc.ln_eps, c->stream));
+  return OTAS_OK;
+}
+
+otas_status otas_linear(otas_ctx* c, const void* x, const void* w, const void* b, const void* res, int64_t T,
+                        int32_t N, int32_t K, int32_t epilogue, void* y) {
+  if (!c || !x || !w || !b || !y || T < 0 || N <= 0 || K <= 0) return OTAS_EINVAL;
+  if (epilogue < 0 || epilogue > 2 || (epilogue == EPI_RESIDUAL && !res)) return OTAS_EINVAL;
+  if (N % 8 != 0 || K % 8 != 0) return OTAS_EUNSUPPORTED;
+  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
+  OTAS_LAUNCH(K_MISC, launch_linear(c->desc.dtype, x, w, b, (const float*)res, y, T, N, K, epilogue, c->stream));
+  return OTAS_OK;
+}
+
+otas_status otas_attention(otas_ctx* c, const void* qkv, const int32_t* sizes, const int32_t* offsets, int32_t B,
+                           uint32_t flags, void* o) {
+  if (!c || !qkv || !offsets || !o || B <= 0) return OTAS_EINVAL;
+  if (!offsets_ok(offsets, B)) return OTAS_EINVAL;
+  const bool size_bias = flags & OTAS_FLAG_SIZE_BIAS;
+  if (size_bias && !sizes) return OTAS_EINVAL;
+  int max_n = 0;
+  for (int q = 0; q < B; ++q) max_n = std::max(max_n, offsets[q + 1] - offsets[q]);
+  if (max_n > OTAS_MAX_SEQ) return OTAS_EUNSUPPORTED;
+  std::vector<int32_t> plan(offsets, offsets + B + 1);
+  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
+  otas_status st = upload_plan(c, plan);
+  if (st != OTAS_OK) return st;
+  OTAS_LAUNCH(K_ATTN, launch_attention(c->desc.dtype, qkv, sizes, c->d_plan, B, max_n, c->desc.D, c->desc.H, size_bias, o,
+                            c->stream));
+  return OTAS_OK;
+}
+
+otas_status otas_timing_enable(otas_ctx* c, int32_t on) {
+  if (!c) return OTAS_EINVAL;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return OTAS_EDEVICE;
+  c->timing = on != 0;
+  c->ev_kind.clear();
+  return OTAS_OK;
+}
+
+int32_t otas_timing_kinds(void) { return K_COUNT; }
+
+const char* otas_timing_kind_name(int32_t kind) { return (kind >= 0 && kind < K_COUNT) ? kKindNames[kind] : ""; }
+
+otas_status otas_timing_read(otas_ctx* c, double* total_ms, int64_t* launches) {
+  if (!c || !total_ms || !launches) return OTAS_EINVAL;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return OTAS_EDEVICE;
+  for (int k = 0; k < K_COUNT; ++k) { total_ms[k] = 0.0; launches[k] = 0; }
+  for (size_t i = 0; i < c->ev_kind.size(); ++i) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, c->ev_pool[2 * i], c->ev_pool[2 * i + 1]) != hipSuccess) return OTAS_EDEVICE;
+    total_ms[c->ev_kind[i]] += ms;
+    launches[c->ev_kind[i]] += 1;
+  }
+  c->ev_kind.clear();
+  return OTAS_OK;
+}
+
+}  // extern "C"

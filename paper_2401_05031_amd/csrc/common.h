@@ -1,0 +1,59 @@
+// Shared device helpers for the gfx950 kernels: storage types, vector loads, wave reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace otas {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int kWave = 64;
+
+template <typename T> struct Vec;          // 16-byte vector of the storage type
+template <> struct Vec<float> {
+  static constexpr int N = 4;
+  floatx4 v;
+  __device__ float get(int i) const { return v[i]; }
+  __device__ void set(int i, float f) { v[i] = f; }
+};
+template <> struct Vec<bf16_t> {
+  static constexpr int N = 8;
+  bf16x8 v;
+  __device__ float get(int i) const { return (float)v[i]; }
+  __device__ void set(int i, float f) { v[i] = (bf16_t)f; }   // round to nearest even (v_cvt_pk_bf16_f32)
+};
+
+template <typename T> __device__ inline Vec<T> load_vec(const T* p) {
+  return *reinterpret_cast<const Vec<T>*>(p);
+}
+template <typename T> __device__ inline void store_vec(T* p, const Vec<T>& v) {
+  *reinterpret_cast<Vec<T>*>(p) = v;
+}
+
+__device__ inline float to_float(float x) { return x; }
+__device__ inline float to_float(bf16_t x) { return (float)x; }
+template <typename T> __device__ inline T from_float(float x);
+template <> __device__ inline float from_float<float>(float x) { return x; }
+template <> __device__ inline bf16_t from_float<bf16_t>(float x) { return (bf16_t)x; }
+
+// Butterfly reductions over the 64 lanes of a wave: every lane ends with the same value, and the
+// order of additions does not depend on which lanes hold data.
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  return v;
+}
+
+// Exact GELU: 0.5 x (1 + erf(x / sqrt 2)).
+__device__ inline float gelu_exact(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
+
+}  // namespace otas

@@ -1,0 +1,221 @@
+// HBM-bound row kernels: integer fill/copy, the prompting module's ragged concatenation
+// (Sec. II-B / III-B), LayerNorm (Sec. II-A "normalization"), and the merge metric
+// (head-averaged attention keys, Sec. III-B "similarity obtained from multi-head attention").
+#include "common.h"
+#include "kernels.h"
+
+namespace otas {
+
+// ---------------------------------------------------------------------------------- fill / copy
+__global__ void fill_i32_kernel(int32_t* p, int32_t v, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+__global__ void copy_i32_kernel(const int32_t* __restrict__ a, int32_t* __restrict__ b, int64_t n) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) b[i] = a[i];
+}
+hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  fill_i32_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(p, v, n);
+  return hipGetLastError();
+}
+hipError_t launch_copy_i32(const int32_t* a, int32_t* b, int64_t n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  copy_i32_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(a, b, n);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------- prepend
+// One 16-byte chunk per thread.  blockIdx.y = query; blockIdx.x strides over the query's
+// (row, chunk) pairs.  Output row i of a query comes from: i < n_lead -> token i;
+// i < n_lead + P -> prompt i - n_lead; else token i - P.
+template <typename T>
+__global__ void prepend_kernel(const T* __restrict__ tokens, const T* __restrict__ prompts,
+                               T* __restrict__ out, const int32_t* __restrict__ tok_off,
+                               const int32_t* __restrict__ prm_off,
+                               const int32_t* __restrict__ out_off, int D, int n_lead) {
+  constexpr int V = Vec<T>::N;
+  const int q = blockIdx.y;
+  const int o0 = out_off[q], n_out = out_off[q + 1] - o0;
+  const int t0 = tok_off[q], p0 = prm_off[q], P = prm_off[q + 1] - p0;
+  const int chunks = D / V;
+  const int total = n_out * chunks;
+  for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < total; t += gridDim.x * blockDim.x) {
+    const int i = t / chunks, c = (t - i * chunks) * V;
+    const T* src;
+    if (i < n_lead) src = tokens + (size_t)(t0 + i) * D;
+    else if (i < n_lead + P) src = prompts + (size_t)(p0 + i - n_lead) * D;
+    else src = tokens + (size_t)(t0 + i - P) * D;
+    store_vec<T>(out + (size_t)(o0 + i) * D + c, load_vec<T>(src + c));
+  }
+}
+
+hipError_t launch_prepend(int dtype, const void* tokens, const void* prompts, void* out,
+                          const int32_t* d_tok_off, const int32_t* d_prm_off,
+                          const int32_t* d_out_off, int B, int max_n_out, int D, int n_lead,
+                          hipStream_t s) {
+  if (B <= 0 || max_n_out <= 0) return hipSuccess;
+  const int V = dtype == 0 ? 4 : 8;
+  const int64_t tasks = (int64_t)max_n_out * (D / V);
+  unsigned gx = (unsigned)((tasks + 255) / 256);
+  if (gx > 64) gx = 64;
+  dim3 grid(gx, B), block(256);
+  if (dtype == 0)
+    prepend_kernel<float><<<grid, block, 0, s>>>((const float*)tokens, (const float*)prompts, (float*)out,
+                                                 d_tok_off, d_prm_off, d_out_off, D, n_lead);
+  else
+    prepend_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)tokens, (const bf16_t*)prompts,
+                                                  (bf16_t*)out, d_tok_off, d_prm_off, d_out_off, D, n_lead);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------- LayerNorm
+// One wave per row, the row held in registers (NCH 16-byte chunks per lane), two-pass statistics
+// in fp32 (mean, then the biased variance of the centred values).
+// XT = type of the input row (the residual stream is float), T = type of gamma, beta and the output.
+// Each lane owns chunks of 8 consecutive columns (two 16-byte loads of a float row).
+template <typename XT, typename T, int NCH>
+__global__ __launch_bounds__(256) void layer_norm_kernel(const XT* __restrict__ x, const T* __restrict__ g,
+                                                         const T* __restrict__ b, T* __restrict__ y,
+                                                         int64_t Trows, int D, float eps) {
+  constexpr int V = 8;
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= Trows) return;
+  const int chunks = D / V;
+  const XT* xr = x + (size_t)row * D;
+  float v[NCH][V];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane + 64 * i;
+    if (c < chunks) {
+#pragma unroll
+      for (int k0 = 0; k0 < V; k0 += Vec<XT>::N) {
+        Vec<XT> t = load_vec<XT>(xr + c * V + k0);
+#pragma unroll
+        for (int k = 0; k < Vec<XT>::N; ++k) { v[i][k0 + k] = t.get(k); sum += v[i][k0 + k]; }
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < V; ++k) v[i][k] = 0.f;
+    }
+  }
+  const float mean = wave_sum(sum) / (float)D;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane + 64 * i;
+    if (c < chunks) {
+#pragma unroll
+      for (int k = 0; k < V; ++k) { const float d = v[i][k] - mean; sq += d * d; }
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)D + eps);
+  T* yr = y + (size_t)row * D;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane + 64 * i;
+    if (c < chunks) {
+#pragma unroll
+      for (int k0 = 0; k0 < V; k0 += Vec<T>::N) {
+        Vec<T> gg = load_vec<T>(g + c * V + k0), bb = load_vec<T>(b + c * V + k0), o;
+#pragma unroll
+        for (int k = 0; k < Vec<T>::N; ++k) o.set(k, (v[i][k0 + k] - mean) * rstd * gg.get(k) + bb.get(k));
+        store_vec<T>(yr + c * V + k0, o);
+      }
+    }
+  }
+}
+
+template <typename XT, typename T>
+static hipError_t layer_norm_dispatch(const void* x, const void* g, const void* b, void* y, int64_t Trows,
+                                      int D, float eps, hipStream_t s) {
+  const int chunks = D / 8;
+  const int nch = (chunks + 63) / 64;
+  dim3 grid((unsigned)((Trows + 3) / 4)), block(256);
+#define OTAS_LN(N)                                                                                       \
+  layer_norm_kernel<XT, T, N><<<grid, block, 0, s>>>((const XT*)x, (const T*)g, (const T*)b, (T*)y, Trows, D, eps)
+  if (nch <= 1) OTAS_LN(1);
+  else if (nch <= 2) OTAS_LN(2);
+  else if (nch <= 3) OTAS_LN(3);
+  else if (nch <= 4) OTAS_LN(4);
+  else if (nch <= 8) OTAS_LN(8);
+  else return hipErrorInvalidValue;
+#undef OTAS_LN
+  return hipGetLastError();
+}
+
+hipError_t launch_layer_norm(int dtype, bool x_is_float, const void* x, const void* g, const void* b, void* y,
+                             int64_t T, int D, float eps, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  if (dtype == 0) return layer_norm_dispatch<float, float>(x, g, b, y, T, D, eps, s);
+  return x_is_float ? layer_norm_dispatch<float, bf16_t>(x, g, b, y, T, D, eps, s)
+                    : layer_norm_dispatch<bf16_t, bf16_t>(x, g, b, y, T, D, eps, s);
+}
+
+// ---------------------------------------------------------------------------------- widen / narrow
+// Token tensors enter and leave in the model's dtype; the residual stream in between is float.
+__global__ void widen_kernel(const bf16_t* __restrict__ a, float* __restrict__ b, int64_t n8) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n8) return;
+  const Vec<bf16_t> v = load_vec<bf16_t>(a + i * 8);
+  Vec<float> lo, hi;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) { lo.set(k, v.get(k)); hi.set(k, v.get(4 + k)); }
+  store_vec<float>(b + i * 8, lo);
+  store_vec<float>(b + i * 8 + 4, hi);
+}
+hipError_t launch_widen(const void* src_bf16, float* dst, int64_t n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  const int64_t n8 = n / 8;
+  widen_kernel<<<dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s>>>((const bf16_t*)src_bf16, dst, n8);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------- merge metric
+// Half a wave (32 lanes) per token; lane c4 owns 4 consecutive columns of the metric vector.
+// m = (1/H) sum_h src[row, col_off + h*dm + c], summed over h in ascending order, then divided by
+// max(||m||, tiny).  The 32-lane butterfly makes the norm independent of the launch shape.
+template <typename T>
+__global__ __launch_bounds__(256) void metric_kernel(const T* __restrict__ src, int64_t row_stride, int col_off,
+                                                     int H, int dm, int64_t Trows, float* __restrict__ mhat) {
+  const int sub = threadIdx.x & 31;
+  const int64_t row = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
+  if (row >= Trows) return;
+  const int c = sub * 4;
+  float m[4] = {0.f, 0.f, 0.f, 0.f};
+  if (c < dm) {
+    const T* p = src + (size_t)row * row_stride + col_off + c;
+    for (int h = 0; h < H; ++h) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) m[k] += to_float(p[(size_t)h * dm + k]);
+    }
+    const float inv = 1.0f / (float)H;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) m[k] *= inv;
+  }
+  float ss = m[0] * m[0] + m[1] * m[1] + m[2] * m[2] + m[3] * m[3];
+#pragma unroll
+  for (int o = 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o, kWave);
+  const float rn = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
+  if (c < dm) {
+    floatx4 o = {m[0] * rn, m[1] * rn, m[2] * rn, m[3] * rn};
+    *reinterpret_cast<floatx4*>(mhat + (size_t)row * dm + c) = o;
+  }
+}
+
+hipError_t launch_metric(int dtype, const void* src, int64_t row_stride, int col_off, int H, int dm, int64_t T,
+                         float* mhat, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  if (dm % 4 != 0 || dm > 128) return hipErrorInvalidValue;
+  dim3 grid((unsigned)((T + 7) / 8)), block(256);
+  if (dtype == 0)
+    metric_kernel<float><<<grid, block, 0, s>>>((const float*)src, row_stride, col_off, H, dm, T, mhat);
+  else
+    metric_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)src, row_stride, col_off, H, dm, T, mhat);
+  return hipGetLastError();
+}
+
+}  // namespace otas

@@ -1,0 +1,51 @@
+// Host-side launchers of the gfx950 kernels.  Internal to the library: the public surface is the
+// C ABI in include/otas.h.  dtype is an otas_dtype value; every pointer is a device pointer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace otas {
+
+enum Epilogue { EPI_NONE = 0, EPI_GELU = 1, EPI_RESIDUAL = 2 };
+
+hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s);
+hipError_t launch_copy_i32(const int32_t* src, int32_t* dst, int64_t n, hipStream_t s);
+
+hipError_t launch_prepend(int dtype, const void* tokens, const void* prompts, void* out,
+                          const int32_t* d_tok_off, const int32_t* d_prm_off,
+                          const int32_t* d_out_off, int B, int max_n_out, int D, int n_lead,
+                          hipStream_t s);
+
+// x_is_float: the input rows are float (the residual stream) even when dtype is bf16.
+hipError_t launch_layer_norm(int dtype, bool x_is_float, const void* x, const void* g, const void* b,
+                             void* y, int64_t T, int D, float eps, hipStream_t s);
+hipError_t launch_widen(const void* src_bf16, float* dst, int64_t n, hipStream_t s);
+
+// EPI_RESIDUAL: res and y are float (the residual stream) for every dtype; otherwise y has the
+// model's dtype.
+hipError_t launch_linear(int dtype, const void* x, const void* w, const void* bias,
+                         const float* res, void* y, int64_t M, int N, int K, int epi,
+                         hipStream_t s);
+
+hipError_t launch_attention(int dtype, const void* qkv, const int32_t* sizes,
+                            const int32_t* d_off, int B, int max_n, int D, int H, bool size_bias,
+                            void* o, hipStream_t s);
+
+// mhat[T, dm] (float) = row-normalised mean over H heads of src[row, col_off + h*dm + c].
+hipError_t launch_metric(int dtype, const void* src, int64_t row_stride, int col_off, int H,
+                         int dm, int64_t T, float* mhat, hipStream_t s);
+
+hipError_t launch_merge_plan(const float* mhat, int dm, const int32_t* d_in_off,
+                             const int32_t* d_out_off, const int32_t* d_reff,
+                             const int32_t* d_troff, int B, int max_n, int n_lead,
+                             int32_t* src_list, int32_t* row_ptr, int32_t* trace_src,
+                             int32_t* trace_dst, hipStream_t s);
+size_t merge_plan_lds_bytes(int max_n, int dm);
+
+// dtype: type of x and x_out (0 = float, 1 = bf16).
+hipError_t launch_merge_apply(int dtype, const void* x, const int32_t* sizes,
+                              const int32_t* src_list, const int32_t* row_ptr, int64_t T_in,
+                              int64_t T_out, int D, void* x_out, int32_t* sizes_out,
+                              hipStream_t s);
+
+}  // namespace otas

@@ -1,0 +1,278 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Bars: f32 -- merge edges and sizes bit-exact, values <= 1e-4 (max abs diff / max abs
+ref); bf16 -- values <= 2e-2 and < 0.1 % of merge decisions differing (near-ties), with the oracle
+rounding at the same storage points and adopting the GPU's decisions layer by layer."""
+import numpy as np
+import pytest
+
+import otas_synth as synth
+from oracle import otas_oracle as orc
+from tests import harness as hz
+
+pytestmark = pytest.mark.gpu
+
+F32_TOL = 1e-4
+BF16_TOL = 2e-2
+BF16_DECISION_TOL = 1e-3
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return torch
+
+
+def _t(torch, a, dt):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda").to(dt).contiguous()
+
+
+# ------------------------------------------------------------------ whole encoder, f32 config
+def test_tiny_f32_encoder_bit_exact_decisions(torch_cuda, lib):
+    cfg = synth.config("tiny")
+    ctx, layers = hz.make_context(cfg)
+    toks, prm, P, R = synth.batch(cfg)
+    x0, off = hz.gpu_prepend(ctx, toks, prm)
+    assert off.tolist() == [0, 201, 402]
+    gpu = hz.gpu_forward(ctx, x0, off, R)
+    ref = hz.oracle_forward(cfg, layers, toks, prm, R)
+    margins = []
+    for q in range(cfg.B):
+        assert np.array_equal(gpu["sizes"][q], ref[q]["sizes"])
+        for l in range(cfg.L):
+            assert np.array_equal(gpu["trace"][q][l][0], ref[q]["trace"][l][0]), (q, l)
+            assert np.array_equal(gpu["trace"][q][l][1], ref[q]["trace"][l][1]), (q, l)
+            margins.append((ref[q]["margins"][l]["argmax_margin"], ref[q]["margins"][l]["rank_margin"]))
+        assert gpu["x"][q].shape == ref[q]["x"].shape == (185, cfg.D)
+        assert hz.rel_err(gpu["x"][q], ref[q]["x"]) <= F32_TOL
+    print("min decision margins (argmax, rank):", np.min(np.array(margins), axis=0))
+    assert gpu["offsets"].tolist() == [0, 185, 370]
+    ctx.close()
+
+
+def test_tiny_f32_size_bias_flag(torch_cuda, lib):
+    cfg = synth.config("tiny")
+    ctx, layers = hz.make_context(cfg)
+    toks, prm, P, R = synth.batch(cfg)
+    x0, off = hz.gpu_prepend(ctx, toks, prm)
+    gpu = hz.gpu_forward(ctx, x0, off, R, flags=lib.OTAS_FLAG_SIZE_BIAS)
+    ref = hz.oracle_forward(cfg, layers, toks, prm, R, size_bias=True)
+    plain = hz.oracle_forward(cfg, layers, toks, prm, R)
+    for q in range(cfg.B):
+        assert np.array_equal(gpu["sizes"][q], ref[q]["sizes"])
+        assert hz.rel_err(gpu["x"][q], ref[q]["x"]) <= F32_TOL
+        assert hz.rel_err(ref[q]["x"], plain[q]["x"]) > 1e-3      # the flag is not a no-op here
+    ctx.close()
+
+
+def test_gamma_zero_is_plain_encoder_f32(torch_cuda, lib):
+    cfg = synth.config("tiny")
+    cfg.strategies = [(0, 0), (0, 0)]
+    ctx, layers = hz.make_context(cfg)
+    toks, prm, P, R = synth.batch(cfg)
+    x0, off = hz.gpu_prepend(ctx, toks, prm)
+    gpu = hz.gpu_forward(ctx, x0, off, R)
+    ref = hz.oracle_forward(cfg, layers, toks, prm, R)
+    for q in range(cfg.B):
+        assert gpu["sizes"][q].tolist() == [1] * 197
+        assert hz.rel_err(gpu["x"][q], ref[q]["x"]) <= F32_TOL
+    ctx.close()
+
+
+# ------------------------------------------------------------------ single steps
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_prompt_prepend_ragged(torch_cuda, lib, dtype):
+    torch = torch_cuda
+    cfg = synth.config("tiny")
+    cfg.dtype = dtype
+    ctx, _ = hz.make_context(cfg)
+    rng = np.random.default_rng(3)
+    ns, Ps = [5, 1, 197, 33, 64], [0, 3, 10, 0, 1]
+    rnd = synth.round_to_bf16 if dtype == "bf16" else (lambda a: a.astype(np.float32))
+    toks = [rnd(rng.standard_normal((n, cfg.D)).astype(np.float32)) for n in ns]
+    prm = [rnd(rng.standard_normal((p, cfg.D)).astype(np.float32)) for p in Ps]
+    out, off = hz.gpu_prepend(ctx, toks, prm)
+    got = out.to(torch.float32).cpu().numpy()
+    assert off.tolist() == np.concatenate([[0], np.cumsum(np.array(ns) + np.array(Ps))]).tolist()
+    for q in range(len(ns)):
+        ref, _ = orc.prompt_prepend(toks[q], prm[q], cfg.n_lead)
+        assert np.array_equal(got[off[q]:off[q + 1]], ref.astype(np.float32))       # a copy: bit-exact
+    ctx.close()
+
+
+def _merge_case(torch, ctx, cfg, ns, rs, dm, seed, sizes_hi=1, dup=False):
+    rng = np.random.default_rng(seed)
+    rnd = synth.round_to_bf16 if cfg.dtype == "bf16" else (lambda a: a.astype(np.float32))
+    xs = [rnd(rng.standard_normal((n, cfg.D)).astype(np.float32)) for n in ns]
+    ms = [rnd(rng.standard_normal((n, dm)).astype(np.float32)) for n in ns]
+    if dup:
+        for m in ms:
+            for k in (1, 4, 7, 10, 13):                 # 5 exact duplicate pairs (fewer than any r below)
+                m[2 * k + 1] = m[2 * k]
+    szs = [rng.integers(1, sizes_hi + 1, n).astype(np.int32) for n in ns]
+    xp, off = synth.pack(xs, cfg.D)
+    mp, _ = synth.pack(ms, dm)
+    T = int(off[-1])
+    reffs = [orc.removal_count(n, r, cfg.n_lead) for n, r in zip(ns, rs)]
+    T_out = T - sum(reffs)
+    dt = ctx.torch_dtype
+    x_d, m_d = _t(torch, xp, dt), _t(torch, mp, dt)
+    s_d = torch.from_numpy(np.concatenate(szs)).to("cuda")
+    ws = torch.empty(ctx.otas_merge_workspace_bytes(len(ns), T), dtype=torch.uint8, device="cuda")
+    x_out = torch.empty((max(T_out, 1), cfg.D), dtype=dt, device="cuda")
+    s_out = torch.empty(max(T_out, 1), dtype=torch.int32, device="cuda")
+    ntr = max(sum(reffs), 1)
+    tsrc = torch.full((ntr,), -1, dtype=torch.int32, device="cuda")
+    tdst = torch.full((ntr,), -1, dtype=torch.int32, device="cuda")
+    out_off = ctx.otas_token_merge(x_d, m_d, dm, s_d if sizes_hi > 1 else None, off, rs, ws, x_out, s_out, tsrc, tdst)
+    torch.cuda.synchronize()
+    gx, gs = x_out.to(torch.float32).cpu().numpy().astype(np.float64), s_out.cpu().numpy()
+    hs, hd = tsrc.cpu().numpy(), tdst.cpu().numpy()
+    st = "bf16" if cfg.dtype == "bf16" else "f32"
+    tr = 0
+    for q, n in enumerate(ns):
+        x2, s2, src, dst, info = orc.token_merge(xs[q], ms[q], szs[q] if sizes_hi > 1 else None, rs[q], cfg.n_lead)
+        k = reffs[q]
+        assert out_off[q + 1] - out_off[q] == n - k
+        if dup:   # cosines of exact duplicates are 1 up to rounding: their mutual order is not unique
+            assert sorted(zip(hs[tr:tr + k].tolist(), hd[tr:tr + k].tolist())) == sorted(zip(src.tolist(), dst.tolist()))
+            assert {(2 * j, 2 * j + 1) for j in (1, 4, 7, 10, 13)} <= set(zip(hs[tr:tr + k].tolist(), hd[tr:tr + k].tolist()))
+        else:
+            assert np.array_equal(hs[tr:tr + k], src) and np.array_equal(hd[tr:tr + k], dst), (q, n, rs[q], info)
+        tr += k
+        assert np.array_equal(gs[out_off[q]:out_off[q + 1]], s2)
+        got = gx[out_off[q]:out_off[q + 1]]
+        if cfg.dtype == "f32":
+            assert hz.rel_err(got, x2) <= 1e-6
+        else:
+            ref = orc.round_storage(x2, "bf16")
+            # fp32 accumulate then one rounding vs float64 then one rounding: at most one bf16 ulp apart
+            assert np.max(np.abs(got - ref) / np.maximum(np.abs(ref), 1e-3)) <= 2 ** -7
+            assert np.mean(got != ref) < 0.01
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_token_merge_ragged_and_edge_cases(torch_cuda, lib, dtype):
+    torch = torch_cuda
+    cfg = synth.config("tiny")
+    cfg.dtype = dtype
+    ctx, _ = hz.make_context(cfg)
+    # ragged lengths spanning several tiles and tails; r = 0, r beyond what can be merged, n = 1, 2, 3
+    ns = [201, 197, 2, 3, 1, 64, 267, 130, 5]
+    rs = [8, 16, 5, 1, 4, 0, 100, 24, 2]
+    _merge_case(torch, ctx, cfg, ns, rs, 64, seed=1)
+    _merge_case(torch, ctx, cfg, ns, rs, 80, seed=2, sizes_hi=5)
+    _merge_case(torch, ctx, cfg, [197] * 3, [16, 8, 50], 64, seed=3, sizes_hi=3, dup=True)   # planted exact ties
+    ctx.close()
+
+
+@pytest.mark.parametrize("dtype,tol", [("f32", 2e-6), ("bf16", 1e-2)])
+def test_layer_norm_linear_attention_steps(torch_cuda, lib, dtype, tol):
+    torch = torch_cuda
+    cfg = synth.config("tiny")
+    cfg.dtype = dtype
+    ctx, layers = hz.make_context(cfg)
+    dt = ctx.torch_dtype
+    rng = np.random.default_rng(7)
+    rnd = synth.round_to_bf16 if dtype == "bf16" else (lambda a: a.astype(np.float32))
+    T, D, H = 333, cfg.D, cfg.H
+    x = rnd((rng.standard_normal((T, D)) * 2 + 0.3).astype(np.float32))
+    w = layers[0]
+    st = "bf16" if dtype == "bf16" else "f64"
+    # LayerNorm
+    y = torch.empty((T, D), dtype=dt, device="cuda")
+    ctx.otas_layer_norm(_t(torch, x, dt), _t(torch, w["ln1_g"], dt), _t(torch, w["ln1_b"], dt), T, y)
+    ref = orc.layer_norm(x.astype(np.float64), w["ln1_g"], w["ln1_b"], cfg.ln_eps)
+    assert hz.rel_err(y.to(torch.float32).cpu().numpy(), ref) <= tol
+    # Linear with each epilogue, M with a ragged tail
+    h = rnd(ref.astype(np.float32))
+    for epi, (wn, bn) in enumerate([("w_qkv", "b_qkv"), ("w_fc1", "b_fc1"), ("w_proj", "b_proj")]):
+        N = w[wn].shape[0]
+        out = torch.empty((T, N), dtype=torch.float32 if epi == 2 else dt, device="cuda")
+        res = rng.standard_normal((T, N)).astype(np.float32)
+        ctx.otas_linear(_t(torch, h, dt), _t(torch, w[wn], dt), _t(torch, w[bn], dt),
+                        _t(torch, res, torch.float32) if epi == 2 else None, T, N, D, epi, out)
+        lin = h.astype(np.float64) @ w[wn].astype(np.float64).T + w[bn]
+        lin = orc.gelu(lin) if epi == 1 else (lin + res if epi == 2 else lin)
+        assert hz.rel_err(out.to(torch.float32).cpu().numpy(), lin) <= tol, wn
+    # Attention over a ragged batch, with and without the size bias
+    ns = [1, 2, 70, 197, 63]
+    off = np.concatenate([[0], np.cumsum(ns)]).astype(np.int32)
+    qkv = rnd(rng.standard_normal((int(off[-1]), 3 * D)).astype(np.float32))
+    sizes = rng.integers(1, 5, int(off[-1])).astype(np.int32)
+    for flags in (0, lib.OTAS_FLAG_SIZE_BIAS):
+        o = torch.empty((int(off[-1]), D), dtype=dt, device="cuda")
+        ctx.otas_attention(_t(torch, qkv, dt), torch.from_numpy(sizes).to("cuda"), off, flags, o)
+        got = o.to(torch.float32).cpu().numpy()
+        for q, n in enumerate(ns):
+            sl = slice(off[q], off[q + 1])
+            ref = orc.attention_heads(qkv[sl].astype(np.float64), H, sizes[sl], bool(flags))
+            assert hz.rel_err(got[sl], ref) <= tol, (q, flags)
+    ctx.close()
+
+
+# ------------------------------------------------------------------ whole encoder, bf16 configs
+# Near-tie threshold for end-to-end runs: tests/test_bf16_noise_floor.py shows on the CPU that the
+# oracle disagrees with a copy of itself fed an input moved by ONE bf16 unit on ~0.5-1 % of the
+# merge decisions of a 12-layer run, all within NEAR_TIE of its own choice, with outputs ~1 %
+# apart.  End to end the GPU is held to that floor; the 0.1 % bar on decisions is applied where
+# both sides see identical inputs (block by block).
+from tests.test_bf16_noise_floor import NEAR_TIE
+
+
+def _bf16_case(cfg, queries):
+    ctx, layers = hz.make_context(cfg)
+    toks, prm, P, R = synth.batch(cfg, queries)
+    x0, off = hz.gpu_prepend(ctx, toks, prm)
+    gpu = hz.gpu_forward(ctx, x0, off, R)
+    rep = hz.compare_lockstep(cfg, layers, toks, prm, R, gpu)
+    for q, qi in enumerate(queries):
+        want = orc.length_schedule(cfg.n0, P[q], R[q], cfg.n_lead, cfg.L)[-1]
+        assert gpu["x"][q].shape == (want, cfg.D)
+        assert int(gpu["sizes"][q].sum()) == cfg.n0 + P[q]
+    per = hz.compare_per_layer(ctx, cfg, layers, toks, prm, R)
+    ctx.close()
+    return rep, per
+
+
+BF16_CASES = [
+    ("vitb_plain", [0, 1]),
+    ("vitb_r16", [0, 1, 2, 3]),
+    ("vitb_p10_r8", [0, 1, 2, 3]),
+    ("vitl_ragged", [0, 1, 32, 33, 64, 65, 96, 97]),           # two queries of each of the 4 groups
+    ("vith_mixed", list(range(8))),
+]
+
+
+@pytest.mark.parametrize("name,queries", BF16_CASES)
+def test_bf16_encoder_parity(torch_cuda, lib, name, queries):
+    cfg = synth.config(name)
+    rep, per = _bf16_case(cfg, queries)
+    print(name, "end-to-end lock-step:", rep)
+    print(name, "per layer, identical inputs:", per)
+    # end to end: values within tolerance under the adopted decisions, sizes identical, and every
+    # differing edge a near-tie in the oracle's own similarities
+    assert rep["sizes_equal"]
+    assert rep["max_err"] <= BF16_TOL
+    assert rep["max_deficit"] <= NEAR_TIE
+    assert rep["disagreements"] <= 0.02 * max(rep["decisions"], 1)
+    # per layer on identical inputs: < 0.1 % of merge decisions differ, values within tolerance
+    assert per["sizes_equal"]
+    assert per["max_err"] <= BF16_TOL
+    assert per["disagreements"] <= BF16_DECISION_TOL * per["decisions"] + (1 if per["decisions"] < 2000 else 0)
+
+
+def test_query_independence_of_batch_composition(torch_cuda, lib):
+    """A query's result must not depend on what else is in the ragged batch."""
+    cfg = synth.config("vitb_p10_r8")
+    cfg.strategies = [(10, 8), (0, 16), (0, 0), (10, 0)] + cfg.strategies[4:]
+    ctx, layers = hz.make_context(cfg)
+    toks, prm, P, R = synth.batch(cfg, [0, 1, 2, 3])
+    x0, off = hz.gpu_prepend(ctx, toks, prm)
+    together = hz.gpu_forward(ctx, x0, off, R)
+    for q in range(4):
+        x1, off1 = hz.gpu_prepend(ctx, toks[q:q + 1], prm[q:q + 1])
+        alone = hz.gpu_forward(ctx, x1, off1, R[q:q + 1])
+        assert np.array_equal(alone["sizes"][0], together["sizes"][q])
+        assert hz.rel_err(alone["x"][0], together["x"][q]) <= 1e-6
+    ctx.close()
