@@ -4,8 +4,9 @@
 // Two kernels:
 //   * gemm_valu_kernel  -- plain fp32 FMA tiles; the true-fp32 path (f32 models) and the fallback
 //                          for shapes the MFMA kernel does not take.
-//   * gemm_mfma_kernel  -- bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32 accumulate, LDS-staged
-//                          tiles, fused bias / GELU / residual epilogue (bf16 models).
+//   * gemm_mfma_kernel, gemm_mfma256_dma_kernel -- bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32
+//                          accumulate, LDS-staged tiles, fused bias / GELU / residual epilogue
+//                          (bf16 models): 128 x 128 tiles for small shapes, 256 x 256 for large.
 #include "common.h"
 #include "kernels.h"
 
@@ -100,10 +101,388 @@ static hipError_t linear_valu(const void* x, const void* w, const void* bias, co
   return hipGetLastError();
 }
 
+
+
+// Epilogue shared by the MFMA kernels.  acc[i][j][e] of a lane belongs to output row
+// m = m_lane + 32 i and columns n = n_lane + 32 j + 8 (e / 4) + (e & 3), where m_lane already
+// includes the lane's row (lane & 31) and n_lane its 4-column half (4 (lane >> 5)).  Loads are
+// clamped to valid addresses and issued in batches ahead of the arithmetic; only stores are masked.
+template <int EPI, int TM, int TN>
+__device__ inline void mfma_epilogue(const floatx16 (&acc)[TM][TN], const bf16_t* __restrict__ bias,
+                                     const float* res, typename OutType<bf16_t, EPI>::type* Y, int64_t M, int N,
+                                     int64_t m_lane, int n_lane) {
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    int nn[4];
+    bf16x4 bb[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      nn[g] = n_lane + j * 32 + g * 8;
+      bb[g] = *reinterpret_cast<const bf16x4*>(bias + (nn[g] < N ? nn[g] : N - 4));
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int64_t m = m_lane + i * 32;
+      const size_t row = (size_t)(m < M ? m : M - 1) * N;
+      floatx4 rr[4];
+      if (EPI == EPI_RESIDUAL) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) rr[g] = *reinterpret_cast<const floatx4*>(res + row + (nn[g] < N ? nn[g] : N - 4));
+      }
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e] + (float)bb[g][e];
+        if (EPI == EPI_GELU) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = gelu_bf16(v[e]);
+        }
+        if (m < M && nn[g] < N) {
+          if (EPI == EPI_RESIDUAL) {
+            floatx4 o = {v[0] + rr[g][0], v[1] + rr[g][1], v[2] + rr[g][2], v[3] + rr[g][3]};
+            *reinterpret_cast<floatx4*>(reinterpret_cast<float*>(Y) + row + nn[g]) = o;
+          } else {
+            bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+            *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16_t*>(Y) + row + nn[g]) = o;
+          }
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------ bf16 MFMA tiles
+// Block tile BM x BN, K step 64, 256 threads = 4 waves in a WGM x WGN grid, each wave owning a
+// (BM/WGM) x (BN/WGN) sub-tile built from 32x32x16 MFMAs.  Operand tiles are staged through LDS,
+// double buffered: while the MFMAs of k-tile t run from one buffer, the global loads of tile t+1
+// are in flight into registers and are written to the other buffer afterwards.
+//
+// LDS rows are 64 bf16 = 128 B = eight 16-byte chunks; chunk c of row r is stored at chunk
+// position c ^ ((r >> 1) & 7).  A ds_read_b128 is served 16 lanes per clock (64 banks x 4 B), and
+// the 16 lanes that read one chunk column of 16 consecutive rows (the MFMA operand pattern) then
+// fall on 16 different (row parity, chunk position) pairs, i.e. on all 64 banks once.
+//
+// The MFMA computes the transposed tile (W rows as the first operand, X rows as the second): a
+// lane then holds, for one output row m, runs of 4 consecutive output columns n, which makes the
+// epilogue's loads and stores 8- or 16-byte vectors along the row.
+template <int EPI, int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+                                                        const bf16_t* __restrict__ bias, const float* res,
+                                                        typename OutType<bf16_t, EPI>::type* Y, int64_t M, int N,
+                                                        int K, int tiles_n) {
+  typedef typename OutType<bf16_t, EPI>::type OT;
+  constexpr int BK = 64;
+  constexpr int WM = BM / WGM, WN = BN / WGN;          // wave sub-tile
+  constexpr int TM = WM / 32, TN = WN / 32;            // 32x32 MFMA tiles per wave
+  constexpr int A_CHUNKS = BM * 8 / 256, W_CHUNKS = BN * 8 / 256;   // 16-byte chunks per thread per k-tile
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                       // [2][BM][64]
+  bf16_t* Ws = As + 2 * BM * BK;                                      // [2][BN][64]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int bid = blockIdx.x;
+  const int tile_m = bid / tiles_n, tile_n = bid - tile_m * tiles_n;
+  const int64_t m0 = (int64_t)tile_m * BM;
+  const int n0 = tile_n * BN;
+
+  // global -> register staging: chunk i = tid + 256 j covers row i / 8, k-chunk i % 8
+  const int ld_row = tid >> 3, ld_c = tid & 7;
+  bf16x8 a_reg[A_CHUNKS], w_reg[W_CHUNKS];
+  auto load_tiles = [&](int k0) {
+#pragma unroll
+    for (int j = 0; j < A_CHUNKS; ++j) {
+      int64_t r = m0 + ld_row + 32 * j;
+      r = r < M ? r : M - 1;                                           // rows past M are never stored
+      a_reg[j] = *reinterpret_cast<const bf16x8*>(A + (size_t)r * K + k0 + ld_c * 8);
+    }
+#pragma unroll
+    for (int j = 0; j < W_CHUNKS; ++j) {
+      int r = n0 + ld_row + 32 * j;
+      r = r < N ? r : N - 1;
+      w_reg[j] = *reinterpret_cast<const bf16x8*>(W + (size_t)r * K + k0 + ld_c * 8);
+    }
+  };
+  auto store_tiles = [&](int buf) {
+    bf16_t* as = As + buf * BM * BK;
+    bf16_t* ws = Ws + buf * BN * BK;
+#pragma unroll
+    for (int j = 0; j < A_CHUNKS; ++j) {
+      const int r = ld_row + 32 * j;
+      *reinterpret_cast<bf16x8*>(as + r * BK + ((ld_c ^ ((r >> 1) & 7)) * 8)) = a_reg[j];
+    }
+#pragma unroll
+    for (int j = 0; j < W_CHUNKS; ++j) {
+      const int r = ld_row + 32 * j;
+      *reinterpret_cast<bf16x8*>(ws + r * BK + ((ld_c ^ ((r >> 1) & 7)) * 8)) = w_reg[j];
+    }
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int KT = K / BK;
+  load_tiles(0);
+  store_tiles(0);
+  __syncthreads();
+  const int fr = lane & 31, fk = lane >> 5;      // fragment row inside a 32-row tile, k half
+  for (int kt = 0; kt < KT; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < KT) load_tiles((kt + 1) * BK);
+    const bf16_t* as = As + buf * BM * BK + (wm * WM) * BK;
+    const bf16_t* ws = Ws + buf * BN * BK + (wn * WN) * BK;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      const int c = ks * 2 + fk;                  // logical 16-byte chunk of this lane
+      bf16x8 af[TM], wf[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int r = i * 32 + fr;
+        af[i] = *reinterpret_cast<const bf16x8*>(as + r * BK + ((c ^ ((r >> 1) & 7)) * 8));
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int r = j * 32 + fr;
+        wf[j] = *reinterpret_cast<const bf16x8*>(ws + r * BK + ((c ^ ((r >> 1) & 7)) * 8));
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < KT) store_tiles(buf ^ 1);
+    __syncthreads();
+  }
+
+  mfma_epilogue<EPI, TM, TN>(acc, bias, res, Y, M, N, m0 + wm * WM + fr, n0 + wn * WN + fk * 4);
+}
+
+template <int BM, int BN, int WGM, int WGN>
+static hipError_t linear_mfma_tile(const void* x, const void* w, const void* bias, const float* res, void* y,
+                                   int64_t M, int N, int K, int epi, hipStream_t s) {
+  const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
+  const size_t lds = (size_t)2 * (BM + BN) * 64 * sizeof(bf16_t);
+  dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
+#define OTAS_MFMA(E)                                                                                              \
+  do {                                                                                                            \
+    auto kern = gemm_mfma_kernel<E, BM, BN, WGM, WGN>;                                                            \
+    static bool attr = false;                                                                                     \
+    if (!attr) {                                                                                                  \
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+      if (e != hipSuccess) return e;                                                                              \
+      attr = true;                                                                                                \
+    }                                                                                                             \
+    kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
+                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_n);                       \
+  } while (0)
+  if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
+  else if (epi == EPI_GELU) OTAS_MFMA(EPI_GELU);
+  else OTAS_MFMA(EPI_RESIDUAL);
+#undef OTAS_MFMA
+  return hipGetLastError();
+}
+
+
+// Tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2, and inside
+// an XCD the ~32 resident workgroups are consecutive in that XCD's sequence.  Give XCD x the
+// sequence positions s = id / 8 of one contiguous band of tiles, and inside the band walk groups of
+// GM tile rows column by column, so that the tiles in flight on one XCD form a compact block that
+// shares activation and weight panels through that L2.
+__device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int& tile_m, int& tile_n) {
+  constexpr int GM = 8;
+  const int nblk = tiles_m * tiles_n;
+  const int per = nblk >> 3;
+  int t = bid;
+  if (bid < per * 8) t = (bid & 7) * per + (bid >> 3);   // full bands; the remainder keeps its id
+  const int group = GM * tiles_n;
+  const int g = t / group, idx = t - g * group;
+  const int rows = min(GM, tiles_m - g * GM);            // the last group may be shorter
+  tile_n = idx / rows;
+  tile_m = g * GM + (idx - tile_n * rows);
+}
+
+// ------------------------------------------------------------------------------ 256x256, LDS DMA
+// The large-shape kernel: block tile 256 x 256, 4 waves (one per SIMD), each wave a 128 x 128
+// sub-tile = 4 x 4 MFMA tiles = 256 accumulator registers.  A wave tile this large keeps the LDS
+// traffic per MFMA (512 B read + 256 B written) and the L2 traffic per MFMA low; measured on
+// MI355X, streaming the operand tiles of 256 x 256 blocks from L2 tops out near 13 TB/s, which
+// caps this tiling near 1.7 PFLOP/s whatever the MFMA schedule.
+// Operand tiles go from global memory straight into LDS (global_load_lds_dwordx4, 16 bytes per
+// lane, no staging registers and no ds_write), through a ring of NS = 4 stages of K step 32
+// (32 KB per stage).
+//   iteration t:  wait until this wave's loads of tile t+1 have landed, barrier  (so every wave's
+//                 have), then run the two k-steps of tile t; after each MFMA one piece of later
+//                 work is issued (a fragment read for the next k-step, or one load instruction of
+//                 tile t+3 into the stage tile t-1 used), so that this issue overlaps the MFMA's
+//                 cycles in the matrix pipe.  A load is in flight for two iterations before use.
+// Stage layout: 256 rows x 64 B; 16-byte chunk c of row r sits at chunk c ^ ((r >> 2) & 3).  The
+// DMA writes are linear (1 KB per wave instruction); a fragment read is served 16 lanes per clock
+// and its 16 consecutive rows of one chunk column fall on 16 different (row mod 4, chunk position)
+// pairs, i.e. on all 64 banks once.
+// lane i of a DMA instruction writes LDS row base + i/4, chunk position i%4, so it must fetch logical
+// chunk (i%4) ^ ((row >> 2) & 3) of that row.
+#define OTAS_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
+#define OTAS_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define OTAS_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+template <int EPI>
+__global__ __launch_bounds__(256, 1) void gemm_mfma256_dma_kernel(const bf16_t* __restrict__ A,
+                                                                  const bf16_t* __restrict__ W,
+                                                                  const bf16_t* __restrict__ bias,
+                                                                  const float* res,
+                                                                  typename OutType<bf16_t, EPI>::type* Y,
+                                                                  int64_t M, int N, int K, int tiles_m,
+                                                                  int tiles_n) {
+  constexpr int BM = 256, BN = 256, BK = 32, WM = 128, WN = 128, TM = 4, TN = 4, NS = 4;
+  constexpr int STAGE = BM * BK;   // elements per operand per stage
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [NS][256][32]
+  bf16_t* Ws = As + NS * STAGE;                   // [NS][256][32]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  const int64_t m0 = (int64_t)tile_m * BM;
+  const int n0 = tile_n * BN;
+
+  // DMA addressing: wave w owns rows w*64 .. w*64+63 of each operand tile, 16 rows per instruction.
+  const bf16_t* a_src[4];
+  const bf16_t* w_src[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int row = wave * 64 + j * 16 + (lane >> 2);
+    const int c = (lane & 3) ^ ((row >> 2) & 3);
+    int64_t ra = m0 + row;
+    ra = ra < M ? ra : M - 1;
+    int rw = n0 + row;
+    rw = rw < N ? rw : N - 1;
+    a_src[j] = A + (size_t)ra * K + c * 8;
+    w_src[j] = W + (size_t)rw * K + c * 8;
+  }
+  const int KT = K / BK;
+  // one DMA instruction (index d = 0..7: A rows j = d/2 for even d, W rows for odd d) of tile kt
+  auto dma_one = [&](int kt, int st, int d) {
+    const int k = (kt < KT ? kt : KT - 1) * BK;   // past the end: reload the last tile (never read)
+    const int j = d >> 1;
+    if ((d & 1) == 0)
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_src[j] + k), OTAS_LPTR(As + st * STAGE + (wave * 64 + j * 16) * BK),
+                                       16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_src[j] + k), OTAS_LPTR(Ws + st * STAGE + (wave * 64 + j * 16) * BK),
+                                       16, 0, 0);
+  };
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int fr = lane & 31, fk = lane >> 5;
+  const int frag_row = fr * BK, sw = (fr >> 2) & 3;
+  bf16x8 af[2][TM], wf[2][TN];
+  // fragment f = 0..3: A rows of MFMA tile f; f = 4..7: W rows of MFMA tile f - 4
+  auto read_frag = [&](int st, int ks, int slot, int f) {
+    const int c = (((ks << 1) + fk) ^ sw) * 8;
+    if (f < 4)
+      af[slot][f] = *reinterpret_cast<const bf16x8*>(As + st * STAGE + (wm * WM + f * 32) * BK + frag_row + c);
+    else
+      wf[slot][f - 4] = *reinterpret_cast<const bf16x8*>(Ws + st * STAGE + (wn * WN + (f - 4) * 32) * BK + frag_row + c);
+  };
+  auto mfma_one = [&](int slot, int t) {
+    const int i = t / TN, j = t % TN;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
+  };
+
+  // Prologue: tiles 0, 1, 2 into stages 0, 1, 2.  Loads complete in issue order, so "at most n
+  // still in flight" (vmcnt <= n) means everything but the n youngest has landed.
+#pragma unroll
+  for (int t = 0; t < 3; ++t)
+#pragma unroll
+    for (int d = 0; d < 8; ++d) dma_one(t, t, d);
+  OTAS_VMCNT(16);   // tile 0 landed (this wave's part)
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+#pragma unroll
+  for (int f = 0; f < 8; ++f) read_frag(0, 0, 0, f);
+
+  for (int kt = 0; kt < KT; ++kt) {
+    const int st = kt & (NS - 1), st1 = (kt + 1) & (NS - 1), st3 = (kt + 3) & (NS - 1);
+    OTAS_VMCNT(8);    // tile kt+1 landed; only tile kt+2 may still be in flight
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {   // k-step 0 of tile kt
+      mfma_one(0, t);
+      if (t < 8) read_frag(st, 1, 1, t);       // fragments of k-step 1
+      else dma_one(kt + 3, st3, t - 8);        // loads of tile kt+3
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {   // k-step 1
+      mfma_one(1, t);
+      if (t < 8) read_frag(st1, 0, 0, t);      // fragments of k-step 0 of tile kt+1
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  OTAS_VMCNT(0);      // nothing may still be writing LDS when the workgroup ends
+  mfma_epilogue<EPI, TM, TN>(acc, bias, res, Y, M, N, m0 + wm * WM + fr, n0 + wn * WN + fk * 4);
+}
+
+static hipError_t linear_mfma256_dma(const void* x, const void* w, const void* bias, const float* res, void* y,
+                                     int64_t M, int N, int K, int epi, hipStream_t s) {
+  const int tiles_m = (int)((M + 255) / 256), tiles_n = (N + 255) / 256;
+  const size_t lds = (size_t)4 * 2 * 256 * 32 * sizeof(bf16_t);
+  dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
+#define OTAS_MFMA(E)                                                                                              \
+  do {                                                                                                            \
+    auto kern = gemm_mfma256_dma_kernel<E>;                                                                       \
+    static bool attr = false;                                                                                     \
+    if (!attr) {                                                                                                  \
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+      if (e != hipSuccess) return e;                                                                              \
+      attr = true;                                                                                                \
+    }                                                                                                             \
+    kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
+                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_m, tiles_n);              \
+  } while (0)
+  if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
+  else if (epi == EPI_GELU) OTAS_MFMA(EPI_GELU);
+  else OTAS_MFMA(EPI_RESIDUAL);
+#undef OTAS_MFMA
+  return hipGetLastError();
+}
+
+int g_gemm_variant = 0;   // tile selection override for tuning runs (0 = automatic)
+
+static hipError_t linear_mfma(const void* x, const void* w, const void* bias, const float* res, void* y, int64_t M,
+                              int N, int K, int epi, hipStream_t s) {
+  // The 256 x 256 kernel wins once its tiles fill the 256 CUs at least twice over; below that the
+  // 128 x 128 kernel (two workgroups per CU, finer tail) is as fast or faster.
+  const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
+  const bool big = g_gemm_variant == 4 || (g_gemm_variant == 0 && tiles256 >= 384 && K % 32 == 0 && K >= 96);
+  if (big) return linear_mfma256_dma(x, w, bias, res, y, M, N, K, epi, s);
+  return linear_mfma_tile<128, 128, 2, 2>(x, w, bias, res, y, M, N, K, epi, s);
+}
+
+int g_gemm_force_valu = 0;   // tuning / test switch: route bf16 through the plain-FMA kernel
+
 hipError_t launch_linear(int dtype, const void* x, const void* w, const void* bias, const float* res, void* y,
                          int64_t M, int N, int K, int epi, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   if (dtype == 0) return linear_valu<float>(x, w, bias, res, y, M, N, K, epi, s);
+  if (K % 64 == 0 && N % 8 == 0 && !g_gemm_force_valu) return linear_mfma(x, w, bias, res, y, M, N, K, epi, s);
   return linear_valu<bf16_t>(x, w, bias, res, y, M, N, K, epi, s);
 }
 
