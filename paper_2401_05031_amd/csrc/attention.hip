@@ -62,6 +62,189 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const T* __restrict
   }
 }
 
+
+// ------------------------------------------------------------------------------ bf16 MFMA
+// grid (ceil(max_n / 128), H, B), 256 threads: each wave owns 32 query rows of one (query, head).
+// The keys and values of the head are staged in LDS in chunks of up to KC = 256 rows (rows padded
+// by 16 bytes so that the 16 lanes served per clock fall on distinct banks); every wave then walks
+// the chunk in blocks of 32 keys with an online softmax (running row maximum and sum, fp32).
+//
+// Both products are computed transposed, so that a lane always owns ONE query row:
+//   S^T[key, row] = K[key, :] . Q[row, :]     A operand = K rows (LDS), B operand = Q rows (registers)
+//   O^T[d, row]  += V^T[d, key] P^T[key, row] A operand = V^T (LDS, transposing read), B = P^T
+// With the 32x32 accumulator layout a lane (row = lane & 31, half = lane >> 5) holds, of a 32-key
+// block, the keys 8 (e / 4) + 4 half + (e & 3), e = 0..15: row maxima and sums are reductions over a
+// lane's own registers plus one exchange with lane ^ 32, and the probabilities feed the second MFMA
+// straight from registers: its k-slot i of half h is defined to be key 16 kk + 8 (i / 4) + 4 h +
+// (i & 3), which is exactly what accumulator registers 8 kk .. 8 kk + 7 hold.  V^T is read with the
+// same key order by ds_read_b64_tr_b16 (gfx950): in every group of 16 lanes, lane s supplies the
+// address of V[k0 + s / 4][d0 + 4 (s & 3) ..+3] and lane i receives V[k0 + 0..3][d0 + i].
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef short short8_t __attribute__((ext_vector_type(8)));
+
+template <int DH>
+__global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __restrict__ qkv,
+                                                             const int32_t* __restrict__ sizes,
+                                                             const int32_t* __restrict__ off, int D, float scale,
+                                                             bf16_t* __restrict__ o) {
+  constexpr int KC = 256;                 // keys per LDS chunk
+  constexpr int KS = DH / 16;             // k-steps of Q K^T
+  constexpr int DT = (DH + 31) / 32;      // 32-row tiles of O^T
+  constexpr int LD = DH + 8;              // LDS row stride in elements (16 bytes of padding)
+  constexpr int VROWS = KC + 4;           // V^T reads of the last d tile may run past DH: keep them in bounds
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem);           // [KC][LD]
+  bf16_t* Vs = Ks + KC * LD;                              // [VROWS][LD]
+  float* lnsz = reinterpret_cast<float*>(Vs + VROWS * LD);  // [KC] ln(size) of the chunk's keys
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int q = blockIdx.z, h = blockIdx.y;
+  const int base = off[q], n = off[q + 1] - base;
+  const int row0 = blockIdx.x * 128;
+  if (row0 >= n) return;
+  const size_t ld = (size_t)3 * D;
+  const int fr = lane & 31, fk = lane >> 5;
+  const int my_row = row0 + wave * 32 + fr;
+  const bool wave_active = row0 + wave * 32 < n;
+
+  // Q fragments (B operand): lane (row, half) holds Q[row][16 ks + 8 half .. +7]
+  bf16x8 qf[KS];
+  {
+    const bf16_t* qrow = qkv + (size_t)(base + (my_row < n ? my_row : n - 1)) * ld + h * DH + fk * 8;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qrow + ks * 16);
+  }
+
+  floatx16 oacc[DT];
+#pragma unroll
+  for (int t = 0; t < DT; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[t][e] = 0.f;
+  float m_run = -INFINITY, l_part = 0.f;
+
+  for (int c0 = 0; c0 < n; c0 += KC) {
+    const int nc = min(KC, n - c0);
+    const int nc_pad = (nc + 31) & ~31;
+    if (c0 > 0) __syncthreads();   // everyone is done with the previous chunk
+    // stage K and V rows c0 .. c0 + nc_pad - 1 (zero beyond n)
+    constexpr int CPR = DH / 8;    // 16-byte chunks per row
+    for (int t = tid; t < nc_pad * CPR; t += 256) {
+      const int r = t / CPR, c = (t - r * CPR) * 8;
+      bf16x8 kv = {0, 0, 0, 0, 0, 0, 0, 0}, vv = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (r < nc) {
+        const bf16_t* src = qkv + (size_t)(base + c0 + r) * ld + D + h * DH + c;
+        kv = *reinterpret_cast<const bf16x8*>(src);
+        vv = *reinterpret_cast<const bf16x8*>(src + D);
+      }
+      *reinterpret_cast<bf16x8*>(Ks + r * LD + c) = kv;
+      *reinterpret_cast<bf16x8*>(Vs + r * LD + c) = vv;
+    }
+    if (sizes) {
+      for (int t = tid; t < nc_pad; t += 256) lnsz[t] = t < nc ? logf((float)sizes[base + c0 + t]) : 0.f;
+    }
+    __syncthreads();
+    if (!wave_active) continue;
+
+    for (int kb = 0; kb < nc_pad; kb += 32) {
+      // S^T block
+      floatx16 sacc;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sacc[e] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + (kb + fr) * LD + ks * 16 + fk * 8);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
+      }
+      // logits, mask, running maximum
+      float mx = -INFINITY;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int key = kb + 8 * (e >> 2) + 4 * fk + (e & 3);
+        float v = sacc[e] * scale;
+        if (sizes) v += lnsz[key];
+        v = key < nc ? v : -INFINITY;
+        sacc[e] = v;
+        mx = fmaxf(mx, v);
+      }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __expf(m_run - m_new);    // 0 on the first block (m_run = -inf)
+      m_run = m_new;
+      float psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const float pv = __expf(sacc[e] - m_new);
+        sacc[e] = pv;
+        psum += pv;
+      }
+      l_part = l_part * alpha + psum;
+#pragma unroll
+      for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
+      // O^T += V^T P^T, two k-steps of 16 keys
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk) {
+        bf16x8 pf;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pf[i] = (bf16_t)sacc[8 * kk + i];
+        // transposing reads: lane s of each 16-lane group points at V[k0 + s/4][d0 + 4 (s & 3)]
+        const int s16 = lane & 15;
+        const int d0 = ((lane >> 4) & 1) * 16;
+        const int k0 = kb + 16 * kk + 4 * fk;
+#pragma unroll
+        for (int t = 0; t < DT; ++t) {
+          const bf16_t* vp = Vs + (k0 + (s16 >> 2)) * LD + t * 32 + d0 + 4 * (s16 & 3);
+          const short4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) short4_t*)(vp));
+          const short4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) short4_t*)(vp + 8 * LD));
+          const short8_t both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          bf16x8 vf;
+          __builtin_memcpy(&vf, &both, 16);
+          oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[t], 0, 0, 0);
+        }
+      }
+    }
+  }
+  if (!wave_active) return;
+  const float l_tot = l_part + __shfl_xor(l_part, 32, kWave);
+  if (my_row < n) {
+    const float inv = 1.0f / l_tot;
+    bf16_t* orow = o + (size_t)(base + my_row) * D + h * DH;
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int d = t * 32 + g * 8 + fk * 4;
+        if (d < DH) {
+          bf16x4 ov = {(bf16_t)(oacc[t][g * 4 + 0] * inv), (bf16_t)(oacc[t][g * 4 + 1] * inv),
+                       (bf16_t)(oacc[t][g * 4 + 2] * inv), (bf16_t)(oacc[t][g * 4 + 3] * inv)};
+          *reinterpret_cast<bf16x4*>(orow + d) = ov;
+        }
+      }
+  }
+}
+
+template <int DH>
+static hipError_t attention_mfma(const void* qkv, const int32_t* sz, const int32_t* d_off, int B, int max_n, int D,
+                                 int H, float scale, void* o, hipStream_t s) {
+  constexpr int LD = DH + 8;
+  const size_t lds = (size_t)(256 + 256 + 4) * LD * sizeof(bf16_t) + 256 * sizeof(float);
+  auto kern = attention_mfma_kernel<DH>;
+  static bool attr = false;
+  if (!attr) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr = true;
+  }
+  dim3 grid((max_n + 127) / 128, H, B), block(256);
+  kern<<<grid, block, lds, s>>>((const bf16_t*)qkv, sz, d_off, D, scale, (bf16_t*)o);
+  return hipGetLastError();
+}
+
+int g_attn_force_rows = 0;   // tuning / test switch: route bf16 through the row-wise kernel
+
 hipError_t launch_attention(int dtype, const void* qkv, const int32_t* sizes, const int32_t* d_off, int B,
                             int max_n, int D, int H, bool size_bias, void* o, hipStream_t s) {
   if (B <= 0 || max_n <= 0) return hipSuccess;
@@ -70,6 +253,12 @@ hipError_t launch_attention(int dtype, const void* qkv, const int32_t* sizes, co
   const int32_t* sz = size_bias ? sizes : nullptr;
   dim3 grid((max_n + 3) / 4, H, B), block(256);
   const size_t lds = (size_t)4 * (max_n + dh) * sizeof(float);
+  if (dtype != 0 && !g_attn_force_rows) {
+    if (dh == 64) return attention_mfma<64>(qkv, sz, d_off, B, max_n, D, H, scale, o, s);
+    if (dh == 80) return attention_mfma<80>(qkv, sz, d_off, B, max_n, D, H, scale, o, s);
+    if (dh == 96) return attention_mfma<96>(qkv, sz, d_off, B, max_n, D, H, scale, o, s);
+    if (dh == 128) return attention_mfma<128>(qkv, sz, d_off, B, max_n, D, H, scale, o, s);
+  }
   if (dtype == 0)
     attention_rows_kernel<float><<<grid, block, lds, s>>>((const float*)qkv, sz, d_off, D, H, max_n, scale, (float*)o);
   else

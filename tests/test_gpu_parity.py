@@ -211,6 +211,29 @@ def test_layer_norm_linear_attention_steps(torch_cuda, lib, dtype, tol):
     ctx.close()
 
 
+@pytest.mark.parametrize("D,H", [(128, 2), (160, 2), (192, 2), (256, 2), (768, 12)])
+def test_attention_bf16_head_widths_and_long_sequences(torch_cuda, lib, D, H):
+    """Head widths 64 / 80 / 96 / 128, sequences that span several 256-key chunks and ragged tails."""
+    torch = torch_cuda
+    cfg = synth.Config("attn", L=1, D=D, H=H, F=2 * D, dtype="bf16", B=1, n0=8, strategies=[(0, 0)], seed=11)
+    ctx, _ = hz.make_context(cfg)
+    rng = np.random.default_rng(D + H)
+    ns = [1, 33, 197, 256, 257, 300, 700, 129]
+    off = np.concatenate([[0], np.cumsum(ns)]).astype(np.int32)
+    qkv = synth.round_to_bf16(rng.standard_normal((int(off[-1]), 3 * D)).astype(np.float32))
+    sizes = rng.integers(1, 6, int(off[-1])).astype(np.int32)
+    for flags in (0, lib.OTAS_FLAG_SIZE_BIAS):
+        o = torch.full((int(off[-1]), D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        ctx.otas_attention(_t(torch, qkv, torch.bfloat16), torch.from_numpy(sizes).to("cuda"), off, flags, o)
+        got = o.to(torch.float32).cpu().numpy()
+        assert np.isfinite(got).all()
+        for q, n in enumerate(ns):
+            sl = slice(off[q], off[q + 1])
+            ref = orc.attention_heads(qkv[sl].astype(np.float64), H, sizes[sl], bool(flags))
+            assert hz.rel_err(got[sl], ref) <= 1e-2, (q, n, flags)
+    ctx.close()
+
+
 # ------------------------------------------------------------------ whole encoder, bf16 configs
 # Near-tie threshold for end-to-end runs: tests/test_bf16_noise_floor.py shows on the CPU that the
 # oracle disagrees with a copy of itself fed an input moved by ONE bf16 unit on ~0.5-1 % of the
