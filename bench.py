@@ -132,7 +132,7 @@ def rooflines(res):
         out["layer_norm"] = {"bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                              "frac": round(a / PEAK_HBM_GBS, 4),
                              "avg_launch_us": round(k["layer_norm"][0] * 1e3 / max(k["layer_norm"][1], 1), 2)}
-    for n in ("merge_plan", "merge_metric", "prompt_prepend"):
+    for n in ("merge_plan", "prompt_prepend"):
         if k[n][1] > 0:
             out[n] = {"avg_launch_us": round(k[n][0] * 1e3 / k[n][1], 2), "launches_per_step": k[n][1]}
     out["kernel_ms_per_step"] = {n: round(v[0], 4) for n, v in k.items()}

@@ -68,7 +68,7 @@ otas_status upload_plan(otas_ctx* c, const std::vector<int32_t>& host) {
 }
 
 struct WorkspaceLayout {
-  size_t xa, xb, h, qkv, hid, mhat, sizes_a, sizes_b, src_list, row_ptr, total;
+  size_t xa, xb, h, qkv, hid, sizes_a, sizes_b, src_list, row_ptr, total;
 };
 
 WorkspaceLayout forward_layout(const otas_model_desc& d, int64_t T0) {
@@ -82,7 +82,6 @@ WorkspaceLayout forward_layout(const otas_model_desc& d, int64_t T0) {
   w.h = take(rows * d.D * es);
   w.qkv = take(rows * 3 * d.D * es);
   w.hid = take(rows * d.F * es);
-  w.mhat = take(rows * (size_t)(d.D / d.H) * sizeof(float));
   w.sizes_a = take(rows * sizeof(int32_t));
   w.sizes_b = take(rows * sizeof(int32_t));
   w.src_list = take(rows * sizeof(int32_t));
@@ -96,9 +95,9 @@ WorkspaceLayout forward_layout(const otas_model_desc& d, int64_t T0) {
     if ((expr) != hipSuccess) return OTAS_EDEVICE; \
   } while (0)
 
-enum Kind { K_PREPEND = 0, K_LN, K_QKV, K_ATTN, K_PROJ, K_METRIC, K_PLAN, K_APPLY, K_FC1, K_FC2, K_MISC, K_COUNT };
+enum Kind { K_PREPEND = 0, K_LN, K_QKV, K_ATTN, K_PROJ, K_PLAN, K_APPLY, K_FC1, K_FC2, K_MISC, K_COUNT };
 const char* const kKindNames[K_COUNT] = {"prompt_prepend", "layer_norm", "gemm_qkv", "attention", "gemm_proj",
-                                         "merge_metric", "merge_plan", "merge_apply", "gemm_fc1", "gemm_fc2", "misc"};
+                                         "merge_plan", "merge_apply", "gemm_fc1", "gemm_fc2", "misc"};
 
 // Brackets one launch with an event pair when timing is on.
 struct LaunchTimer {
@@ -215,9 +214,8 @@ size_t otas_workspace_bytes(const otas_ctx* c, int32_t B, int64_t T0) {
 
 size_t otas_merge_workspace_bytes(int32_t B, int64_t T) {
   if (B <= 0 || T <= 0) return 0;
-  // mhat [T,128] float (worst case), src_list [T], row_ptr [T+1]
-  return align_up((size_t)T * 128 * sizeof(float), kAlign) + align_up((size_t)T * 4, kAlign) +
-         align_up((size_t)(T + 1) * 4, kAlign);
+  // src_list [T], row_ptr [T+1]
+  return align_up((size_t)T * 4, kAlign) + align_up((size_t)(T + 1) * 4, kAlign);
 }
 
 otas_status otas_prompt_prepend(otas_ctx* c, const void* tokens, const int32_t* tok_off, const void* prompts,
@@ -289,12 +287,10 @@ otas_status otas_token_merge(otas_ctx* c, const void* x, const void* metric, int
   otas_status st = upload_plan(c, plan);
   if (st != OTAS_OK) return st;
   char* ws = (char*)workspace;
-  float* mhat = (float*)ws;
-  int32_t* src_list = (int32_t*)(ws + align_up((size_t)T * 128 * sizeof(float), kAlign));
+  int32_t* src_list = (int32_t*)ws;
   int32_t* row_ptr = (int32_t*)((char*)src_list + align_up((size_t)T * 4, kAlign));
   const int32_t* dp = c->d_plan;
-  OTAS_LAUNCH(K_METRIC, launch_metric(c->desc.dtype, metric, dm, 0, 1, dm, T, mhat, c->stream));
-  OTAS_LAUNCH(K_PLAN, launch_merge_plan(mhat, dm, dp, dp + (B + 1), dp + 2 * (B + 1), dp + 2 * (B + 1) + B, B, max_n, n_lead,
+  OTAS_LAUNCH(K_PLAN, launch_merge_plan(c->desc.dtype, metric, dm, 0, 1, dm, dp, dp + (B + 1), dp + 2 * (B + 1), dp + 2 * (B + 1) + B, B, max_n, n_lead,
                              src_list, row_ptr, trace_src, trace_dst, c->stream));
   OTAS_LAUNCH(K_APPLY, launch_merge_apply(c->desc.dtype, x, sizes, src_list, row_ptr, T, T_out, c->desc.D, x_out, sizes_out,
                               c->stream));
@@ -395,7 +391,6 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
   void* hbuf = ws + w.h;
   void* qkv = ws + w.qkv;
   void* hid = ws + w.hid;
-  float* mhat = (float*)(ws + w.mhat);
   int32_t* sizes_cur = (int32_t*)(ws + w.sizes_a);
   int32_t* sizes_alt = (int32_t*)(ws + w.sizes_b);
   int32_t* src_list = (int32_t*)(ws + w.src_list);
@@ -434,8 +429,7 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
     // merging module
     if (any_merge[l]) {
       void* x_other = (x_attn == x_free[0]) ? x_free[1] : x_free[0];
-      OTAS_LAUNCH(K_METRIC, launch_metric(dt, qkv, 3 * (int64_t)D, D, H, dh, T, mhat, s));
-      OTAS_LAUNCH(K_PLAN, launch_merge_plan(mhat, dh, off_l, off_n, dp + o_reff + (size_t)l * B, dp + o_tr + (size_t)l * B, B,
+      OTAS_LAUNCH(K_PLAN, launch_merge_plan(dt, qkv, 3 * (int64_t)D, D, H, dh, off_l, off_n, dp + o_reff + (size_t)l * B, dp + o_tr + (size_t)l * B, B,
                                  max_n[l], n_lead, src_list, row_ptr, trace ? trace_src : nullptr,
                                  trace ? trace_dst : nullptr, s));
       OTAS_LAUNCH(K_APPLY, launch_merge_apply(OTAS_F32, x_attn, sizes_cur, src_list, row_ptr, T, Tn, D, x_other, sizes_alt, s));

@@ -1,6 +1,5 @@
 // HBM-bound row kernels: integer fill/copy, the prompting module's ragged concatenation
-// (Sec. II-B / III-B), LayerNorm (Sec. II-A "normalization"), and the merge metric
-// (head-averaged attention keys, Sec. III-B "similarity obtained from multi-head attention").
+// (Sec. II-B / III-B) and LayerNorm (Sec. II-A "normalization").
 #include "common.h"
 #include "kernels.h"
 
@@ -171,50 +170,6 @@ hipError_t launch_widen(const void* src_bf16, float* dst, int64_t n, hipStream_t
   if (n <= 0) return hipSuccess;
   const int64_t n8 = n / 8;
   widen_kernel<<<dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s>>>((const bf16_t*)src_bf16, dst, n8);
-  return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------------- merge metric
-// Half a wave (32 lanes) per token; lane c4 owns 4 consecutive columns of the metric vector.
-// m = (1/H) sum_h src[row, col_off + h*dm + c], summed over h in ascending order, then divided by
-// max(||m||, tiny).  The 32-lane butterfly makes the norm independent of the launch shape.
-template <typename T>
-__global__ __launch_bounds__(256) void metric_kernel(const T* __restrict__ src, int64_t row_stride, int col_off,
-                                                     int H, int dm, int64_t Trows, float* __restrict__ mhat) {
-  const int sub = threadIdx.x & 31;
-  const int64_t row = (int64_t)blockIdx.x * 8 + (threadIdx.x >> 5);
-  if (row >= Trows) return;
-  const int c = sub * 4;
-  float m[4] = {0.f, 0.f, 0.f, 0.f};
-  if (c < dm) {
-    const T* p = src + (size_t)row * row_stride + col_off + c;
-    for (int h = 0; h < H; ++h) {
-#pragma unroll
-      for (int k = 0; k < 4; ++k) m[k] += to_float(p[(size_t)h * dm + k]);
-    }
-    const float inv = 1.0f / (float)H;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) m[k] *= inv;
-  }
-  float ss = m[0] * m[0] + m[1] * m[1] + m[2] * m[2] + m[3] * m[3];
-#pragma unroll
-  for (int o = 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o, kWave);
-  const float rn = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
-  if (c < dm) {
-    floatx4 o = {m[0] * rn, m[1] * rn, m[2] * rn, m[3] * rn};
-    *reinterpret_cast<floatx4*>(mhat + (size_t)row * dm + c) = o;
-  }
-}
-
-hipError_t launch_metric(int dtype, const void* src, int64_t row_stride, int col_off, int H, int dm, int64_t T,
-                         float* mhat, hipStream_t s) {
-  if (T <= 0) return hipSuccess;
-  if (dm % 4 != 0 || dm > 128) return hipErrorInvalidValue;
-  dim3 grid((unsigned)((T + 7) / 8)), block(256);
-  if (dtype == 0)
-    metric_kernel<float><<<grid, block, 0, s>>>((const float*)src, row_stride, col_off, H, dm, T, mhat);
-  else
-    metric_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)src, row_stride, col_off, H, dm, T, mhat);
   return hipGetLastError();
 }
 

@@ -103,49 +103,65 @@ static hipError_t linear_valu(const void* x, const void* w, const void* bias, co
 
 
 
-// Epilogue shared by the MFMA kernels.  acc[i][j][e] of a lane belongs to output row
-// m = m_lane + 32 i and columns n = n_lane + 32 j + 8 (e / 4) + (e & 3), where m_lane already
-// includes the lane's row (lane & 31) and n_lane its 4-column half (4 (lane >> 5)).  Loads are
-// clamped to valid addresses and issued in batches ahead of the arithmetic; only stores are masked.
+// Epilogue shared by the MFMA kernels.  A lane's accumulators belong to ONE output row and to
+// scattered 4-column groups, so storing them directly would touch 32 rows with 16-byte pieces per
+// instruction.  Instead every wave transposes its tile through its own LDS region, 32 rows at a
+// time: it writes acc[i][j][e] (row = lane & 31, columns 32 j + 8 (e / 4) + 4 (lane >> 5) + (e & 3))
+// as floats into a [32][WN + 4] slab, reads the slab back row-major (16 bytes per lane, WN / 4
+// lanes per row) and applies bias / GELU / residual there, where the bias and residual loads and the
+// output stores are contiguous runs of a full row segment.  stage: this wave's region of
+// 32 * (32 TN + 4) floats, no longer used by anyone else (barrier before the call).
 template <int EPI, int TM, int TN>
-__device__ inline void mfma_epilogue(const floatx16 (&acc)[TM][TN], const bf16_t* __restrict__ bias,
+__device__ inline void mfma_epilogue(const floatx16 (&acc)[TM][TN], float* stage, const bf16_t* __restrict__ bias,
                                      const float* res, typename OutType<bf16_t, EPI>::type* Y, int64_t M, int N,
-                                     int64_t m_lane, int n_lane) {
+                                     int64_t m_wave, int n_wave, int lane) {
+  constexpr int WN = 32 * TN, LDR = WN + 4;
+  constexpr int LPR = WN / 4;      // lanes per row when reading back
+  constexpr int RPI = 64 / LPR;    // rows per read-back instruction
+  constexpr int NIT = 32 / RPI;
+  const int fr = lane & 31, fk = lane >> 5;
+  const int rrow = lane / LPR, rcol = (lane % LPR) * 4;
+  const int n = n_wave + rcol;
+  const bool n_ok = n < N;         // N % 8 == 0: a 4-column group is inside or outside as a whole
+  const bf16x4 bb = *reinterpret_cast<const bf16x4*>(bias + (n_ok ? n : 0));
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    int nn[4];
-    bf16x4 bb[4];
+  for (int i = 0; i < TM; ++i) {
+    const int64_t m_slab = m_wave + i * 32;
+    floatx4 rr[NIT];
+    if (EPI == EPI_RESIDUAL) {
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      nn[g] = n_lane + j * 32 + g * 8;
-      bb[g] = *reinterpret_cast<const bf16x4*>(bias + (nn[g] < N ? nn[g] : N - 4));
+      for (int it = 0; it < NIT; ++it) {
+        const int64_t m = m_slab + it * RPI + rrow;
+        rr[it] = *reinterpret_cast<const floatx4*>(res + (size_t)(m < M ? m : M - 1) * N + (n_ok ? n : 0));
+      }
     }
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-      const int64_t m = m_lane + i * 32;
-      const size_t row = (size_t)(m < M ? m : M - 1) * N;
-      floatx4 rr[4];
-      if (EPI == EPI_RESIDUAL) {
-#pragma unroll
-        for (int g = 0; g < 4; ++g) rr[g] = *reinterpret_cast<const floatx4*>(res + row + (nn[g] < N ? nn[g] : N - 4));
-      }
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        float v[4];
+        const floatx4 v = {acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
+        *reinterpret_cast<floatx4*>(stage + fr * LDR + j * 32 + g * 8 + fk * 4) = v;
+      }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][g * 4 + e] + (float)bb[g][e];
-        if (EPI == EPI_GELU) {
+    for (int it = 0; it < NIT; ++it) {
+      const int row = it * RPI + rrow;
+      const floatx4 a = *reinterpret_cast<const floatx4*>(stage + row * LDR + rcol);
+      float v[4];
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = gelu_bf16(v[e]);
-        }
-        if (m < M && nn[g] < N) {
-          if (EPI == EPI_RESIDUAL) {
-            floatx4 o = {v[0] + rr[g][0], v[1] + rr[g][1], v[2] + rr[g][2], v[3] + rr[g][3]};
-            *reinterpret_cast<floatx4*>(reinterpret_cast<float*>(Y) + row + nn[g]) = o;
-          } else {
-            bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
-            *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16_t*>(Y) + row + nn[g]) = o;
-          }
+      for (int e = 0; e < 4; ++e) v[e] = a[e] + (float)bb[e];
+      if (EPI == EPI_GELU) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = gelu_bf16(v[e]);
+      }
+      const int64_t m = m_slab + row;
+      if (m < M && n_ok) {
+        const size_t idx = (size_t)m * N + n;
+        if (EPI == EPI_RESIDUAL) {
+          floatx4 o = {v[0] + rr[it][0], v[1] + rr[it][1], v[2] + rr[it][2], v[3] + rr[it][3]};
+          *reinterpret_cast<floatx4*>(reinterpret_cast<float*>(Y) + idx) = o;
+        } else {
+          bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+          *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16_t*>(Y) + idx) = o;
         }
       }
     }
@@ -261,7 +277,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict
     __syncthreads();
   }
 
-  mfma_epilogue<EPI, TM, TN>(acc, bias, res, Y, M, N, m0 + wm * WM + fr, n0 + wn * WN + fk * 4);
+  __syncthreads();   // the operand buffers become the epilogue's staging area
+  mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
+                             m0 + wm * WM, n0 + wn * WN, lane);
 }
 
 template <int BM, int BN, int WGM, int WGN>
@@ -436,8 +454,12 @@ __global__ __launch_bounds__(256, 1) void gemm_mfma256_dma_kernel(const bf16_t* 
       __builtin_amdgcn_sched_barrier(0);
     }
   }
-  OTAS_VMCNT(0);      // nothing may still be writing LDS when the workgroup ends
-  mfma_epilogue<EPI, TM, TN>(acc, bias, res, Y, M, N, m0 + wm * WM + fr, n0 + wn * WN + fk * 4);
+  OTAS_VMCNT(0);      // every load of this wave has landed ...
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();   // ... and of every other wave: the stages become the epilogue's staging area
+  asm volatile("" ::: "memory");
+  mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
+                             m0 + wm * WM, n0 + wn * WN, lane);
 }
 
 static hipError_t linear_mfma256_dma(const void* x, const void* w, const void* bias, const float* res, void* y,
@@ -464,16 +486,169 @@ static hipError_t linear_mfma256_dma(const void* x, const void* w, const void* b
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------ 128x128, LDS DMA
+// The mid-size kernel: block tile 128 x 128, 4 waves of 64 x 64, K step 32, operand tiles loaded
+// straight into a ring of NS LDS stages (16 KB each) by global_load_lds_dwordx4.  With NS = 3 a
+// workgroup needs 48 KB of LDS and ~110 registers per lane, so three workgroups share a CU: while
+// one waits at its barrier or for its fragments, the others keep the matrix pipe busy, and one
+// workgroup's epilogue overlaps the others' main loops.
+//   iteration t: wait for this wave's loads of tile t, barrier, start the loads of tile t+NS-1 into
+//                the stage tile t-1 used, then the two k-steps of tile t (fragment reads of the
+//                second step are issued between the MFMAs of the first).
+// Stage layout as in the 256 x 256 kernel: rows of 64 B, chunk c of row r at c ^ ((r >> 2) & 3).
+template <int EPI, int NS>
+__global__ __launch_bounds__(256, 3) void gemm_mfma128_dma_kernel(const bf16_t* __restrict__ A,
+                                                                  const bf16_t* __restrict__ W,
+                                                                  const bf16_t* __restrict__ bias,
+                                                                  const float* res,
+                                                                  typename OutType<bf16_t, EPI>::type* Y,
+                                                                  int64_t M, int N, int K, int tiles_m,
+                                                                  int tiles_n) {
+  constexpr int BM = 128, BN = 128, BK = 32, WM = 64, WN = 64, TM = 2, TN = 2;
+  constexpr int STAGE = BM * BK;   // elements per operand per stage
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [NS][128][32]
+  bf16_t* Ws = As + NS * STAGE;                   // [NS][128][32]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  const int64_t m0 = (int64_t)tile_m * BM;
+  const int n0 = tile_n * BN;
+
+  // DMA addressing: wave w owns rows w*32 .. w*32+31 of each operand tile, 16 rows per instruction.
+  const bf16_t* a_src[2];
+  const bf16_t* w_src[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int row = wave * 32 + j * 16 + (lane >> 2);
+    const int c = (lane & 3) ^ ((row >> 2) & 3);
+    int64_t ra = m0 + row;
+    ra = ra < M ? ra : M - 1;
+    int rw = n0 + row;
+    rw = rw < N ? rw : N - 1;
+    a_src[j] = A + (size_t)ra * K + c * 8;
+    w_src[j] = W + (size_t)rw * K + c * 8;
+  }
+  const int KT = K / BK;
+  auto dma_one = [&](int kt, int st, int d) {   // d = 0..3: A rows j = d/2 (even d), W rows (odd d)
+    const int k = (kt < KT ? kt : KT - 1) * BK;
+    const int j = d >> 1;
+    if ((d & 1) == 0)
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_src[j] + k), OTAS_LPTR(As + st * STAGE + (wave * 32 + j * 16) * BK),
+                                       16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_src[j] + k), OTAS_LPTR(Ws + st * STAGE + (wave * 32 + j * 16) * BK),
+                                       16, 0, 0);
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int fr = lane & 31, fk = lane >> 5;
+  const int frag_row = fr * BK, sw = (fr >> 2) & 3;
+  bf16x8 af[2][TM], wf[2][TN];
+  auto read_frag = [&](int st, int ks, int slot, int f) {   // f = 0,1: A tiles; 2,3: W tiles
+    const int c = (((ks << 1) + fk) ^ sw) * 8;
+    if (f < 2)
+      af[slot][f] = *reinterpret_cast<const bf16x8*>(As + st * STAGE + (wm * WM + f * 32) * BK + frag_row + c);
+    else
+      wf[slot][f - 2] = *reinterpret_cast<const bf16x8*>(Ws + st * STAGE + (wn * WN + (f - 2) * 32) * BK + frag_row + c);
+  };
+  auto mfma_one = [&](int slot, int t) {
+    const int i = t / TN, j = t % TN;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
+  };
+
+  // Prologue: tiles 0 .. NS-2.  Loads complete in issue order: "at most n in flight" = all but the n
+  // youngest have landed.
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t)
+#pragma unroll
+    for (int d = 0; d < 4; ++d) dma_one(t, t, d);
+
+  int st = 0, st_new = NS - 1;
+  for (int kt = 0; kt < KT; ++kt) {
+    OTAS_VMCNT(4 * (NS - 2));   // tile kt landed; tiles kt+1 .. kt+NS-2 may still be in flight
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int f = 0; f < 4; ++f) read_frag(st, 0, 0, f);
+#pragma unroll
+    for (int d = 0; d < 4; ++d) dma_one(kt + NS - 1, st_new, d);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      mfma_one(0, t);
+      read_frag(st, 1, 1, t);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) mfma_one(1, t);
+    st = st + 1 == NS ? 0 : st + 1;
+    st_new = st_new + 1 == NS ? 0 : st_new + 1;
+  }
+  OTAS_VMCNT(0);      // every load of this wave has landed ...
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();   // ... and of every other wave: the stages become the epilogue's staging area
+  asm volatile("" ::: "memory");
+  mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
+                             m0 + wm * WM, n0 + wn * WN, lane);
+}
+
+template <int NS>
+static hipError_t linear_mfma128_dma(const void* x, const void* w, const void* bias, const float* res, void* y,
+                                     int64_t M, int N, int K, int epi, hipStream_t s) {
+  const int tiles_m = (int)((M + 127) / 128), tiles_n = (N + 127) / 128;
+  const size_t lds = (size_t)NS * 2 * 128 * 32 * sizeof(bf16_t);
+  dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
+#define OTAS_MFMA(E)                                                                                              \
+  do {                                                                                                            \
+    auto kern = gemm_mfma128_dma_kernel<E, NS>;                                                                   \
+    static bool attr = false;                                                                                     \
+    if (!attr) {                                                                                                  \
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+      if (e != hipSuccess) return e;                                                                              \
+      attr = true;                                                                                                \
+    }                                                                                                             \
+    kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
+                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_m, tiles_n);              \
+  } while (0)
+  if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
+  else if (epi == EPI_GELU) OTAS_MFMA(EPI_GELU);
+  else OTAS_MFMA(EPI_RESIDUAL);
+#undef OTAS_MFMA
+  return hipGetLastError();
+}
+
 int g_gemm_variant = 0;   // tile selection override for tuning runs (0 = automatic)
 
 static hipError_t linear_mfma(const void* x, const void* w, const void* bias, const float* res, void* y, int64_t M,
                               int N, int K, int epi, hipStream_t s) {
-  // The 256 x 256 kernel wins once its tiles fill the 256 CUs at least twice over; below that the
-  // 128 x 128 kernel (two workgroups per CU, finer tail) is as fast or faster.
+  // Measured on MI355X over the encoder's shapes: the 256 x 256 kernel wins once its tiles fill the
+  // 256 CUs about 1.5 times over (its one workgroup per CU cannot overlap the GELU epilogue with
+  // another workgroup's main loop, so GELU shapes switch later); below that the 128 x 128 kernel
+  // with three workgroups per CU is faster.  K % 32 != 0 falls back to the register-staged kernel.
   const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
-  const bool big = g_gemm_variant == 4 || (g_gemm_variant == 0 && tiles256 >= 384 && K % 32 == 0 && K >= 96);
-  if (big) return linear_mfma256_dma(x, w, bias, res, y, M, N, K, epi, s);
-  return linear_mfma_tile<128, 128, 2, 2>(x, w, bias, res, y, M, N, K, epi, s);
+  int variant = g_gemm_variant;
+  if (variant == 0) {
+    if (K % 32 != 0 || K < 64) variant = 1;
+    else if (tiles256 >= (epi == EPI_GELU ? 1024 : 400)) variant = 4;
+    else variant = 5;
+  }
+  switch (variant) {
+    case 4: return linear_mfma256_dma(x, w, bias, res, y, M, N, K, epi, s);
+    case 5: return linear_mfma128_dma<3>(x, w, bias, res, y, M, N, K, epi, s);
+    case 6: return linear_mfma128_dma<4>(x, w, bias, res, y, M, N, K, epi, s);
+    default: return linear_mfma_tile<128, 128, 2, 2>(x, w, bias, res, y, M, N, K, epi, s);
+  }
 }
 
 int g_gemm_force_valu = 0;   // tuning / test switch: route bf16 through the plain-FMA kernel

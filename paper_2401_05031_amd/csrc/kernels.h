@@ -31,15 +31,12 @@ hipError_t launch_attention(int dtype, const void* qkv, const int32_t* sizes,
                             const int32_t* d_off, int B, int max_n, int D, int H, bool size_bias,
                             void* o, hipStream_t s);
 
-// mhat[T, dm] (float) = row-normalised mean over H heads of src[row, col_off + h*dm + c].
-hipError_t launch_metric(int dtype, const void* src, int64_t row_stride, int col_off, int H,
-                         int dm, int64_t T, float* mhat, hipStream_t s);
-
-hipError_t launch_merge_plan(const float* mhat, int dm, const int32_t* d_in_off,
-                             const int32_t* d_out_off, const int32_t* d_reff,
-                             const int32_t* d_troff, int B, int max_n, int n_lead,
-                             int32_t* src_list, int32_t* row_ptr, int32_t* trace_src,
-                             int32_t* trace_dst, hipStream_t s);
+// The metric of token i is the mean over H heads of src[i * row_stride + col_off + h * dm + c]
+// (dtype = type of src), normalised to unit length inside the kernel.
+hipError_t launch_merge_plan(int dtype, const void* src, int64_t row_stride, int col_off, int H, int dm,
+                             const int32_t* d_in_off, const int32_t* d_out_off, const int32_t* d_reff,
+                             const int32_t* d_troff, int B, int max_n, int n_lead, int32_t* src_list,
+                             int32_t* row_ptr, int32_t* trace_src, int32_t* trace_dst, hipStream_t s);
 size_t merge_plan_lds_bytes(int max_n, int dm);
 
 // dtype: type of x and x_out (0 = float, 1 = bf16).
