@@ -4,9 +4,15 @@
 // Two kernels:
 //   * gemm_valu_kernel  -- plain fp32 FMA tiles; the true-fp32 path (f32 models) and the fallback
 //                          for shapes the MFMA kernel does not take.
-//   * gemm_mfma_kernel, gemm_mfma256_dma_kernel -- bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32
-//                          accumulate, LDS-staged tiles, fused bias / GELU / residual epilogue
-//                          (bf16 models): 128 x 128 tiles for small shapes, 256 x 256 for large.
+//   * gemm_mfma128_dma_kernel, gemm_mfma256w8_kernel, gemm_mfma_kernel -- bf16 MFMA
+//                          (v_mfma_f32_32x32x16_bf16), fp32 accumulate, LDS-staged tiles, fused
+//                          bias / GELU / residual epilogue (bf16 models): 128 x 128 tiles for small
+//                          and mid-size shapes, 256 x 256 for large, and a register-staged
+//                          128 x 128 fallback for K % 32 != 0.
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -326,165 +332,22 @@ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int& til
   tile_m = g * GM + (idx - tile_n * rows);
 }
 
-// ------------------------------------------------------------------------------ 256x256, LDS DMA
-// The large-shape kernel: block tile 256 x 256, 4 waves (one per SIMD), each wave a 128 x 128
-// sub-tile = 4 x 4 MFMA tiles = 256 accumulator registers.  A wave tile this large keeps the LDS
-// traffic per MFMA (512 B read + 256 B written) and the L2 traffic per MFMA low; measured on
-// MI355X, streaming the operand tiles of 256 x 256 blocks from L2 tops out near 13 TB/s, which
-// caps this tiling near 1.7 PFLOP/s whatever the MFMA schedule.
-// Operand tiles go from global memory straight into LDS (global_load_lds_dwordx4, 16 bytes per
-// lane, no staging registers and no ds_write), through a ring of NS = 4 stages of K step 32
-// (32 KB per stage).
-//   iteration t:  wait until this wave's loads of tile t+1 have landed, barrier  (so every wave's
-//                 have), then run the two k-steps of tile t; after each MFMA one piece of later
-//                 work is issued (a fragment read for the next k-step, or one load instruction of
-//                 tile t+3 into the stage tile t-1 used), so that this issue overlaps the MFMA's
-//                 cycles in the matrix pipe.  A load is in flight for two iterations before use.
-// Stage layout: 256 rows x 64 B; 16-byte chunk c of row r sits at chunk c ^ ((r >> 2) & 3).  The
-// DMA writes are linear (1 KB per wave instruction); a fragment read is served 16 lanes per clock
-// and its 16 consecutive rows of one chunk column fall on 16 different (row mod 4, chunk position)
-// pairs, i.e. on all 64 banks once.
-// lane i of a DMA instruction writes LDS row base + i/4, chunk position i%4, so it must fetch logical
-// chunk (i%4) ^ ((row >> 2) & 3) of that row.
+// ------------------------------------------------------------------------------ direct-to-LDS kernels
+// Operand tiles go from global memory straight into LDS (global_load_lds_dwordx4: 16 bytes per lane,
+// each wave instruction fills 1 KB of consecutive LDS; no staging registers, no ds_write) through a
+// ring of stages of K step 32.  Loads complete in issue order, so "at most n still in flight"
+// (s_waitcnt vmcnt(n)) means everything but the n youngest has landed; a wave waits for its own
+// loads, then a raw s_barrier makes every wave's loads visible.  The compiler is kept from moving
+// LDS accesses across these points by empty asm memory clobbers.
+// Stage layout: rows of 64 B (32 bf16); 16-byte chunk c of row r sits at chunk c ^ ((r >> 2) & 3).
+// The DMA writes are linear; a fragment read is served 16 lanes per clock and its 16 consecutive
+// rows of one chunk column fall on 16 different (row mod 4, chunk position) pairs, i.e. on all 64
+// banks once.  Lane i of a DMA instruction writes LDS row base + i/4, chunk position i%4, so it must
+// fetch logical chunk (i%4) ^ ((row >> 2) & 3) of that row.
 #define OTAS_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
 #define OTAS_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define OTAS_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
-template <int EPI>
-__global__ __launch_bounds__(256, 1) void gemm_mfma256_dma_kernel(const bf16_t* __restrict__ A,
-                                                                  const bf16_t* __restrict__ W,
-                                                                  const bf16_t* __restrict__ bias,
-                                                                  const float* res,
-                                                                  typename OutType<bf16_t, EPI>::type* Y,
-                                                                  int64_t M, int N, int K, int tiles_m,
-                                                                  int tiles_n) {
-  constexpr int BM = 256, BN = 256, BK = 32, WM = 128, WN = 128, TM = 4, TN = 4, NS = 4;
-  constexpr int STAGE = BM * BK;   // elements per operand per stage
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [NS][256][32]
-  bf16_t* Ws = As + NS * STAGE;                   // [NS][256][32]
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  int tile_m, tile_n;
-  tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
-  const int64_t m0 = (int64_t)tile_m * BM;
-  const int n0 = tile_n * BN;
-
-  // DMA addressing: wave w owns rows w*64 .. w*64+63 of each operand tile, 16 rows per instruction.
-  const bf16_t* a_src[4];
-  const bf16_t* w_src[4];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int row = wave * 64 + j * 16 + (lane >> 2);
-    const int c = (lane & 3) ^ ((row >> 2) & 3);
-    int64_t ra = m0 + row;
-    ra = ra < M ? ra : M - 1;
-    int rw = n0 + row;
-    rw = rw < N ? rw : N - 1;
-    a_src[j] = A + (size_t)ra * K + c * 8;
-    w_src[j] = W + (size_t)rw * K + c * 8;
-  }
-  const int KT = K / BK;
-  // one DMA instruction (index d = 0..7: A rows j = d/2 for even d, W rows for odd d) of tile kt
-  auto dma_one = [&](int kt, int st, int d) {
-    const int k = (kt < KT ? kt : KT - 1) * BK;   // past the end: reload the last tile (never read)
-    const int j = d >> 1;
-    if ((d & 1) == 0)
-      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_src[j] + k), OTAS_LPTR(As + st * STAGE + (wave * 64 + j * 16) * BK),
-                                       16, 0, 0);
-    else
-      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_src[j] + k), OTAS_LPTR(Ws + st * STAGE + (wave * 64 + j * 16) * BK),
-                                       16, 0, 0);
-  };
-  floatx16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-  const int fr = lane & 31, fk = lane >> 5;
-  const int frag_row = fr * BK, sw = (fr >> 2) & 3;
-  bf16x8 af[2][TM], wf[2][TN];
-  // fragment f = 0..3: A rows of MFMA tile f; f = 4..7: W rows of MFMA tile f - 4
-  auto read_frag = [&](int st, int ks, int slot, int f) {
-    const int c = (((ks << 1) + fk) ^ sw) * 8;
-    if (f < 4)
-      af[slot][f] = *reinterpret_cast<const bf16x8*>(As + st * STAGE + (wm * WM + f * 32) * BK + frag_row + c);
-    else
-      wf[slot][f - 4] = *reinterpret_cast<const bf16x8*>(Ws + st * STAGE + (wn * WN + (f - 4) * 32) * BK + frag_row + c);
-  };
-  auto mfma_one = [&](int slot, int t) {
-    const int i = t / TN, j = t % TN;
-    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
-  };
-
-  // Prologue: tiles 0, 1, 2 into stages 0, 1, 2.  Loads complete in issue order, so "at most n
-  // still in flight" (vmcnt <= n) means everything but the n youngest has landed.
-#pragma unroll
-  for (int t = 0; t < 3; ++t)
-#pragma unroll
-    for (int d = 0; d < 8; ++d) dma_one(t, t, d);
-  OTAS_VMCNT(16);   // tile 0 landed (this wave's part)
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_barrier();
-  asm volatile("" ::: "memory");
-#pragma unroll
-  for (int f = 0; f < 8; ++f) read_frag(0, 0, 0, f);
-
-  for (int kt = 0; kt < KT; ++kt) {
-    const int st = kt & (NS - 1), st1 = (kt + 1) & (NS - 1), st3 = (kt + 3) & (NS - 1);
-    OTAS_VMCNT(8);    // tile kt+1 landed; only tile kt+2 may still be in flight
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-#pragma unroll
-    for (int t = 0; t < 16; ++t) {   // k-step 0 of tile kt
-      mfma_one(0, t);
-      if (t < 8) read_frag(st, 1, 1, t);       // fragments of k-step 1
-      else dma_one(kt + 3, st3, t - 8);        // loads of tile kt+3
-      __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int t = 0; t < 16; ++t) {   // k-step 1
-      mfma_one(1, t);
-      if (t < 8) read_frag(st1, 0, 0, t);      // fragments of k-step 0 of tile kt+1
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  }
-  OTAS_VMCNT(0);      // every load of this wave has landed ...
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_barrier();   // ... and of every other wave: the stages become the epilogue's staging area
-  asm volatile("" ::: "memory");
-  mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
-                             m0 + wm * WM, n0 + wn * WN, lane);
-}
-
-static hipError_t linear_mfma256_dma(const void* x, const void* w, const void* bias, const float* res, void* y,
-                                     int64_t M, int N, int K, int epi, hipStream_t s) {
-  const int tiles_m = (int)((M + 255) / 256), tiles_n = (N + 255) / 256;
-  const size_t lds = (size_t)4 * 2 * 256 * 32 * sizeof(bf16_t);
-  dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
-#define OTAS_MFMA(E)                                                                                              \
-  do {                                                                                                            \
-    auto kern = gemm_mfma256_dma_kernel<E>;                                                                       \
-    static bool attr = false;                                                                                     \
-    if (!attr) {                                                                                                  \
-      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-      if (e != hipSuccess) return e;                                                                              \
-      attr = true;                                                                                                \
-    }                                                                                                             \
-    kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
-                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_m, tiles_n);              \
-  } while (0)
-  if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
-  else if (epi == EPI_GELU) OTAS_MFMA(EPI_GELU);
-  else OTAS_MFMA(EPI_RESIDUAL);
-#undef OTAS_MFMA
-  return hipGetLastError();
-}
 
 // ------------------------------------------------------------------------------ 128x128, LDS DMA
 // The mid-size kernel: block tile 128 x 128, 4 waves of 64 x 64, K step 32, operand tiles loaded
@@ -495,7 +358,6 @@ static hipError_t linear_mfma256_dma(const void* x, const void* w, const void* b
 //   iteration t: wait for this wave's loads of tile t, barrier, start the loads of tile t+NS-1 into
 //                the stage tile t-1 used, then the two k-steps of tile t (fragment reads of the
 //                second step are issued between the MFMAs of the first).
-// Stage layout as in the 256 x 256 kernel: rows of 64 B, chunk c of row r at c ^ ((r >> 2) & 3).
 template <int EPI, int NS>
 __global__ __launch_bounds__(256, 3) void gemm_mfma128_dma_kernel(const bf16_t* __restrict__ A,
                                                                   const bf16_t* __restrict__ W,
@@ -628,25 +490,179 @@ static hipError_t linear_mfma128_dma(const void* x, const void* w, const void* b
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------ 256x256, 8 waves
+// The large-shape kernel: block tile 256 x 256, 8 waves of 128 x 64 (2 x 4 arrangement), a ring of
+// 4 stages (128 KB).  128 accumulator registers per lane let two waves share each SIMD, so one
+// wave's barrier / LDS waits are covered by the other's MFMAs, while the L2 traffic per MFMA is half
+// that of the 128 x 128 tiling (which is bound by L2 -> LDS bandwidth: streaming operand tiles into
+// LDS tops out near 13 TB/s chip-wide on MI355X).
+//   iteration t:  wait until this wave's loads of tile t+1 have landed, barrier, then the two
+//                 k-steps of tile t; after each MFMA one piece of later work is issued (a fragment
+//                 read for the next k-step / next tile, or load instructions of tile t+3 into the
+//                 stage tile t-1 used), so that this issue overlaps the MFMA's cycles in the matrix
+//                 pipe.  A load is in flight for two iterations before it is needed.
+template <int EPI>
+__global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __restrict__ A,
+                                                                const bf16_t* __restrict__ W,
+                                                                const bf16_t* __restrict__ bias, const float* res,
+                                                                typename OutType<bf16_t, EPI>::type* Y, int64_t M,
+                                                                int N, int K, int tiles_m, int tiles_n) {
+  constexpr int BM = 256, BN = 256, BK = 32, WM = 128, WN = 64, TM = 4, TN = 2, NS = 4;
+  constexpr int STAGE = BM * BK;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [NS][256][32]
+  bf16_t* Ws = As + NS * STAGE;                   // [NS][256][32]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 2, wn = wave & 3;
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  const int64_t m0 = (int64_t)tile_m * BM;
+  const int n0 = tile_n * BN;
+
+  // DMA addressing: wave w owns rows w*32 .. w*32+31 of each operand tile, 16 rows per instruction.
+  const bf16_t* a_src[2];
+  const bf16_t* w_src[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int row = wave * 32 + j * 16 + (lane >> 2);
+    const int c = (lane & 3) ^ ((row >> 2) & 3);
+    int64_t ra = m0 + row;
+    ra = ra < M ? ra : M - 1;
+    int rw = n0 + row;
+    rw = rw < N ? rw : N - 1;
+    a_src[j] = A + (size_t)ra * K + c * 8;
+    w_src[j] = W + (size_t)rw * K + c * 8;
+  }
+  const int KT = K / BK;
+  auto dma_one = [&](int kt, int st, int d) {   // d = 0..3
+    const int k = (kt < KT ? kt : KT - 1) * BK;
+    const int j = d >> 1;
+    if ((d & 1) == 0)
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_src[j] + k), OTAS_LPTR(As + st * STAGE + (wave * 32 + j * 16) * BK),
+                                       16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_src[j] + k), OTAS_LPTR(Ws + st * STAGE + (wave * 32 + j * 16) * BK),
+                                       16, 0, 0);
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int fr = lane & 31, fk = lane >> 5;
+  const int frag_row = fr * BK, sw = (fr >> 2) & 3;
+  bf16x8 af[2][TM], wf[2][TN];
+  auto read_frag = [&](int st, int ks, int slot, int f) {   // f = 0..3: A tiles; 4,5: W tiles
+    const int c = (((ks << 1) + fk) ^ sw) * 8;
+    if (f < TM)
+      af[slot][f] = *reinterpret_cast<const bf16x8*>(As + st * STAGE + (wm * WM + f * 32) * BK + frag_row + c);
+    else
+      wf[slot][f - TM] =
+          *reinterpret_cast<const bf16x8*>(Ws + st * STAGE + (wn * WN + (f - TM) * 32) * BK + frag_row + c);
+  };
+  auto mfma_one = [&](int slot, int t) {
+    const int i = t / TN, j = t % TN;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
+  };
+
+#pragma unroll
+  for (int t = 0; t < 3; ++t)
+#pragma unroll
+    for (int d = 0; d < 4; ++d) dma_one(t, t, d);
+  OTAS_VMCNT(8);    // tile 0 landed (this wave's part)
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+#pragma unroll
+  for (int f = 0; f < TM + TN; ++f) read_frag(0, 0, 0, f);
+
+  for (int kt = 0; kt < KT; ++kt) {
+    const int st = kt & (NS - 1), st1 = (kt + 1) & (NS - 1), st3 = (kt + 3) & (NS - 1);
+    OTAS_VMCNT(4);    // tile kt+1 landed; only tile kt+2 may still be in flight
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {    // k-step 0 of tile kt
+      mfma_one(0, t);
+      if (t < 6) read_frag(st, 1, 1, t);
+      else { dma_one(kt + 3, st3, 2 * (t - 6)); dma_one(kt + 3, st3, 2 * (t - 6) + 1); }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {    // k-step 1
+      mfma_one(1, t);
+      if (t < 6) read_frag(st1, 0, 0, t);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  OTAS_VMCNT(0);
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
+                             m0 + wm * WM, n0 + wn * WN, lane);
+}
+
+static hipError_t linear_mfma256w8(const void* x, const void* w, const void* bias, const float* res, void* y,
+                                   int64_t M, int N, int K, int epi, hipStream_t s) {
+  const int tiles_m = (int)((M + 255) / 256), tiles_n = (N + 255) / 256;
+  const size_t lds = (size_t)4 * 2 * 256 * 32 * sizeof(bf16_t);
+  dim3 grid((unsigned)(tiles_m * tiles_n)), block(512);
+#define OTAS_MFMA(E)                                                                                              \
+  do {                                                                                                            \
+    auto kern = gemm_mfma256w8_kernel<E>;                                                                         \
+    static bool attr = false;                                                                                     \
+    if (!attr) {                                                                                                  \
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+      if (e != hipSuccess) return e;                                                                              \
+      attr = true;                                                                                                \
+    }                                                                                                             \
+    kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
+                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_m, tiles_n);              \
+  } while (0)
+  if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
+  else if (epi == EPI_GELU) OTAS_MFMA(EPI_GELU);
+  else OTAS_MFMA(EPI_RESIDUAL);
+#undef OTAS_MFMA
+  return hipGetLastError();
+}
+
 int g_gemm_variant = 0;   // tile selection override for tuning runs (0 = automatic)
 
 static hipError_t linear_mfma(const void* x, const void* w, const void* bias, const float* res, void* y, int64_t M,
                               int N, int K, int epi, hipStream_t s) {
-  // Measured on MI355X over the encoder's shapes: the 256 x 256 kernel wins once its tiles fill the
-  // 256 CUs about 1.5 times over (its one workgroup per CU cannot overlap the GELU epilogue with
-  // another workgroup's main loop, so GELU shapes switch later); below that the 128 x 128 kernel
-  // with three workgroups per CU is faster.  K % 32 != 0 falls back to the register-staged kernel.
-  const int64_t tiles256 = ((M + 255) / 256) * ((N + 255) / 256);
-  int variant = g_gemm_variant;
+  // Kernel choice, from measurements on MI355X inside the encoder (us per launch):
+  //   128 x 128, three workgroups per CU:  ~max(3 + 0.0095 K, 6e-5 K tiles128); bound by L2 -> LDS
+  //       bandwidth (64 FLOP per byte loaded) but free of tile-count quantisation, and its epilogue
+  //       overlaps other workgroups' main loops;
+  //   256 x 256, 8 waves, one workgroup per CU:  ~(11 + 0.018 K) per round of 256 tiles: twice the
+  //       FLOP per byte, whole rounds only.
+  // The large kernel is taken when it runs many rounds (>= 1024 tiles), and for plain-epilogue
+  // shapes (the QKV projection) whenever the model above favours it; the residual / GELU shapes of
+  // mid-size batches stay on the 128 x 128 kernel, which measured faster there in place.
+  // K % 32 != 0 or tiny K falls back to the register-staged kernel.
+  static const int env_variant = [] {
+    const char* e = std::getenv("OTAS_GEMM_VARIANT");   // tuning override, 0 / unset = automatic
+    return e ? std::atoi(e) : 0;
+  }();
+  int variant = g_gemm_variant ? g_gemm_variant : env_variant;
+  if (K % 32 != 0 || K < 64) variant = 1;
   if (variant == 0) {
-    if (K % 32 != 0 || K < 64) variant = 1;
-    else if (tiles256 >= (epi == EPI_GELU ? 1024 : 400)) variant = 4;
-    else variant = 5;
+    const double t128 = (double)((M + 127) / 128) * ((N + 127) / 128);
+    const double t256 = (double)((M + 255) / 256) * ((N + 255) / 256);
+    const double c128 = std::max(3.0 + 0.0095 * K, 6e-5 * K * t128);
+    const double c256 = (11.0 + 0.018 * K) * std::ceil(t256 / 256.0);
+    variant = (t256 >= 1024 || (epi == EPI_NONE && c256 < c128)) ? 7 : 5;
   }
   switch (variant) {
-    case 4: return linear_mfma256_dma(x, w, bias, res, y, M, N, K, epi, s);
     case 5: return linear_mfma128_dma<3>(x, w, bias, res, y, M, N, K, epi, s);
-    case 6: return linear_mfma128_dma<4>(x, w, bias, res, y, M, N, K, epi, s);
+    case 7: return linear_mfma256w8(x, w, bias, res, y, M, N, K, epi, s);
     default: return linear_mfma_tile<128, 128, 2, 2>(x, w, bias, res, y, M, N, K, epi, s);
   }
 }
