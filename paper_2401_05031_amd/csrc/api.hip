@@ -35,6 +35,11 @@ struct otas_ctx {
   hipEvent_t h_done[2];   // staging buffer i may be overwritten once h_done[i] has completed
   bool h_used[2];
   int h_next;
+  // The merge plan of a layer needs only that layer's keys (the QKV projection), so it runs on a
+  // second stream next to attention and the output projection: forked after the QKV GEMM, joined
+  // before merge-apply.
+  hipStream_t side;
+  hipEvent_t ev_fork, ev_join;
   // optional per-launch timing (otas_timing_enable): one event pair per launch, summed per kind
   bool timing;
   std::vector<hipEvent_t> ev_pool;
@@ -103,7 +108,8 @@ const char* const kKindNames[K_COUNT] = {"prompt_prepend", "layer_norm", "gemm_q
 struct LaunchTimer {
   otas_ctx* c;
   bool on;
-  LaunchTimer(otas_ctx* ctx, int kind) : c(ctx), on(ctx->timing) {
+  hipStream_t st;
+  LaunchTimer(otas_ctx* ctx, int kind, hipStream_t stream) : c(ctx), on(ctx->timing), st(stream) {
     if (!on) return;
     const size_t i = c->ev_kind.size();
     while (c->ev_pool.size() < 2 * (i + 1)) {
@@ -112,17 +118,20 @@ struct LaunchTimer {
       c->ev_pool.push_back(e);
     }
     c->ev_kind.push_back(kind);
-    (void)hipEventRecord(c->ev_pool[2 * i], c->stream);
+    idx = i;
+    (void)hipEventRecord(c->ev_pool[2 * i], st);
   }
   ~LaunchTimer() {
-    if (on) (void)hipEventRecord(c->ev_pool[2 * (c->ev_kind.size() - 1) + 1], c->stream);
+    if (on) (void)hipEventRecord(c->ev_pool[2 * idx + 1], st);
   }
+  size_t idx = 0;
 };
-#define OTAS_LAUNCH(kind, expr)   \
-  do {                            \
-    LaunchTimer _t(c, kind);      \
-    OTAS_HIP(expr);               \
+#define OTAS_LAUNCH_ON(kind, stream, expr) \
+  do {                                     \
+    LaunchTimer _t(c, kind, stream);       \
+    OTAS_HIP(expr);                        \
   } while (0)
+#define OTAS_LAUNCH(kind, expr) OTAS_LAUNCH_ON(kind, c->stream, expr)
 
 }  // namespace
 
@@ -180,12 +189,17 @@ otas_status otas_create(otas_ctx** out, const otas_model_desc* desc, const otas_
   c->h_used[0] = c->h_used[1] = false;
   c->h_next = 0;
   c->timing = false;
+  c->side = nullptr;
+  c->ev_fork = c->ev_join = nullptr;
   bool ok = hipGetDevice(&c->device) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->d_plan, kPlanInts * sizeof(int32_t)) == hipSuccess;
   for (int i = 0; i < 2 && ok; ++i) {
     ok = hipHostMalloc((void**)&c->h_plan[i], kPlanInts * sizeof(int32_t), hipHostMallocDefault) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&c->h_done[i], hipEventDisableTiming) == hipSuccess;
   }
+  ok = ok && hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess;   // default priority
+  ok = ok && hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) == hipSuccess;
   if (!ok) {
     otas_destroy(c);
     return OTAS_EDEVICE;
@@ -197,6 +211,12 @@ otas_status otas_create(otas_ctx** out, const otas_model_desc* desc, const otas_
 otas_status otas_destroy(otas_ctx* c) {
   if (!c) return OTAS_OK;
   if (c->stream || c->d_plan) (void)hipStreamSynchronize(c->stream);
+  if (c->side) {
+    (void)hipStreamSynchronize(c->side);
+    (void)hipStreamDestroy(c->side);
+  }
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
   for (int i = 0; i < 2; ++i) {
     if (c->h_done[i]) (void)hipEventDestroy(c->h_done[i]);
     if (c->h_plan[i]) (void)hipHostFree(c->h_plan[i]);
@@ -419,6 +439,17 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
     // normalisation -> QKV -> attention -> projection + residual
     OTAS_LAUNCH(K_LN, launch_layer_norm(dt, true, x_cur, wl.ln1_g, wl.ln1_b, hbuf, T, D, d.ln_eps, s));
     OTAS_LAUNCH(K_QKV, launch_linear(dt, hbuf, wl.w_qkv, wl.b_qkv, nullptr, qkv, T, 3 * D, D, EPI_NONE, s));
+    if (any_merge[l]) {
+      // fork: the merge plan reads only the keys just written; the lists it writes were last read by
+      // the previous layer's merge-apply, which precedes this point on the main stream
+      OTAS_HIP(hipEventRecord(c->ev_fork, s));
+      OTAS_HIP(hipStreamWaitEvent(c->side, c->ev_fork, 0));
+      OTAS_LAUNCH_ON(K_PLAN, c->side,
+                     launch_merge_plan(dt, qkv, 3 * (int64_t)D, D, H, dh, off_l, off_n, dp + o_reff + (size_t)l * B,
+                                       dp + o_tr + (size_t)l * B, B, max_n[l], n_lead, src_list, row_ptr,
+                                       trace ? trace_src : nullptr, trace ? trace_dst : nullptr, c->side));
+      OTAS_HIP(hipEventRecord(c->ev_join, c->side));
+    }
     OTAS_LAUNCH(K_ATTN, launch_attention(dt, qkv, sizes_cur, off_l, B, max_n[l], D, H, size_bias, hbuf, s));
     // in-place residual is safe (each element is read then written by the same thread); the
     // caller's x0 is never written, so layer 0 writes into the workspace.
@@ -429,9 +460,7 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
     // merging module
     if (any_merge[l]) {
       void* x_other = (x_attn == x_free[0]) ? x_free[1] : x_free[0];
-      OTAS_LAUNCH(K_PLAN, launch_merge_plan(dt, qkv, 3 * (int64_t)D, D, H, dh, off_l, off_n, dp + o_reff + (size_t)l * B, dp + o_tr + (size_t)l * B, B,
-                                 max_n[l], n_lead, src_list, row_ptr, trace ? trace_src : nullptr,
-                                 trace ? trace_dst : nullptr, s));
+      OTAS_HIP(hipStreamWaitEvent(s, c->ev_join, 0));   // join
       OTAS_LAUNCH(K_APPLY, launch_merge_apply(OTAS_F32, x_attn, sizes_cur, src_list, row_ptr, T, Tn, D, x_other, sizes_alt, s));
       std::swap(sizes_cur, sizes_alt);
       x_mlp = x_other;
@@ -489,7 +518,7 @@ otas_status otas_attention(otas_ctx* c, const void* qkv, const int32_t* sizes, c
 
 otas_status otas_timing_enable(otas_ctx* c, int32_t on) {
   if (!c) return OTAS_EINVAL;
-  if (hipStreamSynchronize(c->stream) != hipSuccess) return OTAS_EDEVICE;
+  if (hipStreamSynchronize(c->stream) != hipSuccess || hipStreamSynchronize(c->side) != hipSuccess) return OTAS_EDEVICE;
   c->timing = on != 0;
   c->ev_kind.clear();
   return OTAS_OK;
@@ -501,7 +530,7 @@ const char* otas_timing_kind_name(int32_t kind) { return (kind >= 0 && kind < K_
 
 otas_status otas_timing_read(otas_ctx* c, double* total_ms, int64_t* launches) {
   if (!c || !total_ms || !launches) return OTAS_EINVAL;
-  if (hipStreamSynchronize(c->stream) != hipSuccess) return OTAS_EDEVICE;
+  if (hipStreamSynchronize(c->stream) != hipSuccess || hipStreamSynchronize(c->side) != hipSuccess) return OTAS_EDEVICE;
   for (int k = 0; k < K_COUNT; ++k) { total_ms[k] = 0.0; launches[k] = 0; }
   for (size_t i = 0; i < c->ev_kind.size(); ++i) {
     float ms = 0.f;

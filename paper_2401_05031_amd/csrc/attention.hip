@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const T* __restrict
 
 // ------------------------------------------------------------------------------ bf16 MFMA
 // grid (ceil(max_n / 128), H, B), 256 threads: each wave owns 32 query rows of one (query, head).
-// The keys and values of the head are staged in LDS in chunks of up to KC = 256 rows (rows padded
+// The keys and values of the head are staged in LDS in chunks of up to KC rows (rows padded
 // by 16 bytes so that the 16 lanes served per clock fall on distinct banks); every wave then walks
 // the chunk in blocks of 32 keys with an online softmax (running row maximum and sum, fp32).
 //
@@ -82,12 +82,11 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const T* __restrict
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef short short8_t __attribute__((ext_vector_type(8)));
 
-template <int DH>
-__global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __restrict__ qkv,
+template <int DH, bool BIAS, int KC>
+__global__ __launch_bounds__(256, DH <= 64 ? 4 : 2) void attention_mfma_kernel(const bf16_t* __restrict__ qkv,
                                                              const int32_t* __restrict__ sizes,
                                                              const int32_t* __restrict__ off, int D, float scale,
                                                              bf16_t* __restrict__ o) {
-  constexpr int KC = 256;                 // keys per LDS chunk
   constexpr int KS = DH / 16;             // k-steps of Q K^T
   constexpr int DT = (DH + 31) / 32;      // 32-row tiles of O^T
   constexpr int LD = DH + 8;              // LDS row stride in elements (16 bytes of padding)
@@ -95,7 +94,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem);           // [KC][LD]
   bf16_t* Vs = Ks + KC * LD;                              // [VROWS][LD]
-  float* lnsz = reinterpret_cast<float*>(Vs + VROWS * LD);  // [KC] ln(size) of the chunk's keys
+  float* lnsz = reinterpret_cast<float*>(Vs + VROWS * LD);  // [KC] log2(size) of the chunk's keys
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int q = blockIdx.z, h = blockIdx.y;
@@ -121,6 +120,7 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
 #pragma unroll
     for (int e = 0; e < 16; ++e) oacc[t][e] = 0.f;
   float m_run = -INFINITY, l_part = 0.f;
+  const float scale2 = scale * 1.44269504088896340736f;   // logits are kept in units of ln 2
 
   for (int c0 = 0; c0 < n; c0 += KC) {
     const int nc = min(KC, n - c0);
@@ -128,19 +128,36 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
     if (c0 > 0) __syncthreads();   // everyone is done with the previous chunk
     // stage K and V rows c0 .. c0 + nc_pad - 1 (zero beyond n)
     constexpr int CPR = DH / 8;    // 16-byte chunks per row
-    for (int t = tid; t < nc_pad * CPR; t += 256) {
-      const int r = t / CPR, c = (t - r * CPR) * 8;
-      bf16x8 kv = {0, 0, 0, 0, 0, 0, 0, 0}, vv = {0, 0, 0, 0, 0, 0, 0, 0};
-      if (r < nc) {
-        const bf16_t* src = qkv + (size_t)(base + c0 + r) * ld + D + h * DH + c;
-        kv = *reinterpret_cast<const bf16x8*>(src);
-        vv = *reinterpret_cast<const bf16x8*>(src + D);
+    // batches of 4 chunk pairs per thread: all eight loads of a batch are issued before the first
+    // LDS store waits for them, so their latencies overlap
+    const int n_chunks = nc_pad * CPR;
+    for (int t0 = 0; t0 < n_chunks; t0 += 4 * 256) {
+      bf16x8 kv[4], vv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int t = t0 + u * 256 + tid;
+        const int r = t / CPR, c = (t - r * CPR) * 8;
+        const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+        kv[u] = zero;
+        vv[u] = zero;
+        if (t < n_chunks && r < nc) {
+          const bf16_t* src = qkv + (size_t)(base + c0 + r) * ld + D + h * DH + c;
+          kv[u] = *reinterpret_cast<const bf16x8*>(src);
+          vv[u] = *reinterpret_cast<const bf16x8*>(src + D);
+        }
       }
-      *reinterpret_cast<bf16x8*>(Ks + r * LD + c) = kv;
-      *reinterpret_cast<bf16x8*>(Vs + r * LD + c) = vv;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int t = t0 + u * 256 + tid;
+        const int r = t / CPR, c = (t - r * CPR) * 8;
+        if (t < n_chunks) {
+          *reinterpret_cast<bf16x8*>(Ks + r * LD + c) = kv[u];
+          *reinterpret_cast<bf16x8*>(Vs + r * LD + c) = vv[u];
+        }
+      }
     }
-    if (sizes) {
-      for (int t = tid; t < nc_pad; t += 256) lnsz[t] = t < nc ? logf((float)sizes[base + c0 + t]) : 0.f;
+    if (BIAS) {
+      for (int t = tid; t < nc_pad; t += 256) lnsz[t] = t < nc ? log2f((float)sizes[base + c0 + t]) : 0.f;
     }
     __syncthreads();
     if (!wave_active) continue;
@@ -155,33 +172,41 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
         const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + (kb + fr) * LD + ks * 16 + fk * 8);
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
       }
-      // logits, mask, running maximum
+      // Logits in base-2 units: t = s * (scale * log2 e) [+ log2(size)], so that exp(s - m) is one
+      // v_exp_f32 of a difference.  Only the chunk's last block can hold keys past the end.
       float mx = -INFINITY;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int key = kb + 8 * (e >> 2) + 4 * fk + (e & 3);
-        float v = sacc[e] * scale;
-        if (sizes) v += lnsz[key];
-        v = key < nc ? v : -INFINITY;
+        float v = sacc[e] * scale2;
+        if (BIAS) v += lnsz[kb + 8 * (e >> 2) + 4 * fk + (e & 3)];
         sacc[e] = v;
-        mx = fmaxf(mx, v);
       }
+      if (kb + 32 > nc) {   // wave-uniform: keys past the end of the sequence
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          sacc[e] = (kb + 8 * (e >> 2) + 4 * fk + (e & 3)) < nc ? sacc[e] : -INFINITY;
+      }
+#pragma unroll
+      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[e]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = __expf(m_run - m_new);    // 0 on the first block (m_run = -inf)
-      m_run = m_new;
+      if (__any(mx > m_run)) {   // some row's maximum moved: rescale what has been accumulated
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first block (m_run = -inf)
+        m_run = m_new;
+        l_part *= alpha;
+#pragma unroll
+        for (int t = 0; t < DT; ++t)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
+      }
       float psum = 0.f;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const float pv = __expf(sacc[e] - m_new);
+        const float pv = __builtin_amdgcn_exp2f(sacc[e] - m_run);
         sacc[e] = pv;
         psum += pv;
       }
-      l_part = l_part * alpha + psum;
-#pragma unroll
-      for (int t = 0; t < DT; ++t)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[t][e] *= alpha;
+      l_part += psum;
       // O^T += V^T P^T, two k-steps of 16 keys
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk) {
@@ -226,12 +251,15 @@ __global__ __launch_bounds__(256) void attention_mfma_kernel(const bf16_t* __res
   }
 }
 
-template <int DH>
-static hipError_t attention_mfma(const void* qkv, const int32_t* sz, const int32_t* d_off, int B, int max_n, int D,
+template <int DH, bool BIAS>
+static hipError_t attention_mfma_b(const void* qkv, const int32_t* sz, const int32_t* d_off, int B, int max_n, int D,
                                  int H, float scale, void* o, hipStream_t s) {
+  // 128 keys per LDS chunk: (128 + 132) rows of DH + 8 bf16 = 37 KB at DH = 64, so four workgroups
+  // share a CU and cover each other's MFMA-dependency and barrier waits.
+  constexpr int KC = 128;
   constexpr int LD = DH + 8;
-  const size_t lds = (size_t)(256 + 256 + 4) * LD * sizeof(bf16_t) + 256 * sizeof(float);
-  auto kern = attention_mfma_kernel<DH>;
+  const size_t lds = (size_t)(KC + KC + 4) * LD * sizeof(bf16_t) + KC * sizeof(float);
+  auto kern = attention_mfma_kernel<DH, BIAS, KC>;
   static bool attr = false;
   if (!attr) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -241,6 +269,13 @@ static hipError_t attention_mfma(const void* qkv, const int32_t* sz, const int32
   dim3 grid((max_n + 127) / 128, H, B), block(256);
   kern<<<grid, block, lds, s>>>((const bf16_t*)qkv, sz, d_off, D, scale, (bf16_t*)o);
   return hipGetLastError();
+}
+
+template <int DH>
+static hipError_t attention_mfma(const void* qkv, const int32_t* sz, const int32_t* d_off, int B, int max_n, int D,
+                                 int H, float scale, void* o, hipStream_t s) {
+  return sz ? attention_mfma_b<DH, true>(qkv, sz, d_off, B, max_n, D, H, scale, o, s)
+            : attention_mfma_b<DH, false>(qkv, sz, d_off, B, max_n, D, H, scale, o, s);
 }
 
 int g_attn_force_rows = 0;   // tuning / test switch: route bf16 through the row-wise kernel

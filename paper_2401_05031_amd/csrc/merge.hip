@@ -17,6 +17,8 @@ namespace otas {
 
 constexpr int kPlanThreads = 1024;
 
+template <typename T> struct alignas(4 * sizeof(T)) Quad { T x[4]; };   // 4 consecutive elements, one load
+
 // LDS layout of the plan kernel (4-byte words), n = query length, nA = ceil(n/2), nB = floor(n/2):
 //   mh [n][dm+4] normalised metric rows | best [nA] | bcol [nA] | merged [nA] | cnt [nB] |
 //   keep_pos [n] | ent_pos [n] | wave_tot [2][16]
@@ -94,7 +96,8 @@ __global__ __launch_bounds__(kPlanThreads) void merge_plan_kernel(
   int* ent_pos = keep_pos + n;   // [n] exclusive scan of list lengths
   int* wave_tot = ent_pos + n;   // [2][16]
 
-  // Phase 0: head-mean metric rows, 4 columns per thread, heads summed in ascending order.
+  // Phase 0: head-mean metric rows, 4 columns per thread (one 8- or 16-byte load per head), heads
+  // summed in ascending order.
   const int c4n = dm >> 2;
   const float inv_h = 1.0f / (float)H;
   for (int t = tid; t < n * c4n; t += kPlanThreads) {
@@ -102,7 +105,8 @@ __global__ __launch_bounds__(kPlanThreads) void merge_plan_kernel(
     const T* p = src + (size_t)(i0 + i) * row_stride + col_off + c;
     float m0 = 0.f, m1 = 0.f, m2 = 0.f, m3 = 0.f;
     for (int h = 0; h < H; ++h) {
-      m0 += to_float(p[0]); m1 += to_float(p[1]); m2 += to_float(p[2]); m3 += to_float(p[3]);
+      const Quad<T> v = *reinterpret_cast<const Quad<T>*>(p);
+      m0 += to_float(v.x[0]); m1 += to_float(v.x[1]); m2 += to_float(v.x[2]); m3 += to_float(v.x[3]);
       p += dm;
     }
     floatx4 o = {m0 * inv_h, m1 * inv_h, m2 * inv_h, m3 * inv_h};
