@@ -101,15 +101,27 @@ def run_strategy(name, steps, warmup, timing_steps):
     return {"name": name, "cfg": cfg, "ms": ms, "img_s": cfg.B / (ms * 1e-3), "kernels": per_step, "work": work}
 
 
+def measured_traffic(workload):
+    """Per-launch HBM bytes per kernel family measured offline with rocprofv3 --pmc (see
+    paper_2401_05031_amd/traffic.py); None for workloads that were not measured."""
+    path = os.path.join(ROOT, "paper_2401_05031_amd", "hbm_traffic.json")
+    try:
+        d = json.load(open(path))
+    except OSError:
+        return {}
+    return {k: v["bytes"] for k, v in d["families"].items()} if d.get("workload") == workload else {}
+
+
 def rooflines(res):
     k, w = res["kernels"], res["work"]
+    traffic = measured_traffic(res["name"])
     gemm_ms = sum(k[n][0] for n in ("gemm_qkv", "gemm_proj", "gemm_fc1", "gemm_fc2"))
     gemm_launches = sum(k[n][1] for n in ("gemm_qkv", "gemm_proj", "gemm_fc1", "gemm_fc2"))
     gemm_flops = sum(w[n] for n in ("gemm_qkv", "gemm_proj", "gemm_fc1", "gemm_fc2"))
     out = {}
     ach = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     out["gemm"] = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                   "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                   "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": traffic.get("gemm"),
                    "launches_per_step": gemm_launches, "avg_launch_us": round(gemm_ms * 1e3 / max(gemm_launches, 1), 2),
                    "flops_per_launch": gemm_flops / max(gemm_launches, 1)}
     for n in ("gemm_qkv", "gemm_proj", "gemm_fc1", "gemm_fc2"):
@@ -120,17 +132,18 @@ def rooflines(res):
     if k["attention"][0] > 0:
         a = w["attention"] / (k["attention"][0] * 1e-3) / 1e12
         out["attention"] = {"bound": "mfma", "achieved": round(a, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                            "frac": round(a / PEAK_BF16_TFLOPS, 4),
+                            "frac": round(a / PEAK_BF16_TFLOPS, 4), "traffic": traffic.get("attention"),
                             "avg_launch_us": round(k["attention"][0] * 1e3 / max(k["attention"][1], 1), 2)}
     if k["merge_apply"][0] > 0:
         a = w["merge_apply_bytes"] / (k["merge_apply"][0] * 1e-3) / 1e9
         out["merge_apply"] = {"bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                              "frac": round(a / PEAK_HBM_GBS, 4), "traffic": None,
+                              "frac": round(a / PEAK_HBM_GBS, 4), "traffic": traffic.get("merge_apply"),
+                              "algorithmic_bytes_per_launch": round(w["merge_apply_bytes"] / max(k["merge_apply"][1], 1)),
                               "avg_launch_us": round(k["merge_apply"][0] * 1e3 / max(k["merge_apply"][1], 1), 2)}
     if k["layer_norm"][0] > 0:
         a = w["layer_norm_bytes"] / (k["layer_norm"][0] * 1e-3) / 1e9
         out["layer_norm"] = {"bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                             "frac": round(a / PEAK_HBM_GBS, 4),
+                             "frac": round(a / PEAK_HBM_GBS, 4), "traffic": traffic.get("layer_norm"),
                              "avg_launch_us": round(k["layer_norm"][0] * 1e3 / max(k["layer_norm"][1], 1), 2)}
     for n in ("merge_plan", "prompt_prepend"):
         if k[n][1] > 0:
@@ -170,6 +183,9 @@ def main():
     ap.add_argument("--others", default="vitb_plain,vitb_p10_r8", help="further strategies reported per strategy")
     ap.add_argument("--cpu-queries", type=int, default=12)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run one plain device copy of 256 MiB (torch) so that a rocprofv3 --pmc run of this "
+                         "command holds a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (queries are independent, so more GPUs would be plain data "
@@ -180,6 +196,13 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
 
+    if args.calibrate:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").random_(0, 255)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)                      # 256 MiB read + 256 MiB written
+        torch.cuda.synchronize()
+        del a, b
     head = run_strategy(args.workload, args.steps, args.warmup, timing_steps=max(3, min(10, args.steps)))
     per_strategy = {}
     all_res = [head]

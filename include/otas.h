@@ -190,6 +190,9 @@ otas_status otas_timing_enable(otas_ctx *ctx, int32_t on);
 int32_t otas_timing_kinds(void);
 const char *otas_timing_kind_name(int32_t kind);
 otas_status otas_timing_read(otas_ctx *ctx, double *total_ms, int64_t *launches);
+/* The same records one by one, in launch order, without clearing them: kind and milliseconds of up
+ * to cap launches into the host arrays; returns the number of records held (-1 on error). */
+int32_t otas_timing_read_launches(otas_ctx *ctx, int32_t cap, int32_t *kinds, float *ms);
 
 const char *otas_strerror(otas_status s);
 

@@ -73,6 +73,7 @@ def load_library():
         "otas_timing_kinds": (i32, []),
         "otas_timing_kind_name": (C.c_char_p, [i32]),
         "otas_timing_read": (i32, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+        "otas_timing_read_launches": (i32, [vp, i32, _I32P, C.POINTER(C.c_float)]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)          # AttributeError if a declared symbol is not exported
@@ -84,7 +85,8 @@ def load_library():
 EXPORTED = ("otas_create", "otas_destroy", "otas_schedule", "otas_workspace_bytes",
             "otas_merge_workspace_bytes", "otas_prompt_prepend", "otas_token_merge",
             "otas_encoder_forward", "otas_encoder_layers", "otas_layer_norm", "otas_linear", "otas_attention", "otas_strerror",
-            "otas_timing_enable", "otas_timing_kinds", "otas_timing_kind_name", "otas_timing_read")
+            "otas_timing_enable", "otas_timing_kinds", "otas_timing_kind_name", "otas_timing_read",
+            "otas_timing_read_launches")
 
 
 def otas_strerror(status: int) -> str:
@@ -231,6 +233,15 @@ class Context:
         cnt = (C.c_int64 * k)()
         _check(self._lib.otas_timing_read(self._h, ms, cnt), "otas_timing_read")
         return {self._lib.otas_timing_kind_name(i).decode(): (ms[i], int(cnt[i])) for i in range(k)}
+
+    def otas_timing_read_launches(self, cap: int = 65536):
+        """[(kind name, ms)] of the recorded launches in launch order (records are kept)."""
+        kinds = (C.c_int32 * cap)()
+        ms = (C.c_float * cap)()
+        n = self._lib.otas_timing_read_launches(self._h, cap, kinds, ms)
+        if n < 0:
+            raise OtasError(4, "otas_timing_read_launches")
+        return [(self._lib.otas_timing_kind_name(kinds[i]).decode(), float(ms[i])) for i in range(min(n, cap))]
 
     # -- plan arithmetic shared with callers (host only)
     def trace_layout(self, lengths0: Sequence[int], r: Sequence[int],

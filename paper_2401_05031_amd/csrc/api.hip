@@ -528,6 +528,17 @@ int32_t otas_timing_kinds(void) { return K_COUNT; }
 
 const char* otas_timing_kind_name(int32_t kind) { return (kind >= 0 && kind < K_COUNT) ? kKindNames[kind] : ""; }
 
+int32_t otas_timing_read_launches(otas_ctx* c, int32_t cap, int32_t* kinds, float* ms) {
+  if (!c || cap < 0 || (cap > 0 && (!kinds || !ms))) return -1;
+  if (hipStreamSynchronize(c->stream) != hipSuccess || hipStreamSynchronize(c->side) != hipSuccess) return -1;
+  const int32_t n = (int32_t)std::min<size_t>(c->ev_kind.size(), (size_t)cap);
+  for (int32_t i = 0; i < n; ++i) {
+    kinds[i] = c->ev_kind[i];
+    if (hipEventElapsedTime(&ms[i], c->ev_pool[2 * i], c->ev_pool[2 * i + 1]) != hipSuccess) return -1;
+  }
+  return (int32_t)c->ev_kind.size();
+}
+
 otas_status otas_timing_read(otas_ctx* c, double* total_ms, int64_t* launches) {
   if (!c || !total_ms || !launches) return OTAS_EINVAL;
   if (hipStreamSynchronize(c->stream) != hipSuccess || hipStreamSynchronize(c->side) != hipSuccess) return OTAS_EDEVICE;
