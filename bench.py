@@ -43,9 +43,12 @@ def algorithmic_work(cfg, lengths0, r, otas):
         w["gemm_fc1"] += 2.0 * T[l + 1] * D * F
         w["gemm_fc2"] += 2.0 * T[l + 1] * D * F
         w["attention"] += float(np.sum(4.0 * sched[:, l].astype(np.float64) ** 2 * D))
-        w["layer_norm_bytes"] += (T[l] + T[l + 1]) * D * (4.0 + e)   # float residual row in, operand row out
+        w["layer_norm_bytes"] += T[l] * D * (4.0 + e)                # LN1: float residual row in, operand row out
         if T[l + 1] != T[l]:
-            w["merge_apply_bytes"] += (T[l] + T[l + 1]) * (D * 4.0 + 8.0)   # float rows + size + list entry
+            # merge-apply fused with LN2: float rows in and out, a size and a list entry per row, operand row out
+            w["merge_apply_bytes"] += (T[l] + T[l + 1]) * (D * 4.0 + 8.0) + T[l + 1] * D * e
+        else:
+            w["layer_norm_bytes"] += T[l + 1] * D * (4.0 + e)        # LN2 on its own
             w["merge_layers"] += 1
     w["T"] = T.tolist()
     return w

@@ -420,8 +420,17 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
   const int dt = d.dtype;
   const bool size_bias = flags & OTAS_FLAG_SIZE_BIAS;
 
-  if (sizes_in) OTAS_LAUNCH(K_MISC, launch_copy_i32(sizes_in, sizes_cur, T0, s));
-  else OTAS_LAUNCH(K_MISC, launch_fill_i32(sizes_cur, 1, T0, s));
+  // Token sizes: nullptr stands for "all 1" until the first merge (or the caller's sizes_in), so no
+  // fill is needed; the last merging layer writes straight into sizes_out.
+  int32_t* sizes_buf[2] = {sizes_cur, sizes_alt};
+  const int32_t* sizes_now = sizes_in;
+  int last_merge = -1;
+  for (int l = 0; l < L; ++l)
+    if (any_merge[l]) last_merge = l;
+  if (size_bias && !sizes_now) {   // the attention bias reads sizes from the first layer on
+    OTAS_LAUNCH(K_MISC, launch_fill_i32(sizes_buf[0], 1, T0, s));
+    sizes_now = sizes_buf[0];
+  }
   void* x_free[2] = {xa, xb};
   const void* x_cur = x0;   // residual stream entering the block (float)
   bool x_owned = false;     // x_cur is one of the workspace buffers, so it may be updated in place
@@ -450,7 +459,7 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
                                        trace ? trace_src : nullptr, trace ? trace_dst : nullptr, c->side));
       OTAS_HIP(hipEventRecord(c->ev_join, c->side));
     }
-    OTAS_LAUNCH(K_ATTN, launch_attention(dt, qkv, sizes_cur, off_l, B, max_n[l], D, H, size_bias, hbuf, s));
+    OTAS_LAUNCH(K_ATTN, launch_attention(dt, qkv, sizes_now, off_l, B, max_n[l], D, H, size_bias, hbuf, s));
     // in-place residual is safe (each element is read then written by the same thread); the
     // caller's x0 is never written, so layer 0 writes into the workspace.
     void* x_attn = x_owned ? const_cast<void*>(x_cur) : x_free[0];
@@ -461,12 +470,16 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
     if (any_merge[l]) {
       void* x_other = (x_attn == x_free[0]) ? x_free[1] : x_free[0];
       OTAS_HIP(hipStreamWaitEvent(s, c->ev_join, 0));   // join
-      OTAS_LAUNCH(K_APPLY, launch_merge_apply(OTAS_F32, x_attn, sizes_cur, src_list, row_ptr, T, Tn, D, x_other, sizes_alt, s));
-      std::swap(sizes_cur, sizes_alt);
+      int32_t* sizes_next = (l == last_merge) ? sizes_out : (sizes_now == sizes_buf[0] ? sizes_buf[1] : sizes_buf[0]);
+      // merge-apply and the block's second LayerNorm in one pass over the rows
+      OTAS_LAUNCH(K_APPLY, launch_merge_apply_ln(dt, (const float*)x_attn, sizes_now, src_list, row_ptr, T, Tn, D,
+                                                 (float*)x_other, sizes_next, wl.ln2_g, wl.ln2_b, hbuf, d.ln_eps, s));
+      sizes_now = sizes_next;
       x_mlp = x_other;
+    } else {
+      OTAS_LAUNCH(K_LN, launch_layer_norm(dt, true, x_mlp, wl.ln2_g, wl.ln2_b, hbuf, Tn, D, d.ln_eps, s));
     }
-    // normalisation -> MLP + residual
-    OTAS_LAUNCH(K_LN, launch_layer_norm(dt, true, x_mlp, wl.ln2_g, wl.ln2_b, hbuf, Tn, D, d.ln_eps, s));
+    // MLP + residual
     OTAS_LAUNCH(K_FC1, launch_linear(dt, hbuf, wl.w_fc1, wl.b_fc1, nullptr, hid, Tn, F, D, EPI_GELU, s));
     void* x_next = (l == L - 1) ? x_out : x_mlp;
     OTAS_LAUNCH(K_FC2, launch_linear(dt, hid, wl.w_fc2, wl.b_fc2, (const float*)x_mlp, x_next, Tn, D, F,
@@ -474,7 +487,11 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
     x_cur = x_next;
     x_owned = true;
   }
-  OTAS_LAUNCH(K_MISC, launch_copy_i32(sizes_cur, sizes_out, plan[o_off + (size_t)L * (B + 1) + B], s));
+  if (last_merge < 0) {   // nothing merged: the sizes are the input's
+    const int64_t TL = plan[o_off + (size_t)L * (B + 1) + B];
+    if (sizes_in) OTAS_LAUNCH(K_MISC, launch_copy_i32(sizes_in, sizes_out, TL, s));
+    else OTAS_LAUNCH(K_MISC, launch_fill_i32(sizes_out, 1, TL, s));
+  }
   return OTAS_OK;
 }
 }  // namespace

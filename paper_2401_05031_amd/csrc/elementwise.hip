@@ -1,5 +1,6 @@
 // HBM-bound row kernels: integer fill/copy, the prompting module's ragged concatenation
-// (Sec. II-B / III-B) and LayerNorm (Sec. II-A "normalization").
+// (Sec. II-B / III-B), LayerNorm (Sec. II-A "normalization"), and the merging module's data
+// movement fused with the LayerNorm behind it (Sec. II-C).
 #include "common.h"
 #include "kernels.h"
 
@@ -152,6 +153,144 @@ hipError_t launch_layer_norm(int dtype, bool x_is_float, const void* x, const vo
   if (dtype == 0) return layer_norm_dispatch<float, float>(x, g, b, y, T, D, eps, s);
   return x_is_float ? layer_norm_dispatch<float, bf16_t>(x, g, b, y, T, D, eps, s)
                     : layer_norm_dispatch<bf16_t, bf16_t>(x, g, b, y, T, D, eps, s);
+}
+
+// ---------------------------------------------------------------------------------- merge-apply + LayerNorm
+// The merging module's data movement (Sec. II-C: size-weighted average of every surviving token
+// with the tokens merged into it, survivors in their original order) fused with the LayerNorm that
+// follows it in the block.  One wave per OUTPUT row: it gathers the rows listed for it
+// (row_ptr / src_list, the surviving row first, then its sources in ascending position), forms
+// sum(size * x) / sum(size) in fp32 in list order, writes the merged residual row and its size,
+// and normalises the row it still holds in registers.  Same arithmetic, in the same order, as
+// merge_apply_kernel followed by layer_norm_kernel.
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void merge_apply_ln_kernel(
+    const float* __restrict__ x, const int32_t* __restrict__ sizes, const int32_t* __restrict__ src_list,
+    const int32_t* __restrict__ row_ptr, int64_t T_in, int64_t T_out, int D, float* __restrict__ x_out,
+    int32_t* __restrict__ sizes_out, const T* __restrict__ g, const T* __restrict__ b, T* __restrict__ y, float eps) {
+  constexpr int V = 8;
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= T_out) return;
+  const int chunks = D / V;
+  const int beg = row_ptr[row];
+  const int end = (row + 1 < T_out) ? row_ptr[row + 1] : (int)T_in;
+  float v[NCH][V];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i)
+#pragma unroll
+    for (int k = 0; k < V; ++k) v[i][k] = 0.f;
+  int tot = 0;
+  if (end - beg == 1) {   // untouched token: the row itself
+    const int srow = src_list[beg];
+    tot = sizes ? sizes[srow] : 1;
+    const float* xr = x + (size_t)srow * D;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = lane + 64 * i;
+      if (c < chunks) {
+        const Vec<float> lo = load_vec<float>(xr + c * V), hi = load_vec<float>(xr + c * V + 4);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { v[i][k] = lo.get(k); v[i][4 + k] = hi.get(k); }
+      }
+    }
+  } else {
+    for (int e = beg; e < end; ++e) {
+      const int srow = src_list[e];
+      const int sz = sizes ? sizes[srow] : 1;
+      const float w = (float)sz;
+      tot += sz;
+      const float* xr = x + (size_t)srow * D;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const int c = lane + 64 * i;
+        if (c < chunks) {
+          const Vec<float> lo = load_vec<float>(xr + c * V), hi = load_vec<float>(xr + c * V + 4);
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            v[i][k] = fmaf(w, lo.get(k), v[i][k]);
+            v[i][4 + k] = fmaf(w, hi.get(k), v[i][4 + k]);
+          }
+        }
+      }
+    }
+    const float denom = (float)tot;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i)
+#pragma unroll
+      for (int k = 0; k < V; ++k) v[i][k] = v[i][k] / denom;
+  }
+  if (lane == 0) sizes_out[row] = tot;
+  float* xo = x_out + (size_t)row * D;
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane + 64 * i;
+    if (c < chunks) {
+      Vec<float> lo, hi;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { lo.set(k, v[i][k]); hi.set(k, v[i][4 + k]); }
+      store_vec<float>(xo + c * V, lo);
+      store_vec<float>(xo + c * V + 4, hi);
+#pragma unroll
+      for (int k = 0; k < V; ++k) sum += v[i][k];
+    }
+  }
+  const float mean = wave_sum(sum) / (float)D;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane + 64 * i;
+    if (c < chunks) {
+#pragma unroll
+      for (int k = 0; k < V; ++k) { const float d = v[i][k] - mean; sq += d * d; }
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)D + eps);
+  T* yr = y + (size_t)row * D;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane + 64 * i;
+    if (c < chunks) {
+#pragma unroll
+      for (int k0 = 0; k0 < V; k0 += Vec<T>::N) {
+        Vec<T> gg = load_vec<T>(g + c * V + k0), bb = load_vec<T>(b + c * V + k0), o;
+#pragma unroll
+        for (int k = 0; k < Vec<T>::N; ++k) o.set(k, (v[i][k0 + k] - mean) * rstd * gg.get(k) + bb.get(k));
+        store_vec<T>(yr + c * V + k0, o);
+      }
+    }
+  }
+}
+
+template <typename T>
+static hipError_t merge_apply_ln_dispatch(const float* x, const int32_t* sizes, const int32_t* src_list,
+                                          const int32_t* row_ptr, int64_t T_in, int64_t T_out, int D, float* x_out,
+                                          int32_t* sizes_out, const void* g, const void* b, void* y, float eps,
+                                          hipStream_t s) {
+  const int nch = (D / 8 + 63) / 64;
+  dim3 grid((unsigned)((T_out + 3) / 4)), block(256);
+#define OTAS_MLN(N)                                                                                               \
+  merge_apply_ln_kernel<T, N><<<grid, block, 0, s>>>(x, sizes, src_list, row_ptr, T_in, T_out, D, x_out, sizes_out, \
+                                                     (const T*)g, (const T*)b, (T*)y, eps)
+  if (nch <= 1) OTAS_MLN(1);
+  else if (nch <= 2) OTAS_MLN(2);
+  else if (nch <= 3) OTAS_MLN(3);
+  else if (nch <= 4) OTAS_MLN(4);
+  else if (nch <= 8) OTAS_MLN(8);
+  else return hipErrorInvalidValue;
+#undef OTAS_MLN
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_apply_ln(int dtype, const float* x, const int32_t* sizes, const int32_t* src_list,
+                                 const int32_t* row_ptr, int64_t T_in, int64_t T_out, int D, float* x_out,
+                                 int32_t* sizes_out, const void* g, const void* b, void* y, float eps, hipStream_t s) {
+  if (T_out <= 0) return hipSuccess;
+  return dtype == 0 ? merge_apply_ln_dispatch<float>(x, sizes, src_list, row_ptr, T_in, T_out, D, x_out, sizes_out, g,
+                                                     b, y, eps, s)
+                    : merge_apply_ln_dispatch<bf16_t>(x, sizes, src_list, row_ptr, T_in, T_out, D, x_out, sizes_out,
+                                                      g, b, y, eps, s);
 }
 
 // ---------------------------------------------------------------------------------- widen / narrow

@@ -637,15 +637,14 @@ int g_gemm_variant = 0;   // tile selection override for tuning runs (0 = automa
 
 static hipError_t linear_mfma(const void* x, const void* w, const void* bias, const float* res, void* y, int64_t M,
                               int N, int K, int epi, hipStream_t s) {
-  // Kernel choice, from measurements on MI355X inside the encoder (us per launch):
-  //   128 x 128, three workgroups per CU:  ~max(3 + 0.0095 K, 6e-5 K tiles128); bound by L2 -> LDS
-  //       bandwidth (64 FLOP per byte loaded) but free of tile-count quantisation, and its epilogue
-  //       overlaps other workgroups' main loops;
-  //   256 x 256, 8 waves, one workgroup per CU:  ~(11 + 0.018 K) per round of 256 tiles: twice the
-  //       FLOP per byte, whole rounds only.
-  // The large kernel is taken when it runs many rounds (>= 1024 tiles), and for plain-epilogue
-  // shapes (the QKV projection) whenever the model above favours it; the residual / GELU shapes of
-  // mid-size batches stay on the 128 x 128 kernel, which measured faster there in place.
+  // Kernel choice by a cost model fitted to per-launch times measured on MI355X inside the encoder
+  // (microseconds; t128 / t256 = number of 128 x 128 / 256 x 256 tiles):
+  //   128 x 128, three workgroups per CU:  max(10 + 0.0107 K, t128 * a), a = 5.3e-5 K (plain and
+  //       GELU epilogue) or 0.0323 + 4.25e-5 K (residual epilogue, float read + write per element).
+  //       Bound by L2 -> LDS bandwidth (64 FLOP per byte loaded) but free of tile-count
+  //       quantisation, and its epilogue overlaps other workgroups' main loops.
+  //   256 x 256, 8 waves, one workgroup per CU:  ceil(t256 / 256) rounds of 11 + 0.021 K (plain),
+  //       19 + 0.021 K (GELU), 19 + 0.0205 K (residual): twice the FLOP per byte, whole rounds only.
   // K % 32 != 0 or tiny K falls back to the register-staged kernel.
   static const int env_variant = [] {
     const char* e = std::getenv("OTAS_GEMM_VARIANT");   // tuning override, 0 / unset = automatic
@@ -656,9 +655,11 @@ static hipError_t linear_mfma(const void* x, const void* w, const void* bias, co
   if (variant == 0) {
     const double t128 = (double)((M + 127) / 128) * ((N + 127) / 128);
     const double t256 = (double)((M + 255) / 256) * ((N + 255) / 256);
-    const double c128 = std::max(3.0 + 0.0095 * K, 6e-5 * K * t128);
-    const double c256 = (11.0 + 0.018 * K) * std::ceil(t256 / 256.0);
-    variant = (t256 >= 1024 || (epi == EPI_NONE && c256 < c128)) ? 7 : 5;
+    const double a = epi == EPI_RESIDUAL ? 0.0323 + 4.25e-5 * K : 5.3e-5 * K;
+    const double r = epi == EPI_NONE ? 11.0 + 0.021 * K : epi == EPI_GELU ? 19.0 + 0.021 * K : 19.0 + 0.0205 * K;
+    const double c128 = std::max(10.0 + 0.0107 * K, t128 * a);
+    const double c256 = r * std::ceil(t256 / 256.0);
+    variant = c256 < c128 ? 7 : 5;
   }
   switch (variant) {
     case 5: return linear_mfma128_dma<3>(x, w, bias, res, y, M, N, K, epi, s);

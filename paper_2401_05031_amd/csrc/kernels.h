@@ -45,4 +45,11 @@ hipError_t launch_merge_apply(int dtype, const void* x, const int32_t* sizes,
                               int64_t T_out, int D, void* x_out, int32_t* sizes_out,
                               hipStream_t s);
 
+// merge-apply on the float residual stream fused with the following LayerNorm: writes the merged
+// rows x_out (float), their sizes, and y = LN(x_out) in the model's dtype (gamma, beta of that dtype).
+hipError_t launch_merge_apply_ln(int dtype, const float* x, const int32_t* sizes, const int32_t* src_list,
+                                 const int32_t* row_ptr, int64_t T_in, int64_t T_out, int D, float* x_out,
+                                 int32_t* sizes_out, const void* g, const void* b, void* y, float eps,
+                                 hipStream_t s);
+
 }  // namespace otas
