@@ -285,6 +285,104 @@ def test_bf16_encoder_parity(torch_cuda, lib, name, queries):
     assert per["disagreements"] <= BF16_DECISION_TOL * per["decisions"] + (1 if per["decisions"] < 2000 else 0)
 
 
+# ------------------------------------------------------------------ full batches, as bench.py launches them
+FULL_CASES = [
+    ("vitb_plain", [0, 63]),
+    ("vitb_r16", [0, 31, 63]),
+    ("vitb_p10_r8", [0, 31, 63]),
+    ("vitl_ragged", [0, 33, 66, 127]),            # one query of every (P, r) group
+    ("vith_mixed", [0, 100, 255]),
+]
+
+
+@pytest.mark.parametrize("name,sample", FULL_CASES)
+def test_full_batch_sampled_queries(torch_cuda, lib, name, sample):
+    """The whole batch of the workload in one launch (the configuration bench.py times); queries are
+    independent, so a sample of them is checked against the oracle one by one, in lock-step."""
+    cfg = synth.config(name)
+    ctx, layers = hz.make_context(cfg)
+    toks, prm, P, R = synth.batch(cfg)
+    x0, off = hz.gpu_prepend(ctx, toks, prm)
+    gpu = hz.gpu_forward(ctx, x0, off, R)
+    # shape laws for every query of the batch
+    for q in range(cfg.B):
+        want = orc.length_schedule(cfg.n0, P[q], R[q], cfg.n_lead, cfg.L)[-1]
+        assert gpu["x"][q].shape == (want, cfg.D)
+        assert int(gpu["sizes"][q].sum()) == cfg.n0 + P[q] and gpu["sizes"][q].min() >= 1
+        assert np.isfinite(gpu["x"][q]).all()
+    sub = {k: [gpu[k][q] for q in sample] for k in ("x", "sizes", "trace")}
+    rep = hz.compare_lockstep(cfg, layers, [toks[q] for q in sample], [prm[q] for q in sample],
+                              [R[q] for q in sample], sub)
+    print(name, "full batch, sampled", sample, rep)
+    assert rep["sizes_equal"]
+    assert rep["max_err"] <= BF16_TOL
+    assert rep["max_deficit"] <= NEAR_TIE
+    assert rep["disagreements"] <= 0.02 * max(rep["decisions"], 1) + 1
+    ctx.close()
+
+
+def test_edge_cases_through_the_abi(torch_cuda, lib):
+    """Degenerate inputs: one query of one token, sequences at the floor, r beyond what can merge,
+    no protected token, a single-query batch."""
+    torch = torch_cuda
+    for n_lead in (1, 0):
+        cfg = synth.Config("edge", L=3, D=192, H=3, F=384, dtype="f32", B=5, n0=9,
+                           strategies=[(0, 0), (0, 50), (2, 1), (0, 3), (1, 50)], seed=21, n_lead=n_lead)
+        ctx, layers = hz.make_context(cfg)
+        rng = np.random.default_rng(5)
+        ns = [1, 9, 2, 3, 40]
+        toks = [rng.standard_normal((n, cfg.D)).astype(np.float32) for n in ns]
+        prm = [(0.02 * rng.standard_normal((p, cfg.D))).astype(np.float32) for p, _ in cfg.strategies]
+        R = [r for _, r in cfg.strategies]
+        x0, off = hz.gpu_prepend(ctx, toks, prm)
+        gpu = hz.gpu_forward(ctx, x0, off, R)
+        for q in range(cfg.B):
+            xq, _ = orc.prompt_prepend(toks[q], prm[q], n_lead)
+            ref = orc.encoder_forward_query(xq, layers, R[q], H=cfg.H, ln_eps=cfg.ln_eps, n_lead=n_lead)
+            assert gpu["x"][q].shape == ref["x"].shape, (n_lead, q)
+            assert np.array_equal(gpu["sizes"][q], ref["sizes"]), (n_lead, q)
+            for l in range(cfg.L):
+                assert np.array_equal(gpu["trace"][q][l][0], ref["trace"][l][0]), (n_lead, q, l)
+                assert np.array_equal(gpu["trace"][q][l][1], ref["trace"][l][1]), (n_lead, q, l)
+            assert hz.rel_err(gpu["x"][q], ref["x"]) <= F32_TOL, (n_lead, q)
+        ctx.close()
+
+
+def test_argument_errors_on_the_gpu_box(torch_cuda, lib):
+    torch = torch_cuda
+    cfg = synth.config("tiny")
+    ctx, _ = hz.make_context(cfg)
+    x0 = torch.zeros((10, cfg.D), dtype=torch.float32, device="cuda")
+    ws = torch.empty(ctx.otas_workspace_bytes(1, 10), dtype=torch.uint8, device="cuda")
+    xo = torch.empty((10, cfg.D), dtype=torch.float32, device="cuda")
+    so = torch.empty(10, dtype=torch.int32, device="cuda")
+    with pytest.raises(lib.OtasError) as e:                         # workspace too small
+        ctx.otas_encoder_forward(x0, [0, 10], [1], 0, ws[:1024], xo, so)
+    assert e.value.status == 3
+    with pytest.raises(lib.OtasError) as e:                         # offsets not starting at 0
+        ctx.otas_encoder_forward(x0, [1, 10], [1], 0, ws, xo, so)
+    assert e.value.status == 1
+    with pytest.raises(lib.OtasError) as e:                         # negative r
+        ctx.otas_encoder_forward(x0, [0, 10], [-1], 0, ws, xo, so)
+    assert e.value.status == 1
+    with pytest.raises(lib.OtasError) as e:                         # unknown flag
+        ctx.otas_encoder_forward(x0, [0, 10], [1], 64, ws, xo, so)
+    assert e.value.status == 1
+    with pytest.raises(lib.OtasError) as e:                         # trace flag without buffers
+        ctx.otas_encoder_forward(x0, [0, 10], [1], lib.OTAS_FLAG_TRACE, ws, xo, so)
+    assert e.value.status == 1
+    with pytest.raises(lib.OtasError) as e:                         # sequence longer than the kernels take
+        big = torch.zeros((1100, cfg.D), dtype=torch.float32, device="cuda")
+        ctx.otas_encoder_forward(big, [0, 1100], [1], 0, torch.empty(ctx.otas_workspace_bytes(1, 1100), dtype=torch.uint8, device="cuda"),
+                                 torch.empty((1100, cfg.D), dtype=torch.float32, device="cuda"), torch.empty(1100, dtype=torch.int32, device="cuda"))
+    assert e.value.status == 5
+    # a failed call enqueued nothing: the context still works
+    off = ctx.otas_encoder_forward(x0, [0, 10], [1], 0, ws, xo, so)
+    torch.cuda.synchronize()
+    assert off.tolist() == [0, 8]
+    ctx.close()
+
+
 def test_query_independence_of_batch_composition(torch_cuda, lib):
     """A query's result must not depend on what else is in the ragged batch."""
     cfg = synth.config("vitb_p10_r8")
