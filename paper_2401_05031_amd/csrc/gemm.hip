@@ -491,27 +491,28 @@ static hipError_t linear_mfma128_dma(const void* x, const void* w, const void* b
 }
 
 // ------------------------------------------------------------------------------ 256x256, 8 waves
-// The large-shape kernel: block tile 256 x 256, 8 waves of 128 x 64 (2 x 4 arrangement), a ring of
-// 4 stages (128 KB).  128 accumulator registers per lane let two waves share each SIMD, so one
+// The large-shape kernel: block tile 256 x 256, 8 waves of 128 x 64 (2 x 4 arrangement), two LDS
+// stages of K step 64 (128 KB; rows of 128 B, i.e. whole cache lines per row and k-tile: streaming
+// 64-byte row pieces reaches ~13 TB/s from L2 on MI355X, 128-byte pieces 15-16).  128 accumulator registers per lane let two waves share each SIMD, so one
 // wave's barrier / LDS waits are covered by the other's MFMAs, while the L2 traffic per MFMA is half
 // that of the 128 x 128 tiling (which is bound by L2 -> LDS bandwidth: streaming operand tiles into
 // LDS tops out near 13 TB/s chip-wide on MI355X).
-//   iteration t:  wait until this wave's loads of tile t+1 have landed, barrier, then the two
-//                 k-steps of tile t; after each MFMA one piece of later work is issued (a fragment
-//                 read for the next k-step / next tile, or load instructions of tile t+3 into the
-//                 stage tile t-1 used), so that this issue overlaps the MFMA's cycles in the matrix
-//                 pipe.  A load is in flight for two iterations before it is needed.
+// After each MFMA one piece of later work is issued (a fragment read for the next k-step / next
+// tile, or a load instruction of the tile after next), so that this issue overlaps the MFMA's cycles
+// in the matrix pipe.  A load is in flight for one whole 64-wide tile before it is needed.
+// Stage layout: 16-byte chunk c of row r sits at chunk c ^ ((r >> 1) & 7) (conflict-free for the
+// linear DMA writes and for the 16-lanes-per-clock fragment reads).
 template <int EPI>
 __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __restrict__ A,
                                                                 const bf16_t* __restrict__ W,
                                                                 const bf16_t* __restrict__ bias, const float* res,
                                                                 typename OutType<bf16_t, EPI>::type* Y, int64_t M,
                                                                 int N, int K, int tiles_m, int tiles_n) {
-  constexpr int BM = 256, BN = 256, BK = 32, WM = 128, WN = 64, TM = 4, TN = 2, NS = 4;
+  constexpr int BM = 256, BN = 256, BK = 64, WM = 128, WN = 64, TM = 4, TN = 2, NS = 2, KSTEPS = BK / 16;
   constexpr int STAGE = BM * BK;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [NS][256][32]
-  bf16_t* Ws = As + NS * STAGE;                   // [NS][256][32]
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [NS][256][64]
+  bf16_t* Ws = As + NS * STAGE;                   // [NS][256][64]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
@@ -520,13 +521,16 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __
   const int64_t m0 = (int64_t)tile_m * BM;
   const int n0 = tile_n * BN;
 
-  // DMA addressing: wave w owns rows w*32 .. w*32+31 of each operand tile, 16 rows per instruction.
-  const bf16_t* a_src[2];
-  const bf16_t* w_src[2];
+  // DMA addressing: rows of 128 B (a whole cache line of K per row and k-tile), 8 lanes per row, 8 rows
+  // per instruction; wave w owns rows w*32 .. w*32+31 of each operand tile (4 instructions each).
+  // Lane i writes LDS row base + i/8, chunk position i%8, so it fetches logical chunk
+  // (i%8) ^ ((row >> 1) & 7) of that row.
+  const bf16_t* a_src[4];
+  const bf16_t* w_src[4];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int row = wave * 32 + j * 16 + (lane >> 2);
-    const int c = (lane & 3) ^ ((row >> 2) & 3);
+  for (int j = 0; j < 4; ++j) {
+    const int row = wave * 32 + j * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((row >> 1) & 7);
     int64_t ra = m0 + row;
     ra = ra < M ? ra : M - 1;
     int rw = n0 + row;
@@ -535,14 +539,14 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __
     w_src[j] = W + (size_t)rw * K + c * 8;
   }
   const int KT = K / BK;
-  auto dma_one = [&](int kt, int st, int d) {   // d = 0..3
+  auto dma_one = [&](int kt, int st, int d) {   // d = 0..7: A rows j = d/2 (even d), W rows (odd d)
     const int k = (kt < KT ? kt : KT - 1) * BK;
     const int j = d >> 1;
     if ((d & 1) == 0)
-      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_src[j] + k), OTAS_LPTR(As + st * STAGE + (wave * 32 + j * 16) * BK),
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_src[j] + k), OTAS_LPTR(As + st * STAGE + (wave * 32 + j * 8) * BK),
                                        16, 0, 0);
     else
-      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_src[j] + k), OTAS_LPTR(Ws + st * STAGE + (wave * 32 + j * 16) * BK),
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_src[j] + k), OTAS_LPTR(Ws + st * STAGE + (wave * 32 + j * 8) * BK),
                                        16, 0, 0);
   };
 
@@ -555,7 +559,7 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   const int fr = lane & 31, fk = lane >> 5;
-  const int frag_row = fr * BK, sw = (fr >> 2) & 3;
+  const int frag_row = fr * BK, sw = (fr >> 1) & 7;
   bf16x8 af[2][TM], wf[2][TN];
   auto read_frag = [&](int st, int ks, int slot, int f) {   // f = 0..3: A tiles; 4,5: W tiles
     const int c = (((ks << 1) + fk) ^ sw) * 8;
@@ -569,11 +573,26 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __
     const int i = t / TN, j = t % TN;
     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
   };
+  // one k-step: 8 MFMAs, each followed by one piece of later work (6 fragment reads, then `extra`)
+  auto kstep = [&](int slot, int st_next, int ks_next, auto extra) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      mfma_one(slot, t);
+      if (t < 6) read_frag(st_next, ks_next, slot ^ 1, t);
+      else extra(t - 6);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  auto nothing = [](int) {};
 
+  // Two stages of 64 KB.  Per tile t (stage t & 1): k-steps 0..2 (the fragments of k-step 3 are read
+  // during k-step 2), then wait for this wave's loads of tile t+1, barrier -- after it nobody reads
+  // stage t & 1 any more and tile t+1 is visible --, then k-step 3 while the loads of tile t+2 are
+  // issued into stage t & 1 and the first fragments of tile t+1 are read.
 #pragma unroll
-  for (int t = 0; t < 3; ++t)
+  for (int d = 0; d < 8; ++d) dma_one(0, 0, d);
 #pragma unroll
-    for (int d = 0; d < 4; ++d) dma_one(t, t, d);
+  for (int d = 0; d < 8; ++d) dma_one(1, 1, d);
   OTAS_VMCNT(8);    // tile 0 landed (this wave's part)
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
@@ -582,22 +601,20 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __
   for (int f = 0; f < TM + TN; ++f) read_frag(0, 0, 0, f);
 
   for (int kt = 0; kt < KT; ++kt) {
-    const int st = kt & (NS - 1), st1 = (kt + 1) & (NS - 1), st3 = (kt + 3) & (NS - 1);
-    OTAS_VMCNT(4);    // tile kt+1 landed; only tile kt+2 may still be in flight
+    const int st = kt & 1;
+    kstep(0, st, 1, nothing);
+    kstep(1, st, 2, nothing);
+    kstep(0, st, 3, nothing);
+    OTAS_VMCNT(0);    // tile kt+1 landed
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
+    // k-step 3: fragments of (tile kt+1, k-step 0) and the 8 load instructions of tile kt+2
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {    // k-step 0 of tile kt
-      mfma_one(0, t);
-      if (t < 6) read_frag(st, 1, 1, t);
-      else { dma_one(kt + 3, st3, 2 * (t - 6)); dma_one(kt + 3, st3, 2 * (t - 6) + 1); }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {    // k-step 1
+    for (int t = 0; t < 8; ++t) {
       mfma_one(1, t);
-      if (t < 6) read_frag(st1, 0, 0, t);
+      if (t < 6) read_frag(st ^ 1, 0, 0, t);
+      dma_one(kt + 2, st, t);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
@@ -612,11 +629,154 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __
 static hipError_t linear_mfma256w8(const void* x, const void* w, const void* bias, const float* res, void* y,
                                    int64_t M, int N, int K, int epi, hipStream_t s) {
   const int tiles_m = (int)((M + 255) / 256), tiles_n = (N + 255) / 256;
-  const size_t lds = (size_t)4 * 2 * 256 * 32 * sizeof(bf16_t);
+  const size_t lds = (size_t)2 * 2 * 256 * 64 * sizeof(bf16_t);
   dim3 grid((unsigned)(tiles_m * tiles_n)), block(512);
 #define OTAS_MFMA(E)                                                                                              \
   do {                                                                                                            \
     auto kern = gemm_mfma256w8_kernel<E>;                                                                         \
+    static bool attr = false;                                                                                     \
+    if (!attr) {                                                                                                  \
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+      if (e != hipSuccess) return e;                                                                              \
+      attr = true;                                                                                                \
+    }                                                                                                             \
+    kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
+                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_m, tiles_n);              \
+  } while (0)
+  if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
+  else if (epi == EPI_GELU) OTAS_MFMA(EPI_GELU);
+  else OTAS_MFMA(EPI_RESIDUAL);
+#undef OTAS_MFMA
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------ 128x128, K step 64
+// Block tile 128 x 128, 4 waves of 64 x 64, two LDS stages of K step 64 (rows of 128 B = whole cache
+// lines, 64 KB in all, two workgroups per CU).  Same per-tile protocol as gemm_mfma256w8_kernel:
+// k-steps 0..2, wait for the next tile + barrier, k-step 3 while the loads of the tile after next
+// are issued into the stage just freed.
+template <int EPI>
+__global__ __launch_bounds__(256, 2) void gemm_mfma128k64_kernel(const bf16_t* __restrict__ A,
+                                                                 const bf16_t* __restrict__ W,
+                                                                 const bf16_t* __restrict__ bias, const float* res,
+                                                                 typename OutType<bf16_t, EPI>::type* Y, int64_t M,
+                                                                 int N, int K, int tiles_m, int tiles_n) {
+  constexpr int BM = 128, BN = 128, BK = 64, WM = 64, WN = 64, TM = 2, TN = 2;
+  constexpr int STAGE = BM * BK;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [2][128][64]
+  bf16_t* Ws = As + 2 * STAGE;                    // [2][128][64]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  const int64_t m0 = (int64_t)tile_m * BM;
+  const int n0 = tile_n * BN;
+
+  // wave w owns rows w*32 .. w*32+31 of each operand tile, 8 rows (of 128 B) per instruction
+  const bf16_t* a_src[4];
+  const bf16_t* w_src[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int row = wave * 32 + j * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((row >> 1) & 7);
+    int64_t ra = m0 + row;
+    ra = ra < M ? ra : M - 1;
+    int rw = n0 + row;
+    rw = rw < N ? rw : N - 1;
+    a_src[j] = A + (size_t)ra * K + c * 8;
+    w_src[j] = W + (size_t)rw * K + c * 8;
+  }
+  const int KT = K / BK;
+  auto dma_one = [&](int kt, int st, int d) {   // d = 0..7
+    const int k = (kt < KT ? kt : KT - 1) * BK;
+    const int j = d >> 1;
+    if ((d & 1) == 0)
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_src[j] + k), OTAS_LPTR(As + st * STAGE + (wave * 32 + j * 8) * BK),
+                                       16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_src[j] + k), OTAS_LPTR(Ws + st * STAGE + (wave * 32 + j * 8) * BK),
+                                       16, 0, 0);
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int fr = lane & 31, fk = lane >> 5;
+  const int frag_row = fr * BK, sw = (fr >> 1) & 7;
+  bf16x8 af[2][TM], wf[2][TN];
+  auto read_frag = [&](int st, int ks, int slot, int f) {   // f = 0,1: A tiles; 2,3: W tiles
+    const int c = (((ks << 1) + fk) ^ sw) * 8;
+    if (f < TM)
+      af[slot][f] = *reinterpret_cast<const bf16x8*>(As + st * STAGE + (wm * WM + f * 32) * BK + frag_row + c);
+    else
+      wf[slot][f - TM] =
+          *reinterpret_cast<const bf16x8*>(Ws + st * STAGE + (wn * WN + (f - TM) * 32) * BK + frag_row + c);
+  };
+  auto mfma_one = [&](int slot, int t) {
+    const int i = t / TN, j = t % TN;
+    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
+  };
+  auto kstep = [&](int slot, int st_next, int ks_next) {   // 4 MFMAs, the next k-step's 4 fragments in between
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      mfma_one(slot, t);
+      read_frag(st_next, ks_next, slot ^ 1, t);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+
+#pragma unroll
+  for (int d = 0; d < 8; ++d) dma_one(0, 0, d);
+#pragma unroll
+  for (int d = 0; d < 8; ++d) dma_one(1, 1, d);
+  OTAS_VMCNT(8);
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+#pragma unroll
+  for (int f = 0; f < TM + TN; ++f) read_frag(0, 0, 0, f);
+
+  for (int kt = 0; kt < KT; ++kt) {
+    const int st = kt & 1;
+    kstep(0, st, 1);
+    kstep(1, st, 2);
+    kstep(0, st, 3);
+    OTAS_VMCNT(0);    // tile kt+1 landed
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {   // k-step 3: first fragments of tile kt+1, loads of tile kt+2
+      mfma_one(1, t);
+      read_frag(st ^ 1, 0, 0, t);
+      dma_one(kt + 2, st, 2 * t);
+      dma_one(kt + 2, st, 2 * t + 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  OTAS_VMCNT(0);
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
+                             m0 + wm * WM, n0 + wn * WN, lane);
+}
+
+static hipError_t linear_mfma128k64(const void* x, const void* w, const void* bias, const float* res, void* y,
+                                    int64_t M, int N, int K, int epi, hipStream_t s) {
+  const int tiles_m = (int)((M + 127) / 128), tiles_n = (N + 127) / 128;
+  const size_t lds = (size_t)2 * 2 * 128 * 64 * sizeof(bf16_t);
+  dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
+#define OTAS_MFMA(E)                                                                                              \
+  do {                                                                                                            \
+    auto kern = gemm_mfma128k64_kernel<E>;                                                                        \
     static bool attr = false;                                                                                     \
     if (!attr) {                                                                                                  \
       hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
@@ -651,7 +811,7 @@ static hipError_t linear_mfma(const void* x, const void* w, const void* bias, co
     return e ? std::atoi(e) : 0;
   }();
   int variant = g_gemm_variant ? g_gemm_variant : env_variant;
-  if (K % 32 != 0 || K < 64) variant = 1;
+  if (K % 64 != 0 || K < 128) variant = (K % 32 == 0 && K >= 64 && (variant == 0 || variant == 5)) ? 5 : 1;
   if (variant == 0) {
     const double t128 = (double)((M + 127) / 128) * ((N + 127) / 128);
     const double t256 = (double)((M + 255) / 256) * ((N + 255) / 256);
@@ -660,10 +820,16 @@ static hipError_t linear_mfma(const void* x, const void* w, const void* bias, co
     const double c128 = std::max(10.0 + 0.0107 * K, t128 * a);
     const double c256 = r * std::ceil(t256 / 256.0);
     variant = c256 < c128 ? 7 : 5;
+    // Among the 128 x 128 kernels the K-step-64 one (whole cache lines per row, two workgroups per
+    // CU) measured faster in place for the plain-epilogue and the long-K residual shapes once a few
+    // hundred tiles are in flight; the K-step-32 one (three workgroups per CU) elsewhere.
+    if (variant == 5 && K % 64 == 0 && t128 >= 300 && (epi == EPI_NONE || (epi == EPI_RESIDUAL && K >= 2048)))
+      variant = 9;
   }
   switch (variant) {
     case 5: return linear_mfma128_dma<3>(x, w, bias, res, y, M, N, K, epi, s);
     case 7: return linear_mfma256w8(x, w, bias, res, y, M, N, K, epi, s);
+    case 9: return linear_mfma128k64(x, w, bias, res, y, M, N, K, epi, s);
     default: return linear_mfma_tile<128, 128, 2, 2>(x, w, bias, res, y, M, N, K, epi, s);
   }
 }
