@@ -21,47 +21,10 @@ template <typename T> struct alignas(4 * sizeof(T)) Quad { T x[4]; };   // 4 con
 
 // LDS layout of the plan kernel (4-byte words), n = query length, nA = ceil(n/2), nB = floor(n/2):
 //   mh [n][dm+4] normalised metric rows | best [nA] | bcol [nA] | merged [nA] | cnt [nB] |
-//   keep_pos [n] | ent_pos [n] | wave_tot [2][16]
+//   keep_pos [n] | ent_pos [n] | wave_tot [2][16] | part_v [512] | part_c [512]
 size_t merge_plan_lds_bytes(int max_n, int dm) {
   const size_t nA = (max_n + 1) / 2, nB = max_n / 2;
-  return sizeof(float) * ((size_t)max_n * (dm + 4) + 3 * nA + nB + 2 * (size_t)max_n + 32 + 8);
-}
-
-// Similarity row of one A token against a strided subset of the B tokens.  The A row sits in
-// registers (DM4 float4), the B rows are read from LDS as float4 (lanes that share a B row share
-// the read).  The dot product always runs c = 0..dm-1 in one fp32 fma chain, whatever the thread
-// mapping, so the decision does not depend on the launch shape.
-template <int DM4>
-__device__ inline void best_of_subset(const float* __restrict__ mh, int ldm, int a, int part, int nB, float& bv,
-                                      int& bc) {
-  floatx4 av[DM4];
-  const float* pa = mh + (size_t)(2 * a) * ldm;
-#pragma unroll
-  for (int c = 0; c < DM4; ++c) av[c] = *reinterpret_cast<const floatx4*>(pa + 4 * c);
-  for (int b = part; b < nB; b += 8) {
-    const float* pb = mh + (size_t)(2 * b + 1) * ldm;
-    float s = 0.f;
-#pragma unroll
-    for (int c = 0; c < DM4; ++c) {
-      const floatx4 v = *reinterpret_cast<const floatx4*>(pb + 4 * c);
-      s = fmaf(av[c][0], v[0], s);
-      s = fmaf(av[c][1], v[1], s);
-      s = fmaf(av[c][2], v[2], s);
-      s = fmaf(av[c][3], v[3], s);
-    }
-    if (s > bv) { bv = s; bc = b; }   // strict '>' walking upwards: lowest column among equal maxima
-  }
-}
-
-__device__ inline void best_of_subset_any(const float* __restrict__ mh, int ldm, int dm, int a, int part, int nB,
-                                          float& bv, int& bc) {
-  const float* pa = mh + (size_t)(2 * a) * ldm;
-  for (int b = part; b < nB; b += 8) {
-    const float* pb = mh + (size_t)(2 * b + 1) * ldm;
-    float s = 0.f;
-    for (int c = 0; c < dm; ++c) s = fmaf(pa[c], pb[c], s);
-    if (s > bv) { bv = s; bc = b; }
-  }
+  return sizeof(float) * ((size_t)max_n * (dm + 4) + 3 * nA + nB + 2 * (size_t)max_n + 32 + 8 + 2 * 512);
 }
 
 // One workgroup of 1024 threads per query.  src: the vectors the similarity is taken on; the metric
@@ -104,6 +67,7 @@ __global__ __launch_bounds__(kPlanThreads) void merge_plan_kernel(
     const int i = t / c4n, c = (t - i * c4n) * 4;
     const T* p = src + (size_t)(i0 + i) * row_stride + col_off + c;
     float m0 = 0.f, m1 = 0.f, m2 = 0.f, m3 = 0.f;
+#pragma unroll 4
     for (int h = 0; h < H; ++h) {
       const Quad<T> v = *reinterpret_cast<const Quad<T>*>(p);
       m0 += to_float(v.x[0]); m1 += to_float(v.x[1]); m2 += to_float(v.x[2]); m3 += to_float(v.x[3]);
@@ -113,63 +77,122 @@ __global__ __launch_bounds__(kPlanThreads) void merge_plan_kernel(
     *reinterpret_cast<floatx4*>(mh + (size_t)i * ldm + c) = o;
   }
   __syncthreads();
-  // Phase 1: unit length (one thread per row, columns in ascending order)
-  for (int i = tid; i < n; i += kPlanThreads) {
-    float* r = mh + (size_t)i * ldm;
+  // Phase 1: unit length.  4 consecutive lanes share a row: lane j sums the squares of columns
+  // j, j+4, ... in ascending order, the four partial sums are added by a fixed butterfly.
+  for (int i0r = 0; i0r < n; i0r += kPlanThreads / 4) {
+    const int i = i0r + (tid >> 2), j = tid & 3;
     float ss = 0.f;
-    for (int c = 0; c < dm; ++c) ss = fmaf(r[c], r[c], ss);
+    float* r = mh + (size_t)min(i, n - 1) * ldm;
+    for (int c = j; c < dm; c += 4) ss = fmaf(r[c], r[c], ss);
+    ss += __shfl_xor(ss, 1, kWave);
+    ss += __shfl_xor(ss, 2, kWave);
     const float rn = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
-    for (int c = 0; c < dm; ++c) r[c] *= rn;
+    if (i < n)
+      for (int c = j; c < dm; c += 4) r[c] *= rn;
   }
   __syncthreads();
 
-  // Phase 2: every A token picks its most similar B token.  8 consecutive lanes share an A row and
-  // split the B columns (b = part, part + 8, ...); their results are combined by shuffles, ties to
-  // the lowest column.
-  const int part = tid & 7;
-  for (int a0 = 0; a0 < nA; a0 += kPlanThreads / 8) {
-    const int a = a0 + (tid >> 3);
-    float bv = -INFINITY;
-    int bc = 0x7fffffff;
-    if (a < nA) {
-      if (dm == 64) best_of_subset<16>(mh, ldm, a, part, nB, bv, bc);
-      else if (dm == 80) best_of_subset<20>(mh, ldm, a, part, nB, bv, bc);
-      else best_of_subset_any(mh, ldm, dm, a, part, nB, bv, bc);
-    }
+  // Phase 2: every A token picks its most similar B token.  The similarity matrix is a dense
+  // contraction over the metric width, done on the matrix cores in true fp32
+  // (v_mfma_f32_32x32x2_f32), transposed: B tokens are the first operand (rows), A tokens the second
+  // (columns), so a lane owns ONE A token and holds 16 of a 32-token B block's similarities in its
+  // accumulator (rows 8 (e / 4) + 4 (lane >> 5) + (e & 3)): its arg-max is a scan of its own registers
+  // in ascending B order plus one exchange with lane ^ 32.  Wave w owns A block w % nAb and every
+  // G-th B block; the G partial results per A token are combined through LDS.  Ties go to the
+  // lowest B position at every step.
+  const int nAb = (nA + 31) >> 5, nBb = (nB + 31) >> 5;
+  const int G = max(1, 16 / nAb);
+  int* part_c = wave_tot + 32;
+  float* part_v = reinterpret_cast<float*>(part_c + 512);
+  {
+    const int lane = tid & 63, w = tid >> 6;
+    const int fr = lane & 31, fk = lane >> 5;
+    for (int ab = w % nAb, grp = w / nAb; grp < G; grp = G) {   // one (A block, B group) per wave
+      const int a = ab * 32 + fr;
+      const float* pa = mh + (size_t)(2 * min(a, nA - 1)) * ldm + fk;
+      float bv = -INFINITY;
+      int bc = 0x7fffffff;
+      for (int bb = grp; bb < nBb; bb += G) {
+        const float* pb = mh + (size_t)(2 * min(bb * 32 + fr, nB - 1) + 1) * ldm + fk;
+        floatx16 acc;
 #pragma unroll
-    for (int o = 4; o > 0; o >>= 1) {
-      const float v = __shfl_xor(bv, o, kWave);
-      const int c = __shfl_xor(bc, o, kWave);
+        for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+        for (int k0 = 0; k0 < dm; k0 += 16) {   // 8 MFMAs per batch, their 16 operand reads issued first
+          float ra[8], rb[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int k = min(k0 + 2 * u, dm - 2);
+            ra[u] = pa[k];
+            rb[u] = pb[k];
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u)
+            if (k0 + 2 * u < dm) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(rb[u], ra[u], acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int b = bb * 32 + 8 * (e >> 2) + 4 * fk + (e & 3);
+          if (b < nB && acc[e] > bv) { bv = acc[e]; bc = b; }
+        }
+      }
+      const float ov = __shfl_xor(bv, 32, kWave);
+      const int oc = __shfl_xor(bc, 32, kWave);
+      if (ov > bv || (ov == bv && oc < bc)) { bv = ov; bc = oc; }
+      if (fk == 0) {
+        part_v[grp * (nAb * 32) + a] = bv;
+        part_c[grp * (nAb * 32) + a] = bc;
+      }
+    }
+  }
+  __syncthreads();
+  for (int a = tid; a < nA; a += kPlanThreads) {
+    float bv = part_v[a];
+    int bc = part_c[a];
+    for (int g = 1; g < G; ++g) {
+      const float v = part_v[g * (nAb * 32) + a];
+      const int c = part_c[g * (nAb * 32) + a];
       if (v > bv || (v == bv && c < bc)) { bv = v; bc = c; }
     }
-    if (a < nA && part == 0) {
-      best[a] = (2 * a < n_lead) ? -INFINITY : bv;   // protected leading token: never a merge source
-      bcol[a] = bc;
-    }
+    best[a] = (2 * a < n_lead) ? -INFINITY : bv;   // protected leading token: never a merge source
+    bcol[a] = bc;
   }
   __syncthreads();
 
   // Phase 3: keep the r_eff best edges.  rank = number of A tokens that come before this one in
-  // (similarity descending, position ascending) order.
-  for (int a = tid; a < nA; a += kPlanThreads) {
+  // (similarity descending, position ascending) order; 8 consecutive lanes share an A token and
+  // split the tokens it is compared with.  slot = number of kept edges with the same destination
+  // and a lower source position (the order of a destination's source list).
+  for (int b = tid; b < nB; b += kPlanThreads) cnt[b] = 0;
+  for (int a0 = 0; a0 < nA; a0 += kPlanThreads / 8) {
+    const int a = min(a0 + (tid >> 3), nA - 1), part = tid & 7;
     const float v = best[a];
     int rank = 0;
-    for (int k = 0; k < nA; ++k) {
+    for (int k = part; k < nA; k += 8) {
       const float u = best[k];
       rank += (u > v || (u == v && k < a)) ? 1 : 0;
     }
-    const int m = rank < r_eff ? 1 : 0;
-    merged[a] = m;
-    if (m && trace_src) {
+    rank += __shfl_xor(rank, 1, kWave);
+    rank += __shfl_xor(rank, 2, kWave);
+    rank += __shfl_xor(rank, 4, kWave);
+    if (part == 0 && a0 + (tid >> 3) < nA) merged[a] = rank < r_eff ? 1 : 0;
+    if (part == 0 && a0 + (tid >> 3) < nA && rank < r_eff && trace_src) {
       trace_src[troff[q] + rank] = 2 * a;
       trace_dst[troff[q] + rank] = 2 * bcol[a] + 1;
     }
   }
   __syncthreads();
-  for (int b = tid; b < nB; b += kPlanThreads) {
-    int c = 0;
-    for (int a = 0; a < nA; ++a) c += (merged[a] && bcol[a] == b) ? 1 : 0;
-    cnt[b] = c;
+  for (int a0 = 0; a0 < nA; a0 += kPlanThreads / 8) {
+    const int a = min(a0 + (tid >> 3), nA - 1), part = tid & 7;
+    const int dst = bcol[a];
+    int slot = 0;
+    for (int k = part; k < a; k += 8) slot += (merged[k] && bcol[k] == dst) ? 1 : 0;
+    slot += __shfl_xor(slot, 1, kWave);
+    slot += __shfl_xor(slot, 2, kWave);
+    slot += __shfl_xor(slot, 4, kWave);
+    if (part == 0 && a0 + (tid >> 3) < nA && merged[a]) {
+      atomicAdd(&cnt[dst], 1);      // integer count: the result does not depend on the order
+      best[a] = __int_as_float(slot);   // best is dead from here on: reuse it for the slot
+    }
   }
   __syncthreads();
 
@@ -200,18 +223,17 @@ __global__ __launch_bounds__(kPlanThreads) void merge_plan_kernel(
   }
   __syncthreads();
 
-  // Phase 5: write the lists.
+  // Phase 5: write the lists: every surviving row opens its list with itself, every merged A token
+  // enters its destination's list at its slot.
   for (int i = tid; i < n; i += kPlanThreads) {
     const bool odd = i & 1;
-    if (!odd && merged[i >> 1]) continue;
-    const int e = i0 + ent_pos[i];
-    row_ptr[o0 + keep_pos[i]] = e;
-    src_list[e] = i0 + i;
-    if (odd && cnt[i >> 1] > 0) {
-      const int b = i >> 1;
-      int k = 1;
-      for (int a = 0; a < nA; ++a)
-        if (merged[a] && bcol[a] == b) src_list[e + k++] = i0 + 2 * a;
+    if (!odd && merged[i >> 1]) {
+      const int a = i >> 1, d = 2 * bcol[a] + 1;
+      src_list[i0 + ent_pos[d] + 1 + __float_as_int(best[a])] = i0 + i;
+    } else {
+      const int e = i0 + ent_pos[i];
+      row_ptr[o0 + keep_pos[i]] = e;
+      src_list[e] = i0 + i;
     }
   }
 }
