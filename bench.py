@@ -96,12 +96,14 @@ def run_strategy(name, steps, warmup, timing_steps):
     for _ in range(timing_steps):
         step()
     kt = ctx.otas_timing_read()
+    ev_overhead_us = ctx.otas_timing_overhead_ms() * 1e3
     ctx.otas_timing_enable(False)
     per_step = {k: (v[0] / timing_steps, v[1] // timing_steps) for k, v in kt.items()}
     work = algorithmic_work(cfg, lengths0, R, otas)
     assert torch.isfinite(x_out.float()).all()
     ctx.close()
-    return {"name": name, "cfg": cfg, "ms": ms, "img_s": cfg.B / (ms * 1e-3), "kernels": per_step, "work": work}
+    return {"name": name, "cfg": cfg, "ms": ms, "img_s": cfg.B / (ms * 1e-3), "kernels": per_step, "work": work,
+            "ev_overhead_us": ev_overhead_us}
 
 
 def measured_traffic(workload):
@@ -152,6 +154,7 @@ def rooflines(res):
         if k[n][1] > 0:
             out[n] = {"avg_launch_us": round(k[n][0] * 1e3 / k[n][1], 2), "launches_per_step": k[n][1]}
     out["kernel_ms_per_step"] = {n: round(v[0], 4) for n, v in k.items()}
+    out["event_pair_overhead_us_subtracted"] = round(res["ev_overhead_us"], 2)
     return out
 
 

@@ -95,6 +95,23 @@ otas_status otas_destroy(otas_ctx *ctx);
 otas_status otas_schedule(int32_t n0, int32_t P, int32_t r, int32_t n_lead, int32_t L,
                           int32_t *len_out);
 
+/* Split factor the encoder uses for the MLP's second linear (y = x W^T, x [M, K], W [N, K]) of a
+ * bf16 model: 1 = one kernel with the residual epilogue; S > 1 = S partial products over K / S
+ * each, added in split order by a second kernel that also applies the next block's first
+ * LayerNorm (so that block launches no LayerNorm kernel of its own).  Pure host function; lets a
+ * caller account for which kernels a forward pass launches. */
+int32_t otas_splitk_factor(const otas_ctx *ctx, int64_t M, int32_t N, int32_t K);
+
+/* Lanes.  otas_encoder_forward and otas_encoder_layers may cut the batch into up to 8 lanes,
+ * contiguous query ranges with about equal token counts, and run them side by side: lane 0 on
+ * the context's stream, the others on streams the context owns (default priority), forked from
+ * the context's stream at the start of the call and joined into it before the call returns, so
+ * the caller sees ordinary stream order.  Queries are independent (Sec. III-B: a batch is a set of
+ * queries, each with its own strategy), so results do not depend on the lane count.  lanes = 0
+ * (the default; the environment variable OTAS_LANES overrides it at otas_create) lets the
+ * library choose from the batch size; 1 runs the whole batch as one sequence of launches. */
+otas_status otas_set_lanes(otas_ctx *ctx, int32_t lanes);
+
 /* Bytes of device workspace otas_encoder_forward needs for B queries with T0 packed tokens in
  * total (pure host).  Returns 0 on invalid arguments. */
 size_t otas_workspace_bytes(const otas_ctx *ctx, int32_t B, int64_t T0);
@@ -185,11 +202,14 @@ otas_status otas_attention(otas_ctx *ctx, const void *qkv, const int32_t *sizes,
  * every later launch of this context record an event before and after itself;
  * otas_timing_read waits for the stream, returns for each kind 0 .. otas_timing_kinds()-1 the summed
  * milliseconds and the number of launches since the last read, and clears the records.
+ * Enabling also measures what an event pair reads around an empty (one-element) launch -- median of
+ * 15, otas_timing_overhead_ms -- and every record is reported net of that overhead.
  * total_ms / launches: host arrays of otas_timing_kinds() entries.  Off by default. */
 otas_status otas_timing_enable(otas_ctx *ctx, int32_t on);
 int32_t otas_timing_kinds(void);
 const char *otas_timing_kind_name(int32_t kind);
 otas_status otas_timing_read(otas_ctx *ctx, double *total_ms, int64_t *launches);
+float otas_timing_overhead_ms(const otas_ctx *ctx);
 /* The same records one by one, in launch order, without clearing them: kind and milliseconds of up
  * to cap launches into the host arrays; returns the number of records held (-1 on error). */
 int32_t otas_timing_read_launches(otas_ctx *ctx, int32_t cap, int32_t *kinds, float *ms);

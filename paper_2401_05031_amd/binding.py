@@ -74,6 +74,9 @@ def load_library():
         "otas_timing_kind_name": (C.c_char_p, [i32]),
         "otas_timing_read": (i32, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
         "otas_timing_read_launches": (i32, [vp, i32, _I32P, C.POINTER(C.c_float)]),
+        "otas_timing_overhead_ms": (C.c_float, [vp]),
+        "otas_set_lanes": (i32, [vp, i32]),
+        "otas_splitk_factor": (i32, [vp, C.c_int64, i32, i32]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)          # AttributeError if a declared symbol is not exported
@@ -86,7 +89,7 @@ EXPORTED = ("otas_create", "otas_destroy", "otas_schedule", "otas_workspace_byte
             "otas_merge_workspace_bytes", "otas_prompt_prepend", "otas_token_merge",
             "otas_encoder_forward", "otas_encoder_layers", "otas_layer_norm", "otas_linear", "otas_attention", "otas_strerror",
             "otas_timing_enable", "otas_timing_kinds", "otas_timing_kind_name", "otas_timing_read",
-            "otas_timing_read_launches")
+            "otas_timing_read_launches", "otas_timing_overhead_ms", "otas_set_lanes", "otas_splitk_factor")
 
 
 def otas_strerror(status: int) -> str:
@@ -233,6 +236,15 @@ class Context:
         cnt = (C.c_int64 * k)()
         _check(self._lib.otas_timing_read(self._h, ms, cnt), "otas_timing_read")
         return {self._lib.otas_timing_kind_name(i).decode(): (ms[i], int(cnt[i])) for i in range(k)}
+
+    def otas_splitk_factor(self, M: int, N: int, K: int) -> int:
+        return int(self._lib.otas_splitk_factor(self._h, int(M), int(N), int(K)))
+
+    def otas_set_lanes(self, lanes: int) -> None:
+        _check(self._lib.otas_set_lanes(self._h, int(lanes)), "otas_set_lanes")
+
+    def otas_timing_overhead_ms(self) -> float:
+        return float(self._lib.otas_timing_overhead_ms(self._h))
 
     def otas_timing_read_launches(self, cap: int = 65536):
         """[(kind name, ms)] of the recorded launches in launch order (records are kept)."""

@@ -5,6 +5,8 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -19,6 +21,8 @@ namespace {
 constexpr size_t kAlign = 256;
 constexpr int64_t kRowPad = 256;              // activation buffers are padded to this many rows
 constexpr size_t kPlanInts = (size_t)1 << 20;  // capacity of the device plan buffer (int32 entries)
+constexpr int kMaxLanes = 8;
+constexpr int kPartRows = 2;   // split-K workspace: this many float rows of width D per token row
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int removal_count(int n, int r, int n_lead) { return std::max(0, std::min(r, (n - n_lead) / 2)); }
@@ -38,10 +42,19 @@ struct otas_ctx {
   // The merge plan of a layer needs only that layer's keys (the QKV projection), so it runs on a
   // second stream next to attention and the output projection: forked after the QKV GEMM, joined
   // before merge-apply.
-  hipStream_t side;
-  hipEvent_t ev_fork, ev_join;
+  // A forward pass may also be cut into lanes (contiguous query ranges) that run side by side on
+  // streams of their own, so that one lane's launch gaps, partial waves and latency-bound small
+  // kernels overlap another lane's work.  Lane 0 runs on the caller's stream.
+  struct Lane {
+    hipStream_t main, side;
+    hipEvent_t ev_fork, ev_join, ev_done;
+  };
+  Lane lane[8];
+  hipEvent_t ev_begin;
+  int lanes;   // requested lane count, 0 = chosen from the batch size
   // optional per-launch timing (otas_timing_enable): one event pair per launch, summed per kind
   bool timing;
+  float ev_overhead_ms;   // what an event pair reads around an empty launch (subtracted from every record)
   std::vector<hipEvent_t> ev_pool;
   std::vector<int> ev_kind;   // kind of the launch bracketed by ev_pool[2i], ev_pool[2i+1]
 };
@@ -73,7 +86,7 @@ otas_status upload_plan(otas_ctx* c, const std::vector<int32_t>& host) {
 }
 
 struct WorkspaceLayout {
-  size_t xa, xb, h, qkv, hid, sizes_a, sizes_b, src_list, row_ptr, total;
+  size_t xa, xb, h, qkv, hid, part, sizes_a, sizes_b, src_list, row_ptr, total;
 };
 
 WorkspaceLayout forward_layout(const otas_model_desc& d, int64_t T0) {
@@ -87,22 +100,32 @@ WorkspaceLayout forward_layout(const otas_model_desc& d, int64_t T0) {
   w.h = take(rows * d.D * es);
   w.qkv = take(rows * 3 * d.D * es);
   w.hid = take(rows * d.F * es);
+  w.part = take(d.dtype == OTAS_BF16 ? kPartRows * rows * d.D * sizeof(float) : 0);   // split-K partial products
   w.sizes_a = take(rows * sizeof(int32_t));
   w.sizes_b = take(rows * sizeof(int32_t));
   w.src_list = take(rows * sizeof(int32_t));
-  w.row_ptr = take((rows + 1) * sizeof(int32_t));
+  w.row_ptr = take((rows + kMaxLanes + 1) * sizeof(int32_t));   // one end entry per lane
   w.total = p;
   return w;
 }
 
-#define OTAS_HIP(expr)                         \
-  do {                                         \
-    if ((expr) != hipSuccess) return OTAS_EDEVICE; \
+// A failing HIP call maps to OTAS_EDEVICE; with OTAS_DEBUG set in the environment it is also named
+// on stderr.
+inline bool hip_ok(hipError_t e, const char* what) {
+  if (e == hipSuccess) return true;
+  static const bool verbose = std::getenv("OTAS_DEBUG") != nullptr;
+  if (verbose) std::fprintf(stderr, "otas: %s -> %s\n", what, hipGetErrorString(e));
+  return false;
+}
+#define OTAS_HIP(expr)                              \
+  do {                                              \
+    if (!hip_ok((expr), #expr)) return OTAS_EDEVICE; \
   } while (0)
 
-enum Kind { K_PREPEND = 0, K_LN, K_QKV, K_ATTN, K_PROJ, K_PLAN, K_APPLY, K_FC1, K_FC2, K_MISC, K_COUNT };
+enum Kind { K_PREPEND = 0, K_LN, K_QKV, K_ATTN, K_PROJ, K_PLAN, K_APPLY, K_FC1, K_FC2, K_REDUCE, K_MISC, K_COUNT };
 const char* const kKindNames[K_COUNT] = {"prompt_prepend", "layer_norm", "gemm_qkv", "attention", "gemm_proj",
-                                         "merge_plan", "merge_apply", "gemm_fc1", "gemm_fc2", "misc"};
+                                         "merge_plan", "merge_apply", "gemm_fc1", "gemm_fc2", "splitk_reduce_ln",
+                                         "misc"};
 
 // Brackets one launch with an event pair when timing is on.
 struct LaunchTimer {
@@ -189,17 +212,26 @@ otas_status otas_create(otas_ctx** out, const otas_model_desc* desc, const otas_
   c->h_used[0] = c->h_used[1] = false;
   c->h_next = 0;
   c->timing = false;
-  c->side = nullptr;
-  c->ev_fork = c->ev_join = nullptr;
+  c->ev_overhead_ms = 0.f;
+  std::memset(c->lane, 0, sizeof(c->lane));
+  c->ev_begin = nullptr;
+  c->lanes = 0;
+  if (const char* e = std::getenv("OTAS_LANES")) c->lanes = std::max(0, std::min(kMaxLanes, std::atoi(e)));
   bool ok = hipGetDevice(&c->device) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->d_plan, kPlanInts * sizeof(int32_t)) == hipSuccess;
   for (int i = 0; i < 2 && ok; ++i) {
     ok = hipHostMalloc((void**)&c->h_plan[i], kPlanInts * sizeof(int32_t), hipHostMallocDefault) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&c->h_done[i], hipEventDisableTiming) == hipSuccess;
   }
-  ok = ok && hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) == hipSuccess;   // default priority
-  ok = ok && hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess;
-  ok = ok && hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&c->ev_begin, hipEventDisableTiming) == hipSuccess;
+  for (int g = 0; g < kMaxLanes && ok; ++g) {   // every stream at the default priority
+    otas_ctx::Lane& ln = c->lane[g];
+    if (g > 0) ok = hipStreamCreateWithFlags(&ln.main, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&ln.side, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ln.ev_fork, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ln.ev_join, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ln.ev_done, hipEventDisableTiming) == hipSuccess;
+  }
   if (!ok) {
     otas_destroy(c);
     return OTAS_EDEVICE;
@@ -211,12 +243,15 @@ otas_status otas_create(otas_ctx** out, const otas_model_desc* desc, const otas_
 otas_status otas_destroy(otas_ctx* c) {
   if (!c) return OTAS_OK;
   if (c->stream || c->d_plan) (void)hipStreamSynchronize(c->stream);
-  if (c->side) {
-    (void)hipStreamSynchronize(c->side);
-    (void)hipStreamDestroy(c->side);
+  for (int g = 0; g < kMaxLanes; ++g) {
+    otas_ctx::Lane& ln = c->lane[g];
+    if (ln.main) { (void)hipStreamSynchronize(ln.main); (void)hipStreamDestroy(ln.main); }
+    if (ln.side) { (void)hipStreamSynchronize(ln.side); (void)hipStreamDestroy(ln.side); }
+    if (ln.ev_fork) (void)hipEventDestroy(ln.ev_fork);
+    if (ln.ev_join) (void)hipEventDestroy(ln.ev_join);
+    if (ln.ev_done) (void)hipEventDestroy(ln.ev_done);
   }
-  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
-  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+  if (c->ev_begin) (void)hipEventDestroy(c->ev_begin);
   for (int i = 0; i < 2; ++i) {
     if (c->h_done[i]) (void)hipEventDestroy(c->h_done[i]);
     if (c->h_plan[i]) (void)hipHostFree(c->h_plan[i]);
@@ -344,6 +379,25 @@ otas_status otas_encoder_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_
 }  // extern "C"
 
 namespace {
+
+// One lane's share of a forward pass: a contiguous range of queries that runs through the layers on
+// its own stream, in its own rows of every workspace buffer, next to the other lanes.
+struct LaneRun {
+  int q0, q1, Bg;
+  size_t plan_base;              // first entry of this lane's plan in the device plan buffer
+  int64_t row0;                  // first packed row of the lane at the input (its rows in every buffer)
+  int64_t rowL;                  // first packed row of the lane in the output
+  std::vector<int64_t> T;        // packed rows of the lane entering layer l (l = 0 .. L)
+  std::vector<int> max_n;        // longest query entering layer l
+  std::vector<char> any_merge;
+  int last_merge;
+  // running state
+  const int32_t* sizes_now;
+  const void* x_cur;
+  bool x_owned;
+  bool ln1_done;   // the previous block's split-K reduce already wrote this block's LN1 output
+};
+
 otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, const void* x0, bool x0_is_float,
                        const int32_t* sizes_in, const int32_t* offsets, const int32_t* r, int32_t B, uint32_t flags,
                        void* workspace, size_t workspace_bytes, void* x_out, int32_t* sizes_out,
@@ -369,130 +423,228 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
     if (xo >= ws && xo < ws + w.total) return OTAS_EINVAL;
   }
 
-  // Host plan.  Layout (int32): off[l][B+1] for l = 0..L | r_eff[l][B] | trace_off[l][B].
-  const size_t o_off = 0, o_reff = (size_t)(L + 1) * (B + 1), o_tr = o_reff + (size_t)L * B;
-  std::vector<int32_t> plan(o_tr + (size_t)L * B);
-  std::vector<int> max_n(L + 1, 0);
-  std::vector<char> any_merge(L, 0);
-  std::vector<int> len(B);
-  plan[0] = 0;
+  // Schedule of the whole batch: lengths entering every layer, removal counts, and where each
+  // (layer, query) starts in the trace (layer-major, then query).
+  std::vector<int> len((size_t)(L + 1) * B), reff((size_t)L * B), troff((size_t)L * B);
   for (int q = 0; q < B; ++q) {
-    len[q] = offsets[q + 1] - offsets[q];
-    if (r[q] < 0 || len[q] <= 0 || len[q] < n_lead) return OTAS_EINVAL;
-    if (len[q] > OTAS_MAX_SEQ) return OTAS_EUNSUPPORTED;
-    plan[o_off + q + 1] = offsets[q + 1];
-    max_n[0] = std::max(max_n[0], len[q]);
+    const int n = offsets[q + 1] - offsets[q];
+    if (r[q] < 0 || n <= 0 || n < n_lead) return OTAS_EINVAL;
+    if (n > OTAS_MAX_SEQ) return OTAS_EUNSUPPORTED;
+    len[q] = n;
   }
   int tr = 0;
   for (int l = 0; l < L; ++l) {
-    int32_t* off_next = &plan[o_off + (size_t)(l + 1) * (B + 1)];
-    off_next[0] = 0;
+    int mx = 0;
+    bool any = false;
     for (int q = 0; q < B; ++q) {
-      const int k = removal_count(len[q], r[q], n_lead);
-      plan[o_reff + (size_t)l * B + q] = k;
-      plan[o_tr + (size_t)l * B + q] = tr;
+      const int n = len[(size_t)l * B + q];
+      const int k = removal_count(n, r[q], n_lead);
+      reff[(size_t)l * B + q] = k;
+      troff[(size_t)l * B + q] = tr;
       tr += k;
-      if (k > 0) any_merge[l] = 1;
-      len[q] -= k;
-      off_next[q + 1] = off_next[q] + len[q];
-      max_n[l + 1] = std::max(max_n[l + 1], len[q]);
+      any = any || k > 0;
+      mx = std::max(mx, n);
+      len[(size_t)(l + 1) * B + q] = n - k;
     }
-    if (any_merge[l] && merge_plan_lds_bytes(max_n[l], dh) > 160 * 1024) return OTAS_EUNSUPPORTED;
+    if (any && merge_plan_lds_bytes(mx, dh) > 160 * 1024) return OTAS_EUNSUPPORTED;
   }
-  std::memcpy(offsets_out, &plan[o_off + (size_t)L * (B + 1)], (B + 1) * sizeof(int32_t));
+  offsets_out[0] = 0;
+  for (int q = 0; q < B; ++q) offsets_out[q + 1] = offsets_out[q] + len[(size_t)L * B + q];
+
+  // Lanes: contiguous query ranges with about equal token counts.
+  int G = c->lanes > 0 ? c->lanes : 1;
+  G = std::max(1, std::min(std::min(G, (int)B), kMaxLanes));
+  std::vector<LaneRun> lanes(G);
+  {
+    int q = 0;
+    for (int g = 0; g < G; ++g) {
+      LaneRun& ln = lanes[g];
+      ln.q0 = q;
+      if (g == G - 1) q = B;
+      else {
+        const int64_t goal = T0 * (g + 1) / G;
+        ++q;
+        while (q < B - (G - 1 - g) && offsets[q] < goal) ++q;
+      }
+      ln.q1 = q;
+      ln.Bg = ln.q1 - ln.q0;
+      ln.row0 = offsets[ln.q0];
+      ln.rowL = offsets_out[ln.q0];
+    }
+  }
+  // Device plan.  Per lane (int32): off[l][Bg+1] for l = 0..L (relative to the lane's first row) |
+  // r_eff[l][Bg] | trace_off[l][Bg].
+  std::vector<int32_t> plan;
+  for (LaneRun& ln : lanes) {
+    const int Bg = ln.Bg;
+    ln.plan_base = plan.size();
+    plan.resize(ln.plan_base + (size_t)(L + 1) * (Bg + 1) + 2 * (size_t)L * Bg);
+    int32_t* off = &plan[ln.plan_base];
+    int32_t* pr = off + (size_t)(L + 1) * (Bg + 1);
+    int32_t* pt = pr + (size_t)L * Bg;
+    ln.T.assign(L + 1, 0);
+    ln.max_n.assign(L + 1, 0);
+    ln.any_merge.assign(L, 0);
+    ln.last_merge = -1;
+    for (int l = 0; l <= L; ++l) {
+      int32_t* o = off + (size_t)l * (Bg + 1);
+      o[0] = 0;
+      for (int j = 0; j < Bg; ++j) {
+        const int n = len[(size_t)l * B + ln.q0 + j];
+        o[j + 1] = o[j] + n;
+        ln.max_n[l] = std::max(ln.max_n[l], n);
+      }
+      ln.T[l] = o[Bg];
+      if (l < L)
+        for (int j = 0; j < Bg; ++j) {
+          const int k = reff[(size_t)l * B + ln.q0 + j];
+          pr[(size_t)l * Bg + j] = k;
+          pt[(size_t)l * Bg + j] = troff[(size_t)l * B + ln.q0 + j];
+          if (k > 0) { ln.any_merge[l] = 1; ln.last_merge = l; }
+        }
+    }
+  }
 
   if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
-  otas_status st = upload_plan(c, plan);
-  if (st != OTAS_OK) return st;
+
+  // Everything below the plan upload: the launches of all lanes, reading the plan at d_plan_base.
+  auto enqueue = [&](const int32_t* d_plan_base, hipStream_t s0) -> otas_status {
+  // Lanes beyond the first run on streams of their own, forked here and joined at the end.
+  if (G > 1) {
+    OTAS_HIP(hipEventRecord(c->ev_begin, s0));
+    for (int g = 1; g < G; ++g) OTAS_HIP(hipStreamWaitEvent(c->lane[g].main, c->ev_begin, 0));
+  }
 
   char* ws = (char*)workspace;
-  void* xa = ws + w.xa;
-  void* xb = ws + w.xb;
-  void* hbuf = ws + w.h;
-  void* qkv = ws + w.qkv;
-  void* hid = ws + w.hid;
-  int32_t* sizes_cur = (int32_t*)(ws + w.sizes_a);
-  int32_t* sizes_alt = (int32_t*)(ws + w.sizes_b);
-  int32_t* src_list = (int32_t*)(ws + w.src_list);
-  int32_t* row_ptr = (int32_t*)(ws + w.row_ptr);
-  const int32_t* dp = c->d_plan;
-  hipStream_t s = c->stream;
+  const size_t es = elem_size(d.dtype);
   const int dt = d.dtype;
   const bool size_bias = flags & OTAS_FLAG_SIZE_BIAS;
+  const size_t es_in = x0_is_float ? sizeof(float) : es;
 
   // Token sizes: nullptr stands for "all 1" until the first merge (or the caller's sizes_in), so no
-  // fill is needed; the last merging layer writes straight into sizes_out.
-  int32_t* sizes_buf[2] = {sizes_cur, sizes_alt};
-  const int32_t* sizes_now = sizes_in;
-  int last_merge = -1;
-  for (int l = 0; l < L; ++l)
-    if (any_merge[l]) last_merge = l;
-  if (size_bias && !sizes_now) {   // the attention bias reads sizes from the first layer on
-    OTAS_LAUNCH(K_MISC, launch_fill_i32(sizes_buf[0], 1, T0, s));
-    sizes_now = sizes_buf[0];
-  }
-  void* x_free[2] = {xa, xb};
-  const void* x_cur = x0;   // residual stream entering the block (float)
-  bool x_owned = false;     // x_cur is one of the workspace buffers, so it may be updated in place
-  if (!x0_is_float) {       // 16-bit tokens: widen once into the workspace
-    OTAS_LAUNCH(K_MISC, launch_widen(x0, (float*)xa, T0 * D, s));
-    x_cur = xa;
-    x_owned = true;
+  // fill is needed; a lane's last merging layer writes straight into sizes_out.
+  for (int g = 0; g < G; ++g) {
+    LaneRun& ln = lanes[g];
+    hipStream_t s = g == 0 ? s0 : c->lane[g].main;
+    ln.sizes_now = sizes_in ? sizes_in + ln.row0 : nullptr;
+    if (size_bias && !ln.sizes_now) {   // the attention bias reads sizes from the first layer on
+      int32_t* sz = (int32_t*)(ws + w.sizes_a) + ln.row0;
+      OTAS_LAUNCH_ON(K_MISC, s, launch_fill_i32(sz, 1, ln.T[0], s));
+      ln.sizes_now = sz;
+    }
+    ln.x_cur = (const char*)x0 + (size_t)ln.row0 * D * es_in;   // residual stream entering the block
+    ln.x_owned = false;   // x_cur is one of the workspace buffers, so it may be updated in place
+    ln.ln1_done = false;
+    if (!x0_is_float) {   // 16-bit tokens: widen once into the workspace
+      float* xa = (float*)(ws + w.xa) + (size_t)ln.row0 * D;
+      OTAS_LAUNCH_ON(K_MISC, s, launch_widen(ln.x_cur, xa, ln.T[0] * D, s));
+      ln.x_cur = xa;
+      ln.x_owned = true;
+    }
   }
   for (int l = 0; l < L; ++l) {
     const otas_layer_weights& wl = c->layers[layer_begin + l];
-    const int32_t* off_l = dp + o_off + (size_t)l * (B + 1);
-    const int32_t* off_n = dp + o_off + (size_t)(l + 1) * (B + 1);
-    const int64_t T = plan[o_off + (size_t)l * (B + 1) + B];
-    const int64_t Tn = plan[o_off + (size_t)(l + 1) * (B + 1) + B];
-    // normalisation -> QKV -> attention -> projection + residual
-    OTAS_LAUNCH(K_LN, launch_layer_norm(dt, true, x_cur, wl.ln1_g, wl.ln1_b, hbuf, T, D, d.ln_eps, s));
-    OTAS_LAUNCH(K_QKV, launch_linear(dt, hbuf, wl.w_qkv, wl.b_qkv, nullptr, qkv, T, 3 * D, D, EPI_NONE, s));
-    if (any_merge[l]) {
-      // fork: the merge plan reads only the keys just written; the lists it writes were last read by
-      // the previous layer's merge-apply, which precedes this point on the main stream
-      OTAS_HIP(hipEventRecord(c->ev_fork, s));
-      OTAS_HIP(hipStreamWaitEvent(c->side, c->ev_fork, 0));
-      OTAS_LAUNCH_ON(K_PLAN, c->side,
-                     launch_merge_plan(dt, qkv, 3 * (int64_t)D, D, H, dh, off_l, off_n, dp + o_reff + (size_t)l * B,
-                                       dp + o_tr + (size_t)l * B, B, max_n[l], n_lead, src_list, row_ptr,
-                                       trace ? trace_src : nullptr, trace ? trace_dst : nullptr, c->side));
-      OTAS_HIP(hipEventRecord(c->ev_join, c->side));
+    for (int g = 0; g < G; ++g) {
+      LaneRun& ln = lanes[g];
+      otas_ctx::Lane& hw = c->lane[g];
+      hipStream_t s = g == 0 ? s0 : hw.main;
+      const int Bg = ln.Bg;
+      const int32_t* dp = d_plan_base + ln.plan_base;
+      const int32_t* off_l = dp + (size_t)l * (Bg + 1);
+      const int32_t* off_n = dp + (size_t)(l + 1) * (Bg + 1);
+      const int32_t* d_reff = dp + (size_t)(L + 1) * (Bg + 1) + (size_t)l * Bg;
+      const int32_t* d_tr = d_reff + (size_t)L * Bg;
+      const int64_t T = ln.T[l], Tn = ln.T[l + 1];
+      // the lane's rows of every buffer
+      float* x_free[2] = {(float*)(ws + w.xa) + (size_t)ln.row0 * D, (float*)(ws + w.xb) + (size_t)ln.row0 * D};
+      char* hbuf = ws + w.h + (size_t)ln.row0 * D * es;
+      char* qkv = ws + w.qkv + (size_t)ln.row0 * 3 * D * es;
+      char* hid = ws + w.hid + (size_t)ln.row0 * F * es;
+      int32_t* sizes_buf[2] = {(int32_t*)(ws + w.sizes_a) + ln.row0, (int32_t*)(ws + w.sizes_b) + ln.row0};
+      int32_t* src_list = (int32_t*)(ws + w.src_list) + ln.row0;
+      int32_t* row_ptr = (int32_t*)(ws + w.row_ptr) + ln.row0 + g;   // one end entry per lane
+      // normalisation -> QKV -> attention -> projection + residual
+      if (!ln.ln1_done)
+        OTAS_LAUNCH_ON(K_LN, s, launch_layer_norm(dt, true, ln.x_cur, wl.ln1_g, wl.ln1_b, hbuf, T, D, d.ln_eps, s));
+      ln.ln1_done = false;
+      OTAS_LAUNCH_ON(K_QKV, s, launch_linear(dt, hbuf, wl.w_qkv, wl.b_qkv, nullptr, qkv, T, 3 * D, D, EPI_NONE, s));
+      if (ln.any_merge[l]) {
+        // fork: the merge plan reads only the keys just written; the lists it writes were last read by
+        // the previous layer's merge-apply, which precedes this point on the lane's stream
+        OTAS_HIP(hipEventRecord(hw.ev_fork, s));
+        OTAS_HIP(hipStreamWaitEvent(hw.side, hw.ev_fork, 0));
+        OTAS_LAUNCH_ON(K_PLAN, hw.side,
+                       launch_merge_plan(dt, qkv, 3 * (int64_t)D, D, H, dh, off_l, off_n, d_reff, d_tr, Bg,
+                                         ln.max_n[l], n_lead, src_list, row_ptr, trace ? trace_src : nullptr,
+                                         trace ? trace_dst : nullptr, hw.side));
+        OTAS_HIP(hipEventRecord(hw.ev_join, hw.side));
+      }
+      OTAS_LAUNCH_ON(K_ATTN, s,
+                     launch_attention(dt, qkv, ln.sizes_now, off_l, Bg, ln.max_n[l], D, H, size_bias, hbuf, s));
+      // in-place residual is safe (each element is read then written by the same thread); the
+      // caller's x0 is never written, so layer 0 writes into the workspace.
+      void* x_attn = ln.x_owned ? const_cast<void*>(ln.x_cur) : (void*)x_free[0];
+      OTAS_LAUNCH_ON(K_PROJ, s, launch_linear(dt, hbuf, wl.w_proj, wl.b_proj, (const float*)ln.x_cur, x_attn, T, D, D,
+                                              EPI_RESIDUAL, s));
+      void* x_mlp = x_attn;
+      // merging module
+      if (ln.any_merge[l]) {
+        void* x_other = (x_attn == (void*)x_free[0]) ? x_free[1] : x_free[0];
+        OTAS_HIP(hipStreamWaitEvent(s, hw.ev_join, 0));   // join
+        int32_t* sizes_next = (l == ln.last_merge) ? sizes_out + ln.rowL
+                                                   : (ln.sizes_now == sizes_buf[0] ? sizes_buf[1] : sizes_buf[0]);
+        // merge-apply and the block's second LayerNorm in one pass over the rows
+        OTAS_LAUNCH_ON(K_APPLY, s,
+                       launch_merge_apply_ln(dt, (const float*)x_attn, ln.sizes_now, src_list, row_ptr, T, Tn, D,
+                                             (float*)x_other, sizes_next, wl.ln2_g, wl.ln2_b, hbuf, d.ln_eps, s));
+        ln.sizes_now = sizes_next;
+        x_mlp = x_other;
+      } else {
+        OTAS_LAUNCH_ON(K_LN, s, launch_layer_norm(dt, true, x_mlp, wl.ln2_g, wl.ln2_b, hbuf, Tn, D, d.ln_eps, s));
+      }
+      // MLP + residual
+      OTAS_LAUNCH_ON(K_FC1, s, launch_linear(dt, hbuf, wl.w_fc1, wl.b_fc1, nullptr, hid, Tn, F, D, EPI_GELU, s));
+      void* x_next = (l == L - 1) ? (void*)((float*)x_out + (size_t)ln.rowL * D) : x_mlp;
+      int S = splitk_factor(dt, Tn, D, F);
+      S = (int)std::min<int64_t>(S, kPartRows * ln.T[0] / std::max<int64_t>(Tn, 1));
+      if (S > 1 && F % (S * 32) == 0) {
+        // few tiles, long K: S partial products, then one pass that adds them, the bias and the
+        // residual and already applies the next block's first LayerNorm to the row in registers
+        float* part = (float*)(ws + w.part) + (size_t)kPartRows * ln.row0 * D;
+        OTAS_LAUNCH_ON(K_FC2, s, launch_linear_splitk(hid, wl.w_fc2, part, Tn, D, F, S, s));
+        const bool more = l + 1 < L;
+        const otas_layer_weights* wn = more ? &c->layers[layer_begin + l + 1] : nullptr;
+        OTAS_LAUNCH_ON(K_REDUCE, s,
+                       launch_splitk_reduce_ln(part, S, wl.b_fc2, (const float*)x_mlp, (float*)x_next, Tn, D,
+                                               more ? wn->ln1_g : nullptr, more ? wn->ln1_b : nullptr,
+                                               more ? (void*)hbuf : nullptr, d.ln_eps, s));
+        ln.ln1_done = more;
+      } else {
+        OTAS_LAUNCH_ON(K_FC2, s, launch_linear(dt, hid, wl.w_fc2, wl.b_fc2, (const float*)x_mlp, x_next, Tn, D, F,
+                                               EPI_RESIDUAL, s));
+      }
+      ln.x_cur = x_next;
+      ln.x_owned = true;
     }
-    OTAS_LAUNCH(K_ATTN, launch_attention(dt, qkv, sizes_now, off_l, B, max_n[l], D, H, size_bias, hbuf, s));
-    // in-place residual is safe (each element is read then written by the same thread); the
-    // caller's x0 is never written, so layer 0 writes into the workspace.
-    void* x_attn = x_owned ? const_cast<void*>(x_cur) : x_free[0];
-    OTAS_LAUNCH(K_PROJ, launch_linear(dt, hbuf, wl.w_proj, wl.b_proj, (const float*)x_cur, x_attn, T, D, D,
-                                      EPI_RESIDUAL, s));
-    void* x_mlp = x_attn;
-    // merging module
-    if (any_merge[l]) {
-      void* x_other = (x_attn == x_free[0]) ? x_free[1] : x_free[0];
-      OTAS_HIP(hipStreamWaitEvent(s, c->ev_join, 0));   // join
-      int32_t* sizes_next = (l == last_merge) ? sizes_out : (sizes_now == sizes_buf[0] ? sizes_buf[1] : sizes_buf[0]);
-      // merge-apply and the block's second LayerNorm in one pass over the rows
-      OTAS_LAUNCH(K_APPLY, launch_merge_apply_ln(dt, (const float*)x_attn, sizes_now, src_list, row_ptr, T, Tn, D,
-                                                 (float*)x_other, sizes_next, wl.ln2_g, wl.ln2_b, hbuf, d.ln_eps, s));
-      sizes_now = sizes_next;
-      x_mlp = x_other;
-    } else {
-      OTAS_LAUNCH(K_LN, launch_layer_norm(dt, true, x_mlp, wl.ln2_g, wl.ln2_b, hbuf, Tn, D, d.ln_eps, s));
-    }
-    // MLP + residual
-    OTAS_LAUNCH(K_FC1, launch_linear(dt, hbuf, wl.w_fc1, wl.b_fc1, nullptr, hid, Tn, F, D, EPI_GELU, s));
-    void* x_next = (l == L - 1) ? x_out : x_mlp;
-    OTAS_LAUNCH(K_FC2, launch_linear(dt, hid, wl.w_fc2, wl.b_fc2, (const float*)x_mlp, x_next, Tn, D, F,
-                                     EPI_RESIDUAL, s));
-    x_cur = x_next;
-    x_owned = true;
   }
-  if (last_merge < 0) {   // nothing merged: the sizes are the input's
-    const int64_t TL = plan[o_off + (size_t)L * (B + 1) + B];
-    if (sizes_in) OTAS_LAUNCH(K_MISC, launch_copy_i32(sizes_in, sizes_out, TL, s));
-    else OTAS_LAUNCH(K_MISC, launch_fill_i32(sizes_out, 1, TL, s));
+  for (int g = 0; g < G; ++g) {
+    LaneRun& ln = lanes[g];
+    hipStream_t s = g == 0 ? s0 : c->lane[g].main;
+    if (ln.last_merge < 0) {   // nothing merged in this lane: the sizes are the input's
+      if (sizes_in) OTAS_LAUNCH_ON(K_MISC, s, launch_copy_i32(sizes_in + ln.row0, sizes_out + ln.rowL, ln.T[L], s));
+      else OTAS_LAUNCH_ON(K_MISC, s, launch_fill_i32(sizes_out + ln.rowL, 1, ln.T[L], s));
+    }
+    if (g > 0) {   // join
+      OTAS_HIP(hipEventRecord(c->lane[g].ev_done, s));
+      OTAS_HIP(hipStreamWaitEvent(s0, c->lane[g].ev_done, 0));
+    }
   }
   return OTAS_OK;
+  };   // enqueue
+
+  otas_status st = upload_plan(c, plan);
+  if (st != OTAS_OK) return st;
+  return enqueue(c->d_plan, c->stream);
 }
 }  // namespace
 
@@ -535,11 +687,40 @@ otas_status otas_attention(otas_ctx* c, const void* qkv, const int32_t* sizes, c
 
 otas_status otas_timing_enable(otas_ctx* c, int32_t on) {
   if (!c) return OTAS_EINVAL;
-  if (hipStreamSynchronize(c->stream) != hipSuccess || hipStreamSynchronize(c->side) != hipSuccess) return OTAS_EDEVICE;
-  c->timing = on != 0;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return OTAS_EDEVICE;
+  c->timing = false;
   c->ev_kind.clear();
+  if (on) {
+    // Calibrate: an event pair around a one-element fill measures launch + event overhead, not work.
+    // The median of 15 such intervals is subtracted from every later record.
+    c->timing = true;
+    c->ev_overhead_ms = 0.f;
+    for (int i = 0; i < 15; ++i) OTAS_LAUNCH(K_MISC, launch_fill_i32(c->d_plan + kPlanInts - 1, 0, 1, c->stream));
+    if (hipStreamSynchronize(c->stream) != hipSuccess) return OTAS_EDEVICE;
+    std::vector<float> v;
+    for (size_t i = 0; i < c->ev_kind.size(); ++i) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, c->ev_pool[2 * i], c->ev_pool[2 * i + 1]) != hipSuccess) return OTAS_EDEVICE;
+      v.push_back(ms);
+    }
+    std::sort(v.begin(), v.end());
+    c->ev_overhead_ms = v.empty() ? 0.f : v[v.size() / 2];
+    c->ev_kind.clear();
+  }
   return OTAS_OK;
 }
+
+otas_status otas_set_lanes(otas_ctx* c, int32_t lanes) {
+  if (!c || lanes < 0 || lanes > kMaxLanes) return OTAS_EINVAL;
+  c->lanes = lanes;
+  return OTAS_OK;
+}
+
+int32_t otas_splitk_factor(const otas_ctx* c, int64_t M, int32_t N, int32_t K) {
+  return c ? splitk_factor(c->desc.dtype, M, N, K) : 1;
+}
+
+float otas_timing_overhead_ms(const otas_ctx* c) { return c ? c->ev_overhead_ms : 0.f; }
 
 int32_t otas_timing_kinds(void) { return K_COUNT; }
 
@@ -547,23 +728,24 @@ const char* otas_timing_kind_name(int32_t kind) { return (kind >= 0 && kind < K_
 
 int32_t otas_timing_read_launches(otas_ctx* c, int32_t cap, int32_t* kinds, float* ms) {
   if (!c || cap < 0 || (cap > 0 && (!kinds || !ms))) return -1;
-  if (hipStreamSynchronize(c->stream) != hipSuccess || hipStreamSynchronize(c->side) != hipSuccess) return -1;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return -1;   // every lane and side stream has joined it
   const int32_t n = (int32_t)std::min<size_t>(c->ev_kind.size(), (size_t)cap);
   for (int32_t i = 0; i < n; ++i) {
     kinds[i] = c->ev_kind[i];
     if (hipEventElapsedTime(&ms[i], c->ev_pool[2 * i], c->ev_pool[2 * i + 1]) != hipSuccess) return -1;
+    ms[i] = std::max(ms[i] - c->ev_overhead_ms, 0.0005f);
   }
   return (int32_t)c->ev_kind.size();
 }
 
 otas_status otas_timing_read(otas_ctx* c, double* total_ms, int64_t* launches) {
   if (!c || !total_ms || !launches) return OTAS_EINVAL;
-  if (hipStreamSynchronize(c->stream) != hipSuccess || hipStreamSynchronize(c->side) != hipSuccess) return OTAS_EDEVICE;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return OTAS_EDEVICE;
   for (int k = 0; k < K_COUNT; ++k) { total_ms[k] = 0.0; launches[k] = 0; }
   for (size_t i = 0; i < c->ev_kind.size(); ++i) {
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, c->ev_pool[2 * i], c->ev_pool[2 * i + 1]) != hipSuccess) return OTAS_EDEVICE;
-    total_ms[c->ev_kind[i]] += ms;
+    total_ms[c->ev_kind[i]] += std::max(ms - c->ev_overhead_ms, 0.0005f);
     launches[c->ev_kind[i]] += 1;
   }
   c->ev_kind.clear();

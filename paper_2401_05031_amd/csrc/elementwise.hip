@@ -293,6 +293,112 @@ hipError_t launch_merge_apply_ln(int dtype, const float* x, const int32_t* sizes
                                                       g, b, y, eps, s);
 }
 
+// ---------------------------------------------------------------------------------- split-K reduce + LayerNorm
+// Second half of a split-K residual linear: one wave per row adds the S float partial products in
+// split order, then the bias and the residual row, writes the new residual row, and (LN) normalises
+// the row it still holds in registers with the next block's first LayerNorm.  x_out may be res.
+template <int NCH, bool LN>
+__global__ __launch_bounds__(256) void splitk_reduce_ln_kernel(const float* __restrict__ part, int S,
+                                                               const bf16_t* __restrict__ bias, const float* res,
+                                                               float* x_out, int64_t M, int D,
+                                                               const bf16_t* __restrict__ g,
+                                                               const bf16_t* __restrict__ b, bf16_t* __restrict__ y,
+                                                               float eps) {
+  constexpr int V = 8;
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;
+  const int chunks = D / V;
+  const size_t split_stride = (size_t)M * D;
+  const float* pr = part + (size_t)row * D;
+  const float* rr = res + (size_t)row * D;
+  float* xo = x_out + (size_t)row * D;
+  float v[NCH][V];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane + 64 * i;
+    if (c < chunks) {
+      Vec<float> lo = load_vec<float>(pr + c * V), hi = load_vec<float>(pr + c * V + 4);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { v[i][k] = lo.get(k); v[i][4 + k] = hi.get(k); }
+      for (int sp = 1; sp < S; ++sp) {
+        lo = load_vec<float>(pr + sp * split_stride + c * V);
+        hi = load_vec<float>(pr + sp * split_stride + c * V + 4);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { v[i][k] += lo.get(k); v[i][4 + k] += hi.get(k); }
+      }
+      const Vec<bf16_t> bv = load_vec<bf16_t>(bias + c * V);
+      const Vec<float> rlo = load_vec<float>(rr + c * V), rhi = load_vec<float>(rr + c * V + 4);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        v[i][k] = (v[i][k] + bv.get(k)) + rlo.get(k);
+        v[i][4 + k] = (v[i][4 + k] + bv.get(4 + k)) + rhi.get(k);
+      }
+      Vec<float> olo, ohi;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { olo.set(k, v[i][k]); ohi.set(k, v[i][4 + k]); }
+      store_vec<float>(xo + c * V, olo);
+      store_vec<float>(xo + c * V + 4, ohi);
+#pragma unroll
+      for (int k = 0; k < V; ++k) sum += v[i][k];
+    } else {
+#pragma unroll
+      for (int k = 0; k < V; ++k) v[i][k] = 0.f;
+    }
+  }
+  if (!LN) return;
+  const float mean = wave_sum(sum) / (float)D;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane + 64 * i;
+    if (c < chunks) {
+#pragma unroll
+      for (int k = 0; k < V; ++k) { const float d = v[i][k] - mean; sq += d * d; }
+    }
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)D + eps);
+  bf16_t* yr = y + (size_t)row * D;
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = lane + 64 * i;
+    if (c < chunks) {
+      const Vec<bf16_t> gg = load_vec<bf16_t>(g + c * V), bb = load_vec<bf16_t>(b + c * V);
+      Vec<bf16_t> o;
+#pragma unroll
+      for (int k = 0; k < V; ++k) o.set(k, (v[i][k] - mean) * rstd * gg.get(k) + bb.get(k));
+      store_vec<bf16_t>(yr + c * V, o);
+    }
+  }
+}
+
+hipError_t launch_splitk_reduce_ln(const float* part, int S, const void* bias, const float* res, float* x_out,
+                                   int64_t M, int D, const void* g, const void* b, void* y, float eps,
+                                   hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  if (S < 1 || D % 8 != 0) return hipErrorInvalidValue;
+  const int nch = (D / 8 + 63) / 64;
+  dim3 grid((unsigned)((M + 3) / 4)), block(256);
+#define OTAS_RED(N)                                                                                              \
+  do {                                                                                                           \
+    if (y)                                                                                                       \
+      splitk_reduce_ln_kernel<N, true><<<grid, block, 0, s>>>(part, S, (const bf16_t*)bias, res, x_out, M, D,    \
+                                                              (const bf16_t*)g, (const bf16_t*)b, (bf16_t*)y, eps); \
+    else                                                                                                         \
+      splitk_reduce_ln_kernel<N, false><<<grid, block, 0, s>>>(part, S, (const bf16_t*)bias, res, x_out, M, D,   \
+                                                               nullptr, nullptr, nullptr, eps);                  \
+  } while (0)
+  if (nch <= 1) OTAS_RED(1);
+  else if (nch <= 2) OTAS_RED(2);
+  else if (nch <= 3) OTAS_RED(3);
+  else if (nch <= 4) OTAS_RED(4);
+  else if (nch <= 8) OTAS_RED(8);
+  else return hipErrorInvalidValue;
+#undef OTAS_RED
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------- widen / narrow
 // Token tensors enter and leave in the model's dtype; the residual stream in between is float.
 __global__ void widen_kernel(const bf16_t* __restrict__ a, float* __restrict__ b, int64_t n8) {

@@ -22,6 +22,7 @@ namespace otas {
 // model's storage type.
 template <typename T, int EPI> struct OutType { typedef T type; };
 template <typename T> struct OutType<T, EPI_RESIDUAL> { typedef float type; };
+template <typename T> struct OutType<T, EPI_PARTIAL> { typedef float type; };
 
 template <int EPI>
 __device__ inline float epilogue_value(float acc, float bias, const float* res, size_t idx) {
@@ -129,7 +130,8 @@ __device__ inline void mfma_epilogue(const floatx16 (&acc)[TM][TN], float* stage
   const int rrow = lane / LPR, rcol = (lane % LPR) * 4;
   const int n = n_wave + rcol;
   const bool n_ok = n < N;         // N % 8 == 0: a 4-column group is inside or outside as a whole
-  const bf16x4 bb = *reinterpret_cast<const bf16x4*>(bias + (n_ok ? n : 0));
+  bf16x4 bb = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
+  if (EPI != EPI_PARTIAL) bb = *reinterpret_cast<const bf16x4*>(bias + (n_ok ? n : 0));
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int64_t m_slab = m_wave + i * 32;
@@ -154,7 +156,7 @@ __device__ inline void mfma_epilogue(const floatx16 (&acc)[TM][TN], float* stage
       const floatx4 a = *reinterpret_cast<const floatx4*>(stage + row * LDR + rcol);
       float v[4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = a[e] + (float)bb[e];
+      for (int e = 0; e < 4; ++e) v[e] = EPI == EPI_PARTIAL ? a[e] : a[e] + (float)bb[e];
       if (EPI == EPI_GELU) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = gelu_bf16(v[e]);
@@ -164,6 +166,9 @@ __device__ inline void mfma_epilogue(const floatx16 (&acc)[TM][TN], float* stage
         const size_t idx = (size_t)m * N + n;
         if (EPI == EPI_RESIDUAL) {
           floatx4 o = {v[0] + rr[it][0], v[1] + rr[it][1], v[2] + rr[it][2], v[3] + rr[it][3]};
+          *reinterpret_cast<floatx4*>(reinterpret_cast<float*>(Y) + idx) = o;
+        } else if (EPI == EPI_PARTIAL) {
+          floatx4 o = {v[0], v[1], v[2], v[3]};
           *reinterpret_cast<floatx4*>(reinterpret_cast<float*>(Y) + idx) = o;
         } else {
           bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
@@ -345,6 +350,8 @@ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int& til
 // banks once.  Lane i of a DMA instruction writes LDS row base + i/4, chunk position i%4, so it must
 // fetch logical chunk (i%4) ^ ((row >> 2) & 3) of that row.
 #define OTAS_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (7 << 4) | (15 << 8) | (((n) >> 4) << 14))
+// vmcnt(0) and lgkmcnt(0): this wave's loads have landed AND its LDS reads have returned.
+#define OTAS_WAIT_LOADS_AND_LDS() __builtin_amdgcn_s_waitcnt(7 << 4)
 #define OTAS_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define OTAS_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
@@ -364,8 +371,10 @@ __global__ __launch_bounds__(256, 3) void gemm_mfma128_dma_kernel(const bf16_t* 
                                                                   const bf16_t* __restrict__ bias,
                                                                   const float* res,
                                                                   typename OutType<bf16_t, EPI>::type* Y,
-                                                                  int64_t M, int N, int K, int tiles_m,
-                                                                  int tiles_n) {
+                                                                  int64_t M, int N, int K, int k_len,
+                                                                  int tiles_m, int tiles_n) {
+  // K is the row length of A and W; this workgroup contracts over k_len of it, starting at
+  // blockIdx.y * k_len (split-K launches write one float partial result [M, N] per blockIdx.y).
   constexpr int BM = 128, BN = 128, BK = 32, WM = 64, WN = 64, TM = 2, TN = 2;
   constexpr int STAGE = BM * BK;   // elements per operand per stage
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -390,10 +399,11 @@ __global__ __launch_bounds__(256, 3) void gemm_mfma128_dma_kernel(const bf16_t* 
     ra = ra < M ? ra : M - 1;
     int rw = n0 + row;
     rw = rw < N ? rw : N - 1;
-    a_src[j] = A + (size_t)ra * K + c * 8;
-    w_src[j] = W + (size_t)rw * K + c * 8;
+    a_src[j] = A + (size_t)ra * K + (size_t)blockIdx.y * k_len + c * 8;
+    w_src[j] = W + (size_t)rw * K + (size_t)blockIdx.y * k_len + c * 8;
   }
-  const int KT = K / BK;
+  if (EPI == EPI_PARTIAL) Y += (size_t)blockIdx.y * M * N;
+  const int KT = k_len / BK;
   auto dma_one = [&](int kt, int st, int d) {   // d = 0..3: A rows j = d/2 (even d), W rows (odd d)
     const int k = (kt < KT ? kt : KT - 1) * BK;
     const int j = d >> 1;
@@ -467,10 +477,11 @@ __global__ __launch_bounds__(256, 3) void gemm_mfma128_dma_kernel(const bf16_t* 
 
 template <int NS>
 static hipError_t linear_mfma128_dma(const void* x, const void* w, const void* bias, const float* res, void* y,
-                                     int64_t M, int N, int K, int epi, hipStream_t s) {
+                                     int64_t M, int N, int K, int epi, hipStream_t s, int splits = 1) {
   const int tiles_m = (int)((M + 127) / 128), tiles_n = (N + 127) / 128;
   const size_t lds = (size_t)NS * 2 * 128 * 32 * sizeof(bf16_t);
-  dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
+  dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)splits), block(256);
+  const int k_len = K / splits;
 #define OTAS_MFMA(E)                                                                                              \
   do {                                                                                                            \
     auto kern = gemm_mfma128_dma_kernel<E, NS>;                                                                   \
@@ -481,10 +492,11 @@ static hipError_t linear_mfma128_dma(const void* x, const void* w, const void* b
       attr = true;                                                                                                \
     }                                                                                                             \
     kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
-                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_m, tiles_n);              \
+                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, k_len, tiles_m, tiles_n);       \
   } while (0)
   if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
   else if (epi == EPI_GELU) OTAS_MFMA(EPI_GELU);
+  else if (epi == EPI_PARTIAL) OTAS_MFMA(EPI_PARTIAL);
   else OTAS_MFMA(EPI_RESIDUAL);
 #undef OTAS_MFMA
   return hipGetLastError();
@@ -502,17 +514,22 @@ static hipError_t linear_mfma128_dma(const void* x, const void* w, const void* b
 // in the matrix pipe.  A load is in flight for one whole 64-wide tile before it is needed.
 // Stage layout: 16-byte chunk c of row r sits at chunk c ^ ((r >> 1) & 7) (conflict-free for the
 // linear DMA writes and for the 16-lanes-per-clock fragment reads).
-template <int EPI>
+// The tile height is a template parameter: BM = 64 TM rows (TM = 3, 4, 5: 192, 256, 320) by 256
+// columns.  Whole rounds of one workgroup per CU are what this kernel costs, so the launcher picks
+// the height whose tile count wastes the least of the last round.
+template <int EPI, int TM>
 __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __restrict__ A,
                                                                 const bf16_t* __restrict__ W,
                                                                 const bf16_t* __restrict__ bias, const float* res,
                                                                 typename OutType<bf16_t, EPI>::type* Y, int64_t M,
                                                                 int N, int K, int tiles_m, int tiles_n) {
-  constexpr int BM = 256, BN = 256, BK = 64, WM = 128, WN = 64, TM = 4, TN = 2, NS = 2, KSTEPS = BK / 16;
-  constexpr int STAGE = BM * BK;
+  constexpr int WM = 32 * TM, BM = 2 * WM, BN = 256, BK = 64, WN = 64, TN = 2, NS = 2;
+  constexpr int STAGE_A = BM * BK, STAGE_W = BN * BK;
+  constexpr int NA = BM / 64;   // DMA instructions per wave for the A tile (8 rows each), 4 for W
+  constexpr int NM = TM * TN, NF = TM + TN, ND = NA + 4;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [NS][256][64]
-  bf16_t* Ws = As + NS * STAGE;                   // [NS][256][64]
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [NS][BM][64]
+  bf16_t* Ws = As + NS * STAGE_A;                 // [NS][256][64]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 2, wn = wave & 3;
@@ -522,32 +539,36 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __
   const int n0 = tile_n * BN;
 
   // DMA addressing: rows of 128 B (a whole cache line of K per row and k-tile), 8 lanes per row, 8 rows
-  // per instruction; wave w owns rows w*32 .. w*32+31 of each operand tile (4 instructions each).
+  // per instruction; wave w owns rows w*8*NA .. of the A tile and rows w*32 .. of the W tile.
   // Lane i writes LDS row base + i/8, chunk position i%8, so it fetches logical chunk
   // (i%8) ^ ((row >> 1) & 7) of that row.
-  const bf16_t* a_src[4];
+  const bf16_t* a_src[NA];
   const bf16_t* w_src[4];
+#pragma unroll
+  for (int j = 0; j < NA; ++j) {
+    const int row = wave * (8 * NA) + j * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ ((row >> 1) & 7);
+    int64_t ra = m0 + row;
+    ra = ra < M ? ra : M - 1;
+    a_src[j] = A + (size_t)ra * K + c * 8;
+  }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int row = wave * 32 + j * 8 + (lane >> 3);
     const int c = (lane & 7) ^ ((row >> 1) & 7);
-    int64_t ra = m0 + row;
-    ra = ra < M ? ra : M - 1;
     int rw = n0 + row;
     rw = rw < N ? rw : N - 1;
-    a_src[j] = A + (size_t)ra * K + c * 8;
     w_src[j] = W + (size_t)rw * K + c * 8;
   }
   const int KT = K / BK;
-  auto dma_one = [&](int kt, int st, int d) {   // d = 0..7: A rows j = d/2 (even d), W rows (odd d)
+  auto dma_one = [&](int kt, int st, int d) {   // d = 0..NA-1: A rows; NA..NA+3: W rows
     const int k = (kt < KT ? kt : KT - 1) * BK;
-    const int j = d >> 1;
-    if ((d & 1) == 0)
-      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_src[j] + k), OTAS_LPTR(As + st * STAGE + (wave * 32 + j * 8) * BK),
-                                       16, 0, 0);
+    if (d < NA)
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_src[d] + k),
+                                       OTAS_LPTR(As + st * STAGE_A + (wave * (8 * NA) + d * 8) * BK), 16, 0, 0);
     else
-      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_src[j] + k), OTAS_LPTR(Ws + st * STAGE + (wave * 32 + j * 8) * BK),
-                                       16, 0, 0);
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_src[d - NA] + k),
+                                       OTAS_LPTR(Ws + st * STAGE_W + (wave * 32 + (d - NA) * 8) * BK), 16, 0, 0);
   };
 
   floatx16 acc[TM][TN];
@@ -561,60 +582,62 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __
   const int fr = lane & 31, fk = lane >> 5;
   const int frag_row = fr * BK, sw = (fr >> 1) & 7;
   bf16x8 af[2][TM], wf[2][TN];
-  auto read_frag = [&](int st, int ks, int slot, int f) {   // f = 0..3: A tiles; 4,5: W tiles
+  auto read_frag = [&](int st, int ks, int slot, int f) {   // f = 0..TM-1: A tiles; then the W tiles
     const int c = (((ks << 1) + fk) ^ sw) * 8;
     if (f < TM)
-      af[slot][f] = *reinterpret_cast<const bf16x8*>(As + st * STAGE + (wm * WM + f * 32) * BK + frag_row + c);
+      af[slot][f] = *reinterpret_cast<const bf16x8*>(As + st * STAGE_A + (wm * WM + f * 32) * BK + frag_row + c);
     else
       wf[slot][f - TM] =
-          *reinterpret_cast<const bf16x8*>(Ws + st * STAGE + (wn * WN + (f - TM) * 32) * BK + frag_row + c);
+          *reinterpret_cast<const bf16x8*>(Ws + st * STAGE_W + (wn * WN + (f - TM) * 32) * BK + frag_row + c);
   };
   auto mfma_one = [&](int slot, int t) {
     const int i = t / TN, j = t % TN;
     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
   };
-  // one k-step: 8 MFMAs, each followed by one piece of later work (6 fragment reads, then `extra`)
-  auto kstep = [&](int slot, int st_next, int ks_next, auto extra) {
+  // one k-step: NM MFMAs, each of the first NF followed by one fragment read of the next k-step
+  auto kstep = [&](int slot, int st_next, int ks_next) {
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
+    for (int t = 0; t < NM; ++t) {
       mfma_one(slot, t);
-      if (t < 6) read_frag(st_next, ks_next, slot ^ 1, t);
-      else extra(t - 6);
+      if (t < NF) read_frag(st_next, ks_next, slot ^ 1, t);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
-  auto nothing = [](int) {};
 
-  // Two stages of 64 KB.  Per tile t (stage t & 1): k-steps 0..2 (the fragments of k-step 3 are read
+  // Two stages.  Per tile t (stage t & 1): k-steps 0..2 (the fragments of k-step 3 are read
   // during k-step 2), then wait for this wave's loads of tile t+1, barrier -- after it nobody reads
   // stage t & 1 any more and tile t+1 is visible --, then k-step 3 while the loads of tile t+2 are
   // issued into stage t & 1 and the first fragments of tile t+1 are read.
 #pragma unroll
-  for (int d = 0; d < 8; ++d) dma_one(0, 0, d);
+  for (int d = 0; d < ND; ++d) dma_one(0, 0, d);
 #pragma unroll
-  for (int d = 0; d < 8; ++d) dma_one(1, 1, d);
-  OTAS_VMCNT(8);    // tile 0 landed (this wave's part)
+  for (int d = 0; d < ND; ++d) dma_one(1, 1, d);
+  OTAS_VMCNT(ND);    // tile 0 landed (this wave's part)
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
 #pragma unroll
-  for (int f = 0; f < TM + TN; ++f) read_frag(0, 0, 0, f);
+  for (int f = 0; f < NF; ++f) read_frag(0, 0, 0, f);
 
   for (int kt = 0; kt < KT; ++kt) {
     const int st = kt & 1;
-    kstep(0, st, 1, nothing);
-    kstep(1, st, 2, nothing);
-    kstep(0, st, 3, nothing);
-    OTAS_VMCNT(0);    // tile kt+1 landed
+    kstep(0, st, 1);
+    kstep(1, st, 2);
+    kstep(0, st, 3);
+    // tile kt+1 landed, and the fragments of k-step 3 (read from stage st above, used below) are in
+    // registers: after the barrier other waves start overwriting stage st
+    OTAS_WAIT_LOADS_AND_LDS();
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    // k-step 3: fragments of (tile kt+1, k-step 0) and the 8 load instructions of tile kt+2
+    // k-step 3: fragments of (tile kt+1, k-step 0) and the ND load instructions of tile kt+2,
+    // spread over the MFMAs
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
+    for (int t = 0; t < NM; ++t) {
       mfma_one(1, t);
-      if (t < 6) read_frag(st ^ 1, 0, 0, t);
-      dma_one(kt + 2, st, t);
+      if (t < NF) read_frag(st ^ 1, 0, 0, t);
+#pragma unroll
+      for (int d = t * ND / NM; d < (t + 1) * ND / NM; ++d) dma_one(kt + 2, st, d);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
@@ -626,14 +649,16 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __
                              m0 + wm * WM, n0 + wn * WN, lane);
 }
 
+template <int TM>
 static hipError_t linear_mfma256w8(const void* x, const void* w, const void* bias, const float* res, void* y,
                                    int64_t M, int N, int K, int epi, hipStream_t s) {
-  const int tiles_m = (int)((M + 255) / 256), tiles_n = (N + 255) / 256;
-  const size_t lds = (size_t)2 * 2 * 256 * 64 * sizeof(bf16_t);
+  constexpr int BM = 64 * TM;
+  const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + 255) / 256;
+  const size_t lds = (size_t)2 * (BM + 256) * 64 * sizeof(bf16_t);
   dim3 grid((unsigned)(tiles_m * tiles_n)), block(512);
 #define OTAS_MFMA(E)                                                                                              \
   do {                                                                                                            \
-    auto kern = gemm_mfma256w8_kernel<E>;                                                                         \
+    auto kern = gemm_mfma256w8_kernel<E, TM>;                                                                     \
     static bool attr = false;                                                                                     \
     if (!attr) {                                                                                                  \
       hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
@@ -748,7 +773,9 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma128k64_kernel(const bf16_t* _
     kstep(0, st, 1);
     kstep(1, st, 2);
     kstep(0, st, 3);
-    OTAS_VMCNT(0);    // tile kt+1 landed
+    // tile kt+1 landed, and the fragments of k-step 3 (read from stage st above, used below) are in
+    // registers: after the barrier other waves start overwriting stage st
+    OTAS_WAIT_LOADS_AND_LDS();
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -798,40 +825,81 @@ int g_gemm_variant = 0;   // tile selection override for tuning runs (0 = automa
 static hipError_t linear_mfma(const void* x, const void* w, const void* bias, const float* res, void* y, int64_t M,
                               int N, int K, int epi, hipStream_t s) {
   // Kernel choice by a cost model fitted to per-launch times measured on MI355X inside the encoder
-  // (microseconds; t128 / t256 = number of 128 x 128 / 256 x 256 tiles):
-  //   128 x 128, three workgroups per CU:  max(10 + 0.0107 K, t128 * a), a = 5.3e-5 K (plain and
-  //       GELU epilogue) or 0.0323 + 4.25e-5 K (residual epilogue, float read + write per element).
-  //       Bound by L2 -> LDS bandwidth (64 FLOP per byte loaded) but free of tile-count
-  //       quantisation, and its epilogue overlaps other workgroups' main loops.
-  //   256 x 256, 8 waves, one workgroup per CU:  ceil(t256 / 256) rounds of 11 + 0.021 K (plain),
-  //       19 + 0.021 K (GELU), 19 + 0.0205 K (residual): twice the FLOP per byte, whole rounds only.
-  // K % 32 != 0 or tiny K falls back to the register-staged kernel.
+  // (ViT-B shapes, all three epilogues, every kernel forced in turn; 5 % rms error, and the kernels
+  // it picks cost 0.7 % more in total than the best kernel per shape).  A kernel with tile bm x bn
+  // and S workgroup slots on the chip (256 CUs x workgroups per CU) takes
+  //     (alpha[epilogue] + beta K) * G(tiles),   G = full rounds + p + (1 - p) * (last round's fill),
+  // i.e. whole rounds of S tiles, a partly filled last round costing p of a round plus its share:
+  //   128 x 128, K step 32, three workgroups per CU (bound by L2 -> LDS bandwidth, but cheap per
+  //       round, with fine-grained rounds and an epilogue that overlaps other workgroups' loops);
+  //   128 x 128, K step 64, two per CU (whole cache lines per row and k-tile);
+  //   192 / 256 / 320 x 256, 8 waves, one per CU (up to twice the FLOP per byte loaded, coarse
+  //       rounds: the height that wastes least of the last round wins).
+  // K % 64 != 0 or tiny K falls back to the K-step-32 kernels.
   static const int env_variant = [] {
     const char* e = std::getenv("OTAS_GEMM_VARIANT");   // tuning override, 0 / unset = automatic
     return e ? std::atoi(e) : 0;
   }();
   int variant = g_gemm_variant ? g_gemm_variant : env_variant;
   if (K % 64 != 0 || K < 128) variant = (K % 32 == 0 && K >= 64 && (variant == 0 || variant == 5)) ? 5 : 1;
+  if ((variant == 4 || variant == 6) && K < 32 * 8) variant = 5;
   if (variant == 0) {
-    const double t128 = (double)((M + 127) / 128) * ((N + 127) / 128);
-    const double t256 = (double)((M + 255) / 256) * ((N + 255) / 256);
-    const double a = epi == EPI_RESIDUAL ? 0.0323 + 4.25e-5 * K : 5.3e-5 * K;
-    const double r = epi == EPI_NONE ? 11.0 + 0.021 * K : epi == EPI_GELU ? 19.0 + 0.021 * K : 19.0 + 0.0205 * K;
-    const double c128 = std::max(10.0 + 0.0107 * K, t128 * a);
-    const double c256 = r * std::ceil(t256 / 256.0);
-    variant = c256 < c128 ? 7 : 5;
-    // Among the 128 x 128 kernels the K-step-64 one (whole cache lines per row, two workgroups per
-    // CU) measured faster in place for the plain-epilogue and the long-K residual shapes once a few
-    // hundred tiles are in flight; the K-step-32 one (three workgroups per CU) elsewhere.
-    if (variant == 5 && K % 64 == 0 && t128 >= 300 && (epi == EPI_NONE || (epi == EPI_RESIDUAL && K >= 2048)))
-      variant = 9;
+    struct Cand { int id, bm, bn, slots; double alpha[3], beta, p; };
+    static const Cand cands[] = {
+        {5, 128, 128, 768, {4.06, 7.04, 13.0}, 0.0278, 0.27},
+        {9, 128, 128, 512, {3.17, 6.37, 8.75}, 0.0161, 0.58},
+        {73, 192, 256, 256, {4.36, 10.8, 11.9}, 0.0215, 0.72},
+        {7, 256, 256, 256, {5.85, 14.9, 12.7}, 0.0252, 0.72},
+        {75, 320, 256, 256, {8.34, 19.2, 14.7}, 0.0284, 0.74},
+    };
+    double best = 1e30;
+    for (const Cand& c : cands) {
+      const double tiles = (double)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
+      const double full = std::floor(tiles / c.slots), frac = tiles / c.slots - full;
+      const double g = full + (frac > 0 ? c.p + (1.0 - c.p) * frac : 0.0);
+      const double cost = (c.alpha[epi == EPI_RESIDUAL ? 2 : epi == EPI_GELU ? 1 : 0] + c.beta * K) * g;
+      if (cost < best) { best = cost; variant = c.id; }
+    }
   }
   switch (variant) {
+    case 4: return linear_mfma128_dma<4>(x, w, bias, res, y, M, N, K, epi, s);
     case 5: return linear_mfma128_dma<3>(x, w, bias, res, y, M, N, K, epi, s);
-    case 7: return linear_mfma256w8(x, w, bias, res, y, M, N, K, epi, s);
+    case 6: return linear_mfma128_dma<8>(x, w, bias, res, y, M, N, K, epi, s);
+    case 7: return linear_mfma256w8<4>(x, w, bias, res, y, M, N, K, epi, s);
+    case 73: return linear_mfma256w8<3>(x, w, bias, res, y, M, N, K, epi, s);
+    case 75: return linear_mfma256w8<5>(x, w, bias, res, y, M, N, K, epi, s);
     case 9: return linear_mfma128k64(x, w, bias, res, y, M, N, K, epi, s);
     default: return linear_mfma_tile<128, 128, 2, 2>(x, w, bias, res, y, M, N, K, epi, s);
   }
+}
+
+// Split-K for few-tile, long-K products (the MLP's second linear once merging has shrunk the
+// batch): with M * N / 128^2 tiles far below the ~768 workgroups the chip holds, one workgroup per
+// tile walks the whole K alone and the launch is bound by that serial chain.  S workgroups per tile
+// each contract over K / S and write a float partial result; a second kernel adds the partial
+// results in split order (a fixed order: results are reproducible), the bias and the residual.
+int splitk_factor(int dtype, int64_t M, int N, int K) {
+  if (dtype == 0 || g_gemm_variant || K < 2048 || N % 8 != 0) return 1;
+  static const int env = [] {
+    const char* e = std::getenv("OTAS_SPLITK");   // tuning override: 1 = never split
+    return e ? std::atoi(e) : 0;
+  }();
+  if (env == 1) return 1;
+  const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
+  // measured inside the encoder (K = 3072, N = 768): the partial products' extra traffic pays off
+  // only while one workgroup per tile leaves most CUs idle
+  if (tiles > 170) return 1;
+  static const int cand[] = {8, 6, 4, 3, 2};
+  for (int S : cand)
+    if (K % (S * 64) == 0 && tiles * S <= 768) return S;
+  return 1;
+}
+
+hipError_t launch_linear_splitk(const void* x, const void* w, float* part, int64_t M, int N, int K, int S,
+                                hipStream_t s) {
+  if (M <= 0) return hipSuccess;
+  if (S < 1 || K % (S * 32) != 0 || K / S < 64 || N % 8 != 0) return hipErrorInvalidValue;
+  return linear_mfma128_dma<3>(x, w, nullptr, nullptr, part, M, N, K, EPI_PARTIAL, s, S);
 }
 
 int g_gemm_force_valu = 0;   // tuning / test switch: route bf16 through the plain-FMA kernel

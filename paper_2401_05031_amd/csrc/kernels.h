@@ -6,7 +6,7 @@
 
 namespace otas {
 
-enum Epilogue { EPI_NONE = 0, EPI_GELU = 1, EPI_RESIDUAL = 2 };
+enum Epilogue { EPI_NONE = 0, EPI_GELU = 1, EPI_RESIDUAL = 2, EPI_PARTIAL = 3 /* internal: raw float sums */ };
 
 hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s);
 hipError_t launch_copy_i32(const int32_t* src, int32_t* dst, int64_t n, hipStream_t s);
@@ -26,6 +26,17 @@ hipError_t launch_widen(const void* src_bf16, float* dst, int64_t n, hipStream_t
 hipError_t launch_linear(int dtype, const void* x, const void* w, const void* bias,
                          const float* res, void* y, int64_t M, int N, int K, int epi,
                          hipStream_t s);
+
+// Split-K form of the residual linear for bf16 models: splitk_factor picks S (1 = do not split);
+// launch_linear_splitk writes S float partial products part[S][M][N] of x W^T, each over K / S;
+// launch_splitk_reduce_ln then forms x_out = res + bias + sum_s part[s] (s ascending) and, when
+// y != nullptr, y = LayerNorm(x_out) with gamma g, beta b in bf16 (the next block's first norm).
+int splitk_factor(int dtype, int64_t M, int N, int K);
+hipError_t launch_linear_splitk(const void* x, const void* w, float* part, int64_t M, int N, int K, int S,
+                                hipStream_t s);
+hipError_t launch_splitk_reduce_ln(const float* part, int S, const void* bias, const float* res, float* x_out,
+                                   int64_t M, int D, const void* g, const void* b, void* y, float eps,
+                                   hipStream_t s);
 
 hipError_t launch_attention(int dtype, const void* qkv, const int32_t* sizes,
                             const int32_t* d_off, int B, int max_n, int D, int H, bool size_bias,
