@@ -29,81 +29,110 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 BASELINE_METRIC = "images/sec per (prompts, r) strategy, ViT-B/16 batch 64 bf16; merge-kernel HBM GB/s"
 
 
-def algorithmic_work(cfg, lengths0, r, otas):
-    """Per-kind algorithmic FLOPs / bytes of ONE forward, from the host-known length schedule."""
+def algorithmic_work(cfg, lengths0, r, otas, ctx):
+    """Per-kind algorithmic FLOPs / bytes of ONE forward, from the host-known length schedule and the
+    library's own split-K decision (which decides whether a block's first LayerNorm is a launch of its
+    own or part of the previous block's split-K reduce)."""
     D, H, F, L = cfg.D, cfg.H, cfg.F, cfg.L
     e = 4 if cfg.dtype == "f32" else 2
     sched = np.array([otas.otas_schedule(int(n), 0, int(rr), cfg.n_lead, L) for n, rr in zip(lengths0, r)])  # [B, L+1]
     T = sched.sum(axis=0)
     w = {"gemm_qkv": 0.0, "gemm_proj": 0.0, "gemm_fc1": 0.0, "gemm_fc2": 0.0, "attention": 0.0,
-         "merge_apply_bytes": 0.0, "layer_norm_bytes": 0.0, "merge_layers": 0}
+         "merge_apply_bytes": 0.0, "layer_norm_bytes": 0.0, "splitk_reduce_bytes": 0.0,
+         "merge_apply_bytes_per_layer": [], "splits": []}
+    ln1_fused = False
     for l in range(L):
         w["gemm_qkv"] += 2.0 * T[l] * D * 3 * D
         w["gemm_proj"] += 2.0 * T[l] * D * D
         w["gemm_fc1"] += 2.0 * T[l + 1] * D * F
         w["gemm_fc2"] += 2.0 * T[l + 1] * D * F
         w["attention"] += float(np.sum(4.0 * sched[:, l].astype(np.float64) ** 2 * D))
-        w["layer_norm_bytes"] += T[l] * D * (4.0 + e)                # LN1: float residual row in, operand row out
+        if not ln1_fused:
+            w["layer_norm_bytes"] += T[l] * D * (4.0 + e)            # LN1: float residual row in, operand row out
         if T[l + 1] != T[l]:
             # merge-apply fused with LN2: float rows in and out, a size and a list entry per row, operand row out
-            w["merge_apply_bytes"] += (T[l] + T[l + 1]) * (D * 4.0 + 8.0) + T[l + 1] * D * e
+            b = (T[l] + T[l + 1]) * (D * 4.0 + 8.0) + T[l + 1] * D * e
+            w["merge_apply_bytes"] += b
+            w["merge_apply_bytes_per_layer"].append(b)
         else:
             w["layer_norm_bytes"] += T[l + 1] * D * (4.0 + e)        # LN2 on its own
-            w["merge_layers"] += 1
+        S = min(ctx.otas_splitk_factor(int(T[l + 1]), D, F), int(2 * T[0] // max(T[l + 1], 1))) if e == 2 else 1
+        S = S if S > 1 and F % (S * 32) == 0 else 1
+        w["splits"].append(S)
+        ln1_fused = S > 1 and l + 1 < L
+        if S > 1:   # S float partial rows + residual row in, residual row out, next block's operand row out
+            w["splitk_reduce_bytes"] += T[l + 1] * D * (4.0 * (S + 2) + (e if l + 1 < L else 0))
     w["T"] = T.tolist()
     return w
 
 
-def run_strategy(name, steps, warmup, timing_steps):
-    import torch
-    import paper_2401_05031_amd as otas
+class Strategy:
+    """One workload resident on the GPU: context, inputs, workspace, outputs."""
 
-    cfg = synth.config(name)
-    ctx = otas.Context.from_host_weights(cfg.L, cfg.D, cfg.H, cfg.F,
-                                         otas.OTAS_F32 if cfg.dtype == "f32" else otas.OTAS_BF16,
-                                         cfg.ln_eps, cfg.n_lead, synth.all_weights(cfg))
-    toks, prm, P, R = synth.batch(cfg)
-    D = cfg.D
-    tok_packed, tok_off = synth.pack(toks, D)
-    prm_packed, prm_off = synth.pack(prm, D)
-    t_tok = torch.from_numpy(tok_packed).to("cuda").to(ctx.torch_dtype)
-    t_prm = torch.from_numpy(prm_packed).to("cuda").to(ctx.torch_dtype) if prm_packed.shape[0] else None
-    T0 = int(tok_off[-1] + prm_off[-1])
-    x0 = torch.empty((T0, D), dtype=ctx.torch_dtype, device="cuda")
-    lengths0 = np.diff(tok_off) + np.diff(prm_off)
-    reff, _ = ctx.trace_layout(lengths0, R)
-    T_out = int(T0 - reff.sum())
-    ws = torch.empty(ctx.otas_workspace_bytes(cfg.B, T0), dtype=torch.uint8, device="cuda")
-    x_out = torch.empty((T_out, D), dtype=torch.float32, device="cuda")
-    sizes_out = torch.empty(T_out, dtype=torch.int32, device="cuda")
+    def __init__(self, name):
+        import torch
+        import paper_2401_05031_amd as otas
+        self.name = name
+        self.cfg = cfg = synth.config(name)
+        self.ctx = otas.Context.from_host_weights(cfg.L, cfg.D, cfg.H, cfg.F,
+                                                  otas.OTAS_F32 if cfg.dtype == "f32" else otas.OTAS_BF16,
+                                                  cfg.ln_eps, cfg.n_lead, synth.all_weights(cfg))
+        ctx = self.ctx
+        toks, prm, P, self.R = synth.batch(cfg)
+        D = cfg.D
+        tok_packed, self.tok_off = synth.pack(toks, D)
+        prm_packed, self.prm_off = synth.pack(prm, D)
+        self.t_tok = torch.from_numpy(tok_packed).to("cuda").to(ctx.torch_dtype)
+        self.t_prm = torch.from_numpy(prm_packed).to("cuda").to(ctx.torch_dtype) if prm_packed.shape[0] else None
+        T0 = int(self.tok_off[-1] + self.prm_off[-1])
+        self.x0 = torch.empty((T0, D), dtype=ctx.torch_dtype, device="cuda")
+        self.lengths0 = np.diff(self.tok_off) + np.diff(self.prm_off)
+        reff, _ = ctx.trace_layout(self.lengths0, self.R)
+        T_out = int(T0 - reff.sum())
+        self.ws = torch.empty(ctx.otas_workspace_bytes(cfg.B, T0), dtype=torch.uint8, device="cuda")
+        self.x_out = torch.empty((T_out, D), dtype=torch.float32, device="cuda")
+        self.sizes_out = torch.empty(T_out, dtype=torch.int32, device="cuda")
 
-    def step():
-        off = ctx.otas_prompt_prepend(t_tok, tok_off, t_prm, prm_off, x0)
-        ctx.otas_encoder_forward(x0, off, R, 0, ws, x_out, sizes_out)
+    def step(self):
+        off = self.ctx.otas_prompt_prepend(self.t_tok, self.tok_off, self.t_prm, self.prm_off, self.x0)
+        self.ctx.otas_encoder_forward(self.x0, off, self.R, 0, self.ws, self.x_out, self.sizes_out)
 
-    for _ in range(warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms = dt / steps * 1e3
+    def time_steps(self, steps, warmup):
+        import torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step()
+        torch.cuda.synchronize()
+        self.ms_step = (time.perf_counter() - t0) / steps * 1e3
 
-    # per-kernel durations: the same steps again with an event pair around every launch
-    ctx.otas_timing_enable(True)
-    for _ in range(timing_steps):
-        step()
-    kt = ctx.otas_timing_read()
-    ev_overhead_us = ctx.otas_timing_overhead_ms() * 1e3
-    ctx.otas_timing_enable(False)
-    per_step = {k: (v[0] / timing_steps, v[1] // timing_steps) for k, v in kt.items()}
-    work = algorithmic_work(cfg, lengths0, R, otas)
-    assert torch.isfinite(x_out.float()).all()
-    ctx.close()
-    return {"name": name, "cfg": cfg, "ms": ms, "img_s": cfg.B / (ms * 1e-3), "kernels": per_step, "work": work,
-            "ev_overhead_us": ev_overhead_us}
+    def time_launches(self, timing_steps):
+        """Per-kernel durations: the same steps again with an event pair around every launch."""
+        import torch
+        import paper_2401_05031_amd as otas
+        ctx, cfg = self.ctx, self.cfg
+        ctx.otas_timing_enable(True)
+        for _ in range(timing_steps):
+            self.step()
+        recs = ctx.otas_timing_read_launches()
+        ev_overhead_us = ctx.otas_timing_overhead_ms() * 1e3
+        ctx.otas_timing_enable(False)
+        n_per = len(recs) // timing_steps
+        assert n_per * timing_steps == len(recs)
+        per_step, per_launch = {}, {}
+        for i in range(n_per):          # launch i of a step: its kind, and its mean duration over the steps
+            kind = recs[i][0]
+            ms = float(np.mean([recs[s * n_per + i][1] for s in range(timing_steps)]))
+            per_launch.setdefault(kind, []).append(ms)
+        for kind in ctx.otas_timing_kind_names():
+            v = per_launch.get(kind, [])
+            per_step[kind] = (float(sum(v)), len(v))
+        work = algorithmic_work(cfg, self.lengths0, self.R, otas, ctx)
+        assert torch.isfinite(self.x_out.float()).all()
+        return {"name": self.name, "cfg": cfg, "ms": self.ms_step, "img_s": cfg.B / (self.ms_step * 1e-3),
+                "kernels": per_step, "launches": per_launch, "work": work, "ev_overhead_us": ev_overhead_us}
 
 
 def measured_traffic(workload):
@@ -145,6 +174,18 @@ def rooflines(res):
                               "frac": round(a / PEAK_HBM_GBS, 4), "traffic": traffic.get("merge_apply"),
                               "algorithmic_bytes_per_launch": round(w["merge_apply_bytes"] / max(k["merge_apply"][1], 1)),
                               "avg_launch_us": round(k["merge_apply"][0] * 1e3 / max(k["merge_apply"][1], 1), 2)}
+    if k["merge_apply"][0] > 0 and w["merge_apply_bytes_per_layer"]:
+        # the largest launch (the first merging layer): later layers shrink until launch latency dominates
+        b0, t0 = w["merge_apply_bytes_per_layer"][0], res["launches"]["merge_apply"][0]
+        a = b0 / (t0 * 1e-3) / 1e9
+        out["merge_apply_first_layer"] = {"bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                          "frac": round(a / PEAK_HBM_GBS, 4), "algorithmic_bytes": round(b0),
+                                          "launch_us": round(t0 * 1e3, 2)}
+    if k.get("splitk_reduce_ln", (0, 0))[0] > 0:
+        a = w["splitk_reduce_bytes"] / (k["splitk_reduce_ln"][0] * 1e-3) / 1e9
+        out["splitk_reduce_ln"] = {"bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                   "frac": round(a / PEAK_HBM_GBS, 4), "launches_per_step": k["splitk_reduce_ln"][1],
+                                   "avg_launch_us": round(k["splitk_reduce_ln"][0] * 1e3 / k["splitk_reduce_ln"][1], 2)}
     if k["layer_norm"][0] > 0:
         a = w["layer_norm_bytes"] / (k["layer_norm"][0] * 1e-3) / 1e9
         out["layer_norm"] = {"bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -187,7 +228,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="vitb_r16", choices=list(synth.CONFIG_NAMES))
     ap.add_argument("--others", default="vitb_plain,vitb_p10_r8", help="further strategies reported per strategy")
-    ap.add_argument("--cpu-queries", type=int, default=12)
+    ap.add_argument("--cpu-queries", type=int, default=64)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run one plain device copy of 256 MiB (torch) so that a rocprofv3 --pmc run of this "
@@ -209,11 +250,19 @@ def main():
         b.copy_(a)                      # 256 MiB read + 256 MiB written
         torch.cuda.synchronize()
         del a, b
-    head = run_strategy(args.workload, args.steps, args.warmup, timing_steps=max(3, min(10, args.steps)))
+    # Wall-clock runs of every strategy first, the per-launch event passes afterwards: once timing
+    # events have been recorded in a process, cross-stream dependencies cost more (measured: the
+    # merge plan's fork/join adds ~170 us per layer), which must not leak into a later strategy's
+    # throughput.
+    names = [args.workload] + [n for n in args.others.split(",") if n and n != args.workload]
+    strategies = [Strategy(n) for n in names]
+    for i, st in enumerate(strategies):
+        st.time_steps(args.steps if i == 0 else max(5, args.steps // 2), args.warmup)
+    all_res = [st.time_launches(max(3, min(10, args.steps)) if i == 0 else 3) for i, st in enumerate(strategies)]
+    for st in strategies:
+        st.ctx.close()
+    head = all_res[0]
     per_strategy = {}
-    all_res = [head]
-    for n in [s for s in args.others.split(",") if s and s != args.workload]:
-        all_res.append(run_strategy(n, max(5, args.steps // 2), args.warmup, timing_steps=3))
     for r in all_res:
         P, R = r["cfg"].strategies[0]
         mixed = len(set(r["cfg"].strategies)) > 1

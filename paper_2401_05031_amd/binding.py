@@ -237,6 +237,9 @@ class Context:
         _check(self._lib.otas_timing_read(self._h, ms, cnt), "otas_timing_read")
         return {self._lib.otas_timing_kind_name(i).decode(): (ms[i], int(cnt[i])) for i in range(k)}
 
+    def otas_timing_kind_names(self) -> List[str]:
+        return [self._lib.otas_timing_kind_name(i).decode() for i in range(self._lib.otas_timing_kinds())]
+
     def otas_splitk_factor(self, M: int, N: int, K: int) -> int:
         return int(self._lib.otas_splitk_factor(self._h, int(M), int(N), int(K)))
 

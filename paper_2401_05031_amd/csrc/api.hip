@@ -52,6 +52,7 @@ struct otas_ctx {
   Lane lane[8];
   hipEvent_t ev_begin;
   int lanes;   // requested lane count, 0 = chosen from the batch size
+  int lanes_ready;   // lanes whose streams and events exist
   // optional per-launch timing (otas_timing_enable): one event pair per launch, summed per kind
   bool timing;
   float ev_overhead_ms;   // what an event pair reads around an empty launch (subtracted from every record)
@@ -156,6 +157,23 @@ struct LaunchTimer {
   } while (0)
 #define OTAS_LAUNCH(kind, expr) OTAS_LAUNCH_ON(kind, c->stream, expr)
 
+// Streams and events of lanes 0 .. n-1, created on first use (every stream at the default priority).
+// Streams share a few hardware queues, so a context creates no more of them than it runs.
+bool ensure_lanes(otas_ctx* c, int n) {
+  for (int g = c->lanes_ready; g < n; ++g) {
+    otas_ctx::Lane& ln = c->lane[g];
+    bool ok = true;
+    if (g > 0) ok = hipStreamCreateWithFlags(&ln.main, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&ln.side, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ln.ev_fork, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ln.ev_join, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ln.ev_done, hipEventDisableTiming) == hipSuccess;
+    if (!ok) return false;   // otas_destroy releases what was created
+    c->lanes_ready = g + 1;
+  }
+  return true;
+}
+
 }  // namespace
 
 extern "C" {
@@ -216,6 +234,7 @@ otas_status otas_create(otas_ctx** out, const otas_model_desc* desc, const otas_
   std::memset(c->lane, 0, sizeof(c->lane));
   c->ev_begin = nullptr;
   c->lanes = 0;
+  c->lanes_ready = 0;
   if (const char* e = std::getenv("OTAS_LANES")) c->lanes = std::max(0, std::min(kMaxLanes, std::atoi(e)));
   bool ok = hipGetDevice(&c->device) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->d_plan, kPlanInts * sizeof(int32_t)) == hipSuccess;
@@ -224,14 +243,7 @@ otas_status otas_create(otas_ctx** out, const otas_model_desc* desc, const otas_
     ok = ok && hipEventCreateWithFlags(&c->h_done[i], hipEventDisableTiming) == hipSuccess;
   }
   ok = ok && hipEventCreateWithFlags(&c->ev_begin, hipEventDisableTiming) == hipSuccess;
-  for (int g = 0; g < kMaxLanes && ok; ++g) {   // every stream at the default priority
-    otas_ctx::Lane& ln = c->lane[g];
-    if (g > 0) ok = hipStreamCreateWithFlags(&ln.main, hipStreamNonBlocking) == hipSuccess;
-    ok = ok && hipStreamCreateWithFlags(&ln.side, hipStreamNonBlocking) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&ln.ev_fork, hipEventDisableTiming) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&ln.ev_join, hipEventDisableTiming) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&ln.ev_done, hipEventDisableTiming) == hipSuccess;
-  }
+  ok = ok && ensure_lanes(c, 1);
   if (!ok) {
     otas_destroy(c);
     return OTAS_EDEVICE;
@@ -506,6 +518,7 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
   }
 
   if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
+  if (!ensure_lanes(c, G)) return OTAS_EDEVICE;
 
   // Everything below the plan upload: the launches of all lanes, reading the plan at d_plan_base.
   auto enqueue = [&](const int32_t* d_plan_base, hipStream_t s0) -> otas_status {
