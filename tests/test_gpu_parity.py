@@ -457,3 +457,65 @@ def test_lanes_do_not_change_results(torch_cuda, lib):
     for q in range(6):
         assert hz.rel_err(got["x"][q], ref["x"][q]) <= BF16_TOL
     ctx.close()
+
+
+def test_lanes_bit_identical_full_batch_bf16(torch_cuda, lib):
+    """Full ViT-B batch without merging (no split-K at these row counts): every GEMM kernel variant
+    accumulates over K in the same order, so three lanes running side by side -- different tile
+    shapes per lane, kernels of different lanes sharing CUs -- must reproduce the single-lane result
+    bit for bit.  Guards the kernels' LDS stage reuse against co-resident workgroups."""
+    import torch
+    cfg = synth.config("vitb_plain")
+    ctx, layers = hz.make_context(cfg)
+    toks, prm, P, R = synth.batch(cfg)
+    x0, off = hz.gpu_prepend(ctx, toks, prm)
+    T0 = int(off[-1])
+    assert all(ctx.otas_splitk_factor(T0 // g, cfg.D, cfg.F) == 1 for g in (1, 2, 3))
+    ws = torch.empty(ctx.otas_workspace_bytes(cfg.B, T0), dtype=torch.uint8, device="cuda")
+    outs = []
+    for lanes in (1, 3, 2, 3):
+        ctx.otas_set_lanes(lanes)
+        x_out = torch.zeros((T0, cfg.D), dtype=torch.float32, device="cuda")
+        sz = torch.zeros(T0, dtype=torch.int32, device="cuda")
+        ctx.otas_encoder_forward(x0, off, R, 0, ws, x_out, sz)
+        torch.cuda.synchronize()
+        outs.append(x_out)
+    for o in outs[1:]:
+        assert torch.equal(o, outs[0])
+    ctx.close()
+
+
+@pytest.mark.parametrize("M,N,K,epi", [
+    (12608, 2304, 768, 0), (10560, 2304, 768, 0), (8512, 2304, 768, 0),      # 256-, 192-, 320-row tiles
+    (12608 + 37, 3072, 768, 1), (10560 - 3, 768, 3072, 2), (4416 + 5, 768, 768, 2),
+    (1344, 768, 3072, 2), (67, 2304, 768, 0), (12608, 768, 3072, 2)])
+def test_linear_bf16_every_kernel_ragged_rows(torch_cuda, lib, M, N, K, epi):
+    """otas_linear at the encoder's own shapes, chosen so that every MFMA kernel and tile height the
+    dispatch knows is exercised, with row counts that leave ragged last tiles.  Checked on sampled
+    rows (first, last, around every tile boundary, random) against float64."""
+    torch = torch_cuda
+    cfg = synth.config("vitb_plain")
+    cfg.L = 1
+    ctx, layers = hz.make_context(cfg)
+    rng = np.random.default_rng(M + N + K + epi)
+    x = synth.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+    w = synth.round_to_bf16((rng.standard_normal((N, K)) * 0.03).astype(np.float32))
+    b = synth.round_to_bf16((rng.standard_normal(N) * 0.1).astype(np.float32))
+    res = rng.standard_normal((M, N)).astype(np.float32)
+    dt = torch.bfloat16
+    out = torch.full((M, N), float("nan"), dtype=torch.float32 if epi == 2 else dt, device="cuda")
+    ctx.otas_linear(_t(torch, x, dt), _t(torch, w, dt), _t(torch, b, dt),
+                    _t(torch, res, torch.float32) if epi == 2 else None, M, N, K, epi, out)
+    got = out.to(torch.float32).cpu().numpy()
+    assert np.isfinite(got).all()
+    rows = {0, 1, M - 1, M - 2, M // 2}
+    for t in (128, 192, 256, 320):
+        for k in range(1, M // t + 1):
+            if k in (1, 2, M // t):
+                rows.update({k * t - 1, k * t})
+    rows.update(rng.integers(0, M, 40).tolist())
+    rows = sorted(r for r in rows if 0 <= r < M)
+    lin = x[rows].astype(np.float64) @ w.astype(np.float64).T + b
+    lin = orc.gelu(lin) if epi == 1 else (lin + res[rows] if epi == 2 else lin)
+    assert hz.rel_err(got[rows], lin) <= 1e-2
+    ctx.close()
