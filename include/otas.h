@@ -202,8 +202,9 @@ otas_status otas_attention(otas_ctx *ctx, const void *qkv, const int32_t *sizes,
  * every later launch of this context record an event before and after itself;
  * otas_timing_read waits for the stream, returns for each kind 0 .. otas_timing_kinds()-1 the summed
  * milliseconds and the number of launches since the last read, and clears the records.
- * Enabling also measures what an event pair reads around an empty (one-element) launch -- median of
- * 15, otas_timing_overhead_ms -- and every record is reported net of that overhead.
+ * Enabling also measures the event pair's own overhead -- 2 t1 - t2 with t1 / t2 the median reading
+ * of a pair around one / two one-element fill launches, otas_timing_overhead_ms -- and every record
+ * is reported net of it.
  * total_ms / launches: host arrays of otas_timing_kinds() entries.  Off by default. */
 otas_status otas_timing_enable(otas_ctx *ctx, int32_t on);
 int32_t otas_timing_kinds(void);

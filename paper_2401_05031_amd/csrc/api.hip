@@ -704,20 +704,32 @@ otas_status otas_timing_enable(otas_ctx* c, int32_t on) {
   c->timing = false;
   c->ev_kind.clear();
   if (on) {
-    // Calibrate: an event pair around a one-element fill measures launch + event overhead, not work.
-    // The median of 15 such intervals is subtracted from every later record.
+    // Calibrate: an event pair around a one-element fill reads t1 = overhead + one tiny kernel, a pair
+    // around two such fills t2 = overhead + two of them, so overhead = 2 t1 - t2 (medians of 15).
+    // That overhead -- not the tiny kernel's own duration, which every real kernel has too -- is
+    // subtracted from every later record.
     c->timing = true;
     c->ev_overhead_ms = 0.f;
-    for (int i = 0; i < 15; ++i) OTAS_LAUNCH(K_MISC, launch_fill_i32(c->d_plan + kPlanInts - 1, 0, 1, c->stream));
+    int32_t* cell = c->d_plan + kPlanInts - 1;
+    for (int i = 0; i < 15; ++i) {
+      OTAS_LAUNCH(K_MISC, launch_fill_i32(cell, 0, 1, c->stream));
+      {
+        LaunchTimer t(c, K_MISC, c->stream);
+        OTAS_HIP(launch_fill_i32(cell, 0, 1, c->stream));
+        OTAS_HIP(launch_fill_i32(cell, 0, 1, c->stream));
+      }
+    }
     if (hipStreamSynchronize(c->stream) != hipSuccess) return OTAS_EDEVICE;
-    std::vector<float> v;
+    std::vector<float> one, two;
     for (size_t i = 0; i < c->ev_kind.size(); ++i) {
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, c->ev_pool[2 * i], c->ev_pool[2 * i + 1]) != hipSuccess) return OTAS_EDEVICE;
-      v.push_back(ms);
+      (i % 2 == 0 ? one : two).push_back(ms);
     }
-    std::sort(v.begin(), v.end());
-    c->ev_overhead_ms = v.empty() ? 0.f : v[v.size() / 2];
+    std::sort(one.begin(), one.end());
+    std::sort(two.begin(), two.end());
+    if (!one.empty() && !two.empty())
+      c->ev_overhead_ms = std::max(0.f, 2.f * one[one.size() / 2] - two[two.size() / 2]);
     c->ev_kind.clear();
   }
   return OTAS_OK;

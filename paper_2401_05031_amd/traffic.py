@@ -16,7 +16,8 @@ CAL_BYTES = 256 << 20
 FAMILIES = {
     "gemm": ("gemm_mfma", "gemm_valu"),
     "attention": ("attention_",),
-    "merge_apply": ("merge_apply_kernel",),
+    "merge_apply": ("merge_apply_ln_kernel", "merge_apply_kernel"),
+    "splitk_reduce_ln": ("splitk_reduce_ln_kernel",),
     "merge_plan": ("merge_plan_kernel",),
     "layer_norm": ("layer_norm_kernel",),
 }
