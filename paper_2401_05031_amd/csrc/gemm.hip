@@ -381,7 +381,8 @@ __global__ __launch_bounds__(256, 3) void gemm_mfma128_dma_kernel(const bf16_t* 
   bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [NS][128][32]
   bf16_t* Ws = As + NS * STAGE;                   // [NS][128][32]
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: LDS addresses of the DMA stay scalar
   const int wm = wave >> 1, wn = wave & 1;
   int tile_m, tile_n;
   tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
@@ -389,30 +390,32 @@ __global__ __launch_bounds__(256, 3) void gemm_mfma128_dma_kernel(const bf16_t* 
   const int n0 = tile_n * BN;
 
   // DMA addressing: wave w owns rows w*32 .. w*32+31 of each operand tile, 16 rows per instruction.
-  const bf16_t* a_src[2];
-  const bf16_t* w_src[2];
+  // Global addresses: uniform base (tile origin + this split's k range + k) plus a constant per-lane
+  // 32-bit byte offset.
+  uint32_t a_off[2], w_off[2];
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int row = wave * 32 + j * 16 + (lane >> 2);
     const int c = (lane & 3) ^ ((row >> 2) & 3);
-    int64_t ra = m0 + row;
-    ra = ra < M ? ra : M - 1;
-    int rw = n0 + row;
-    rw = rw < N ? rw : N - 1;
-    a_src[j] = A + (size_t)ra * K + (size_t)blockIdx.y * k_len + c * 8;
-    w_src[j] = W + (size_t)rw * K + (size_t)blockIdx.y * k_len + c * 8;
+    const int64_t a_last = M - 1 - m0;                // rows past the end repeat the last row
+    const int w_last = N - 1 - n0;
+    const uint32_t ra = (uint32_t)(row < a_last ? row : a_last), rw = (uint32_t)(row < w_last ? row : w_last);
+    a_off[j] = (ra * (uint32_t)K + (uint32_t)c * 8u) * (uint32_t)sizeof(bf16_t);
+    w_off[j] = (rw * (uint32_t)K + (uint32_t)c * 8u) * (uint32_t)sizeof(bf16_t);
   }
+  const char* a_base = reinterpret_cast<const char*>(A + (size_t)m0 * K + (size_t)blockIdx.y * k_len);
+  const char* w_base = reinterpret_cast<const char*>(W + (size_t)n0 * K + (size_t)blockIdx.y * k_len);
   if (EPI == EPI_PARTIAL) Y += (size_t)blockIdx.y * M * N;
   const int KT = k_len / BK;
   auto dma_one = [&](int kt, int st, int d) {   // d = 0..3: A rows j = d/2 (even d), W rows (odd d)
-    const int k = (kt < KT ? kt : KT - 1) * BK;
+    const size_t kb = (size_t)((kt < KT ? kt : KT - 1) * BK) * sizeof(bf16_t);
     const int j = d >> 1;
     if ((d & 1) == 0)
-      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_src[j] + k), OTAS_LPTR(As + st * STAGE + (wave * 32 + j * 16) * BK),
-                                       16, 0, 0);
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_base + kb + a_off[j]),
+                                       OTAS_LPTR(As + st * STAGE + (wave * 32 + j * 16) * BK), 16, 0, 0);
     else
-      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_src[j] + k), OTAS_LPTR(Ws + st * STAGE + (wave * 32 + j * 16) * BK),
-                                       16, 0, 0);
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_base + kb + w_off[j]),
+                                       OTAS_LPTR(Ws + st * STAGE + (wave * 32 + j * 16) * BK), 16, 0, 0);
   };
 
   floatx16 acc[TM][TN];
@@ -531,7 +534,8 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __
   bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [NS][BM][64]
   bf16_t* Ws = As + NS * STAGE_A;                 // [NS][256][64]
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: LDS addresses of the DMA stay scalar
   const int wm = wave >> 2, wn = wave & 3;
   int tile_m, tile_n;
   tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
@@ -542,32 +546,35 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __
   // per instruction; wave w owns rows w*8*NA .. of the A tile and rows w*32 .. of the W tile.
   // Lane i writes LDS row base + i/8, chunk position i%8, so it fetches logical chunk
   // (i%8) ^ ((row >> 1) & 7) of that row.
-  const bf16_t* a_src[NA];
-  const bf16_t* w_src[4];
+  // Global addresses are a uniform base (tile origin + k, scalar registers) plus a per-lane 32-bit
+  // byte offset that never changes, so issuing a load costs no vector arithmetic.
+  uint32_t a_off[NA], w_off[4];
 #pragma unroll
   for (int j = 0; j < NA; ++j) {
     const int row = wave * (8 * NA) + j * 8 + (lane >> 3);
     const int c = (lane & 7) ^ ((row >> 1) & 7);
-    int64_t ra = m0 + row;
-    ra = ra < M ? ra : M - 1;
-    a_src[j] = A + (size_t)ra * K + c * 8;
+    const int64_t last = M - 1 - m0;                  // rows past the end repeat the last row
+    const uint32_t r = (uint32_t)(row < last ? row : last);
+    a_off[j] = (r * (uint32_t)K + (uint32_t)c * 8u) * (uint32_t)sizeof(bf16_t);
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int row = wave * 32 + j * 8 + (lane >> 3);
     const int c = (lane & 7) ^ ((row >> 1) & 7);
-    int rw = n0 + row;
-    rw = rw < N ? rw : N - 1;
-    w_src[j] = W + (size_t)rw * K + c * 8;
+    const int last = N - 1 - n0;
+    const uint32_t r = (uint32_t)(row < last ? row : last);
+    w_off[j] = (r * (uint32_t)K + (uint32_t)c * 8u) * (uint32_t)sizeof(bf16_t);
   }
+  const char* a_base = reinterpret_cast<const char*>(A + (size_t)m0 * K);
+  const char* w_base = reinterpret_cast<const char*>(W + (size_t)n0 * K);
   const int KT = K / BK;
   auto dma_one = [&](int kt, int st, int d) {   // d = 0..NA-1: A rows; NA..NA+3: W rows
-    const int k = (kt < KT ? kt : KT - 1) * BK;
+    const size_t kb = (size_t)((kt < KT ? kt : KT - 1) * BK) * sizeof(bf16_t);
     if (d < NA)
-      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_src[d] + k),
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_base + kb + a_off[d]),
                                        OTAS_LPTR(As + st * STAGE_A + (wave * (8 * NA) + d * 8) * BK), 16, 0, 0);
     else
-      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_src[d - NA] + k),
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_base + kb + w_off[d - NA]),
                                        OTAS_LPTR(Ws + st * STAGE_W + (wave * 32 + (d - NA) * 8) * BK), 16, 0, 0);
   };
 
@@ -692,37 +699,39 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma128k64_kernel(const bf16_t* _
   bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [2][128][64]
   bf16_t* Ws = As + 2 * STAGE;                    // [2][128][64]
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: LDS addresses of the DMA stay scalar
   const int wm = wave >> 1, wn = wave & 1;
   int tile_m, tile_n;
   tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
   const int64_t m0 = (int64_t)tile_m * BM;
   const int n0 = tile_n * BN;
 
-  // wave w owns rows w*32 .. w*32+31 of each operand tile, 8 rows (of 128 B) per instruction
-  const bf16_t* a_src[4];
-  const bf16_t* w_src[4];
+  // wave w owns rows w*32 .. w*32+31 of each operand tile, 8 rows (of 128 B) per instruction.
+  // Global addresses: uniform base (tile origin + k) plus a constant per-lane 32-bit byte offset.
+  uint32_t a_off[4], w_off[4];
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int row = wave * 32 + j * 8 + (lane >> 3);
     const int c = (lane & 7) ^ ((row >> 1) & 7);
-    int64_t ra = m0 + row;
-    ra = ra < M ? ra : M - 1;
-    int rw = n0 + row;
-    rw = rw < N ? rw : N - 1;
-    a_src[j] = A + (size_t)ra * K + c * 8;
-    w_src[j] = W + (size_t)rw * K + c * 8;
+    const int64_t a_last = M - 1 - m0;                // rows past the end repeat the last row
+    const int w_last = N - 1 - n0;
+    const uint32_t ra = (uint32_t)(row < a_last ? row : a_last), rw = (uint32_t)(row < w_last ? row : w_last);
+    a_off[j] = (ra * (uint32_t)K + (uint32_t)c * 8u) * (uint32_t)sizeof(bf16_t);
+    w_off[j] = (rw * (uint32_t)K + (uint32_t)c * 8u) * (uint32_t)sizeof(bf16_t);
   }
+  const char* a_base = reinterpret_cast<const char*>(A + (size_t)m0 * K);
+  const char* w_base = reinterpret_cast<const char*>(W + (size_t)n0 * K);
   const int KT = K / BK;
   auto dma_one = [&](int kt, int st, int d) {   // d = 0..7
-    const int k = (kt < KT ? kt : KT - 1) * BK;
+    const size_t kb = (size_t)((kt < KT ? kt : KT - 1) * BK) * sizeof(bf16_t);
     const int j = d >> 1;
     if ((d & 1) == 0)
-      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_src[j] + k), OTAS_LPTR(As + st * STAGE + (wave * 32 + j * 8) * BK),
-                                       16, 0, 0);
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_base + kb + a_off[j]),
+                                       OTAS_LPTR(As + st * STAGE + (wave * 32 + j * 8) * BK), 16, 0, 0);
     else
-      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_src[j] + k), OTAS_LPTR(Ws + st * STAGE + (wave * 32 + j * 8) * BK),
-                                       16, 0, 0);
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_base + kb + w_off[j]),
+                                       OTAS_LPTR(Ws + st * STAGE + (wave * 32 + j * 8) * BK), 16, 0, 0);
   };
 
   floatx16 acc[TM][TN];
