@@ -53,7 +53,10 @@ enum {
 
 /* Limits of this build: D % H == 0, head width d_h in {64, 80, 96, 128} for bf16 and any
  * multiple of 4 up to 128 for f32, D % 8 == 0, F % 8 == 0, sequence length per query <= 1024,
- * n_lead in {0, 1}. */
+ * n_lead in {0, 1}.  A query that merges tokens in a layer (r_eff > 0) must also fit the plan
+ * kernel, which keeps the unit metric vector of every token of the query in LDS:
+ * 4 (n (d_m + 8) + 1064) <= 163840 bytes, i.e. n <= 554 at metric width d_m = 64, n <= 453 at 80,
+ * n <= 293 at 128; longer merging queries are refused with OTAS_EUNSUPPORTED before any launch. */
 #define OTAS_MAX_SEQ 1024
 
 typedef struct {

@@ -519,3 +519,68 @@ def test_linear_bf16_every_kernel_ragged_rows(torch_cuda, lib, M, N, K, epi):
     lin = orc.gelu(lin) if epi == 1 else (lin + res[rows] if epi == 2 else lin)
     assert hz.rel_err(got[rows], lin) <= 1e-2
     ctx.close()
+
+
+def test_longest_sequences_f32(torch_cuda, lib):
+    """The longest query that can merge (554 tokens at d_h = 64: the plan kernel keeps every unit
+    metric vector of a query in LDS) next to a short one, fp32, r larger than half the tokens:
+    decisions checked against the oracle in lock-step (bit-exact unless the oracle itself sees an
+    exact tie).  One token more is refused; without merging 1024 tokens (OTAS_MAX_SEQ) run."""
+    torch = torch_cuda
+    cfg = synth.config("tiny")
+    cfg.n0 = 1020
+    cfg.strategies = [(4, 600), (0, 3)]
+    ctx, layers = hz.make_context(cfg)
+    long_tok = synth.query_tokens(cfg, 0)
+    toks = [long_tok[:550], synth.query_tokens(cfg, 1)[:9]]
+    prm = [synth.query_prompts(cfg, 0), synth.query_prompts(cfg, 1)]
+    R = [600, 3]
+    x0, off = hz.gpu_prepend(ctx, toks, prm)
+    assert off.tolist() == [0, 554, 563]
+    gpu = hz.gpu_forward(ctx, x0, off, R)
+    rep = hz.compare_lockstep(cfg, layers, toks, prm, R, gpu)
+    print("n = 554:", rep)
+    assert rep["sizes_equal"] and rep["max_err"] <= F32_TOL
+    assert rep["disagreements"] == 0 or rep["max_deficit"] <= 1e-6
+    assert gpu["offsets"].tolist() == [0, 140, 144]   # 554 -> 278 -> 140 ; 9 -> 6 -> 4 (r clamps to 2)
+    # 556 merging tokens do not fit the plan kernel
+    x1, off1 = hz.gpu_prepend(ctx, [long_tok[:552]], [prm[0]])
+    with pytest.raises(lib.OtasError) as e:
+        hz.gpu_forward(ctx, x1, off1, [1])
+    assert e.value.status == 5
+    # no merging: the full 1024 tokens
+    x2, off2 = hz.gpu_prepend(ctx, [long_tok], [prm[0]])
+    assert off2.tolist() == [0, 1024]
+    g2 = hz.gpu_forward(ctx, x2, off2, [0])
+    cfg.strategies = [(4, 0)]
+    ref = hz.oracle_forward(cfg, layers, [long_tok], [prm[0]], [0])
+    assert hz.rel_err(g2["x"][0], ref[0]["x"]) <= F32_TOL
+    ctx.close()
+
+
+def test_per_launch_timing_api(torch_cuda, lib):
+    """otas_timing_*: one record per launch in launch order, kinds named, the event-pair overhead is
+    calibrated and non-negative, records stop when timing is off, and timing changes no result."""
+    torch = torch_cuda
+    cfg = synth.config("tiny")
+    ctx, layers = hz.make_context(cfg)
+    toks, prm, P, R = synth.batch(cfg)
+    x0, off = hz.gpu_prepend(ctx, toks, prm)
+    ref = hz.gpu_forward(ctx, x0, off, R, trace=False)
+    ctx.otas_timing_enable(True)
+    assert 0.0 <= ctx.otas_timing_overhead_ms() < 0.1
+    got = hz.gpu_forward(ctx, x0, off, R, trace=False)
+    recs = ctx.otas_timing_read_launches()
+    kinds = [k for k, _ in recs]
+    per_layer = ["layer_norm", "gemm_qkv", "merge_plan", "attention", "gemm_proj", "merge_apply", "gemm_fc1", "gemm_fc2"]
+    assert kinds == per_layer * cfg.L, kinds
+    assert all(ms > 0 for _, ms in recs)
+    assert set(kinds) <= set(ctx.otas_timing_kind_names())
+    totals = ctx.otas_timing_read()
+    assert totals["gemm_qkv"][1] == cfg.L and totals["merge_apply"][1] == cfg.L
+    ctx.otas_timing_enable(False)
+    hz.gpu_forward(ctx, x0, off, R, trace=False)
+    assert ctx.otas_timing_read_launches() == []
+    for q in range(cfg.B):
+        assert np.array_equal(got["x"][q], ref["x"][q]) and np.array_equal(got["sizes"][q], ref["sizes"][q])
+    ctx.close()
