@@ -520,8 +520,10 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
   if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
   if (!ensure_lanes(c, G)) return OTAS_EDEVICE;
 
-  // Everything below the plan upload: the launches of all lanes, reading the plan at d_plan_base.
-  auto enqueue = [&](const int32_t* d_plan_base, hipStream_t s0) -> otas_status {
+  otas_status st = upload_plan(c, plan);
+  if (st != OTAS_OK) return st;
+  const int32_t* d_plan_base = c->d_plan;
+  hipStream_t s0 = c->stream;   // lane 0 runs on the caller's stream
   // Lanes beyond the first run on streams of their own, forked here and joined at the end.
   if (G > 1) {
     OTAS_HIP(hipEventRecord(c->ev_begin, s0));
@@ -653,11 +655,6 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
     }
   }
   return OTAS_OK;
-  };   // enqueue
-
-  otas_status st = upload_plan(c, plan);
-  if (st != OTAS_OK) return st;
-  return enqueue(c->d_plan, c->stream);
 }
 }  // namespace
 

@@ -1,14 +1,16 @@
 // Linear layers of the encoder block (Sec. II-A: per-head Q/K/V projections, the linear after
 // the concatenated heads, and the MLP):  Y[M,N] = epilogue(X[M,K] W[N,K]^T + bias[N]).
 //
-// Two kernels:
+// Kernels:
 //   * gemm_valu_kernel  -- plain fp32 FMA tiles; the true-fp32 path (f32 models) and the fallback
-//                          for shapes the MFMA kernel does not take.
-//   * gemm_mfma128_dma_kernel, gemm_mfma256w8_kernel, gemm_mfma_kernel -- bf16 MFMA
-//                          (v_mfma_f32_32x32x16_bf16), fp32 accumulate, LDS-staged tiles, fused
-//                          bias / GELU / residual epilogue (bf16 models): 128 x 128 tiles for small
-//                          and mid-size shapes, 256 x 256 for large, and a register-staged
-//                          128 x 128 fallback for K % 32 != 0.
+//                          for shapes the MFMA kernels do not take.
+//   * bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32 accumulate, operand tiles loaded straight into
+//     swizzled LDS stages, fused bias / GELU / residual epilogue (bf16 models):
+//       gemm_mfma128_dma_kernel  128 x 128, K step 32, three workgroups per CU (also split-K)
+//       gemm_mfma128k64_kernel   128 x 128, K step 64, two per CU
+//       gemm_mfma256w8_kernel    192 / 256 / 320 x 256, eight waves, one per CU
+//       gemm_mfma_kernel         register-staged 128 x 128 fallback for K % 32 != 0
+//     linear_mfma picks among them with a cost model fitted to measured launch times.
 #include <algorithm>
 #include <cmath>
 #include <cstdlib>
@@ -851,7 +853,6 @@ static hipError_t linear_mfma(const void* x, const void* w, const void* bias, co
   }();
   int variant = g_gemm_variant ? g_gemm_variant : env_variant;
   if (K % 64 != 0 || K < 128) variant = (K % 32 == 0 && K >= 64 && (variant == 0 || variant == 5)) ? 5 : 1;
-  if ((variant == 4 || variant == 6) && K < 32 * 8) variant = 5;
   if (variant == 0) {
     struct Cand { int id, bm, bn, slots; double alpha[3], beta, p; };
     static const Cand cands[] = {
@@ -871,9 +872,7 @@ static hipError_t linear_mfma(const void* x, const void* w, const void* bias, co
     }
   }
   switch (variant) {
-    case 4: return linear_mfma128_dma<4>(x, w, bias, res, y, M, N, K, epi, s);
     case 5: return linear_mfma128_dma<3>(x, w, bias, res, y, M, N, K, epi, s);
-    case 6: return linear_mfma128_dma<8>(x, w, bias, res, y, M, N, K, epi, s);
     case 7: return linear_mfma256w8<4>(x, w, bias, res, y, M, N, K, epi, s);
     case 73: return linear_mfma256w8<3>(x, w, bias, res, y, M, N, K, epi, s);
     case 75: return linear_mfma256w8<5>(x, w, bias, res, y, M, N, K, epi, s);
