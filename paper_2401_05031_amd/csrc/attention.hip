@@ -5,6 +5,8 @@
 //   * attention_rows_kernel -- one wave per query row, fp32 arithmetic throughout (f32 models,
 //                              and the fallback for head widths the MFMA kernel does not take).
 //   * attention_mfma_kernel -- bf16 MFMA with one head's K and V staged in LDS (bf16 models).
+#include <cstdlib>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -64,7 +66,7 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const T* __restrict
 
 
 // ------------------------------------------------------------------------------ bf16 MFMA
-// grid (ceil(max_n / 128), H, B), 256 threads: each wave owns 32 query rows of one (query, head).
+// grid (ceil(max_n / (32 NW)), H, B), NW waves (4 or 8): each wave owns 32 query rows of one (query, head).
 // The keys and values of the head are staged in LDS in chunks of up to KC rows (rows padded
 // by 16 bytes so that the 16 lanes served per clock fall on distinct banks); every wave then walks
 // the chunk in blocks of 32 keys with an online softmax (running row maximum and sum, fp32).
@@ -82,8 +84,8 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const T* __restrict
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef short short8_t __attribute__((ext_vector_type(8)));
 
-template <int DH, bool BIAS, int KC>
-__global__ __launch_bounds__(256, DH <= 64 ? 4 : 2) void attention_mfma_kernel(const bf16_t* __restrict__ qkv,
+template <int DH, bool BIAS, int KC, int NW>
+__global__ __launch_bounds__(64 * NW, (DH <= 64 ? 16 : 8) / NW) void attention_mfma_kernel(const bf16_t* __restrict__ qkv,
                                                              const int32_t* __restrict__ sizes,
                                                              const int32_t* __restrict__ off, int D, float scale,
                                                              bf16_t* __restrict__ o) {
@@ -99,7 +101,8 @@ __global__ __launch_bounds__(256, DH <= 64 ? 4 : 2) void attention_mfma_kernel(c
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int q = blockIdx.z, h = blockIdx.y;
   const int base = off[q], n = off[q + 1] - base;
-  const int row0 = blockIdx.x * 128;
+  constexpr int NT = 64 * NW;             // threads: NW waves of 32 query rows each
+  const int row0 = blockIdx.x * (32 * NW);
   if (row0 >= n) return;
   const size_t ld = (size_t)3 * D;
   const int fr = lane & 31, fk = lane >> 5;
@@ -131,11 +134,11 @@ __global__ __launch_bounds__(256, DH <= 64 ? 4 : 2) void attention_mfma_kernel(c
     // batches of 4 chunk pairs per thread: all eight loads of a batch are issued before the first
     // LDS store waits for them, so their latencies overlap
     const int n_chunks = nc_pad * CPR;
-    for (int t0 = 0; t0 < n_chunks; t0 += 4 * 256) {
+    for (int t0 = 0; t0 < n_chunks; t0 += 4 * NT) {
       bf16x8 kv[4], vv[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const int t = t0 + u * 256 + tid;
+        const int t = t0 + u * NT + tid;
         const int r = t / CPR, c = (t - r * CPR) * 8;
         const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
         kv[u] = zero;
@@ -148,7 +151,7 @@ __global__ __launch_bounds__(256, DH <= 64 ? 4 : 2) void attention_mfma_kernel(c
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        const int t = t0 + u * 256 + tid;
+        const int t = t0 + u * NT + tid;
         const int r = t / CPR, c = (t - r * CPR) * 8;
         if (t < n_chunks) {
           *reinterpret_cast<bf16x8*>(Ks + r * LD + c) = kv[u];
@@ -157,7 +160,7 @@ __global__ __launch_bounds__(256, DH <= 64 ? 4 : 2) void attention_mfma_kernel(c
       }
     }
     if (BIAS) {
-      for (int t = tid; t < nc_pad; t += 256) lnsz[t] = t < nc ? log2f((float)sizes[base + c0 + t]) : 0.f;
+      for (int t = tid; t < nc_pad; t += NT) lnsz[t] = t < nc ? log2f((float)sizes[base + c0 + t]) : 0.f;
     }
     __syncthreads();
     if (!wave_active) continue;
@@ -259,15 +262,23 @@ static hipError_t attention_mfma_b(const void* qkv, const int32_t* sz, const int
   constexpr int KC = 128;
   constexpr int LD = DH + 8;
   const size_t lds = (size_t)(KC + KC + 4) * LD * sizeof(bf16_t) + KC * sizeof(float);
-  auto kern = attention_mfma_kernel<DH, BIAS, KC>;
-  static bool attr = false;
-  if (!attr) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return e;
-    attr = true;
-  }
-  dim3 grid((max_n + 127) / 128, H, B), block(256);
-  kern<<<grid, block, lds, s>>>((const bf16_t*)qkv, sz, d_off, D, scale, (bf16_t*)o);
+  // Sequences of 129 .. 256 rows take one workgroup of eight waves per (query, head) instead of two
+  // of four: the head's keys and values are staged once, not twice.
+#define OTAS_ATTN(NWV)                                                                                            \
+  do {                                                                                                            \
+    auto kern = attention_mfma_kernel<DH, BIAS, KC, NWV>;                                                         \
+    static bool attr = false;                                                                                     \
+    if (!attr) {                                                                                                  \
+      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
+      if (e != hipSuccess) return e;                                                                              \
+      attr = true;                                                                                                \
+    }                                                                                                             \
+    dim3 grid((max_n + 32 * NWV - 1) / (32 * NWV), H, B), block(64 * NWV);                                        \
+    kern<<<grid, block, lds, s>>>((const bf16_t*)qkv, sz, d_off, D, scale, (bf16_t*)o);                           \
+  } while (0)
+  if (max_n > 128 && max_n <= 256) OTAS_ATTN(8);
+  else OTAS_ATTN(4);
+#undef OTAS_ATTN
   return hipGetLastError();
 }
 
