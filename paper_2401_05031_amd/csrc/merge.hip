@@ -22,9 +22,12 @@ template <typename T> struct alignas(4 * sizeof(T)) Quad { T x[4]; };   // 4 con
 // LDS layout of the plan kernel (4-byte words), n = query length, nA = ceil(n/2), nB = floor(n/2):
 //   mh [n][dm+4] normalised metric rows | best [nA] | bcol [nA] | merged [nA] | cnt [nB] |
 //   keep_pos [n] | ent_pos [n] | wave_tot [2][16] | part_v [512] | part_c [512]
+// Floats per metric row in LDS: the even and the odd columns each padded to a multiple of 4, plus 4.
+static inline int plan_row_floats(int dm) { return 2 * (((dm >> 1) + 3) & ~3) + 4; }
+
 size_t merge_plan_lds_bytes(int max_n, int dm) {
   const size_t nA = (max_n + 1) / 2, nB = max_n / 2;
-  return sizeof(float) * ((size_t)max_n * (dm + 4) + 3 * nA + nB + 2 * (size_t)max_n + 32 + 8 + 2 * 512);
+  return sizeof(float) * ((size_t)max_n * plan_row_floats(dm) + 3 * nA + nB + 2 * (size_t)max_n + 32 + 8 + 2 * 512);
 }
 
 // One workgroup of 1024 threads per query.  src: the vectors the similarity is taken on; the metric
@@ -49,7 +52,15 @@ __global__ __launch_bounds__(kPlanThreads) void merge_plan_kernel(
     }
     return;
   }
-  const int nA = (n + 1) >> 1, nB = n >> 1, ldm = dm + 4;
+  const int half = dm >> 1, hp = (half + 3) & ~3;   // columns per parity, and their padded count
+  const int nA = (n + 1) >> 1, nB = n >> 1, ldm = 2 * hp + 4;
+  // Metric rows in LDS: the A tokens (even positions) first, then the B tokens, one row of ldm
+  // floats per token, so that consecutive tokens of one set are ldm = dm + 4 floats apart (16 lanes
+  // reading 16 bytes each from 16 consecutive rows then fall on all 64 banks once).  Inside a row the
+  // columns are stored even ones first, then odd ones (each group zero-padded to a multiple of 4):
+  // column c sits at (c & 1) * hp + c / 2, so
+  // the two halves of a wave (which feed the even and the odd k of every fp32 MFMA) each read
+  // consecutive floats.
   float* mh = lds;
   float* best = mh + (size_t)n * ldm;
   int* bcol = (int*)(best + nA);
@@ -58,9 +69,11 @@ __global__ __launch_bounds__(kPlanThreads) void merge_plan_kernel(
   int* keep_pos = cnt + nB;      // [n] exclusive scan of "row survives"
   int* ent_pos = keep_pos + n;   // [n] exclusive scan of list lengths
   int* wave_tot = ent_pos + n;   // [2][16]
+  auto row_of = [&](int i) { return mh + (size_t)((i & 1) ? nA + (i >> 1) : (i >> 1)) * ldm; };
 
   // Phase 0: head-mean metric rows, 4 columns per thread (one 8- or 16-byte load per head), heads
-  // summed in ascending order.
+  // summed in ascending order.  (This phase is bound by instruction issue on the one CU that runs
+  // the query, not by load latency: deeper load batches made it slower.)
   const int c4n = dm >> 2;
   const float inv_h = 1.0f / (float)H;
   for (int t = tid; t < n * c4n; t += kPlanThreads) {
@@ -73,22 +86,31 @@ __global__ __launch_bounds__(kPlanThreads) void merge_plan_kernel(
       m0 += to_float(v.x[0]); m1 += to_float(v.x[1]); m2 += to_float(v.x[2]); m3 += to_float(v.x[3]);
       p += dm;
     }
-    floatx4 o = {m0 * inv_h, m1 * inv_h, m2 * inv_h, m3 * inv_h};
-    *reinterpret_cast<floatx4*>(mh + (size_t)i * ldm + c) = o;
+    float* r = row_of(i);
+    const int ce = c >> 1;   // columns c, c+2 are even ones, c+1, c+3 odd ones
+    r[ce] = m0 * inv_h;
+    r[ce + 1] = m2 * inv_h;
+    r[hp + ce] = m1 * inv_h;
+    r[hp + ce + 1] = m3 * inv_h;
   }
+  if (hp != half)   // the padding columns take part in the contraction: zero
+    for (int t = tid; t < n * 2 * (hp - half); t += kPlanThreads) {
+      const int i = t / (2 * (hp - half)), c = t - i * (2 * (hp - half));
+      row_of(i)[(c & 1) * hp + half + (c >> 1)] = 0.f;
+    }
   __syncthreads();
   // Phase 1: unit length.  4 consecutive lanes share a row: lane j sums the squares of columns
   // j, j+4, ... in ascending order, the four partial sums are added by a fixed butterfly.
   for (int i0r = 0; i0r < n; i0r += kPlanThreads / 4) {
     const int i = i0r + (tid >> 2), j = tid & 3;
     float ss = 0.f;
-    float* r = mh + (size_t)min(i, n - 1) * ldm;
-    for (int c = j; c < dm; c += 4) ss = fmaf(r[c], r[c], ss);
+    float* r = row_of(min(i, n - 1)) + (j & 1) * hp + (j >> 1);   // column c = j + 4 m sits at (j & 1) hp + (j >> 1) + 2 m
+    for (int m = 0; m < c4n; ++m) ss = fmaf(r[2 * m], r[2 * m], ss);
     ss += __shfl_xor(ss, 1, kWave);
     ss += __shfl_xor(ss, 2, kWave);
     const float rn = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
     if (i < n)
-      for (int c = j; c < dm; c += 4) r[c] *= rn;
+      for (int m = 0; m < c4n; ++m) r[2 * m] *= rn;
   }
   __syncthreads();
 
@@ -109,25 +131,30 @@ __global__ __launch_bounds__(kPlanThreads) void merge_plan_kernel(
     const int fr = lane & 31, fk = lane >> 5;
     for (int ab = w % nAb, grp = w / nAb; grp < G; grp = G) {   // one (A block, B group) per wave
       const int a = ab * 32 + fr;
-      const float* pa = mh + (size_t)(2 * min(a, nA - 1)) * ldm + fk;
+      const float* pa = mh + (size_t)min(a, nA - 1) * ldm + fk * hp;
       float bv = -INFINITY;
       int bc = 0x7fffffff;
       for (int bb = grp; bb < nBb; bb += G) {
-        const float* pb = mh + (size_t)(2 * min(bb * 32 + fr, nB - 1) + 1) * ldm + fk;
+        const float* pb = mh + (size_t)(nA + min(bb * 32 + fr, nB - 1)) * ldm + fk * hp;
         floatx16 acc;
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-        for (int k0 = 0; k0 < dm; k0 += 16) {   // 8 MFMAs per batch, their 16 operand reads issued first
-          float ra[8], rb[8];
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const int k = min(k0 + 2 * u, dm - 2);
-            ra[u] = pa[k];
-            rb[u] = pb[k];
+        // MFMA u contracts over columns 2u (lanes 0..31) and 2u + 1 (lanes 32..63): with the even /
+        // odd column split a lane's operands of four consecutive MFMAs are one 16-byte read
+        for (int k0 = 0; k0 < hp; k0 += 8) {   // 8 MFMAs per batch, their operand reads issued first
+          const floatx4 ra0 = *reinterpret_cast<const floatx4*>(pa + k0);
+          const floatx4 rb0 = *reinterpret_cast<const floatx4*>(pb + k0);
+          floatx4 ra1 = ra0, rb1 = rb0;
+          if (k0 + 4 < hp) {
+            ra1 = *reinterpret_cast<const floatx4*>(pa + k0 + 4);
+            rb1 = *reinterpret_cast<const floatx4*>(pb + k0 + 4);
           }
 #pragma unroll
-          for (int u = 0; u < 8; ++u)
-            if (k0 + 2 * u < dm) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(rb[u], ra[u], acc, 0, 0, 0);
+          for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(rb0[u], ra0[u], acc, 0, 0, 0);
+          if (k0 + 4 < hp) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(rb1[u], ra1[u], acc, 0, 0, 0);
+          }
         }
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
