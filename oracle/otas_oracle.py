@@ -33,11 +33,22 @@ Readings taken where the paper is silent (each is also listed in the design note
       every Linear, no final norm and no head: the encoder is the stack of blocks.
   R10 optional size bias: + ln(size_j) on the logits of key j (not defined by the paper; off
       unless asked for; with all sizes 1 it changes nothing).
+  R13 per-layer prompting (Sec. III-B puts the prompting module in front of the normalisation
+      of EVERY layer and counts gamma "per layer"; Sec. II-B speaks of prompts "added per layer"):
+      two further readings next to R8, both only for queries that do not merge (Sec. III-B: a
+      model performs either prompting or reduction during inference).  "replace": the P prompt
+      rows of the sequence are overwritten with layer l's own trained prompts before the
+      normalisation of every layer l >= 1, length constant n_i + P.  "grow": P new prompt rows
+      are inserted in front of the input tokens (after the lead tokens, R1) before the
+      normalisation of every layer l >= 1, length n_i + (l + 1) P.  Layer 0's prompts are the
+      ones prompt_prepend put there.
 
 Parity pins (tests/test_oracle_pins.py): gamma = 0 against torch.nn.TransformerEncoderLayer in
 float64; length schedule closed forms; size conservation; size-weighted mean conservation;
 brute-force edge selection on tiny inputs; closed-form tie cases; planted duplicate pairs;
-identity cases.  The paper prints no worked numeric example for this path, so nothing here is
+identity cases; per-layer prompting against the torch layer applied block by block with the rows
+replaced / inserted by hand, closed forms with the residual branches switched off, and the
+replacement of the prompt rows by their own values being a no-op.  The paper prints no worked numeric example for this path, so nothing here is
 pinned to a paper-printed value.
 
 Storage modes.  storage="f64" computes everything in float64.  storage="bf16" keeps float64
@@ -100,6 +111,35 @@ def prompt_prepend(tokens: np.ndarray, prompts: np.ndarray, n_lead: int) -> Tupl
     prompts = np.asarray(prompts, dtype=np.float64).reshape(-1, tokens.shape[1])
     x = np.concatenate([tokens[:n_lead], prompts, tokens[n_lead:]], axis=0)
     return x, np.ones(x.shape[0], dtype=np.int64)
+
+
+def deep_length_schedule(n0: int, P: int, L: int, mode: str) -> List[int]:
+    """R13: length entering layer 0..L-1 and the output length for per-layer prompting without
+    merging: constant n0 + P ("replace"), or n0 + (l + 1) P entering layer l ("grow")."""
+    if mode not in ("replace", "grow"):
+        raise ValueError(mode)
+    ent = [n0 + P * ((l + 1) if mode == "grow" else 1) for l in range(L)]
+    return ent + [ent[-1] if L > 0 else n0 + P]
+
+
+def deep_prompt_step(x: np.ndarray, sizes: np.ndarray, prompts: np.ndarray, n_lead: int, mode: str):
+    """R13: the prompting module in front of layer l >= 1.  "replace": rows n_lead .. n_lead + P - 1
+    take the values of this layer's prompts; "grow": the P prompts are inserted at row n_lead.
+    Prompt rows stand for one token each (size 1)."""
+    prompts = np.asarray(prompts, dtype=np.float64).reshape(-1, x.shape[1])
+    P = prompts.shape[0]
+    if mode == "replace":
+        if n_lead + P > x.shape[0]:
+            raise ValueError("more prompt rows than the sequence holds")
+        x = x.copy()
+        sizes = sizes.copy()
+        x[n_lead:n_lead + P] = prompts
+        sizes[n_lead:n_lead + P] = 1
+        return x, sizes
+    if mode == "grow":
+        return (np.concatenate([x[:n_lead], prompts, x[n_lead:]], axis=0),
+                np.concatenate([sizes[:n_lead], np.ones(P, dtype=sizes.dtype), sizes[n_lead:]]))
+    raise ValueError(mode)
 
 
 # ----------------------------------------------------------------------------- encoder pieces
@@ -242,8 +282,14 @@ def validate_decision(n: int, r_eff: int, n_lead: int, src, dst) -> None:
 def encoder_forward_query(x0: np.ndarray, layers: Sequence[Dict[str, np.ndarray]], r: int, *,
                           H: int, ln_eps: float, n_lead: int, storage: str = "f64",
                           size_bias: bool = False, adopt: Optional[Sequence] = None,
-                          taps: Optional[dict] = None, sizes0: Optional[np.ndarray] = None):
+                          taps: Optional[dict] = None, sizes0: Optional[np.ndarray] = None,
+                          deep_prompts: Optional[Sequence[Optional[np.ndarray]]] = None,
+                          deep_mode: Optional[str] = None):
     """Token-adapted encoder for ONE query (prompts already prepended).
+
+    deep_prompts / deep_mode (R13): per-layer prompting; deep_prompts[l] ([P, D]) is applied in
+    front of layer l for l >= 1 (entry 0 is not used: layer 0's prompts are part of x0); needs
+    r = 0 when any prompt row is given.
 
     adopt: optional per-layer (src, dst) decisions to apply instead of the oracle's own
     (lock-step comparison); the oracle still computes its own decision and reports how many edges
@@ -257,8 +303,19 @@ def encoder_forward_query(x0: np.ndarray, layers: Sequence[Dict[str, np.ndarray]
     n = x.shape[0]
     sizes = np.ones(n, dtype=np.int64) if sizes0 is None else np.array(sizes0, dtype=np.int64)
     trace, disagree, margins, lengths, deficits = [], [], [], [n], []
+    if deep_prompts is not None:
+        if deep_mode not in ("replace", "grow"):
+            raise ValueError("deep_mode must be 'replace' or 'grow'")
+        if r != 0 and any(p is not None and np.asarray(p).size for p in deep_prompts[1:]):
+            raise ValueError("per-layer prompting is defined for queries that do not merge")
     for l, w in enumerate(layers):
         W = {k: np.asarray(v, dtype=np.float64) for k, v in w.items()}
+        if deep_prompts is not None and l >= 1 and deep_prompts[l] is not None:
+            # prompting module, in front of the normalisation (stored like the residual stream)
+            x, sizes = deep_prompt_step(x, sizes, round_storage(np.asarray(deep_prompts[l], dtype=np.float64), rs),
+                                        n_lead, deep_mode)
+            if deep_mode == "grow":
+                lengths[-1] = x.shape[0]
         if taps is not None:
             taps.setdefault("x_in", []).append(x.copy())
             taps.setdefault("sizes_in", []).append(sizes.copy())

@@ -47,6 +47,77 @@ def _torch_encoder(layers, D, H, F, eps):
     return mods
 
 
+# ------------------------------------------------------------------ per-layer prompting (R13)
+@pytest.mark.parametrize("mode", ["replace", "grow"])
+@pytest.mark.parametrize("n_lead", [0, 1])
+def test_per_layer_prompting_against_library_blocks(mode, n_lead):
+    """Sec. III-B: the prompting module sits in front of every layer's normalisation.  Independent
+    statement: torch's own encoder layer applied block by block, with the prompt rows overwritten /
+    inserted by hand (torch tensor surgery) between the blocks."""
+    rng = np.random.default_rng(11)
+    n0, P, D, H, F, L = 9, 3, 16, 2, 32, 4
+    layers = _rand_layers(rng, L, D, F)
+    toks = rng.standard_normal((n0, D))
+    prm = [rng.standard_normal((P, D)) for _ in range(L)]
+    x0, _ = orc.prompt_prepend(toks, prm[0], n_lead)
+    got = orc.encoder_forward_query(x0, layers, 0, H=H, ln_eps=1e-6, n_lead=n_lead,
+                                    deep_prompts=prm, deep_mode=mode)
+    with torch.no_grad():
+        t = torch.from_numpy(x0)[None]
+        for l, m in enumerate(_torch_encoder(layers, D, H, F, 1e-6)):
+            if l >= 1:
+                pl = torch.from_numpy(prm[l])[None]
+                if mode == "replace":
+                    t = torch.cat([t[:, :n_lead], pl, t[:, n_lead + P:]], dim=1)
+                else:
+                    t = torch.cat([t[:, :n_lead], pl, t[:, n_lead:]], dim=1)
+            t = m(t)
+    ref = t[0].numpy()
+    assert got["x"].shape == ref.shape == (orc.deep_length_schedule(n0, P, L, mode)[-1], D)
+    assert np.max(np.abs(got["x"] - ref)) <= 1e-11 * max(1.0, np.max(np.abs(ref)))
+    assert got["lengths"] == orc.deep_length_schedule(n0, P, L, mode)
+    assert got["sizes"].tolist() == [1] * ref.shape[0]
+
+
+def test_per_layer_prompting_closed_forms_and_noop():
+    """With both residual branches switched off (projection and second MLP linear zero) a block is
+    the identity, so the output is known in closed form: "replace" leaves the last layer's prompts
+    in the prompt rows, "grow" stacks the layers' prompts newest first in front of the tokens.
+    Replacing the prompt rows by the values they already hold changes nothing; one layer has no
+    per-layer step at all; merging together with per-layer prompts is refused."""
+    rng = np.random.default_rng(12)
+    n0, P, D, H, F, L = 7, 2, 8, 2, 16, 3
+    layers = _rand_layers(rng, L, D, F)
+    toks = rng.standard_normal((n0, D))
+    prm = [rng.standard_normal((P, D)) for _ in range(L)]
+    x0, _ = orc.prompt_prepend(toks, prm[0], 1)
+    off = [dict(w, w_proj=np.zeros((D, D)), b_proj=np.zeros(D), w_fc2=np.zeros((D, F)), b_fc2=np.zeros(D)) for w in layers]
+    rep = orc.encoder_forward_query(x0, off, 0, H=H, ln_eps=1e-6, n_lead=1, deep_prompts=prm, deep_mode="replace")
+    assert np.array_equal(rep["x"], np.concatenate([toks[:1], prm[L - 1], toks[1:]]))
+    grw = orc.encoder_forward_query(x0, off, 0, H=H, ln_eps=1e-6, n_lead=1, deep_prompts=prm, deep_mode="grow")
+    assert np.array_equal(grw["x"], np.concatenate([toks[:1]] + [prm[l] for l in range(L - 1, -1, -1)] + [toks[1:]]))
+    assert orc.deep_length_schedule(n0, P, L, "grow") == [n0 + P, n0 + 2 * P, n0 + 3 * P, n0 + 3 * P]
+    assert orc.deep_length_schedule(n0, P, L, "replace") == [n0 + P] * (L + 1)
+    # replacing the prompt rows with what they hold is a no-op
+    taps = {}
+    plain = orc.encoder_forward_query(x0, layers, 0, H=H, ln_eps=1e-6, n_lead=1, taps=taps)
+    same = [None] + [taps["x_in"][l][1:1 + P] for l in range(1, L)]
+    again = orc.encoder_forward_query(x0, layers, 0, H=H, ln_eps=1e-6, n_lead=1, deep_prompts=same, deep_mode="replace")
+    assert np.array_equal(again["x"], plain["x"])
+    # no prompt rows: both modes are the plain encoder
+    none = [np.zeros((0, D))] * L
+    for mode in ("replace", "grow"):
+        z = orc.encoder_forward_query(x0, layers, 0, H=H, ln_eps=1e-6, n_lead=1, deep_prompts=none, deep_mode=mode)
+        assert np.array_equal(z["x"], plain["x"])
+    # a single layer has no per-layer step
+    one = orc.encoder_forward_query(x0, layers[:1], 0, H=H, ln_eps=1e-6, n_lead=1, deep_prompts=prm[:1], deep_mode="grow")
+    assert np.array_equal(one["x"], orc.encoder_forward_query(x0, layers[:1], 0, H=H, ln_eps=1e-6, n_lead=1)["x"])
+    with pytest.raises(ValueError):
+        orc.encoder_forward_query(x0, layers, 2, H=H, ln_eps=1e-6, n_lead=1, deep_prompts=prm, deep_mode="replace")
+    with pytest.raises(ValueError):
+        orc.encoder_forward_query(x0, layers, 0, H=H, ln_eps=1e-6, n_lead=1, deep_prompts=prm, deep_mode="append")
+
+
 @pytest.mark.parametrize("n,D,H,F,L", [(7, 16, 2, 32, 2), (33, 48, 3, 96, 3)])
 def test_gamma_zero_equals_library_prenorm_encoder(n, D, H, F, L):
     """Sec. III-D: gamma = 0 is the unmodified transformer.  The independent implementation is
@@ -350,3 +421,33 @@ def test_pins_catch_planted_mistakes(monkeypatch):
     q, k, v = (t[:, i * 8:(i + 1) * 8].reshape(7, 2, 4).transpose(0, 1) for i in range(3))
     ref = torch.nn.functional.scaled_dot_product_attention(q, k, v).transpose(0, 1).reshape(7, 8).numpy()
     assert not np.allclose(orc.attention_heads(qkv, 2), ref, atol=1e-6)
+
+
+def test_per_layer_prompting_pins_catch_planted_mistakes(monkeypatch):
+    """A prompting step that writes one row too late, or appends instead of inserting, must break the
+    closed form of the residual-free model."""
+    rng = np.random.default_rng(13)
+    n0, P, D, H, F, L = 6, 2, 8, 2, 16, 3
+    layers = _rand_layers(rng, L, D, F)
+    off = [dict(w, w_proj=np.zeros((D, D)), b_proj=np.zeros(D), w_fc2=np.zeros((D, F)), b_fc2=np.zeros(D)) for w in layers]
+    toks = rng.standard_normal((n0, D))
+    prm = [rng.standard_normal((P, D)) for _ in range(L)]
+    x0, _ = orc.prompt_prepend(toks, prm[0], 1)
+    want_rep = np.concatenate([toks[:1], prm[L - 1], toks[1:]])
+    want_grw = np.concatenate([toks[:1]] + [prm[l] for l in range(L - 1, -1, -1)] + [toks[1:]])
+    good = orc.deep_prompt_step
+
+    def late(x, sizes, prompts, n_lead, mode):
+        return good(x, sizes, prompts, n_lead + 1, mode)
+
+    def appended(x, sizes, prompts, n_lead, mode):
+        if mode == "grow":
+            return np.concatenate([x, prompts]), np.concatenate([sizes, np.ones(len(prompts), dtype=sizes.dtype)])
+        return good(x, sizes, prompts, n_lead, mode)
+
+    monkeypatch.setattr(orc, "deep_prompt_step", late)
+    bad = orc.encoder_forward_query(x0, off, 0, H=H, ln_eps=1e-6, n_lead=1, deep_prompts=prm, deep_mode="replace")
+    assert not np.array_equal(bad["x"], want_rep)
+    monkeypatch.setattr(orc, "deep_prompt_step", appended)
+    bad = orc.encoder_forward_query(x0, off, 0, H=H, ln_eps=1e-6, n_lead=1, deep_prompts=prm, deep_mode="grow")
+    assert not np.array_equal(bad["x"], want_grw)
