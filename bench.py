@@ -35,8 +35,15 @@ def algorithmic_work(cfg, lengths0, r, otas, ctx):
     own or part of the previous block's split-K reduce)."""
     D, H, F, L = cfg.D, cfg.H, cfg.F, cfg.L
     e = 4 if cfg.dtype == "f32" else 2
-    sched = np.array([otas.otas_schedule(int(n), 0, int(rr), cfg.n_lead, L) for n, rr in zip(lengths0, r)])  # [B, L+1]
-    T = sched.sum(axis=0)
+    if cfg.deep:   # per-layer prompting: no merging; lengths constant (replace) or + P per layer (grow)
+        P = np.array([p for p, _ in cfg.strategies])
+        grow = cfg.deep == "grow"
+        ent = [np.asarray(lengths0) + (l * P if grow else 0) for l in range(L)]
+        sched = np.stack(ent + [ent[-1]], axis=1)
+    else:
+        sched = np.array([otas.otas_schedule(int(n), 0, int(rr), cfg.n_lead, L) for n, rr in zip(lengths0, r)])  # [B, L+1]
+    T = sched.sum(axis=0)                       # rows entering layer l (l = 0..L-1), then the output rows
+    Tm = T[:L] if cfg.deep else T[1:]           # rows of layer l behind its merging module (MLP rows)
     w = {"gemm_qkv": 0.0, "gemm_proj": 0.0, "gemm_fc1": 0.0, "gemm_fc2": 0.0, "attention": 0.0,
          "merge_apply_bytes": 0.0, "layer_norm_bytes": 0.0, "splitk_reduce_bytes": 0.0,
          "merge_apply_bytes_per_layer": [], "splits": []}
@@ -44,24 +51,24 @@ def algorithmic_work(cfg, lengths0, r, otas, ctx):
     for l in range(L):
         w["gemm_qkv"] += 2.0 * T[l] * D * 3 * D
         w["gemm_proj"] += 2.0 * T[l] * D * D
-        w["gemm_fc1"] += 2.0 * T[l + 1] * D * F
-        w["gemm_fc2"] += 2.0 * T[l + 1] * D * F
+        w["gemm_fc1"] += 2.0 * Tm[l] * D * F
+        w["gemm_fc2"] += 2.0 * Tm[l] * D * F
         w["attention"] += float(np.sum(4.0 * sched[:, l].astype(np.float64) ** 2 * D))
         if not ln1_fused:
             w["layer_norm_bytes"] += T[l] * D * (4.0 + e)            # LN1: float residual row in, operand row out
-        if T[l + 1] != T[l]:
+        if Tm[l] != T[l]:
             # merge-apply fused with LN2: float rows in and out, a size and a list entry per row, operand row out
-            b = (T[l] + T[l + 1]) * (D * 4.0 + 8.0) + T[l + 1] * D * e
+            b = (T[l] + Tm[l]) * (D * 4.0 + 8.0) + Tm[l] * D * e
             w["merge_apply_bytes"] += b
             w["merge_apply_bytes_per_layer"].append(b)
         else:
-            w["layer_norm_bytes"] += T[l + 1] * D * (4.0 + e)        # LN2 on its own
-        S = min(ctx.otas_splitk_factor(int(T[l + 1]), D, F), int(2 * T[0] // max(T[l + 1], 1))) if e == 2 else 1
+            w["layer_norm_bytes"] += Tm[l] * D * (4.0 + e)           # LN2 on its own
+        S = min(ctx.otas_splitk_factor(int(Tm[l]), D, F), int(2 * T[0] // max(Tm[l], 1))) if e == 2 and not cfg.deep else 1
         S = S if S > 1 and F % (S * 32) == 0 else 1
         w["splits"].append(S)
         ln1_fused = S > 1 and l + 1 < L
         if S > 1:   # S float partial rows + residual row in, residual row out, next block's operand row out
-            w["splitk_reduce_bytes"] += T[l + 1] * D * (4.0 * (S + 2) + (e if l + 1 < L else 0))
+            w["splitk_reduce_bytes"] += Tm[l] * D * (4.0 * (S + 2) + (e if l + 1 < L else 0))
     w["T"] = T.tolist()
     return w
 
@@ -89,13 +96,25 @@ class Strategy:
         self.lengths0 = np.diff(self.tok_off) + np.diff(self.prm_off)
         reff, _ = ctx.trace_layout(self.lengths0, self.R)
         T_out = int(T0 - reff.sum())
-        self.ws = torch.empty(ctx.otas_workspace_bytes(cfg.B, T0), dtype=torch.uint8, device="cuda")
+        self.deep = None
+        if cfg.deep:   # per-layer prompting: prompts [L, sum P, D]; block 0 (layer 0) is what prepend inserts
+            assert all(r == 0 for r in self.R)
+            blocks = [prm_packed] + [synth.pack([synth.query_layer_prompts(cfg, q, l) for q in range(cfg.B)], D)[0]
+                                     for l in range(1, cfg.L)]
+            self.deep = torch.from_numpy(np.stack(blocks, axis=0)).to("cuda").to(ctx.torch_dtype).contiguous()
+            self.deep_mode = otas.OTAS_PROMPT_GROW if cfg.deep == "grow" else otas.OTAS_PROMPT_REPLACE
+            T_out = T0 + (cfg.L - 1) * int(self.prm_off[-1]) if cfg.deep == "grow" else T0
+        self.ws = torch.empty(ctx.otas_workspace_bytes(cfg.B, max(T0, T_out)), dtype=torch.uint8, device="cuda")
         self.x_out = torch.empty((T_out, D), dtype=torch.float32, device="cuda")
         self.sizes_out = torch.empty(T_out, dtype=torch.int32, device="cuda")
 
     def step(self):
         off = self.ctx.otas_prompt_prepend(self.t_tok, self.tok_off, self.t_prm, self.prm_off, self.x0)
-        self.ctx.otas_encoder_forward(self.x0, off, self.R, 0, self.ws, self.x_out, self.sizes_out)
+        if self.deep is not None:
+            self.ctx.otas_encoder_forward_deep(self.x0, off, self.deep_mode, self.deep, self.prm_off, self.ws,
+                                               self.x_out, self.sizes_out)
+        else:
+            self.ctx.otas_encoder_forward(self.x0, off, self.R, 0, self.ws, self.x_out, self.sizes_out)
 
     def time_steps(self, steps, warmup):
         import torch
@@ -227,7 +246,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="vitb_r16", choices=list(synth.CONFIG_NAMES))
-    ap.add_argument("--others", default="vitb_plain,vitb_p10_r8", help="further strategies reported per strategy")
+    ap.add_argument("--others", default="vitb_plain,vitb_p10_r8,vitb_deep10_replace,vitb_deep2_grow", help="further strategies reported per strategy")
     ap.add_argument("--cpu-queries", type=int, default=64)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--calibrate", action="store_true",
@@ -268,7 +287,8 @@ def main():
         mixed = len(set(r["cfg"].strategies)) > 1
         rf = rooflines(r)
         per_strategy[r["name"]] = {
-            "strategy": "mixed" if mixed else {"prompts": P, "r": R},
+            "strategy": "mixed" if mixed else ({"prompts": P, "r": R, "per_layer": r["cfg"].deep} if r["cfg"].deep
+                                               else {"prompts": P, "r": R}),
             "images_per_s": round(r["img_s"], 1), "ms_per_step": round(r["ms"], 4),
             "gemm_tflops": rf["gemm"]["achieved"],
             "merge_apply_gbs": rf.get("merge_apply", {}).get("achieved"),

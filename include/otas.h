@@ -184,6 +184,28 @@ otas_status otas_encoder_layers(otas_ctx *ctx, int32_t layer_begin, int32_t laye
                                 size_t workspace_bytes, void *x_out, int32_t *sizes_out,
                                 int32_t *offsets_out, int32_t *trace_src, int32_t *trace_dst);
 
+/* Per-layer prompting (Sec. III-B: the prompting module sits in front of the normalisation of
+ * EVERY layer; Sec. II-B: prompts "added per layer").  Two readings, both for batches that do not
+ * merge (Sec. III-B: a model performs either prompting or reduction during inference):
+ *   OTAS_PROMPT_REPLACE  before the normalisation of every layer l >= 1 the P_q prompt rows of query
+ *                        q (rows n_lead .. n_lead + P_q - 1) are overwritten with layer l's prompts;
+ *                        lengths stay n_q.
+ *   OTAS_PROMPT_GROW     before the normalisation of every layer l >= 1 P_q new prompt rows are
+ *                        inserted at row n_lead; query q enters layer l with n_q + l P_q rows.
+ *   x0      dev [T0, D]  tokens with layer 0's prompts already prepended (otas_prompt_prepend)
+ *   offsets host [B+1]   of x0;  prompt_offsets host [B+1]: P_q = difference, P = prompt_offsets[B]
+ *   prompts dev [L, P, D] model dtype: prompts[l] holds every query's rows for layer l in batch
+ *           order (prompts[0] is not read); may be NULL if P == 0
+ *   workspace dev >= otas_workspace_bytes(ctx, B, T_L), T_L = T0 (replace) or T0 + (L - 1) P (grow)
+ *   x_out   dev float [T_L, D], sizes_out dev [T_L] (all 1), offsets_out host [B+1]
+ * A query needs n_q >= n_lead + P_q; every length must stay <= OTAS_MAX_SEQ (EUNSUPPORTED). */
+enum { OTAS_PROMPT_REPLACE = 1, OTAS_PROMPT_GROW = 2 };
+otas_status otas_encoder_forward_deep(otas_ctx *ctx, const void *x0, const int32_t *offsets, int32_t B,
+                                      int32_t mode, const void *prompts,
+                                      const int32_t *prompt_offsets, void *workspace,
+                                      size_t workspace_bytes, void *x_out, int32_t *sizes_out,
+                                      int32_t *offsets_out);
+
 /* Individual steps of the path, exposed for parity tests and profiling.  All pointers dev,
  * model dtype, enqueued on the context's stream.
  *   otas_layer_norm: y[T,D] = LN(x[T,D]) with biased variance and the context's eps.

@@ -17,7 +17,7 @@ from typing import Dict, List, Optional, Sequence, Tuple
 
 import numpy as np
 
-_TAG_TOKENS, _TAG_PROMPTS, _TAG_WEIGHTS, _TAG_STRATEGY = 1, 2, 3, 4
+_TAG_TOKENS, _TAG_PROMPTS, _TAG_WEIGHTS, _TAG_STRATEGY, _TAG_LAYER_PROMPTS = 1, 2, 3, 4, 5
 
 WEIGHT_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
                 "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -38,6 +38,7 @@ class Config:
     seed: int = 0
     ln_eps: float = 1e-6
     n_lead: int = 1               # protected leading tokens (the CLS token)
+    deep: str = ""                # "", "replace" or "grow": per-layer prompting (r must be 0 then)
 
     @property
     def dh(self) -> int:
@@ -80,6 +81,10 @@ def config(name: str) -> Config:
         return Config(name, 12, 768, 12, 3072, "bf16", 64, 197, [(0, 16)] * 64, seed=1)
     if name == "vitb_p10_r8":
         return Config(name, 12, 768, 12, 3072, "bf16", 64, 197, [(10, 8)] * 64, seed=2)
+    if name == "vitb_deep10_replace":   # ten prompt rows, re-written with every layer's own prompts
+        return Config(name, 12, 768, 12, 3072, "bf16", 64, 197, [(10, 0)] * 64, seed=5, deep="replace")
+    if name == "vitb_deep2_grow":       # two prompts added in front of every layer: 199, 201, ..., 221 rows
+        return Config(name, 12, 768, 12, 3072, "bf16", 64, 197, [(2, 0)] * 64, seed=6, deep="grow")
     if name == "vitl_ragged":
         strat = [(10, 0)] * 32 + [(0, 8)] * 32 + [(0, 16)] * 32 + [(0, 24)] * 32
         return Config(name, 24, 1024, 16, 4096, "bf16", 128, 197, strat, seed=3)
@@ -88,7 +93,8 @@ def config(name: str) -> Config:
     raise KeyError(name)
 
 
-CONFIG_NAMES = ("tiny", "vitb_plain", "vitb_r16", "vitb_p10_r8", "vitl_ragged", "vith_mixed")
+CONFIG_NAMES = ("tiny", "vitb_plain", "vitb_r16", "vitb_p10_r8", "vitl_ragged", "vith_mixed",
+                "vitb_deep10_replace", "vitb_deep2_grow")
 
 
 def _maybe_round(a: np.ndarray, dtype: str) -> np.ndarray:
@@ -104,6 +110,14 @@ def query_prompts(cfg: Config, q: int) -> np.ndarray:
     """[P_q, D] float32 prompt rows of query q, i.i.d. N(0, std 0.02)."""
     P = cfg.strategies[q][0]
     return _maybe_round(0.02 * _rng(cfg.seed, _TAG_PROMPTS, q).standard_normal((P, cfg.D)), cfg.dtype)
+
+
+def query_layer_prompts(cfg: Config, q: int, l: int) -> np.ndarray:
+    """[P_q, D] float32 prompt rows of query q for layer l >= 1 (per-layer prompting; layer 0's rows
+    are query_prompts), i.i.d. N(0, std 0.02)."""
+    P = cfg.strategies[q][0]
+    g = _rng(cfg.seed, _TAG_LAYER_PROMPTS, q * 4096 + l)
+    return _maybe_round(0.02 * g.standard_normal((P, cfg.D)), cfg.dtype)
 
 
 def layer_weights(cfg: Config, l: int) -> Dict[str, np.ndarray]:

@@ -14,6 +14,7 @@ import numpy as np
 
 OTAS_F32, OTAS_BF16 = 0, 1
 OTAS_FLAG_SIZE_BIAS, OTAS_FLAG_TRACE = 1, 2
+OTAS_PROMPT_REPLACE, OTAS_PROMPT_GROW = 1, 2
 _WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
                   "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 
@@ -65,6 +66,7 @@ def load_library():
         "otas_token_merge": (i32, [vp, vp, vp, i32, vp, _I32P, _I32P, i32, vp, sz, vp, vp, _I32P, vp, vp]),
         "otas_encoder_forward": (i32, [vp, vp, _I32P, _I32P, i32, u32, vp, sz, vp, vp, _I32P, vp, vp]),
         "otas_encoder_layers": (i32, [vp, i32, i32, vp, vp, _I32P, _I32P, i32, u32, vp, sz, vp, vp, _I32P, vp, vp]),
+        "otas_encoder_forward_deep": (i32, [vp, vp, _I32P, i32, i32, vp, _I32P, vp, sz, vp, vp, _I32P]),
         "otas_layer_norm": (i32, [vp, vp, vp, vp, i64, vp]),
         "otas_linear": (i32, [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]),
         "otas_attention": (i32, [vp, vp, vp, _I32P, i32, u32, vp]),
@@ -87,7 +89,7 @@ def load_library():
 
 EXPORTED = ("otas_create", "otas_destroy", "otas_schedule", "otas_workspace_bytes",
             "otas_merge_workspace_bytes", "otas_prompt_prepend", "otas_token_merge",
-            "otas_encoder_forward", "otas_encoder_layers", "otas_layer_norm", "otas_linear", "otas_attention", "otas_strerror",
+            "otas_encoder_forward", "otas_encoder_layers", "otas_encoder_forward_deep", "otas_layer_norm", "otas_linear", "otas_attention", "otas_strerror",
             "otas_timing_enable", "otas_timing_kinds", "otas_timing_kind_name", "otas_timing_read",
             "otas_timing_read_launches", "otas_timing_overhead_ms", "otas_set_lanes", "otas_splitk_factor")
 
@@ -212,6 +214,19 @@ class Context:
                                              flags, _ptr(workspace), workspace.numel() * workspace.element_size(),
                                              _ptr(x_out), _ptr(sizes_out), oo.ctypes.data_as(_I32P),
                                              _ptr(trace_src), _ptr(trace_dst)), "otas_encoder_layers")
+        return oo
+
+    def otas_encoder_forward_deep(self, x0, offsets, mode, prompts, prompt_offsets, workspace, x_out,
+                                  sizes_out) -> np.ndarray:
+        """Per-layer prompting (mode OTAS_PROMPT_REPLACE / OTAS_PROMPT_GROW); prompts [L, P, D]."""
+        B = len(offsets) - 1
+        oa, op = _i32(offsets)
+        pa, pp = _i32(prompt_offsets)
+        oo = np.zeros(B + 1, dtype=np.int32)
+        _check(self._lib.otas_encoder_forward_deep(self._h, _ptr(x0), op, B, int(mode), _ptr(prompts), pp,
+                                                   _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                                   _ptr(x_out), _ptr(sizes_out), oo.ctypes.data_as(_I32P)),
+               "otas_encoder_forward_deep")
         return oo
 
     def otas_layer_norm(self, x, g, b, T, y) -> None:

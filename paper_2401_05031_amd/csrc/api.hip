@@ -660,6 +660,102 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
 
 extern "C" {
 
+otas_status otas_encoder_forward_deep(otas_ctx* c, const void* x0, const int32_t* offsets, int32_t B, int32_t mode,
+                                      const void* prompts, const int32_t* prompt_offsets, void* workspace,
+                                      size_t workspace_bytes, void* x_out, int32_t* sizes_out, int32_t* offsets_out) {
+  if (!c || !x0 || !offsets || !prompt_offsets || !workspace || !x_out || !sizes_out || !offsets_out || B <= 0)
+    return OTAS_EINVAL;
+  if (mode != OTAS_PROMPT_REPLACE && mode != OTAS_PROMPT_GROW) return OTAS_EINVAL;
+  if (!offsets_ok(offsets, B) || !offsets_ok(prompt_offsets, B)) return OTAS_EINVAL;
+  if (x_out == x0 || ((uintptr_t)workspace) % kAlign != 0) return OTAS_EINVAL;
+  const bool grow = mode == OTAS_PROMPT_GROW;
+  const otas_model_desc& d = c->desc;
+  const int L = d.L, D = d.D, H = d.H, F = d.F, n_lead = d.n_lead, dt = d.dtype;
+  const int64_t T0 = offsets[B];
+  const int P_total = prompt_offsets[B];
+  if (T0 <= 0) return OTAS_EINVAL;
+  if (P_total > 0 && !prompts) return OTAS_EINVAL;
+
+  // Length schedule: constant (replace) or + P_q per layer (grow); x0 holds layer 0's prompts.
+  // Plan layout (int32): off[l][B+1] for l = 0..L-1 | prompt offsets [B+1].
+  std::vector<int32_t> plan((size_t)(L + 1) * (B + 1));
+  std::vector<int> max_n(L, 0);
+  int max_p = 0;
+  for (int l = 0; l < L; ++l) {
+    int32_t* off = &plan[(size_t)l * (B + 1)];
+    off[0] = 0;
+    for (int q = 0; q < B; ++q) {
+      const int n = offsets[q + 1] - offsets[q], P = prompt_offsets[q + 1] - prompt_offsets[q];
+      if (n <= 0 || n < n_lead + P) return OTAS_EINVAL;   // x0 must already hold the P rows of layer 0
+      const int nl = n + (grow ? l * P : 0);
+      if (nl > OTAS_MAX_SEQ) return OTAS_EUNSUPPORTED;
+      off[q + 1] = off[q] + nl;
+      max_n[l] = std::max(max_n[l], nl);
+      max_p = std::max(max_p, P);
+    }
+  }
+  std::memcpy(&plan[(size_t)L * (B + 1)], prompt_offsets, (B + 1) * sizeof(int32_t));
+  const int32_t* off_last = &plan[(size_t)(L - 1) * (B + 1)];
+  const int64_t T_max = off_last[B];
+  const WorkspaceLayout w = forward_layout(d, T_max);
+  if (workspace_bytes < w.total) return OTAS_ENOMEM;
+  {
+    const char* ws = (const char*)workspace;
+    const char* xo = (const char*)x_out;
+    if (xo >= ws && xo < ws + w.total) return OTAS_EINVAL;
+  }
+  std::memcpy(offsets_out, off_last, (B + 1) * sizeof(int32_t));
+
+  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
+  otas_status st = upload_plan(c, plan);
+  if (st != OTAS_OK) return st;
+  hipStream_t s = c->stream;
+  char* ws = (char*)workspace;
+  float* x_buf[2] = {(float*)(ws + w.xa), (float*)(ws + w.xb)};
+  void* hbuf = ws + w.h;
+  void* qkv = ws + w.qkv;
+  void* hid = ws + w.hid;
+  const int32_t* d_prm_off = c->d_plan + (size_t)L * (B + 1);
+  const size_t es = elem_size(dt);
+
+  const float* x_cur = (const float*)x0;   // float residual stream entering the block
+  int cur = -1;                            // which workspace buffer holds x_cur (-1: the caller's x0)
+  if (dt != OTAS_F32) {                    // 16-bit tokens: widen once into the workspace
+    OTAS_LAUNCH(K_MISC, launch_widen(x0, x_buf[0], T0 * D, s));
+    x_cur = x_buf[0];
+    cur = 0;
+  }
+  for (int l = 0; l < L; ++l) {
+    const otas_layer_weights& wl = c->layers[l];
+    const int32_t* off_l = c->d_plan + (size_t)l * (B + 1);
+    const int64_t T = plan[(size_t)l * (B + 1) + B];
+    if (l >= 1 && P_total > 0) {   // prompting module (cur >= 0 here: layer 0 wrote into the workspace)
+      const char* pl = (const char*)prompts + (size_t)l * P_total * D * es;
+      if (grow) {
+        OTAS_LAUNCH(K_PREPEND, launch_deep_prompt(dt, x_cur, x_buf[cur ^ 1], pl, off_l - (B + 1), off_l, d_prm_off, B,
+                                                  max_n[l], D, n_lead, true, s));
+        cur ^= 1;
+        x_cur = x_buf[cur];
+      } else {
+        OTAS_LAUNCH(K_PREPEND, launch_deep_prompt(dt, x_cur, x_buf[cur], pl, off_l, off_l, d_prm_off, B, max_p, D,
+                                                  n_lead, false, s));
+      }
+    }
+    OTAS_LAUNCH(K_LN, launch_layer_norm(dt, true, x_cur, wl.ln1_g, wl.ln1_b, hbuf, T, D, d.ln_eps, s));
+    OTAS_LAUNCH(K_QKV, launch_linear(dt, hbuf, wl.w_qkv, wl.b_qkv, nullptr, qkv, T, 3 * D, D, EPI_NONE, s));
+    OTAS_LAUNCH(K_ATTN, launch_attention(dt, qkv, nullptr, off_l, B, max_n[l], D, H, false, hbuf, s));
+    if (cur < 0) cur = 0;   // the caller's x0 is never written: layer 0 of an f32 model writes into the workspace
+    OTAS_LAUNCH(K_PROJ, launch_linear(dt, hbuf, wl.w_proj, wl.b_proj, x_cur, x_buf[cur], T, D, D, EPI_RESIDUAL, s));
+    x_cur = x_buf[cur];
+    OTAS_LAUNCH(K_LN, launch_layer_norm(dt, true, x_cur, wl.ln2_g, wl.ln2_b, hbuf, T, D, d.ln_eps, s));
+    OTAS_LAUNCH(K_FC1, launch_linear(dt, hbuf, wl.w_fc1, wl.b_fc1, nullptr, hid, T, F, D, EPI_GELU, s));
+    void* x_next = (l == L - 1) ? x_out : (void*)x_buf[cur];
+    OTAS_LAUNCH(K_FC2, launch_linear(dt, hid, wl.w_fc2, wl.b_fc2, x_cur, x_next, T, D, F, EPI_RESIDUAL, s));
+  }
+  OTAS_LAUNCH(K_MISC, launch_fill_i32(sizes_out, 1, T_max, s));
+  return OTAS_OK;
+}
+
 otas_status otas_layer_norm(otas_ctx* c, const void* x, const void* g, const void* b, int64_t T, void* y) {
   if (!c || !x || !g || !b || !y || T < 0) return OTAS_EINVAL;
   if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;

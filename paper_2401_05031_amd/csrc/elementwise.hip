@@ -70,6 +70,55 @@ hipError_t launch_prepend(int dtype, const void* tokens, const void* prompts, vo
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------- per-layer prompting
+// The prompting module in front of a layer l >= 1 (Sec. III-B: it sits before the normalisation of
+// every layer), on the float residual stream.  grow = false: rows n_lead .. n_lead + P - 1 of every
+// query are overwritten with this layer's prompts (x_new == x_old, only those rows are touched).
+// grow = true: the P prompts are inserted at row n_lead, the old rows are copied around them into
+// x_new (a different buffer; old_off / new_off are the packed offsets before and after).
+// 4 floats per thread; blockIdx.y = query.
+template <typename T>
+__global__ void deep_prompt_kernel(const float* __restrict__ x_old, float* __restrict__ x_new,
+                                   const T* __restrict__ prompts, const int32_t* __restrict__ old_off,
+                                   const int32_t* __restrict__ new_off, const int32_t* __restrict__ prm_off,
+                                   int D, int n_lead, bool grow) {
+  const int q = blockIdx.y;
+  const int p0 = prm_off[q], P = prm_off[q + 1] - p0;
+  const int o0 = new_off[q], n_new = new_off[q + 1] - o0, i0 = old_off[q];
+  const int chunks = D / 4;
+  const int first = grow ? 0 : n_lead, rows = grow ? n_new : P;   // rows this launch writes
+  for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < rows * chunks; t += gridDim.x * blockDim.x) {
+    const int i = first + t / chunks, c = (t % chunks) * 4;
+    Vec<float> v;
+    if (i >= n_lead && i < n_lead + P) {
+      const T* src = prompts + (size_t)(p0 + i - n_lead) * D + c;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) v.set(k, to_float(src[k]));
+    } else {
+      v = load_vec<float>(x_old + (size_t)(i0 + (i < n_lead ? i : i - P)) * D + c);
+    }
+    store_vec<float>(x_new + (size_t)(o0 + i) * D + c, v);
+  }
+}
+
+hipError_t launch_deep_prompt(int dtype, const float* x_old, float* x_new, const void* prompts,
+                              const int32_t* d_old_off, const int32_t* d_new_off, const int32_t* d_prm_off, int B,
+                              int max_rows, int D, int n_lead, bool grow, hipStream_t s) {
+  if (B <= 0 || max_rows <= 0) return hipSuccess;
+  if (D % 4 != 0 || (grow && x_old == x_new)) return hipErrorInvalidValue;
+  const int64_t tasks = (int64_t)max_rows * (D / 4);
+  unsigned gx = (unsigned)((tasks + 255) / 256);
+  if (gx > 64) gx = 64;
+  dim3 grid(gx, B), block(256);
+  if (dtype == 0)
+    deep_prompt_kernel<float><<<grid, block, 0, s>>>(x_old, x_new, (const float*)prompts, d_old_off, d_new_off,
+                                                     d_prm_off, D, n_lead, grow);
+  else
+    deep_prompt_kernel<bf16_t><<<grid, block, 0, s>>>(x_old, x_new, (const bf16_t*)prompts, d_old_off, d_new_off,
+                                                      d_prm_off, D, n_lead, grow);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------- LayerNorm
 // One wave per row, the row held in registers (NCH 16-byte chunks per lane), two-pass statistics
 // in fp32 (mean, then the biased variance of the centred values).

@@ -16,6 +16,14 @@ hipError_t launch_prepend(int dtype, const void* tokens, const void* prompts, vo
                           const int32_t* d_out_off, int B, int max_n_out, int D, int n_lead,
                           hipStream_t s);
 
+// Prompting module in front of a layer l >= 1 on the float residual stream: overwrite the P prompt
+// rows of every query in place (grow = false, x_new == x_old) or insert P rows at n_lead while
+// copying into another buffer (grow = true).  prompts: this layer's rows, model dtype.  max_rows:
+// the largest number of rows one query writes (P, or its new length).
+hipError_t launch_deep_prompt(int dtype, const float* x_old, float* x_new, const void* prompts,
+                              const int32_t* d_old_off, const int32_t* d_new_off, const int32_t* d_prm_off, int B,
+                              int max_rows, int D, int n_lead, bool grow, hipStream_t s);
+
 // x_is_float: the input rows are float (the residual stream) even when dtype is bf16.
 hipError_t launch_layer_norm(int dtype, bool x_is_float, const void* x, const void* g, const void* b,
                              void* y, int64_t T, int D, float eps, hipStream_t s);

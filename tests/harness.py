@@ -156,3 +156,50 @@ def compare_per_layer(ctx, cfg, layers_host, toks, prm, r, size_bias: bool = Fal
                 sizes_equal = sizes_equal and np.array_equal(g["sizes"][q], want_s)
                 max_err = max(max_err, rel_err(g["x"][q], taps[q]["x_out"][l]))
     return {"decisions": dec, "disagreements": dis, "max_err": max_err, "sizes_equal": sizes_equal}
+
+
+def deep_prompt_tensor(cfg: synth.Config, queries: Sequence[int]):
+    """Host array [L, sum P_q, D] of the per-layer prompts of the given queries (row block l = layer l's
+    prompts of every query in order; block 0 repeats layer 0's prompts, which the library does not
+    read) and the prompt offsets [len(queries) + 1]."""
+    blocks = []
+    for l in range(cfg.L):
+        rows = [synth.query_prompts(cfg, q) if l == 0 else synth.query_layer_prompts(cfg, q, l) for q in queries]
+        blocks.append(np.concatenate(rows, axis=0) if rows else np.zeros((0, cfg.D), dtype=np.float32))
+    poff = np.concatenate([[0], np.cumsum([cfg.strategies[q][0] for q in queries])]).astype(np.int32)
+    return np.stack(blocks, axis=0), poff
+
+
+def gpu_forward_deep(ctx, cfg: synth.Config, queries: Sequence[int], mode: str):
+    """otas_prompt_prepend + otas_encoder_forward_deep for the given queries.  Returns per-query
+    outputs (float64) and the output offsets."""
+    import torch
+    import paper_2401_05031_amd as otas
+    toks = [synth.query_tokens(cfg, q) for q in queries]
+    prm0 = [synth.query_prompts(cfg, q) for q in queries]
+    x0, off = gpu_prepend(ctx, toks, prm0)
+    deep, poff = deep_prompt_tensor(cfg, queries)
+    t_deep = torch.from_numpy(deep).to("cuda").to(ctx.torch_dtype).contiguous()
+    grow = mode == "grow"
+    T0 = int(off[-1])
+    T_L = T0 + (cfg.L - 1) * int(poff[-1]) if grow else T0
+    ws = torch.empty(ctx.otas_workspace_bytes(len(queries), T_L), dtype=torch.uint8, device="cuda")
+    x_out = torch.full((T_L, cfg.D), float("nan"), dtype=torch.float32, device="cuda")
+    sizes = torch.zeros(T_L, dtype=torch.int32, device="cuda")
+    out_off = ctx.otas_encoder_forward_deep(x0, off, otas.OTAS_PROMPT_GROW if grow else otas.OTAS_PROMPT_REPLACE,
+                                            t_deep if deep.shape[1] else None, poff, ws, x_out, sizes)
+    torch.cuda.synchronize()
+    xo = x_out.cpu().numpy().astype(np.float64)
+    so = sizes.cpu().numpy()
+    return {"x": [xo[out_off[i]:out_off[i + 1]] for i in range(len(queries))],
+            "sizes": [so[out_off[i]:out_off[i + 1]] for i in range(len(queries))], "offsets": out_off}
+
+
+def oracle_forward_deep(cfg: synth.Config, layers_host, queries: Sequence[int], mode: str):
+    outs = []
+    for q in queries:
+        x0, _ = orc.prompt_prepend(synth.query_tokens(cfg, q), synth.query_prompts(cfg, q), cfg.n_lead)
+        deep = [None] + [synth.query_layer_prompts(cfg, q, l) for l in range(1, cfg.L)]
+        outs.append(orc.encoder_forward_query(x0, layers_host, 0, H=cfg.H, ln_eps=cfg.ln_eps, n_lead=cfg.n_lead,
+                                              storage=storage_of(cfg), deep_prompts=deep, deep_mode=mode))
+    return outs

@@ -584,3 +584,71 @@ def test_per_launch_timing_api(torch_cuda, lib):
     for q in range(cfg.B):
         assert np.array_equal(got["x"][q], ref["x"][q]) and np.array_equal(got["sizes"][q], ref["sizes"][q])
     ctx.close()
+
+
+@pytest.mark.parametrize("mode", ["replace", "grow"])
+def test_per_layer_prompting_f32(torch_cuda, lib, mode):
+    """otas_encoder_forward_deep in fp32 against the oracle: a ragged batch in which queries carry
+    different prompt counts (one none at all), four layers so that the replaced / inserted rows pass
+    through several prompting steps."""
+    cfg = synth.config("tiny")
+    cfg.L = 4
+    cfg.B = 4
+    cfg.strategies = [(4, 0), (0, 0), (7, 0), (1, 0)]
+    cfg.deep = mode
+    ctx, layers = hz.make_context(cfg)
+    qs = [0, 1, 2, 3]
+    gpu = hz.gpu_forward_deep(ctx, cfg, qs, mode)
+    ref = hz.oracle_forward_deep(cfg, layers, qs, mode)
+    for i, q in enumerate(qs):
+        P = cfg.strategies[q][0]
+        want = orc.deep_length_schedule(cfg.n0, P, cfg.L, mode)[-1]
+        assert gpu["x"][i].shape == ref[i]["x"].shape == (want, cfg.D)
+        assert np.all(gpu["sizes"][i] == 1)
+        assert hz.rel_err(gpu["x"][i], ref[i]["x"]) <= F32_TOL, (mode, q)
+    ctx.close()
+
+
+@pytest.mark.parametrize("name", ["vitb_deep10_replace", "vitb_deep2_grow"])
+def test_per_layer_prompting_bf16_full_batch(torch_cuda, lib, name):
+    """The ViT-B per-layer prompting workloads at full batch (the launch configuration bench.py times),
+    sampled queries against the oracle."""
+    cfg = synth.config(name)
+    ctx, layers = hz.make_context(cfg)
+    gpu = hz.gpu_forward_deep(ctx, cfg, list(range(cfg.B)), cfg.deep)
+    sample = [0, 29, 63]
+    ref = hz.oracle_forward_deep(cfg, layers, sample, cfg.deep)
+    for i, q in enumerate(sample):
+        assert gpu["x"][q].shape == ref[i]["x"].shape
+        err = hz.rel_err(gpu["x"][q], ref[i]["x"])
+        print(name, "query", q, "rel err", err)
+        assert err <= BF16_TOL
+    ctx.close()
+
+
+def test_per_layer_prompting_argument_errors(torch_cuda, lib):
+    torch = torch_cuda
+    cfg = synth.config("tiny")
+    ctx, layers = hz.make_context(cfg)
+    x0 = torch.zeros((10, cfg.D), dtype=torch.float32, device="cuda")
+    pr = torch.zeros((cfg.L, 3, cfg.D), dtype=torch.float32, device="cuda")
+    ws = torch.empty(ctx.otas_workspace_bytes(1, 64), dtype=torch.uint8, device="cuda")
+    xo = torch.empty((64, cfg.D), dtype=torch.float32, device="cuda")
+    so = torch.empty(64, dtype=torch.int32, device="cuda")
+    for bad_mode in (0, 3):
+        with pytest.raises(lib.OtasError) as e:
+            ctx.otas_encoder_forward_deep(x0, [0, 10], bad_mode, pr, [0, 3], ws, xo, so)
+        assert e.value.status == 1
+    with pytest.raises(lib.OtasError) as e:      # more prompt rows than the query holds
+        ctx.otas_encoder_forward_deep(x0, [0, 3], lib.OTAS_PROMPT_REPLACE, pr, [0, 3], ws, xo, so)
+    assert e.value.status == 1
+    with pytest.raises(lib.OtasError) as e:      # prompts missing
+        ctx.otas_encoder_forward_deep(x0, [0, 10], lib.OTAS_PROMPT_GROW, None, [0, 3], ws, xo, so)
+    assert e.value.status == 1
+    with pytest.raises(lib.OtasError) as e:      # workspace too small for the grown sequence
+        ctx.otas_encoder_forward_deep(x0, [0, 10], lib.OTAS_PROMPT_GROW, pr, [0, 3], ws[:4096], xo, so)
+    assert e.value.status == 3
+    off = ctx.otas_encoder_forward_deep(x0, [0, 10], lib.OTAS_PROMPT_GROW, pr, [0, 3], ws, xo, so)
+    torch.cuda.synchronize()
+    assert off.tolist() == [0, 10 + 3 * (cfg.L - 1)]
+    ctx.close()
