@@ -33,6 +33,9 @@ Readings taken where the paper is silent (each is also listed in the design note
       every Linear, no final norm and no head: the encoder is the stack of blocks.
   R10 optional size bias: + ln(size_j) on the logits of key j (not defined by the paper; off
       unless asked for; with all sizes 1 it changes nothing).
+  R14 model ends (Sec. II-A vision transformer, Sec. III-B task heads): patches are taken row by
+      row, flattened channel-major, projected linearly; [class token | patch tokens] + position
+      embedding; the head of a query's task reads LayerNorm_final(first token).
   R13 per-layer prompting (Sec. III-B puts the prompting module in front of the normalisation
       of EVERY layer and counts gamma "per layer"; Sec. II-B speaks of prompts "added per layer"):
       two further readings next to R8, both only for queries that do not merge (Sec. III-B: a
@@ -140,6 +143,49 @@ def deep_prompt_step(x: np.ndarray, sizes: np.ndarray, prompts: np.ndarray, n_le
         return (np.concatenate([x[:n_lead], prompts, x[n_lead:]], axis=0),
                 np.concatenate([sizes[:n_lead], np.ones(P, dtype=sizes.dtype), sizes[n_lead:]]))
     raise ValueError(mode)
+
+
+# ----------------------------------------------------------------------------- model ends
+def patch_embed(image: np.ndarray, w_patch: np.ndarray, b_patch: np.ndarray, cls: Optional[np.ndarray],
+                pos: np.ndarray, patch: int, storage: str = "f64") -> np.ndarray:
+    """Sec. II-A (vision transformer): the image [C, Hi, Wi] is split into fixed-size patches (row
+    by row, left to right), every patch is flattened (channel, then row, then column: the layout of
+    a [D, C, p, p] projection weight) and projected linearly; the class token goes in front (if the
+    model has one) and the position embedding pos[1 + N, D] (or [N, D] without class token) is added
+    to every row.  Returns tokens [n_lead + N, D].  storage: where the HIP path stores a tensor
+    (patch matrix, projection output, tokens) the value is rounded accordingly."""
+    img = np.asarray(image, dtype=np.float64)
+    C, Hi, Wi = img.shape
+    p = int(patch)
+    if Hi % p or Wi % p:
+        raise ValueError("image size must be a multiple of the patch size")
+    nh, nw = Hi // p, Wi // p
+    rows = []
+    for py in range(nh):
+        for px in range(nw):
+            rows.append(img[:, py * p:(py + 1) * p, px * p:(px + 1) * p].reshape(-1))
+    pm = round_storage(np.stack(rows, axis=0), storage)                       # [N, C p p]
+    W = np.asarray(w_patch, dtype=np.float64).reshape(-1, C * p * p)
+    proj = round_storage(pm @ W.T + np.asarray(b_patch, dtype=np.float64), storage)
+    pos = np.asarray(pos, dtype=np.float64)
+    if cls is not None:
+        seq = np.concatenate([np.asarray(cls, dtype=np.float64).reshape(1, -1), proj], axis=0)
+    else:
+        seq = proj
+    if pos.shape != seq.shape:
+        raise ValueError("position embedding must have one row per token")
+    return round_storage(seq + pos, storage)
+
+
+def task_head(x: np.ndarray, lnf_g: np.ndarray, lnf_b: np.ndarray, w_head: np.ndarray, b_head: np.ndarray,
+              eps: float, storage: str = "f64") -> np.ndarray:
+    """Sec. III-B / IV: every task has its own head parameters and a query is forwarded to the head of
+    its task.  The head reads the first token of the encoder output (the class token) after a final
+    LayerNorm (the vision transformer's, Sec. II-A): logits = W_task LN(x[0]) + b_task."""
+    h = layer_norm(np.asarray(x, dtype=np.float64)[:1], np.asarray(lnf_g, dtype=np.float64),
+                   np.asarray(lnf_b, dtype=np.float64), eps)
+    h = round_storage(h, storage)
+    return (h @ np.asarray(w_head, dtype=np.float64).T + np.asarray(b_head, dtype=np.float64))[0]
 
 
 # ----------------------------------------------------------------------------- encoder pieces

@@ -451,3 +451,47 @@ def test_per_layer_prompting_pins_catch_planted_mistakes(monkeypatch):
     monkeypatch.setattr(orc, "deep_prompt_step", appended)
     bad = orc.encoder_forward_query(x0, off, 0, H=H, ln_eps=1e-6, n_lead=1, deep_prompts=prm, deep_mode="grow")
     assert not np.array_equal(bad["x"], want_grw)
+
+
+# ------------------------------------------------------------------ model ends (R14)
+@pytest.mark.parametrize("with_cls", [True, False])
+def test_patch_embed_matches_library_convolution(with_cls):
+    """Splitting into p x p patches and projecting linearly is a convolution with kernel = stride = p
+    (torch.nn.functional.conv2d, float64); class token and position embedding placed by hand."""
+    rng = np.random.default_rng(21)
+    C, Hi, Wi, p, D = 3, 8, 12, 4, 10
+    img = rng.standard_normal((C, Hi, Wi))
+    w = rng.standard_normal((D, C, p, p))
+    b = rng.standard_normal(D)
+    cls = rng.standard_normal(D) if with_cls else None
+    N = (Hi // p) * (Wi // p)
+    pos = rng.standard_normal((N + (1 if with_cls else 0), D))
+    got = orc.patch_embed(img, w, b, cls, pos, p)
+    conv = torch.nn.functional.conv2d(torch.from_numpy(img)[None], torch.from_numpy(w), torch.from_numpy(b), stride=p)
+    ref = conv[0].flatten(1).T.numpy()          # [N, D], patches row by row
+    if with_cls:
+        ref = np.concatenate([cls[None], ref], axis=0)
+    ref = ref + pos
+    assert got.shape == ref.shape
+    assert np.max(np.abs(got - ref)) <= 1e-12 * max(1.0, np.max(np.abs(ref)))
+    # a planted mistake (patches walked column by column) is caught on a non-square patch grid
+    wrong = orc.patch_embed(img.transpose(0, 2, 1), w.transpose(0, 1, 3, 2), b, cls, pos, p)
+    assert not np.allclose(wrong, ref)
+    with pytest.raises(ValueError):
+        orc.patch_embed(img[:, :7], w, b, cls, pos, p)
+
+
+def test_task_head_matches_library_norm_and_linear():
+    rng = np.random.default_rng(22)
+    n, D, K = 6, 12, 5
+    x = rng.standard_normal((n, D))
+    g, bb = 1 + 0.1 * rng.standard_normal(D), 0.1 * rng.standard_normal(D)
+    w, b = rng.standard_normal((K, D)), rng.standard_normal(K)
+    got = orc.task_head(x, g, bb, w, b, 1e-6)
+    t = torch.nn.functional.layer_norm(torch.from_numpy(x[0]), (D,), torch.from_numpy(g), torch.from_numpy(bb), 1e-6)
+    ref = torch.nn.functional.linear(t, torch.from_numpy(w), torch.from_numpy(b)).numpy()
+    assert got.shape == (K,)
+    assert np.max(np.abs(got - ref)) <= 1e-12 * max(1.0, np.max(np.abs(ref)))
+    # only the first token counts
+    x2 = x.copy(); x2[1:] += 1.0
+    assert np.array_equal(orc.task_head(x2, g, bb, w, b, 1e-6), got)
