@@ -206,6 +206,36 @@ otas_status otas_encoder_forward_deep(otas_ctx *ctx, const void *x0, const int32
                                       size_t workspace_bytes, void *x_out, int32_t *sizes_out,
                                       int32_t *offsets_out);
 
+/* Model ends (Sec. II-A: the image is split into fixed-size patches, projected linearly and added
+ * to the position embedding; Sec. III-B / IV: every task has its own head parameters and a query is
+ * forwarded to the head of its task).
+ * otas_patch_embed: images dev [B, C, Hi, Wi] (model dtype) -> tokens dev [B (n_lead + N), D],
+ *   N = (Hi / patch)(Wi / patch) patches taken row by row, each flattened channel-major (the layout
+ *   of a [D, C, patch, patch] projection weight w_patch, bias b_patch [D]); the class token cls [D]
+ *   goes in front when n_lead = 1 (NULL allowed when n_lead = 0); pos [n_lead + N, D] is added to
+ *   every row.  tok_offsets host [B+1] is filled.  workspace dev >=
+ *   otas_patch_embed_workspace_bytes (patch matrix + projection).  Hi, Wi multiples of patch
+ *   (EINVAL), C patch^2 % 8 == 0 and n_lead + N <= OTAS_MAX_SEQ (EUNSUPPORTED).
+ * otas_task_heads: logits[q, k] = W_t LN_final(x[offsets[q]]) + b_t for t = task[q], k < classes_t,
+ *   0 for classes_t <= k < k_max.  x dev float [T, D] (the encoder's output), offsets / task host,
+ *   heads host [n_tasks] of dev pointers (w [classes, D], b [classes], model dtype), lnf_g / lnf_b
+ *   dev [D], logits dev float [B, k_max]. */
+typedef struct {
+  const void *w;
+  const void *b;
+  int32_t classes;
+} otas_task_head;
+size_t otas_patch_embed_workspace_bytes(const otas_ctx *ctx, int32_t B, int32_t C, int32_t Hi,
+                                        int32_t Wi, int32_t patch);
+otas_status otas_patch_embed(otas_ctx *ctx, const void *images, int32_t B, int32_t C, int32_t Hi,
+                             int32_t Wi, int32_t patch, const void *w_patch, const void *b_patch,
+                             const void *cls, const void *pos, void *workspace,
+                             size_t workspace_bytes, void *tokens, int32_t *tok_offsets);
+otas_status otas_task_heads(otas_ctx *ctx, const float *x, const int32_t *offsets,
+                            const int32_t *task, int32_t B, const otas_task_head *heads,
+                            int32_t n_tasks, const void *lnf_g, const void *lnf_b, float *logits,
+                            int32_t k_max);
+
 /* Individual steps of the path, exposed for parity tests and profiling.  All pointers dev,
  * model dtype, enqueued on the context's stream.
  *   otas_layer_norm: y[T,D] = LN(x[T,D]) with biased variance and the context's eps.

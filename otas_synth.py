@@ -17,7 +17,7 @@ from typing import Dict, List, Optional, Sequence, Tuple
 
 import numpy as np
 
-_TAG_TOKENS, _TAG_PROMPTS, _TAG_WEIGHTS, _TAG_STRATEGY, _TAG_LAYER_PROMPTS = 1, 2, 3, 4, 5
+_TAG_TOKENS, _TAG_PROMPTS, _TAG_WEIGHTS, _TAG_STRATEGY, _TAG_LAYER_PROMPTS, _TAG_IMAGES, _TAG_ENDS = 1, 2, 3, 4, 5, 6, 7
 
 WEIGHT_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
                 "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
@@ -118,6 +118,26 @@ def query_layer_prompts(cfg: Config, q: int, l: int) -> np.ndarray:
     P = cfg.strategies[q][0]
     g = _rng(cfg.seed, _TAG_LAYER_PROMPTS, q * 4096 + l)
     return _maybe_round(0.02 * g.standard_normal((P, cfg.D)), cfg.dtype)
+
+
+def query_image(cfg: Config, q: int, C: int, Hi: int, Wi: int) -> np.ndarray:
+    """[C, Hi, Wi] float32 image of query q, i.i.d. N(0,1) (stands in for a normalised picture)."""
+    return _maybe_round(_rng(cfg.seed, _TAG_IMAGES, q).standard_normal((C, Hi, Wi)), cfg.dtype)
+
+
+def ends_weights(cfg: Config, C: int, patch: int, n_patches: int, classes: Sequence[int]) -> Dict[str, np.ndarray]:
+    """Parameters of the model ends: patch projection [D, C p p] + bias, class token, position
+    embedding [n_lead + N, D], final LayerNorm, one head [K_t, D] + bias per task; N(0, std 0.02),
+    LayerNorm scale 1, shift 0."""
+    g = _rng(cfg.seed, _TAG_ENDS, 0)
+    D = cfg.D
+    w = {"w_patch": 0.02 * g.standard_normal((D, C * patch * patch)), "b_patch": 0.02 * g.standard_normal(D),
+         "cls": 0.02 * g.standard_normal(D), "pos": 0.02 * g.standard_normal((cfg.n_lead + n_patches, D)),
+         "lnf_g": np.ones(D), "lnf_b": np.zeros(D)}
+    for t, K in enumerate(classes):
+        w[f"head_w{t}"] = 0.02 * g.standard_normal((K, D))
+        w[f"head_b{t}"] = 0.02 * g.standard_normal(K)
+    return {k: _maybe_round(v, cfg.dtype) for k, v in w.items()}
 
 
 def layer_weights(cfg: Config, l: int) -> Dict[str, np.ndarray]:

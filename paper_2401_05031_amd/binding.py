@@ -25,6 +25,10 @@ class OtasError(RuntimeError):
         super().__init__(f"{where}: {otas_strerror(status)} (status {status})")
 
 
+class _TaskHead(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("b", C.c_void_p), ("classes", C.c_int32)]
+
+
 class _ModelDesc(C.Structure):
     _fields_ = [("L", C.c_int32), ("D", C.c_int32), ("H", C.c_int32), ("F", C.c_int32),
                 ("dtype", C.c_int32), ("ln_eps", C.c_float), ("n_lead", C.c_int32)]
@@ -67,6 +71,9 @@ def load_library():
         "otas_encoder_forward": (i32, [vp, vp, _I32P, _I32P, i32, u32, vp, sz, vp, vp, _I32P, vp, vp]),
         "otas_encoder_layers": (i32, [vp, i32, i32, vp, vp, _I32P, _I32P, i32, u32, vp, sz, vp, vp, _I32P, vp, vp]),
         "otas_encoder_forward_deep": (i32, [vp, vp, _I32P, i32, i32, vp, _I32P, vp, sz, vp, vp, _I32P]),
+        "otas_patch_embed_workspace_bytes": (sz, [vp, i32, i32, i32, i32, i32]),
+        "otas_patch_embed": (i32, [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp, _I32P]),
+        "otas_task_heads": (i32, [vp, vp, _I32P, _I32P, i32, C.POINTER(_TaskHead), i32, vp, vp, vp, i32]),
         "otas_layer_norm": (i32, [vp, vp, vp, vp, i64, vp]),
         "otas_linear": (i32, [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]),
         "otas_attention": (i32, [vp, vp, vp, _I32P, i32, u32, vp]),
@@ -89,7 +96,7 @@ def load_library():
 
 EXPORTED = ("otas_create", "otas_destroy", "otas_schedule", "otas_workspace_bytes",
             "otas_merge_workspace_bytes", "otas_prompt_prepend", "otas_token_merge",
-            "otas_encoder_forward", "otas_encoder_layers", "otas_encoder_forward_deep", "otas_layer_norm", "otas_linear", "otas_attention", "otas_strerror",
+            "otas_encoder_forward", "otas_encoder_layers", "otas_encoder_forward_deep", "otas_patch_embed_workspace_bytes", "otas_patch_embed", "otas_task_heads", "otas_layer_norm", "otas_linear", "otas_attention", "otas_strerror",
             "otas_timing_enable", "otas_timing_kinds", "otas_timing_kind_name", "otas_timing_read",
             "otas_timing_read_launches", "otas_timing_overhead_ms", "otas_set_lanes", "otas_splitk_factor")
 
@@ -228,6 +235,30 @@ class Context:
                                                    _ptr(x_out), _ptr(sizes_out), oo.ctypes.data_as(_I32P)),
                "otas_encoder_forward_deep")
         return oo
+
+    def otas_patch_embed_workspace_bytes(self, B, C, Hi, Wi, patch) -> int:
+        return int(self._lib.otas_patch_embed_workspace_bytes(self._h, B, C, Hi, Wi, patch))
+
+    def otas_patch_embed(self, images, patch, w_patch, b_patch, cls, pos, workspace, tokens) -> np.ndarray:
+        """images [B, C, Hi, Wi] -> tokens [B (n_lead + N), D]; returns the token offsets."""
+        B, Cc, Hi, Wi = images.shape
+        off = np.zeros(B + 1, dtype=np.int32)
+        _check(self._lib.otas_patch_embed(self._h, _ptr(images), B, Cc, Hi, Wi, int(patch), _ptr(w_patch), _ptr(b_patch),
+                                          _ptr(cls), _ptr(pos), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _ptr(tokens),
+                                          off.ctypes.data_as(_I32P)), "otas_patch_embed")
+        return off
+
+    def otas_task_heads(self, x, offsets, task, heads, lnf_g, lnf_b, logits) -> None:
+        """heads: list of (w [K, D], b [K]) device tensors; logits [B, k_max] float32."""
+        B = len(offsets) - 1
+        oa, op = _i32(offsets)
+        ta, tp = _i32(task)
+        arr = (_TaskHead * len(heads))()
+        for i, (w, b) in enumerate(heads):
+            arr[i].w, arr[i].b, arr[i].classes = w.data_ptr(), b.data_ptr(), int(w.shape[0])
+        _check(self._lib.otas_task_heads(self._h, _ptr(x), op, tp, B, arr, len(heads), _ptr(lnf_g), _ptr(lnf_b),
+                                         _ptr(logits), int(logits.shape[1])), "otas_task_heads")
 
     def otas_layer_norm(self, x, g, b, T, y) -> None:
         _check(self._lib.otas_layer_norm(self._h, _ptr(x), _ptr(g), _ptr(b), T, _ptr(y)), "otas_layer_norm")

@@ -756,6 +756,63 @@ otas_status otas_encoder_forward_deep(otas_ctx* c, const void* x0, const int32_t
   return OTAS_OK;
 }
 
+size_t otas_patch_embed_workspace_bytes(const otas_ctx* c, int32_t B, int32_t C, int32_t Hi, int32_t Wi, int32_t patch) {
+  if (!c || B <= 0 || C <= 0 || patch <= 0 || Hi <= 0 || Wi <= 0 || Hi % patch || Wi % patch) return 0;
+  const size_t rows = (size_t)B * (Hi / patch) * (Wi / patch), es = elem_size(c->desc.dtype);
+  return align_up(rows * C * patch * patch * es, kAlign) + align_up(rows * c->desc.D * es, kAlign);
+}
+
+otas_status otas_patch_embed(otas_ctx* c, const void* images, int32_t B, int32_t C, int32_t Hi, int32_t Wi,
+                             int32_t patch, const void* w_patch, const void* b_patch, const void* cls, const void* pos,
+                             void* workspace, size_t workspace_bytes, void* tokens, int32_t* tok_offsets) {
+  if (!c || !images || !w_patch || !b_patch || !pos || !workspace || !tokens || !tok_offsets) return OTAS_EINVAL;
+  if (B <= 0 || C <= 0 || patch <= 0 || Hi <= 0 || Wi <= 0 || Hi % patch || Wi % patch) return OTAS_EINVAL;
+  const int n_lead = c->desc.n_lead, D = c->desc.D, dt = c->desc.dtype;
+  if (n_lead > 0 && !cls) return OTAS_EINVAL;
+  if (((uintptr_t)workspace) % kAlign != 0 || tokens == images) return OTAS_EINVAL;
+  const int N = (Hi / patch) * (Wi / patch), kp = C * patch * patch;
+  if (n_lead + N > OTAS_MAX_SEQ) return OTAS_EUNSUPPORTED;
+  if (kp % 8 != 0) return OTAS_EUNSUPPORTED;
+  if (workspace_bytes < otas_patch_embed_workspace_bytes(c, B, C, Hi, Wi, patch)) return OTAS_ENOMEM;
+  const size_t es = elem_size(dt);
+  char* pm = (char*)workspace;
+  char* proj = pm + align_up((size_t)B * N * kp * es, kAlign);
+  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
+  OTAS_LAUNCH(K_PREPEND, launch_patchify(dt, images, pm, B, C, Hi, Wi, patch, c->stream));
+  OTAS_LAUNCH(K_MISC, launch_linear(dt, pm, w_patch, b_patch, nullptr, proj, (int64_t)B * N, D, kp, EPI_NONE, c->stream));
+  OTAS_LAUNCH(K_PREPEND, launch_embed_finish(dt, proj, cls, pos, tokens, B, N, D, n_lead, c->stream));
+  for (int q = 0; q <= B; ++q) tok_offsets[q] = q * (n_lead + N);
+  return OTAS_OK;
+}
+
+otas_status otas_task_heads(otas_ctx* c, const float* x, const int32_t* offsets, const int32_t* task, int32_t B,
+                            const otas_task_head* heads, int32_t n_tasks, const void* lnf_g, const void* lnf_b,
+                            float* logits, int32_t k_max) {
+  if (!c || !x || !offsets || !task || !heads || !lnf_g || !lnf_b || !logits || B <= 0 || n_tasks <= 0 || k_max <= 0)
+    return OTAS_EINVAL;
+  if (!offsets_ok(offsets, B)) return OTAS_EINVAL;
+  for (int q = 0; q < B; ++q)
+    if (task[q] < 0 || task[q] >= n_tasks || offsets[q + 1] <= offsets[q]) return OTAS_EINVAL;
+  for (int t = 0; t < n_tasks; ++t)
+    if (!heads[t].w || !heads[t].b || heads[t].classes <= 0 || heads[t].classes > k_max) return OTAS_EINVAL;
+  // plan (int32): offsets [B] | task [B] | pad to 8 bytes | head records [n_tasks] of 6 ints
+  const size_t o_task = B, o_heads = (2 * (size_t)B + 1) & ~(size_t)1;
+  std::vector<int32_t> plan(o_heads + 6 * (size_t)n_tasks);
+  std::memcpy(&plan[0], offsets, B * sizeof(int32_t));
+  std::memcpy(&plan[o_task], task, B * sizeof(int32_t));
+  for (int t = 0; t < n_tasks; ++t) {
+    HeadRef r = {heads[t].w, heads[t].b, heads[t].classes, 0};
+    static_assert(sizeof(HeadRef) == 6 * sizeof(int32_t), "head record layout");
+    std::memcpy(&plan[o_heads + 6 * (size_t)t], &r, sizeof(r));
+  }
+  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
+  otas_status st = upload_plan(c, plan);   // the plan buffer is 256-byte aligned, the records 8-byte
+  if (st != OTAS_OK) return st;
+  OTAS_LAUNCH(K_MISC, launch_task_heads(c->desc.dtype, x, c->d_plan, c->d_plan + o_task, c->d_plan + o_heads, lnf_g, lnf_b,
+                                        B, c->desc.D, c->desc.ln_eps, logits, k_max, c->stream));
+  return OTAS_OK;
+}
+
 otas_status otas_layer_norm(otas_ctx* c, const void* x, const void* g, const void* b, int64_t T, void* y) {
   if (!c || !x || !g || !b || !y || T < 0) return OTAS_EINVAL;
   if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;

@@ -448,6 +448,118 @@ hipError_t launch_splitk_reduce_ln(const float* part, int S, const void* bias, c
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------- model ends
+// Front end of the vision transformer (Sec. II-A): the image [C, Hi, Wi] is cut into p x p patches
+// (row by row), every patch flattened channel-major into one row of the patch matrix [N, C p p]
+// (the layout of a [D, C, p, p] projection weight); the linear projection is the GEMM kernel;
+// embed_finish then builds [class token | projected patches] + position embedding.
+template <typename T>
+__global__ void patchify_kernel(const T* __restrict__ img, T* __restrict__ out, int C, int Hi, int Wi, int p,
+                                int64_t total) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= total) return;   // one element per thread: total = B N C p p
+  const int nw = Wi / p, nh = Hi / p, kp = C * p * p;
+  const int64_t row = t / kp;
+  const int k = (int)(t - row * kp);
+  const int b = (int)(row / (nh * nw)), pi = (int)(row - (int64_t)b * nh * nw);
+  const int py = pi / nw, px = pi - py * nw;
+  const int c = k / (p * p), ij = k - c * p * p, i = ij / p, j = ij - i * p;
+  out[t] = img[(((size_t)b * C + c) * Hi + (size_t)py * p + i) * Wi + (size_t)px * p + j];
+}
+
+template <typename T>
+__global__ void embed_finish_kernel(const T* __restrict__ proj, const T* __restrict__ cls, const T* __restrict__ pos,
+                                    T* __restrict__ tokens, int N, int D, int n_lead, int64_t total) {
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= total) return;   // total = B (n_lead + N) D
+  const int n = n_lead + N;
+  const int64_t row = t / D;
+  const int d = (int)(t - row * D);
+  const int b = (int)(row / n), i = (int)(row - (int64_t)b * n);
+  const float v = i < n_lead ? to_float(cls[d]) : to_float(proj[((size_t)b * N + (i - n_lead)) * D + d]);
+  tokens[t] = from_float<T>(v + to_float(pos[(size_t)i * D + d]));
+}
+
+hipError_t launch_patchify(int dtype, const void* img, void* out, int B, int C, int Hi, int Wi, int p, hipStream_t s) {
+  const int64_t total = (int64_t)B * (Hi / p) * (Wi / p) * C * p * p;
+  if (total <= 0) return hipSuccess;
+  dim3 grid((unsigned)((total + 255) / 256)), block(256);
+  if (dtype == 0) patchify_kernel<float><<<grid, block, 0, s>>>((const float*)img, (float*)out, C, Hi, Wi, p, total);
+  else patchify_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)img, (bf16_t*)out, C, Hi, Wi, p, total);
+  return hipGetLastError();
+}
+
+hipError_t launch_embed_finish(int dtype, const void* proj, const void* cls, const void* pos, void* tokens, int B,
+                               int N, int D, int n_lead, hipStream_t s) {
+  const int64_t total = (int64_t)B * (n_lead + N) * D;
+  if (total <= 0) return hipSuccess;
+  dim3 grid((unsigned)((total + 255) / 256)), block(256);
+  if (dtype == 0)
+    embed_finish_kernel<float><<<grid, block, 0, s>>>((const float*)proj, (const float*)cls, (const float*)pos,
+                                                      (float*)tokens, N, D, n_lead, total);
+  else
+    embed_finish_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)proj, (const bf16_t*)cls, (const bf16_t*)pos,
+                                                       (bf16_t*)tokens, N, D, n_lead, total);
+  return hipGetLastError();
+}
+
+// Back end (Sec. III-B: every task has its own head): one workgroup per query normalises the first row
+// of the query's output (final LayerNorm, two-pass fp32 statistics, stored in the model's dtype like
+// every GEMM operand) and multiplies it with its task's head [K, D]: one class per thread and pass,
+// fp32 accumulate in ascending d.  heads: per task {w, b, K}; task[q] picks the head.
+template <typename T>
+__global__ __launch_bounds__(256) void task_head_kernel(const float* __restrict__ x, const int32_t* __restrict__ off,
+                                                        const int32_t* __restrict__ task, const HeadRef* __restrict__ heads,
+                                                        const T* __restrict__ g, const T* __restrict__ bta, int D,
+                                                        float eps, float* __restrict__ logits, int k_max) {
+  extern __shared__ float hrow[];   // [D] normalised row, then 8 floats of reduction scratch
+  float* red = hrow + D;
+  const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* xr = x + (size_t)off[q] * D;
+  float sum = 0.f;
+  for (int d = tid; d < D; d += 256) sum += xr[d];
+  sum = wave_sum(sum);
+  if (lane == 0) red[wave] = sum;
+  __syncthreads();
+  const float mean = (red[0] + red[1] + red[2] + red[3]) / (float)D;
+  __syncthreads();
+  float sq = 0.f;
+  for (int d = tid; d < D; d += 256) { const float c = xr[d] - mean; sq += c * c; }
+  sq = wave_sum(sq);
+  if (lane == 0) red[wave] = sq;
+  __syncthreads();
+  const float rstd = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)D + eps);
+  for (int d = tid; d < D; d += 256)
+    hrow[d] = to_float(from_float<T>((xr[d] - mean) * rstd * to_float(g[d]) + to_float(bta[d])));
+  __syncthreads();
+  const HeadRef h = heads[task[q]];
+  const T* w = (const T*)h.w;
+  const T* b = (const T*)h.b;
+  for (int k = tid; k < k_max; k += 256) {
+    float acc = 0.f;
+    if (k < h.K) {
+      const T* wr = w + (size_t)k * D;
+      for (int d = 0; d < D; ++d) acc = fmaf(hrow[d], to_float(wr[d]), acc);
+      acc += to_float(b[k]);
+    }
+    logits[(size_t)q * k_max + k] = acc;   // classes beyond the task's count read 0
+  }
+}
+
+hipError_t launch_task_heads(int dtype, const float* x, const int32_t* d_off, const int32_t* d_task,
+                             const void* d_heads, const void* g, const void* b, int B, int D, float eps,
+                             float* logits, int k_max, hipStream_t s) {
+  if (B <= 0 || k_max <= 0) return hipSuccess;
+  const size_t lds = (size_t)(D + 8) * sizeof(float);
+  if (dtype == 0)
+    task_head_kernel<float><<<dim3(B), dim3(256), lds, s>>>(x, d_off, d_task, (const HeadRef*)d_heads, (const float*)g,
+                                                            (const float*)b, D, eps, logits, k_max);
+  else
+    task_head_kernel<bf16_t><<<dim3(B), dim3(256), lds, s>>>(x, d_off, d_task, (const HeadRef*)d_heads,
+                                                             (const bf16_t*)g, (const bf16_t*)b, D, eps, logits, k_max);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------- widen / narrow
 // Token tensors enter and leave in the model's dtype; the residual stream in between is float.
 __global__ void widen_kernel(const bf16_t* __restrict__ a, float* __restrict__ b, int64_t n8) {

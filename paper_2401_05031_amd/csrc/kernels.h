@@ -24,6 +24,18 @@ hipError_t launch_deep_prompt(int dtype, const float* x_old, float* x_new, const
                               const int32_t* d_old_off, const int32_t* d_new_off, const int32_t* d_prm_off, int B,
                               int max_rows, int D, int n_lead, bool grow, hipStream_t s);
 
+// Model ends.  patchify: images [B, C, Hi, Wi] -> patch matrix [B N, C p p] (patches row by row,
+// flattened channel-major).  embed_finish: tokens [B, n_lead + N, D] = [cls | proj rows] + pos.
+// task_heads: logits[q, :K_task] = W_task LN_final(x[off[q]]) + b_task; d_heads is a device array of
+// {const void* w, const void* b, int K} records (16-byte stride + padding as laid out by the host).
+struct HeadRef { const void* w; const void* b; int32_t K; int32_t pad; };   // 24 bytes, 8-byte aligned
+hipError_t launch_patchify(int dtype, const void* img, void* out, int B, int C, int Hi, int Wi, int p, hipStream_t s);
+hipError_t launch_embed_finish(int dtype, const void* proj, const void* cls, const void* pos, void* tokens, int B,
+                               int N, int D, int n_lead, hipStream_t s);
+hipError_t launch_task_heads(int dtype, const float* x, const int32_t* d_off, const int32_t* d_task,
+                             const void* d_heads, const void* g, const void* b, int B, int D, float eps,
+                             float* logits, int k_max, hipStream_t s);
+
 // x_is_float: the input rows are float (the residual stream) even when dtype is bf16.
 hipError_t launch_layer_norm(int dtype, bool x_is_float, const void* x, const void* g, const void* b,
                              void* y, int64_t T, int D, float eps, hipStream_t s);

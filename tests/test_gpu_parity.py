@@ -652,3 +652,109 @@ def test_per_layer_prompting_argument_errors(torch_cuda, lib):
     torch.cuda.synchronize()
     assert off.tolist() == [0, 10 + 3 * (cfg.L - 1)]
     ctx.close()
+
+
+@pytest.mark.parametrize("dtype,tol", [("f32", 2e-6), ("bf16", 1e-2)])
+def test_model_ends_patch_embed_and_task_heads(torch_cuda, lib, dtype, tol):
+    """Model ends against the oracle: patch embedding of 3 x 64 x 48 images (patch 16: a 4 x 3 grid, so a
+    wrong patch order shows) with class token and position embedding, and two task heads of different
+    widths reading LayerNorm_final of each query's first row from a ragged float tensor."""
+    torch = torch_cuda
+    cfg = synth.config("tiny")
+    cfg.dtype = dtype
+    cfg.B = 3
+    ctx, layers = hz.make_context(cfg)
+    dt = ctx.torch_dtype
+    C, Hi, Wi, p = 3, 64, 48, 16
+    N = (Hi // p) * (Wi // p)
+    classes = [10, 37]
+    ends = synth.ends_weights(cfg, C, p, N, classes)
+    imgs = np.stack([synth.query_image(cfg, q, C, Hi, Wi) for q in range(cfg.B)])
+    st = "bf16" if dtype == "bf16" else "f64"
+    ws = torch.empty(ctx.otas_patch_embed_workspace_bytes(cfg.B, C, Hi, Wi, p), dtype=torch.uint8, device="cuda")
+    toks = torch.empty((cfg.B * (1 + N), cfg.D), dtype=dt, device="cuda")
+    off = ctx.otas_patch_embed(_t(torch, imgs, dt), p, _t(torch, ends["w_patch"], dt), _t(torch, ends["b_patch"], dt),
+                               _t(torch, ends["cls"], dt), _t(torch, ends["pos"], dt), ws, toks)
+    torch.cuda.synchronize()
+    assert off.tolist() == [q * (1 + N) for q in range(cfg.B + 1)]
+    got = toks.to(torch.float32).cpu().numpy()
+    for q in range(cfg.B):
+        ref = orc.patch_embed(imgs[q], ends["w_patch"], ends["b_patch"], ends["cls"], ends["pos"], p, storage=st)
+        assert hz.rel_err(got[off[q]:off[q + 1]], ref) <= tol, q
+    # heads on a ragged float "encoder output"
+    rng = np.random.default_rng(3)
+    ns = [5, 1, 9]
+    xoff = np.concatenate([[0], np.cumsum(ns)]).astype(np.int32)
+    x = (rng.standard_normal((int(xoff[-1]), cfg.D)) * 3 + 0.5).astype(np.float32)
+    task = [1, 0, 1]
+    heads = [(_t(torch, ends[f"head_w{t}"], dt), _t(torch, ends[f"head_b{t}"], dt)) for t in range(2)]
+    logits = torch.full((cfg.B, 40), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.otas_task_heads(_t(torch, x, torch.float32), xoff, task, heads, _t(torch, ends["lnf_g"], dt),
+                        _t(torch, ends["lnf_b"], dt), logits)
+    torch.cuda.synchronize()
+    lg = logits.cpu().numpy()
+    for q in range(cfg.B):
+        t = task[q]
+        ref = orc.task_head(x[xoff[q]:xoff[q + 1]].astype(np.float64), ends["lnf_g"], ends["lnf_b"],
+                            ends[f"head_w{t}"], ends[f"head_b{t}"], cfg.ln_eps, storage=st)
+        assert hz.rel_err(lg[q, :classes[t]], ref) <= tol, q
+        assert np.all(lg[q, classes[t]:] == 0)
+    # argument errors
+    with pytest.raises(lib.OtasError) as e:      # image height not a multiple of the patch
+        ctx.otas_patch_embed(_t(torch, imgs[:, :, :60], dt), p, _t(torch, ends["w_patch"], dt), _t(torch, ends["b_patch"], dt),
+                             _t(torch, ends["cls"], dt), _t(torch, ends["pos"], dt), ws, toks)
+    assert e.value.status == 1
+    with pytest.raises(lib.OtasError) as e:      # task id out of range
+        ctx.otas_task_heads(_t(torch, x, torch.float32), xoff, [0, 2, 1], heads, _t(torch, ends["lnf_g"], dt),
+                            _t(torch, ends["lnf_b"], dt), logits)
+    assert e.value.status == 1
+    with pytest.raises(lib.OtasError) as e:      # head wider than the logits rows
+        ctx.otas_task_heads(_t(torch, x, torch.float32), xoff, task, heads, _t(torch, ends["lnf_g"], dt),
+                            _t(torch, ends["lnf_b"], dt), logits[:, :20].contiguous())
+    assert e.value.status == 1
+    ctx.close()
+
+
+def test_image_to_logits_f32_with_prompts_and_merging(torch_cuda, lib):
+    """The whole forward pass of the serving model (Sec. IV: inputs, tasks, task parameters, gamma):
+    patch embedding -> prompt prepend -> token-adapted encoder -> task heads, fp32, against the oracle
+    composed the same way; two queries of different tasks and strategies."""
+    torch = torch_cuda
+    cfg = synth.config("tiny")
+    cfg.n0 = 1 + 14 * 14
+    cfg.strategies = [(4, 8), (0, 16)]
+    ctx, layers = hz.make_context(cfg)
+    dt = ctx.torch_dtype
+    C, Hi, Wi, p = 3, 224, 224, 16
+    N = 196
+    classes = [10, 100]
+    ends = synth.ends_weights(cfg, C, p, N, classes)
+    imgs = np.stack([synth.query_image(cfg, q, C, Hi, Wi) for q in range(2)])
+    ws = torch.empty(ctx.otas_patch_embed_workspace_bytes(2, C, Hi, Wi, p), dtype=torch.uint8, device="cuda")
+    toks = torch.empty((2 * (1 + N), cfg.D), dtype=dt, device="cuda")
+    toff = ctx.otas_patch_embed(_t(torch, imgs, dt), p, _t(torch, ends["w_patch"], dt), _t(torch, ends["b_patch"], dt),
+                                _t(torch, ends["cls"], dt), _t(torch, ends["pos"], dt), ws, toks)
+    prm = [synth.query_prompts(cfg, q) for q in range(2)]
+    prm_packed, prm_off = synth.pack(prm, cfg.D)
+    x0 = torch.empty((int(toff[-1] + prm_off[-1]), cfg.D), dtype=dt, device="cuda")
+    off = ctx.otas_prompt_prepend(toks, toff, _t(torch, prm_packed, dt), prm_off, x0)
+    R = [8, 16]
+    gpu = hz.gpu_forward(ctx, x0, off, R)
+    x_packed = np.concatenate(gpu["x"], axis=0).astype(np.float32)
+    heads = [(_t(torch, ends[f"head_w{t}"], dt), _t(torch, ends[f"head_b{t}"], dt)) for t in range(2)]
+    logits = torch.zeros((2, 100), dtype=torch.float32, device="cuda")
+    task = [0, 1]
+    ctx.otas_task_heads(_t(torch, x_packed, torch.float32), gpu["offsets"], task, heads, _t(torch, ends["lnf_g"], dt),
+                        _t(torch, ends["lnf_b"], dt), logits)
+    torch.cuda.synchronize()
+    lg = logits.cpu().numpy()
+    for q in range(2):
+        tk = orc.patch_embed(imgs[q], ends["w_patch"], ends["b_patch"], ends["cls"], ends["pos"], p)
+        xq, _ = orc.prompt_prepend(tk, prm[q], cfg.n_lead)
+        out = orc.encoder_forward_query(xq, layers, R[q], H=cfg.H, ln_eps=cfg.ln_eps, n_lead=cfg.n_lead)
+        for l in range(cfg.L):
+            assert np.array_equal(gpu["trace"][q][l][0], out["trace"][l][0]), (q, l)
+        ref = orc.task_head(out["x"], ends["lnf_g"], ends["lnf_b"], ends[f"head_w{task[q]}"], ends[f"head_b{task[q]}"],
+                            cfg.ln_eps)
+        assert hz.rel_err(lg[q, :classes[task[q]]], ref) <= 1e-4, q
+    ctx.close()
