@@ -28,6 +28,15 @@ Readings taken where the paper is silent or garbled:
   S8  ties: strict comparisons as printed (the first candidate reaching a value keeps it); the final
       arg max takes the lowest index.
 
+  S9  Alg. 2's tables start at dp = 0, S = 1, and a candidate is recorded only when strictly larger
+      than the entry.  Taken literally, a state whose best accumulated utility is exactly 0 (all
+      earlier batches skipped, or zero-utility requests) keeps S = 1 and C = T, which names a
+      predecessor that may be infeasible and loses the clock; the backtracking would then execute a
+      batch that cannot meet its deadline, against what the text says J and C are for.  Here the
+      initial 0 means "no candidate yet": the first feasible candidate of a state is always
+      recorded, later ones only when strictly larger.  Identical to the listing whenever the
+      accumulated utility of a state is positive.
+
 Pins (tests/test_sched_pins.py): hand-worked queues for every branch of Alg. 1; Alg. 3 on a
 hand-worked queue; Alg. 2 against exhaustive enumeration of all assignments on small queues
 (equal to the optimum whenever the deadlines do not bind, never above it, always feasible), and
@@ -158,7 +167,7 @@ def allocate(B: List[Batch], T: float, gammas: Sequence[int], q: float, beta: in
                 if dp[b - 1][lp] == NEG:
                     continue
                 if lb == 0:
-                    if dp[b - 1][lp] > dp[b][lb]:
+                    if J[b][lb] == 0 or dp[b - 1][lp] > dp[b][lb]:          # S9
                         dp[b][lb] = dp[b - 1][lp]
                         S[b][lb] = lp
                         C[b][lb] = C[b - 1][lp]
@@ -167,8 +176,9 @@ def allocate(B: List[Batch], T: float, gammas: Sequence[int], q: float, beta: in
                     t, U = profile(B[b - 1], lb - 1, latency, accuracy)
                     if C[b - 1][lp] + t < B[b - 1].d:
                         u = dp[b - 1][lp] + U
+                        first = J[b][lb] == 0                               # S9
                         J[b][lb] = 1
-                        if u > dp[b][lb]:
+                        if first or u > dp[b][lb]:
                             dp[b][lb] = u
                             S[b][lb] = lp
                             C[b][lb] = C[b - 1][lp] + t

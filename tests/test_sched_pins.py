@@ -252,6 +252,25 @@ def test_alg2_single_gamma_reduces_to_deadline_scheduling_with_rejection():
     assert best == pytest.approx(34.0)
 
 
+def test_alg2_hopeless_head_batches_are_skipped_not_executed():
+    # the first two batches cannot finish under any gamma: every state that skips them has accumulated
+    # utility exactly 0, the case in which the listing's initial S = 1 would name an infeasible predecessor
+    lat, acc = [[0.01, 0.02]], [[0.8, 0.9]]
+    mk = lambda n, d, u=1.0: so.Batch([Q(0.0, d, u) for _ in range(n)])
+    B = [mk(10, 0.05), mk(10, 0.06), mk(5, 1.0), mk(5, 1.1), mk(5, 1.2), mk(5, 1.3)]
+    T = 0.0
+    best = so.allocate(B, T, [0, 8], 0.0, 5, False, [], 0.8, lat, acc)
+    assert [b.gamma for b in B] == [None, None, 1, 1, 1, 1]
+    got, clock, ok = so.replay(B, T, lat, acc)
+    assert ok and got == pytest.approx(best) and best == pytest.approx(20 * 0.9)
+    assert clock == pytest.approx(20 * 0.02)
+    # zero-utility requests: the plan still carries the clock through the batches it executes
+    B = [mk(10, 0.25, 0.0), mk(10, 0.25, 0.0), mk(5, 0.30), mk(1, 9.0), mk(1, 9.0), mk(1, 9.0)]
+    best = so.allocate(B, 0.0, [0, 8], 0.0, 5, False, [], 0.8, lat, acc)
+    got, clock, ok = so.replay(B, 0.0, lat, acc)
+    assert ok and got == pytest.approx(best)
+
+
 # ------------------------------------------------------------------------------------------- planted mistakes
 def test_planted_mistakes_are_caught():
     """Each plausible slip, planted in the oracle, fails at least one of the pins above."""
