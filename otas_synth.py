@@ -179,3 +179,46 @@ def pack(rows: Sequence[np.ndarray], D: int):
     if len(rows) == 0:
         return np.zeros((0, D), dtype=np.float32), offs
     return np.concatenate([np.asarray(a, dtype=np.float32).reshape(-1, D) for a in rows], axis=0), offs
+
+
+# ------------------------------------------------------------------------------------------ serving traces
+# Query types of the paper's synthetic trace (Table II): (task, latency requirement in s, utility).  Tasks 0, 1, 2
+# stand for the three data sets of the experiment.
+QUERY_TYPES: Tuple[Tuple[int, float, float], ...] = ((0, 0.6, 0.3), (0, 1.0, 0.01), (1, 0.6, 1.0), (1, 1.0, 0.2),
+                                                     (2, 0.6, 0.3), (2, 1.0, 0.01))
+GAMMA_LIST: Tuple[int, ...] = (-20, -15, -10, -5, 0, 2, 4, 8)      # selection list of the experiment (Sec. V)
+TASK_CLASSES: Tuple[int, ...] = (10, 100, 10)                      # classes of the three tasks' heads
+
+
+def poisson_trace(seed: int, seconds: int, rate_lo: float = 200.0, rate_hi: float = 700.0,
+                  time_scale: float = 1.0) -> List[Tuple[float, float, float, int]]:
+    """Synthetic query trace shaped like the paper's (Sec. V, workloads): in every second the request rate is
+    drawn uniformly from [rate_lo, rate_hi] and arrivals within the second are a Poisson process of that rate;
+    each request takes one of the six query types uniformly.  Returns rows (s_r, l_r, u_r, task) in arrival
+    order.  time_scale < 1 compresses the clock (arrival times AND latency requirements) so that a faster
+    device sees the same load relative to its capacity; rates scale by 1 / time_scale."""
+    rng = np.random.default_rng([seed, 0x7A])
+    rows = []
+    for sec in range(seconds):
+        rate = rng.uniform(rate_lo, rate_hi)
+        t = float(sec)
+        while True:
+            t += rng.exponential(1.0 / rate)
+            if t >= sec + 1:
+                break
+            task, lat, u = QUERY_TYPES[int(rng.integers(len(QUERY_TYPES)))]
+            rows.append((t * time_scale, lat * time_scale, u, task))
+    return rows
+
+
+def stand_in_accuracy(gammas: Sequence[int] = GAMMA_LIST, n_tasks: int = 3) -> np.ndarray:
+    """[n_tasks][len(gammas)] accuracy table standing in for the paper's profiled accuracies, which need its
+    data sets and trained prompts.  Shaped like what the paper reports for token merging (Sec. II-C): a slight
+    loss down to 15 merged tokens per layer, a sharp one beyond, roughly halving the accuracy at 25; prompts
+    add a little, saturating.  Offset and scaled per task.  The shape, not the values, is what the scheduler
+    needs."""
+    base = np.array([0.97, 0.88, 0.95])[:n_tasks, None]
+    g = np.asarray(gammas, dtype=np.float64)[None, :]
+    m = np.maximum(-g, 0.0)
+    drop = np.where(g < 0, 0.0015 * m + 0.0043 * np.maximum(m - 15.0, 0.0) ** 2, -0.012 * (1.0 - np.exp(-g / 4.0)))
+    return np.clip(base - drop * (1.0 + 0.5 * np.arange(n_tasks)[:, None]), 0.0, 1.0)

@@ -38,7 +38,15 @@ class _LayerWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _WEIGHT_FIELDS]
 
 
+class _SchedParams(C.Structure):
+    _fields_ = [("delta", C.c_double), ("eta", C.c_double), ("mu", C.c_double), ("kappa", C.c_double),
+                ("epsilon", C.c_int32), ("beta", C.c_int32)]
+
+
+OTAS_GAMMA_SKIP, OTAS_GAMMA_UNDECIDED = -1, -2
 _I32P = C.POINTER(C.c_int32)
+_I64P = C.POINTER(C.c_int64)
+_F64P = C.POINTER(C.c_double)
 _LIB = None
 
 
@@ -86,6 +94,16 @@ def load_library():
         "otas_timing_overhead_ms": (C.c_float, [vp]),
         "otas_set_lanes": (i32, [vp, i32]),
         "otas_splitk_factor": (i32, [vp, C.c_int64, i32, i32]),
+        "otas_sched_create": (i32, [C.POINTER(_SchedParams), i32, _I32P, i32, _F64P, _F64P, i32, _F64P, _I32P,
+                                    C.POINTER(vp)]),
+        "otas_sched_destroy": (None, [vp]),
+        "otas_sched_add_query": (i32, [vp, i64, C.c_double, C.c_double, C.c_double, i32, _I32P]),
+        "otas_sched_allocate": (i32, [vp, C.c_double, C.c_double, i32, _F64P]),
+        "otas_sched_num_batches": (i32, [vp]),
+        "otas_sched_batch_info": (i32, [vp, i32, _I32P, _F64P, _F64P, _F64P, _I32P]),
+        "otas_sched_batch_queries": (i32, [vp, i32, _I64P, _I32P, i32, _I32P]),
+        "otas_sched_estimate": (i32, [vp, i32, i32, _F64P, _F64P]),
+        "otas_sched_remove": (i32, [vp, i32]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)          # AttributeError if a declared symbol is not exported
@@ -98,7 +116,10 @@ EXPORTED = ("otas_create", "otas_destroy", "otas_schedule", "otas_workspace_byte
             "otas_merge_workspace_bytes", "otas_prompt_prepend", "otas_token_merge",
             "otas_encoder_forward", "otas_encoder_layers", "otas_encoder_forward_deep", "otas_patch_embed_workspace_bytes", "otas_patch_embed", "otas_task_heads", "otas_layer_norm", "otas_linear", "otas_attention", "otas_strerror",
             "otas_timing_enable", "otas_timing_kinds", "otas_timing_kind_name", "otas_timing_read",
-            "otas_timing_read_launches", "otas_timing_overhead_ms", "otas_set_lanes", "otas_splitk_factor")
+            "otas_timing_read_launches", "otas_timing_overhead_ms", "otas_set_lanes", "otas_splitk_factor",
+            "otas_sched_create", "otas_sched_destroy", "otas_sched_add_query", "otas_sched_allocate",
+            "otas_sched_num_batches", "otas_sched_batch_info", "otas_sched_batch_queries", "otas_sched_estimate",
+            "otas_sched_remove")
 
 
 def otas_strerror(status: int) -> str:
@@ -318,3 +339,81 @@ class Context:
         flat = reff.reshape(-1)
         troff = np.concatenate([[0], np.cumsum(flat)[:-1]]).reshape(nl, B)
         return reff, troff
+
+
+class Scheduler:
+    """Handle of an otas_sched object (include/otas_sched.h): batch queue, adaptive batching, token
+    adaptation.  Host only; the methods carry the C names and marshal arguments."""
+
+    def __init__(self, gammas: Sequence[int], latency, accuracy, rate_table: Sequence[Tuple[float, int]] = (),
+                 delta: float = 0.5, epsilon: int = 64, eta: float = 0.5, mu: float = 0.8, beta: int = 5,
+                 kappa: float = 0.8):
+        """otas_sched_create.  latency / accuracy: [n_tasks][len(gammas)]; rate_table: rows of (largest
+        request rate, index into gammas), ascending.  The defaults are the paper's settings (Sec. V)."""
+        self._lib = load_library()
+        self._h = C.c_void_p()
+        lat = np.ascontiguousarray(np.asarray(latency, dtype=np.float64))
+        acc = np.ascontiguousarray(np.asarray(accuracy, dtype=np.float64))
+        if lat.ndim != 2 or lat.shape != acc.shape or lat.shape[1] != len(gammas):
+            raise ValueError("latency and accuracy must be [n_tasks][len(gammas)]")
+        self.gammas = [int(g) for g in gammas]
+        ga, gp = _i32(self.gammas)
+        rm = np.ascontiguousarray(np.asarray([r[0] for r in rate_table], dtype=np.float64))
+        rg, rgp = _i32([r[1] for r in rate_table])
+        prm = _SchedParams(delta, eta, mu, kappa, epsilon, beta)
+        _check(self._lib.otas_sched_create(C.byref(prm), len(self.gammas), gp, lat.shape[0],
+                                           lat.ctypes.data_as(_F64P), acc.ctypes.data_as(_F64P), len(rate_table),
+                                           rm.ctypes.data_as(_F64P) if len(rate_table) else None,
+                                           rgp if len(rate_table) else None, C.byref(self._h)), "otas_sched_create")
+
+    def otas_sched_destroy(self) -> None:
+        if self._h:
+            self._lib.otas_sched_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.otas_sched_destroy()
+        except Exception:
+            pass
+
+    def otas_sched_add_query(self, id: int, s_r: float, l_r: float, u_r: float, task: int) -> int:
+        b = C.c_int32()
+        _check(self._lib.otas_sched_add_query(self._h, int(id), s_r, l_r, u_r, int(task), C.byref(b)),
+               "otas_sched_add_query")
+        return b.value
+
+    def otas_sched_allocate(self, T: float, q: float, initial_stage: bool) -> float:
+        out = C.c_double()
+        _check(self._lib.otas_sched_allocate(self._h, T, q, 1 if initial_stage else 0, C.byref(out)),
+               "otas_sched_allocate")
+        return out.value
+
+    def otas_sched_num_batches(self) -> int:
+        return int(self._lib.otas_sched_num_batches(self._h))
+
+    def otas_sched_batch_info(self, b: int) -> dict:
+        n, g = C.c_int32(), C.c_int32()
+        s_b, d_b, u_b = C.c_double(), C.c_double(), C.c_double()
+        _check(self._lib.otas_sched_batch_info(self._h, int(b), C.byref(n), C.byref(s_b), C.byref(d_b), C.byref(u_b),
+                                               C.byref(g)), "otas_sched_batch_info")
+        return {"size": n.value, "s_b": s_b.value, "d_b": d_b.value, "u_b": u_b.value, "gamma_index": g.value}
+
+    def otas_sched_batch_queries(self, b: int) -> Tuple[List[int], List[int]]:
+        n = C.c_int32()
+        _check(self._lib.otas_sched_batch_queries(self._h, int(b), None, None, 0, C.byref(n)),
+               "otas_sched_batch_queries")
+        ids = (C.c_int64 * max(n.value, 1))()
+        tasks = (C.c_int32 * max(n.value, 1))()
+        _check(self._lib.otas_sched_batch_queries(self._h, int(b), ids, tasks, n.value, None),
+               "otas_sched_batch_queries")
+        return list(ids[:n.value]), list(tasks[:n.value])
+
+    def otas_sched_estimate(self, b: int, gamma_index: int) -> Tuple[float, float]:
+        t, U = C.c_double(), C.c_double()
+        _check(self._lib.otas_sched_estimate(self._h, int(b), int(gamma_index), C.byref(t), C.byref(U)),
+               "otas_sched_estimate")
+        return t.value, U.value
+
+    def otas_sched_remove(self, b: int) -> None:
+        _check(self._lib.otas_sched_remove(self._h, int(b)), "otas_sched_remove")

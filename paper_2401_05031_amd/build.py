@@ -1,4 +1,4 @@
-"""Builds libotas.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree."""
+"""Builds libotas.so (HIP kernels + C ABI + the host scheduler) for gfx950 with hipcc, in-tree."""
 from __future__ import annotations
 
 import os
@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libotas.so")
-SOURCES = ["api.hip", "elementwise.hip", "gemm.hip", "attention.hip", "merge.hip"]
+SOURCES = ["api.hip", "elementwise.hip", "gemm.hip", "attention.hip", "merge.hip", "sched.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
@@ -20,7 +20,7 @@ def build(verbose: bool = True) -> str:
     procs = []
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
     for src in SOURCES:
-        obj = os.path.join(HERE, "_build", src.replace(".hip", ".o"))
+        obj = os.path.join(HERE, "_build", os.path.splitext(src)[0] + ".o")
         cmd = [hipcc] + [f for f in FLAGS if f != "-shared"] + ["-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
