@@ -138,7 +138,7 @@ def replay_trace(sched, trace: Sequence[Tuple[float, float, float, int]], engine
     n = len(trace)
     T, i = 0.0, 0
     res = {"utility": 0.0, "offered_utility": float(sum(row[2] for row in trace)), "served": 0, "late": 0,
-           "given_up": 0, "batches": 0, "busy": 0.0, "gamma_batches": {g: 0 for g in gammas}, "log": []}
+           "given_up": 0, "batches": 0, "busy": 0.0, "allocate_seconds": 0.0, "allocate_calls": 0, "gamma_batches": {g: 0 for g in gammas}, "log": []}
     while i < n or sched.otas_sched_num_batches() > 0:
         while i < n and arrivals[i] <= T:
             s_r, l_r, u_r, task = trace[i]
@@ -151,7 +151,10 @@ def replay_trace(sched, trace: Sequence[Tuple[float, float, float, int]], engine
         lo = int(np.searchsorted(arrivals, T - rate_window, side="right"))
         hi = int(np.searchsorted(arrivals, T, side="right"))
         q = (hi - lo) / rate_window
+        t_host = time.perf_counter()
         sched.otas_sched_allocate(T, q, T < initial_stage)
+        res["allocate_seconds"] += time.perf_counter() - t_host
+        res["allocate_calls"] += 1
         pick = -1
         hopeless = []
         for b in range(nb):
@@ -195,3 +198,56 @@ def replay_trace(sched, trace: Sequence[Tuple[float, float, float, int]], engine
             sched.otas_sched_remove(b)
     res["end_time"] = T
     return res
+
+
+def main(argv=None) -> None:
+    """Profiles the library on this GPU for every gamma of the paper's selection list, then replays a
+    synthetic trace (Sec. V workload shape) through the loop with the GPU engine: once with token
+    adaptation, once with every batch at gamma = 0.  The trace's clock is compressed so that the plain
+    model's measured capacity stands where the paper's machine had it (580 requests / s at gamma = 0,
+    Sec. II-C) relative to the 200..700 requests / s load; thresholds given in seconds scale with it.
+    Prints one JSON line."""
+    import argparse
+    import json
+    import os
+    import sys
+
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import otas_synth as synth
+
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="vitb_plain")
+    ap.add_argument("--seconds", type=int, default=60, help="length of the trace on the paper's clock")
+    ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--load", type=float, default=1.0, help="multiplies the trace's request rates")
+    args = ap.parse_args(argv)
+    cfg = synth.config(args.workload)
+    ctx = Context.from_host_weights(cfg.L, cfg.D, cfg.H, cfg.F, OTAS_BF16, cfg.ln_eps, cfg.n_lead,
+                                    synth.all_weights(cfg))
+    gammas = list(synth.GAMMA_LIST)
+    n_tasks = len(synth.TASK_CLASSES)
+    eng = GpuEngine(ctx, cfg.n0, synth.TASK_CLASSES, max(gammas), pool=64)
+    lat = eng.measure_profile(gammas, n_tasks, batch=64)
+    acc = synth.stand_in_accuracy(gammas, n_tasks)
+    thr0 = 1.0 / float(lat[:, gammas.index(0)].mean())
+    scale = 580.0 / thr0
+    trace = synth.poisson_trace(args.seed, args.seconds, 200.0 * args.load, 700.0 * args.load, time_scale=scale)
+    kw = dict(delta=0.5 * scale, eta=0.5 * scale)
+    out = {"workload": args.workload, "batch": 64, "gammas": gammas,
+           "images_per_s": [round(1.0 / float(lat[:, i].mean()), 1) for i in range(len(gammas))],
+           "time_scale": scale, "load": args.load, "requests": len(trace)}
+    for name, gl in (("adaptive", gammas), ("fixed_gamma_0", [0])):
+        idx = [gammas.index(g) for g in gl]
+        l2, a2 = lat[:, idx], acc[:, idx]
+        sched = Scheduler(gl, l2, a2, rate_table_from_latency(gl, l2), **kw)
+        t0 = time.perf_counter()
+        r = replay_trace(sched, trace, eng, a2, initial_stage=2.0 * scale, rate_window=1.0 * scale)
+        r.pop("log")
+        r["wall_seconds"] = time.perf_counter() - t0
+        r["gamma_batches"] = {str(k): v for k, v in r["gamma_batches"].items()}
+        out[name] = {k: (round(v, 6) if isinstance(v, float) else v) for k, v in r.items()}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

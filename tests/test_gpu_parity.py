@@ -758,3 +758,45 @@ def test_image_to_logits_f32_with_prompts_and_merging(torch_cuda, lib):
                             cfg.ln_eps)
         assert hz.rel_err(lg[q, :classes[task[q]]], ref) <= 1e-4, q
     ctx.close()
+
+
+# ------------------------------------------------------------------------------------------- serving loop
+def test_serving_engine_batches_match_oracle_and_loop_accounts(torch_cuda, lib):
+    """The GPU engine of the serving loop (Sec. IV: a batch of inputs, their tasks, the task parameters and
+    gamma in, per-task results out): one mixed-task batch per kind of gamma against the oracle composed the same
+    way, then a short trace replayed through batching + token adaptation with every batch really executed."""
+    torch = torch_cuda
+    from paper_2401_05031_amd import serve
+    cfg = synth.config("tiny")
+    ctx, layers = hz.make_context(cfg)
+    classes = (10, 100, 10)
+    gammas = [-8, 0, 4]
+    eng = serve.GpuEngine(ctx, cfg.n0, classes, max_prompts=4, pool=8, seed=3)
+    toks = eng.tokens.float().cpu().numpy().reshape(8, cfg.n0, cfg.D)
+    tasks = [2, 0, 1]
+    for gi, g in enumerate(gammas):
+        assert eng.run(tasks, gi, g) > 0.0
+        lg = eng.logits[:3].cpu().numpy()
+        P, r = serve.gamma_to_strategy(g)
+        for q, task in enumerate(tasks):
+            prm = eng.prompts[task][:P].float().cpu().numpy()
+            xq, _ = orc.prompt_prepend(toks[q], prm, cfg.n_lead)
+            out = orc.encoder_forward_query(xq, layers, r, H=cfg.H, ln_eps=cfg.ln_eps, n_lead=cfg.n_lead)
+            w, b = eng.heads[task]
+            ref = orc.task_head(out["x"], eng.lnf_g.float().cpu().numpy(), eng.lnf_b.float().cpu().numpy(),
+                                w.float().cpu().numpy(), b.float().cpu().numpy(), cfg.ln_eps)
+            assert hz.rel_err(lg[q, :classes[task]], ref) <= 1e-4, (g, q)
+    lat = eng.measure_profile(gammas, 3, batch=8, repeats=3)
+    assert (lat > 0).all()
+    acc = synth.stand_in_accuracy(gammas, 3)
+    thr0 = 1.0 / float(lat[:, 1].mean())
+    scale = 580.0 / thr0
+    trace = synth.poisson_trace(5, 3, time_scale=scale)
+    sched = lib.Scheduler(gammas, lat, acc, serve.rate_table_from_latency(gammas, lat), delta=0.5 * scale,
+                          eta=0.5 * scale, epsilon=8)
+    res = serve.replay_trace(sched, trace, eng, acc, initial_stage=2.0 * scale, rate_window=scale, log=True)
+    assert res["served"] + res["late"] + res["given_up"] == len(trace)
+    assert res["batches"] > 0 and 0.0 < res["utility"] <= res["offered_utility"]
+    assert sorted(i for rec in res["log"] for i in rec[2]) == list(range(len(trace)))
+    assert all(len(rec[2]) <= 8 for rec in res["log"] if rec[0] == "run")
+    ctx.close()
