@@ -257,9 +257,10 @@ otas_status otas_attention(otas_ctx *ctx, const void *qkv, const int32_t *sizes,
  * every later launch of this context record an event before and after itself;
  * otas_timing_read waits for the stream, returns for each kind 0 .. otas_timing_kinds()-1 the summed
  * milliseconds and the number of launches since the last read, and clears the records.
- * Enabling also measures the event pair's own overhead -- 2 t1 - t2 with t1 / t2 the median reading
- * of a pair around one / two one-element fill launches, otas_timing_overhead_ms -- and every record
- * is reported net of it.
+ * Enabling also measures what an event pair adds to the launch it brackets -- the median reading of
+ * pairs around a one-wave kernel that spins for 10 us / 30 us of the device's wall clock, less the
+ * spin and less 1 us for the dispatch's own ramp (otas_timing_overhead_ms; 0 when the calibration
+ * is not self-consistent) -- and every record is reported net of it.
  * total_ms / launches: host arrays of otas_timing_kinds() entries.  Off by default. */
 otas_status otas_timing_enable(otas_ctx *ctx, int32_t on);
 int32_t otas_timing_kinds(void);

@@ -854,32 +854,39 @@ otas_status otas_timing_enable(otas_ctx* c, int32_t on) {
   c->timing = false;
   c->ev_kind.clear();
   if (on) {
-    // Calibrate: an event pair around a one-element fill reads t1 = overhead + one tiny kernel, a pair
-    // around two such fills t2 = overhead + two of them, so overhead = 2 t1 - t2 (medians of 15).
-    // That overhead -- not the tiny kernel's own duration, which every real kernel has too -- is
-    // subtracted from every later record.
+    // Calibrate what an event pair adds to the launch it brackets, on kernels of known duration: one
+    // wave that spins for 10 us and for 30 us of the device's constant-rate wall clock, 15 pairs each.
+    // A pair reads spin + overhead + the dispatch's own ramp (launch to first instruction, last
+    // instruction to completion), which a profiler counts as kernel time for every kernel: 1 us is
+    // taken for it (a kernel-trace profiler reports 0.8 .. 1.9 us for an empty one-wave kernel on MI355X),
+    // so overhead = median(reading - spin) - 1 us.  If the two spin lengths do not differ by 20 us within
+    // 5 %, or the result is negative, nothing is subtracted (durations then read long, never short).
     c->timing = true;
     c->ev_overhead_ms = 0.f;
     int32_t* cell = c->d_plan + kPlanInts - 1;
-    for (int i = 0; i < 15; ++i) {
-      OTAS_LAUNCH(K_MISC, launch_fill_i32(cell, 0, 1, c->stream));
-      {
-        LaunchTimer t(c, K_MISC, c->stream);
-        OTAS_HIP(launch_fill_i32(cell, 0, 1, c->stream));
-        OTAS_HIP(launch_fill_i32(cell, 0, 1, c->stream));
-      }
-    }
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0)
+      khz = 100000;
+    const double spin_us[2] = {10.0, 30.0};
+    OTAS_HIP(launch_spin((int64_t)(spin_us[0] * khz / 1000.0), cell, c->stream));   // warm the code object
+    for (int i = 0; i < 15; ++i)
+      for (int j = 0; j < 2; ++j) OTAS_LAUNCH(K_MISC, launch_spin((int64_t)(spin_us[j] * khz / 1000.0), cell, c->stream));
     if (hipStreamSynchronize(c->stream) != hipSuccess) return OTAS_EDEVICE;
-    std::vector<float> one, two;
+    std::vector<float> rd[2];
     for (size_t i = 0; i < c->ev_kind.size(); ++i) {
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, c->ev_pool[2 * i], c->ev_pool[2 * i + 1]) != hipSuccess) return OTAS_EDEVICE;
-      (i % 2 == 0 ? one : two).push_back(ms);
+      rd[i % 2].push_back(ms * 1e3f);
     }
-    std::sort(one.begin(), one.end());
-    std::sort(two.begin(), two.end());
-    if (!one.empty() && !two.empty())
-      c->ev_overhead_ms = std::max(0.f, 2.f * one[one.size() / 2] - two[two.size() / 2]);
+    if (!rd[0].empty() && !rd[1].empty()) {
+      std::sort(rd[0].begin(), rd[0].end());
+      std::sort(rd[1].begin(), rd[1].end());
+      const double m0 = rd[0][rd[0].size() / 2], m1 = rd[1][rd[1].size() / 2];
+      const double step = m1 - m0, want = spin_us[1] - spin_us[0];
+      const double over = 0.5 * ((m0 - spin_us[0]) + (m1 - spin_us[1])) - 1.0;
+      if (step > 0.95 * want && step < 1.05 * want && over > 0.0) c->ev_overhead_ms = (float)(over * 1e-3);
+    }
     c->ev_kind.clear();
   }
   return OTAS_OK;

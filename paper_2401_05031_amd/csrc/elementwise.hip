@@ -15,6 +15,19 @@ __global__ void copy_i32_kernel(const int32_t* __restrict__ a, int32_t* __restri
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) b[i] = a[i];
 }
+// One wave that stays busy for `ticks` periods of the constant-rate wall clock (a kernel of known
+// duration, used to calibrate what an event pair adds to a launch).  The iteration cap makes the loop end
+// whatever the clock does.
+__global__ void spin_kernel(int64_t ticks, int32_t* sink) {
+  const int64_t t0 = wall_clock64();
+  int32_t it = 0;
+  while (it < (1 << 22) && wall_clock64() - t0 < ticks) ++it;
+  if (threadIdx.x == 0) sink[0] = it;
+}
+hipError_t launch_spin(int64_t ticks, int32_t* sink, hipStream_t s) {
+  spin_kernel<<<dim3(1), dim3(64), 0, s>>>(ticks, sink);
+  return hipGetLastError();
+}
 hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   fill_i32_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(p, v, n);

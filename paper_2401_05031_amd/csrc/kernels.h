@@ -8,6 +8,8 @@ namespace otas {
 
 enum Epilogue { EPI_NONE = 0, EPI_GELU = 1, EPI_RESIDUAL = 2, EPI_PARTIAL = 3 /* internal: raw float sums */ };
 
+// One wave busy for `ticks` wall-clock periods (hipDeviceAttributeWallClockRate); sink: one int.
+hipError_t launch_spin(int64_t ticks, int32_t* sink, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s);
 hipError_t launch_copy_i32(const int32_t* src, int32_t* dst, int64_t n, hipStream_t s);
 
