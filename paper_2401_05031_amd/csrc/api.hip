@@ -21,6 +21,8 @@ namespace {
 constexpr size_t kAlign = 256;
 constexpr int64_t kRowPad = 256;              // activation buffers are padded to this many rows
 constexpr size_t kPlanInts = (size_t)1 << 20;  // capacity of the device plan buffer (int32 entries)
+constexpr int kStageSlots = 32;
+constexpr size_t kSlotInts = kPlanInts / kStageSlots;
 constexpr int kMaxLanes = 8;
 constexpr int kPartRows = 2;   // split-K workspace: this many float rows of width D per token row
 
@@ -35,9 +37,13 @@ struct otas_ctx {
   hipStream_t stream;
   int device;
   int32_t* d_plan;        // device plan buffer [kPlanInts]
-  int32_t* h_plan[2];     // pinned host staging, double buffered
-  hipEvent_t h_done[2];   // staging buffer i may be overwritten once h_done[i] has completed
-  bool h_used[2];
+  // Pinned host staging for the plan: a ring of kStageSlots slots of kSlotInts entries, so that the host
+  // can enqueue that many calls ahead of the device (a host thread that is descheduled for tens of
+  // milliseconds then costs nothing as long as the queue holds work).  Slot i may be overwritten once
+  // h_done[i] has completed.  A plan larger than a slot uses the whole buffer and waits for the copy.
+  int32_t* h_plan;
+  hipEvent_t h_done[kStageSlots];
+  bool h_used[kStageSlots];
   int h_next;
   // The merge plan of a layer needs only that layer's keys (the QKV projection), so it runs on a
   // second stream next to attention and the output projection: forked after the QKV GEMM, joined
@@ -74,13 +80,24 @@ bool offsets_ok(const int32_t* off, int B) {
 // Copies `count` ints to the device plan buffer at entry `at` through pinned staging.
 otas_status upload_plan(otas_ctx* c, const std::vector<int32_t>& host) {
   if (host.size() > kPlanInts) return OTAS_ENOMEM;
+  const size_t bytes = host.size() * sizeof(int32_t);
+  if (host.size() > kSlotInts) {
+    for (int j = 0; j < kStageSlots; ++j) {
+      if (c->h_used[j] && hipEventSynchronize(c->h_done[j]) != hipSuccess) return OTAS_EDEVICE;
+      c->h_used[j] = false;
+    }
+    std::memcpy(c->h_plan, host.data(), bytes);
+    if (hipMemcpyAsync(c->d_plan, c->h_plan, bytes, hipMemcpyHostToDevice, c->stream) != hipSuccess ||
+        hipStreamSynchronize(c->stream) != hipSuccess)
+      return OTAS_EDEVICE;
+    return OTAS_OK;
+  }
   const int i = c->h_next;
-  c->h_next ^= 1;
+  c->h_next = (c->h_next + 1) % kStageSlots;
   if (c->h_used[i] && hipEventSynchronize(c->h_done[i]) != hipSuccess) return OTAS_EDEVICE;
-  std::memcpy(c->h_plan[i], host.data(), host.size() * sizeof(int32_t));
-  if (hipMemcpyAsync(c->d_plan, c->h_plan[i], host.size() * sizeof(int32_t), hipMemcpyHostToDevice, c->stream) !=
-      hipSuccess)
-    return OTAS_EDEVICE;
+  int32_t* slot = c->h_plan + (size_t)i * kSlotInts;
+  std::memcpy(slot, host.data(), bytes);
+  if (hipMemcpyAsync(c->d_plan, slot, bytes, hipMemcpyHostToDevice, c->stream) != hipSuccess) return OTAS_EDEVICE;
   if (hipEventRecord(c->h_done[i], c->stream) != hipSuccess) return OTAS_EDEVICE;
   c->h_used[i] = true;
   return OTAS_OK;
@@ -225,9 +242,8 @@ otas_status otas_create(otas_ctx** out, const otas_model_desc* desc, const otas_
   c->layers.assign(layers, layers + d.L);
   c->stream = (hipStream_t)hip_stream;
   c->d_plan = nullptr;
-  c->h_plan[0] = c->h_plan[1] = nullptr;
-  c->h_done[0] = c->h_done[1] = nullptr;
-  c->h_used[0] = c->h_used[1] = false;
+  c->h_plan = nullptr;
+  for (int i = 0; i < kStageSlots; ++i) { c->h_done[i] = nullptr; c->h_used[i] = false; }
   c->h_next = 0;
   c->timing = false;
   c->ev_overhead_ms = 0.f;
@@ -238,10 +254,9 @@ otas_status otas_create(otas_ctx** out, const otas_model_desc* desc, const otas_
   if (const char* e = std::getenv("OTAS_LANES")) c->lanes = std::max(0, std::min(kMaxLanes, std::atoi(e)));
   bool ok = hipGetDevice(&c->device) == hipSuccess;
   ok = ok && hipMalloc((void**)&c->d_plan, kPlanInts * sizeof(int32_t)) == hipSuccess;
-  for (int i = 0; i < 2 && ok; ++i) {
-    ok = hipHostMalloc((void**)&c->h_plan[i], kPlanInts * sizeof(int32_t), hipHostMallocDefault) == hipSuccess;
-    ok = ok && hipEventCreateWithFlags(&c->h_done[i], hipEventDisableTiming) == hipSuccess;
-  }
+  ok = ok && hipHostMalloc((void**)&c->h_plan, kPlanInts * sizeof(int32_t), hipHostMallocDefault) == hipSuccess;
+  for (int i = 0; i < kStageSlots && ok; ++i)
+    ok = hipEventCreateWithFlags(&c->h_done[i], hipEventDisableTiming) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&c->ev_begin, hipEventDisableTiming) == hipSuccess;
   ok = ok && ensure_lanes(c, 1);
   if (!ok) {
@@ -264,10 +279,9 @@ otas_status otas_destroy(otas_ctx* c) {
     if (ln.ev_done) (void)hipEventDestroy(ln.ev_done);
   }
   if (c->ev_begin) (void)hipEventDestroy(c->ev_begin);
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < kStageSlots; ++i)
     if (c->h_done[i]) (void)hipEventDestroy(c->h_done[i]);
-    if (c->h_plan[i]) (void)hipHostFree(c->h_plan[i]);
-  }
+  if (c->h_plan) (void)hipHostFree(c->h_plan);
   for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
   if (c->d_plan) (void)hipFree(c->d_plan);
   delete c;

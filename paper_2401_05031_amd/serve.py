@@ -208,6 +208,7 @@ def main(argv=None) -> None:
     Sec. II-C) relative to the 200..700 requests / s load; thresholds given in seconds scale with it.
     Prints one JSON line."""
     import argparse
+    import gc
     import json
     import os
     import sys
@@ -229,6 +230,8 @@ def main(argv=None) -> None:
     eng = GpuEngine(ctx, cfg.n0, synth.TASK_CLASSES, max(gammas), pool=64)
     lat = eng.measure_profile(gammas, n_tasks, batch=64)
     acc = synth.stand_in_accuracy(gammas, n_tasks)
+    gc.collect()
+    gc.freeze()     # a full collection (tens of ms with torch imported) must not land inside a measured batch
     thr0 = 1.0 / float(lat[:, gammas.index(0)].mean())
     scale = 580.0 / thr0
     trace = synth.poisson_trace(args.seed, args.seconds, 200.0 * args.load, 700.0 * args.load, time_scale=scale)

@@ -800,3 +800,32 @@ def test_serving_engine_batches_match_oracle_and_loop_accounts(torch_cuda, lib):
     assert sorted(i for rec in res["log"] for i in rec[2]) == list(range(len(trace)))
     assert all(len(rec[2]) <= 8 for rec in res["log"] if rec[0] == "run")
     ctx.close()
+
+
+def test_many_short_queries_plan_larger_than_a_staging_slot(torch_cuda, lib):
+    """6000 queries of 3 to 5 tokens: the per-call plan (offsets, merge counts and trace offsets per layer)
+    is larger than one slot of the host staging ring, so the whole-buffer upload path runs; followed by an
+    ordinary small call on the same context.  Sampled queries against the oracle, fp32."""
+    cfg = synth.config("tiny")
+    B = 6000
+    rng = np.random.default_rng(17)
+    n = rng.integers(3, 6, B)
+    R = rng.integers(0, 3, B).tolist()
+    base = synth.query_tokens(cfg, 0)
+    toks = [np.ascontiguousarray(base[(7 * q) % 150:(7 * q) % 150 + n[q]]) for q in range(B)]
+    prm = [np.zeros((0, cfg.D), dtype=np.float32)] * B
+    ctx, layers = hz.make_context(cfg)
+    x0, off = hz.gpu_prepend(ctx, toks, prm)
+    gpu = hz.gpu_forward(ctx, x0, off, R, trace=False)
+    for q in [0, 1, 2, 2999, 5998, 5999] + rng.integers(0, B, 10).tolist():
+        ref = hz.oracle_forward(cfg, layers, [toks[q]], [prm[q]], [R[q]])
+        assert gpu["x"][q].shape == ref[0]["x"].shape, q
+        assert hz.rel_err(gpu["x"][q], ref[0]["x"]) <= F32_TOL, q
+        assert np.array_equal(gpu["sizes"][q], ref[0]["sizes"]), q
+    toks2, prm2, P2, R2 = synth.batch(cfg)
+    x0, off = hz.gpu_prepend(ctx, toks2, prm2)
+    gpu = hz.gpu_forward(ctx, x0, off, R2, trace=False)
+    ref = hz.oracle_forward(cfg, layers, toks2, prm2, R2)
+    for q in range(cfg.B):
+        assert hz.rel_err(gpu["x"][q], ref[q]["x"]) <= F32_TOL
+    ctx.close()
