@@ -21,6 +21,7 @@ namespace {
 constexpr size_t kAlign = 256;
 constexpr int64_t kRowPad = 256;              // activation buffers are padded to this many rows
 constexpr size_t kPlanInts = (size_t)1 << 20;  // capacity of the device plan buffer (int32 entries)
+constexpr int64_t kPlanSideMinRows = 4096;   // batches below this many rows plan inline (see run_layers)
 constexpr int kStageSlots = 32;
 constexpr size_t kSlotInts = kPlanInts / kStageSlots;
 constexpr int kMaxLanes = 8;
@@ -571,6 +572,14 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
       ln.x_owned = true;
     }
   }
+  // The merge plan runs beside attention and the projection on a side stream when the batch is large
+  // enough for that to pay: forking and joining costs the host ~45 us per layer, more than a small
+  // batch's layer takes on the GPU, so small batches keep the plan on the lane's own stream.
+  static const int plan_mode = [] {
+    const char* e = std::getenv("OTAS_PLAN_STREAM");   // tuning override: 1 = always inline, 2 = always side
+    return e ? std::atoi(e) : 0;
+  }();
+  const bool plan_inline = plan_mode == 1 || (plan_mode == 0 && T0 < kPlanSideMinRows);
   for (int l = 0; l < L; ++l) {
     const otas_layer_weights& wl = c->layers[layer_begin + l];
     for (int g = 0; g < G; ++g) {
@@ -600,13 +609,16 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
       if (ln.any_merge[l]) {
         // fork: the merge plan reads only the keys just written; the lists it writes were last read by
         // the previous layer's merge-apply, which precedes this point on the lane's stream
-        OTAS_HIP(hipEventRecord(hw.ev_fork, s));
-        OTAS_HIP(hipStreamWaitEvent(hw.side, hw.ev_fork, 0));
-        OTAS_LAUNCH_ON(K_PLAN, hw.side,
+        hipStream_t ps = plan_inline ? s : hw.side;
+        if (!plan_inline) {
+          OTAS_HIP(hipEventRecord(hw.ev_fork, s));
+          OTAS_HIP(hipStreamWaitEvent(hw.side, hw.ev_fork, 0));
+        }
+        OTAS_LAUNCH_ON(K_PLAN, ps,
                        launch_merge_plan(dt, qkv, 3 * (int64_t)D, D, H, dh, off_l, off_n, d_reff, d_tr, Bg,
                                          ln.max_n[l], n_lead, src_list, row_ptr, trace ? trace_src : nullptr,
-                                         trace ? trace_dst : nullptr, hw.side));
-        OTAS_HIP(hipEventRecord(hw.ev_join, hw.side));
+                                         trace ? trace_dst : nullptr, ps));
+        if (!plan_inline) OTAS_HIP(hipEventRecord(hw.ev_join, hw.side));
       }
       OTAS_LAUNCH_ON(K_ATTN, s,
                      launch_attention(dt, qkv, ln.sizes_now, off_l, Bg, ln.max_n[l], D, H, size_bias, hbuf, s));
@@ -619,7 +631,7 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
       // merging module
       if (ln.any_merge[l]) {
         void* x_other = (x_attn == (void*)x_free[0]) ? x_free[1] : x_free[0];
-        OTAS_HIP(hipStreamWaitEvent(s, hw.ev_join, 0));   // join
+        if (!plan_inline) OTAS_HIP(hipStreamWaitEvent(s, hw.ev_join, 0));   // join
         int32_t* sizes_next = (l == ln.last_merge) ? sizes_out + ln.rowL
                                                    : (ln.sizes_now == sizes_buf[0] ? sizes_buf[1] : sizes_buf[0]);
         // merge-apply and the block's second LayerNorm in one pass over the rows
