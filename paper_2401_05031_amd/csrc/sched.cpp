@@ -150,18 +150,23 @@ int otas_sched_create(const otas_sched_params* params, int32_t n_gamma, const in
   }
   otas_sched* s = new (std::nothrow) otas_sched();
   if (!s) return OTAS_ENOMEM;
-  s->p = *params;
-  s->NG = n_gamma;
-  s->NT = n_tasks;
-  s->gammas.assign(gammas, gammas + n_gamma);
-  s->latency.assign(latency, latency + (size_t)n_gamma * n_tasks);
-  s->accuracy.assign(accuracy, accuracy + (size_t)n_gamma * n_tasks);
-  if (n_rate > 0) {
-    s->rate_max.assign(rate_max, rate_max + n_rate);
-    s->rate_gamma.assign(rate_gamma, rate_gamma + n_rate);
+  try {
+    s->p = *params;
+    s->NG = n_gamma;
+    s->NT = n_tasks;
+    s->gammas.assign(gammas, gammas + n_gamma);
+    s->latency.assign(latency, latency + (size_t)n_gamma * n_tasks);
+    s->accuracy.assign(accuracy, accuracy + (size_t)n_gamma * n_tasks);
+    if (n_rate > 0) {
+      s->rate_max.assign(rate_max, rate_max + n_rate);
+      s->rate_gamma.assign(rate_gamma, rate_gamma + n_rate);
+    }
+    s->g_smallest = (int32_t)(std::min_element(s->gammas.begin(), s->gammas.end()) - s->gammas.begin());
+    s->g_largest = (int32_t)(std::max_element(s->gammas.begin(), s->gammas.end()) - s->gammas.begin());
+  } catch (const std::bad_alloc&) {
+    delete s;
+    return OTAS_ENOMEM;
   }
-  s->g_smallest = (int32_t)(std::min_element(s->gammas.begin(), s->gammas.end()) - s->gammas.begin());
-  s->g_largest = (int32_t)(std::max_element(s->gammas.begin(), s->gammas.end()) - s->gammas.begin());
   *out = s;
   return OTAS_OK;
 }
@@ -179,7 +184,11 @@ int otas_sched_add_query(otas_sched* s, int64_t id, double s_r, double l_r, doub
     if ((int32_t)bt.req.size() >= s->p.epsilon) continue;          // full
     if (std::fabs(bt.d_b - d_r) > s->p.eta) continue;              // deadlines too far apart
     if (std::fabs(bt.u_first - u_r) > s->p.mu) continue;           // utilities too far apart
-    bt.req.push_back(r);
+    try {
+      bt.req.push_back(r);
+    } catch (const std::bad_alloc&) {
+      return OTAS_ENOMEM;
+    }
     bt.per_task[task] += 1;
     bt.s_b = std::min(bt.s_b, s_r);
     bt.d_b = std::min(bt.d_b, d_r);
@@ -187,16 +196,20 @@ int otas_sched_add_query(otas_sched* s, int64_t id, double s_r, double l_r, doub
     if (batch) *batch = b;
     return OTAS_OK;
   }
-  Batch nb;
-  nb.req.push_back(r);
-  nb.per_task.assign(s->NT, 0);
-  nb.per_task[task] = 1;
-  nb.s_b = s_r;
-  nb.d_b = d_r;
-  nb.u_first = u_r;
-  nb.u_sum = u_r;
-  nb.gamma = OTAS_GAMMA_UNDECIDED;
-  s->queue.push_back(std::move(nb));
+  try {
+    Batch nb;
+    nb.req.push_back(r);
+    nb.per_task.assign(s->NT, 0);
+    nb.per_task[task] = 1;
+    nb.s_b = s_r;
+    nb.d_b = d_r;
+    nb.u_first = u_r;
+    nb.u_sum = u_r;
+    nb.gamma = OTAS_GAMMA_UNDECIDED;
+    s->queue.push_back(std::move(nb));
+  } catch (const std::bad_alloc&) {
+    return OTAS_ENOMEM;
+  }
   if (batch) *batch = (int32_t)s->queue.size() - 1;
   return OTAS_OK;
 }
@@ -205,12 +218,16 @@ int otas_sched_allocate(otas_sched* s, double T, double q, int32_t initial_stage
   if (!s || std::isnan(T) || std::isnan(q)) return OTAS_EINVAL;
   if (planned_utility) *planned_utility = std::numeric_limits<double>::quiet_NaN();
   if (s->queue.empty()) return OTAS_OK;
-  std::stable_sort(s->queue.begin(), s->queue.end(), [](const Batch& a, const Batch& b) { return a.d_b < b.d_b; });
-  if ((int32_t)s->queue.size() <= s->p.beta || initial_stage) {
-    s->allocate_by_rate(T, q);
-  } else {
-    const double best = s->allocate_by_dp(T);
-    if (planned_utility) *planned_utility = best;
+  try {   // the sort's buffer and the tables are the only allocations; the gammas are written last
+    std::stable_sort(s->queue.begin(), s->queue.end(), [](const Batch& a, const Batch& b) { return a.d_b < b.d_b; });
+    if ((int32_t)s->queue.size() <= s->p.beta || initial_stage) {
+      s->allocate_by_rate(T, q);
+    } else {
+      const double best = s->allocate_by_dp(T);
+      if (planned_utility) *planned_utility = best;
+    }
+  } catch (const std::bad_alloc&) {
+    return OTAS_ENOMEM;
   }
   return OTAS_OK;
 }
