@@ -181,6 +181,56 @@ __device__ inline void mfma_epilogue(const floatx16 (&acc)[TM][TN], float* stage
   }
 }
 
+// Epilogue for the 16-bit outputs (no residual).  Bias and GELU are applied to the accumulators in
+// registers (a lane owns runs of 4 consecutive columns of one row), the results are rounded to bf16
+// and only then transposed through the wave's LDS slab, [32][WN + 8] bf16: half the LDS traffic of the
+// float slab, and the read-back hands every lane 8 consecutive columns, so the global stores are
+// 16 bytes per lane and a row segment of 2 WN bytes goes out in one instruction.
+template <int EPI, int TM, int TN>
+__device__ inline void mfma_epilogue_bf16(const floatx16 (&acc)[TM][TN], bf16_t* stage, const bf16_t* __restrict__ bias,
+                                          bf16_t* Y, int64_t M, int N, int64_t m_wave, int n_wave, int lane) {
+  constexpr int WN = 32 * TN, LDR = WN + 8;
+  constexpr int LPR = WN / 8;      // lanes per row when reading back
+  constexpr int RPI = 64 / LPR;    // rows per read-back instruction
+  constexpr int NIT = 32 / RPI;
+  const int fr = lane & 31, fk = lane >> 5;
+  const int rrow = lane / LPR, rcol = (lane % LPR) * 8;
+  const int n_out = n_wave + rcol;
+  const bool n_ok = n_out < N;     // N % 8 == 0: an 8-column group is inside or outside as a whole
+  bf16x4 bb[TN][4];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int n = n_wave + 32 * j + 8 * g + 4 * fk;
+      bb[j][g] = *reinterpret_cast<const bf16x4*>(bias + (n < N ? n : 0));
+    }
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int64_t m_slab = m_wave + i * 32;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          v[e] = acc[i][j][g * 4 + e] + (float)bb[j][g][e];
+          if (EPI == EPI_GELU) v[e] = gelu_bf16(v[e]);
+        }
+        const bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
+        *reinterpret_cast<bf16x4*>(stage + fr * LDR + j * 32 + g * 8 + fk * 4) = o;
+      }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int row = it * RPI + rrow;
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(stage + row * LDR + rcol);
+      const int64_t m = m_slab + row;
+      if (m < M && n_ok) *reinterpret_cast<bf16x8*>(Y + (size_t)m * N + n_out) = a;
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------ bf16 MFMA tiles
 // Block tile BM x BN, K step 64, 256 threads = 4 waves in a WGM x WGN grid, each wave owning a
 // (BM/WGM) x (BN/WGN) sub-tile built from 32x32x16 MFMAs.  Operand tiles are staged through LDS,
@@ -291,8 +341,12 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict
   }
 
   __syncthreads();   // the operand buffers become the epilogue's staging area
-  mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
-                             m0 + wm * WM, n0 + wn * WN, lane);
+  if constexpr (EPI == EPI_NONE || EPI == EPI_GELU)
+    mfma_epilogue_bf16<EPI, TM, TN>(acc, reinterpret_cast<bf16_t*>(smem) + wave * 32 * (WN + 8), bias, Y, M, N,
+                                    m0 + wm * WM, n0 + wn * WN, lane);
+  else
+    mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
+                               m0 + wm * WM, n0 + wn * WN, lane);
 }
 
 template <int BM, int BN, int WGM, int WGN>
@@ -476,8 +530,12 @@ __global__ __launch_bounds__(256, 3) void gemm_mfma128_dma_kernel(const bf16_t* 
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();   // ... and of every other wave: the stages become the epilogue's staging area
   asm volatile("" ::: "memory");
-  mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
-                             m0 + wm * WM, n0 + wn * WN, lane);
+  if constexpr (EPI == EPI_NONE || EPI == EPI_GELU)
+    mfma_epilogue_bf16<EPI, TM, TN>(acc, reinterpret_cast<bf16_t*>(smem) + wave * 32 * (WN + 8), bias, Y, M, N,
+                                    m0 + wm * WM, n0 + wn * WN, lane);
+  else
+    mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
+                               m0 + wm * WM, n0 + wn * WN, lane);
 }
 
 template <int NS>
@@ -654,8 +712,12 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
-                             m0 + wm * WM, n0 + wn * WN, lane);
+  if constexpr (EPI == EPI_NONE || EPI == EPI_GELU)
+    mfma_epilogue_bf16<EPI, TM, TN>(acc, reinterpret_cast<bf16_t*>(smem) + wave * 32 * (WN + 8), bias, Y, M, N,
+                                    m0 + wm * WM, n0 + wn * WN, lane);
+  else
+    mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
+                               m0 + wm * WM, n0 + wn * WN, lane);
 }
 
 template <int TM>
@@ -803,8 +865,12 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma128k64_kernel(const bf16_t* _
   asm volatile("" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
-  mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
-                             m0 + wm * WM, n0 + wn * WN, lane);
+  if constexpr (EPI == EPI_NONE || EPI == EPI_GELU)
+    mfma_epilogue_bf16<EPI, TM, TN>(acc, reinterpret_cast<bf16_t*>(smem) + wave * 32 * (WN + 8), bias, Y, M, N,
+                                    m0 + wm * WM, n0 + wn * WN, lane);
+  else
+    mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
+                               m0 + wm * WM, n0 + wn * WN, lane);
 }
 
 static hipError_t linear_mfma128k64(const void* x, const void* w, const void* bias, const float* res, void* y,
