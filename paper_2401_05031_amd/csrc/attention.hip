@@ -175,14 +175,15 @@ __global__ __launch_bounds__(64 * NW, (DH <= 64 ? 16 : 8) / NW) void attention_m
         const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + (kb + fr) * LD + ks * 16 + fk * 8);
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
       }
-      // Logits in base-2 units: t = s * (scale * log2 e) [+ log2(size)], so that exp(s - m) is one
-      // v_exp_f32 of a difference.  Only the chunk's last block can hold keys past the end.
+      // Logits in base-2 units, t = s * (scale * log2 e) [+ log2(size)], so that exp(s - m) is one
+      // v_exp_f32.  Without the size bias the scaling is folded into the exponent's argument,
+      // exp2(fma(s, scale2, -m)): the maximum is taken over the raw products (scale2 > 0) and scaled
+      // once per row.  Only the chunk's last block can hold keys past the end.
       float mx = -INFINITY;
+      if (BIAS) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float v = sacc[e] * scale2;
-        if (BIAS) v += lnsz[kb + 8 * (e >> 2) + 4 * fk + (e & 3)];
-        sacc[e] = v;
+        for (int e = 0; e < 16; ++e)
+          sacc[e] = sacc[e] * scale2 + lnsz[kb + 8 * (e >> 2) + 4 * fk + (e & 3)];
       }
       if (kb + 32 > nc) {   // wave-uniform: keys past the end of the sequence
 #pragma unroll
@@ -192,6 +193,7 @@ __global__ __launch_bounds__(64 * NW, (DH <= 64 ? 16 : 8) / NW) void attention_m
 #pragma unroll
       for (int e = 0; e < 16; ++e) mx = fmaxf(mx, sacc[e]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+      if (!BIAS) mx *= scale2;
       if (__any(mx > m_run)) {   // some row's maximum moved: rescale what has been accumulated
         const float m_new = fmaxf(m_run, mx);
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);   // 0 on the first block (m_run = -inf)
@@ -205,7 +207,8 @@ __global__ __launch_bounds__(64 * NW, (DH <= 64 ? 16 : 8) / NW) void attention_m
       float psum = 0.f;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const float pv = __builtin_amdgcn_exp2f(sacc[e] - m_run);
+        const float pv = BIAS ? __builtin_amdgcn_exp2f(sacc[e] - m_run)
+                              : __builtin_amdgcn_exp2f(fmaf(sacc[e], scale2, -m_run));
         sacc[e] = pv;
         psum += pv;
       }
