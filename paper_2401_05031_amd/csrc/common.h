@@ -59,15 +59,19 @@ __device__ inline float gelu_exact(float x) { return 0.5f * x * (1.0f + erff(x *
 // The same GELU for results that are rounded to bf16 afterwards: erf by the rational-exponential
 // formula 7.1.26 of Abramowitz & Stegun (|error| < 1.5e-7, three orders below half a bf16 unit),
 // which costs one exp, one reciprocal and a short polynomial instead of the library erff.
+// With z = |x| / sqrt 2, t = 1 / (1 + p z) and erf z = 1 - poly(t) t exp(-z^2):
+//   0.5 x (1 + erf(x / sqrt 2)) = max(x, 0) - |x| * (0.5 poly(t)) * t * exp(-x^2 / 2),
+// which needs neither the sign transfer nor z itself (the halves are folded into the coefficients).
 __device__ inline float gelu_bf16(float x) {
-  const float z = fabsf(x) * 0.70710678118654752440f;
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, z, 1.0f));   // 1 ulp reciprocal
-  float p = fmaf(1.061405429f, t, -1.453152027f);
-  p = fmaf(p, t, 1.421413741f);
-  p = fmaf(p, t, -0.284496736f);
-  p = fmaf(p, t, 0.254829592f);
-  const float erfz = 1.0f - p * t * __expf(-z * z);
-  return 0.5f * x * (1.0f + copysignf(erfz, x));
+  const float ax = fabsf(x);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752440f, ax, 1.0f));   // 1 ulp reciprocal
+  const float e = __builtin_amdgcn_exp2f(x * x * (-0.5f * 1.44269504088896340736f));
+  float p = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
+  p = fmaf(p, t, 0.5f * 1.421413741f);
+  p = fmaf(p, t, 0.5f * -0.284496736f);
+  p = fmaf(p, t, 0.5f * 0.254829592f);
+  const float relu = __builtin_amdgcn_fmed3f(x, 0.0f, 3.0e38f);   // max(x, 0) in one instruction
+  return fmaf(-ax, p * t * e, relu);
 }
 
 }  // namespace otas
