@@ -565,11 +565,14 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
     ln.x_cur = (const char*)x0 + (size_t)ln.row0 * D * es_in;   // residual stream entering the block
     ln.x_owned = false;   // x_cur is one of the workspace buffers, so it may be updated in place
     ln.ln1_done = false;
-    if (!x0_is_float) {   // 16-bit tokens: widen once into the workspace
+    if (!x0_is_float) {   // 16-bit tokens: widened into the workspace by the first block's LayerNorm
       float* xa = (float*)(ws + w.xa) + (size_t)ln.row0 * D;
-      OTAS_LAUNCH_ON(K_MISC, s, launch_widen(ln.x_cur, xa, ln.T[0] * D, s));
+      char* hbuf = ws + w.h + (size_t)ln.row0 * D * es;
+      const otas_layer_weights& w0 = c->layers[layer_begin];
+      OTAS_LAUNCH_ON(K_LN, s, launch_layer_norm_widen(ln.x_cur, w0.ln1_g, w0.ln1_b, hbuf, xa, ln.T[0], D, d.ln_eps, s));
       ln.x_cur = xa;
       ln.x_owned = true;
+      ln.ln1_done = true;
     }
   }
   // The merge plan runs beside attention and the projection on a side stream when the batch is large

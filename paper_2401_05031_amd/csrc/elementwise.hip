@@ -137,10 +137,12 @@ hipError_t launch_deep_prompt(int dtype, const float* x_old, float* x_new, const
 // in fp32 (mean, then the biased variance of the centred values).
 // XT = type of the input row (the residual stream is float), T = type of gamma, beta and the output.
 // Each lane owns chunks of 8 consecutive columns (two 16-byte loads of a float row).
+// xw != nullptr: the row is also written out as floats (16-bit tokens entering the float residual
+// stream: the widening copy rides on the first block's LayerNorm).
 template <typename XT, typename T, int NCH>
 __global__ __launch_bounds__(256) void layer_norm_kernel(const XT* __restrict__ x, const T* __restrict__ g,
                                                          const T* __restrict__ b, T* __restrict__ y,
-                                                         int64_t Trows, int D, float eps) {
+                                                         int64_t Trows, int D, float eps, float* __restrict__ xw) {
   constexpr int V = 8;
   const int lane = threadIdx.x & 63;
   const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -162,6 +164,20 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(const XT* __restrict__ 
     } else {
 #pragma unroll
       for (int k = 0; k < V; ++k) v[i][k] = 0.f;
+    }
+  }
+  if (xw) {
+    float* wr = xw + (size_t)row * D;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = lane + 64 * i;
+      if (c < chunks) {
+        Vec<float> lo, hi;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) { lo.set(k, v[i][k]); hi.set(k, v[i][4 + k]); }
+        store_vec<float>(wr + c * V, lo);
+        store_vec<float>(wr + c * V + 4, hi);
+      }
     }
   }
   const float mean = wave_sum(sum) / (float)D;
@@ -193,12 +209,12 @@ __global__ __launch_bounds__(256) void layer_norm_kernel(const XT* __restrict__ 
 
 template <typename XT, typename T>
 static hipError_t layer_norm_dispatch(const void* x, const void* g, const void* b, void* y, int64_t Trows,
-                                      int D, float eps, hipStream_t s) {
+                                      int D, float eps, hipStream_t s, float* xw = nullptr) {
   const int chunks = D / 8;
   const int nch = (chunks + 63) / 64;
   dim3 grid((unsigned)((Trows + 3) / 4)), block(256);
 #define OTAS_LN(N)                                                                                       \
-  layer_norm_kernel<XT, T, N><<<grid, block, 0, s>>>((const XT*)x, (const T*)g, (const T*)b, (T*)y, Trows, D, eps)
+  layer_norm_kernel<XT, T, N><<<grid, block, 0, s>>>((const XT*)x, (const T*)g, (const T*)b, (T*)y, Trows, D, eps, xw)
   if (nch <= 1) OTAS_LN(1);
   else if (nch <= 2) OTAS_LN(2);
   else if (nch <= 3) OTAS_LN(3);
@@ -215,6 +231,12 @@ hipError_t launch_layer_norm(int dtype, bool x_is_float, const void* x, const vo
   if (dtype == 0) return layer_norm_dispatch<float, float>(x, g, b, y, T, D, eps, s);
   return x_is_float ? layer_norm_dispatch<float, bf16_t>(x, g, b, y, T, D, eps, s)
                     : layer_norm_dispatch<bf16_t, bf16_t>(x, g, b, y, T, D, eps, s);
+}
+
+hipError_t launch_layer_norm_widen(const void* x_bf16, const void* g, const void* b, void* y, float* x_float,
+                                   int64_t T, int D, float eps, hipStream_t s) {
+  if (T <= 0) return hipSuccess;
+  return layer_norm_dispatch<bf16_t, bf16_t>(x_bf16, g, b, y, T, D, eps, s, x_float);
 }
 
 // ---------------------------------------------------------------------------------- merge-apply + LayerNorm

@@ -42,6 +42,9 @@ hipError_t launch_task_heads(int dtype, const float* x, const int32_t* d_off, co
 hipError_t launch_layer_norm(int dtype, bool x_is_float, const void* x, const void* g, const void* b,
                              void* y, int64_t T, int D, float eps, hipStream_t s);
 hipError_t launch_widen(const void* src_bf16, float* dst, int64_t n, hipStream_t s);
+// LayerNorm of bf16 rows that also writes the rows out as floats (x_float [T, D]).
+hipError_t launch_layer_norm_widen(const void* x_bf16, const void* g, const void* b, void* y, float* x_float,
+                                   int64_t T, int D, float eps, hipStream_t s);
 
 // EPI_RESIDUAL: res and y are float (the residual stream) for every dtype; otherwise y has the
 // model's dtype.
