@@ -749,10 +749,13 @@ otas_status otas_encoder_forward_deep(otas_ctx* c, const void* x0, const int32_t
 
   const float* x_cur = (const float*)x0;   // float residual stream entering the block
   int cur = -1;                            // which workspace buffer holds x_cur (-1: the caller's x0)
-  if (dt != OTAS_F32) {                    // 16-bit tokens: widen once into the workspace
-    OTAS_LAUNCH(K_MISC, launch_widen(x0, x_buf[0], T0 * D, s));
+  bool ln1_done = false;
+  if (dt != OTAS_F32) {                    // 16-bit tokens: widened into the workspace by the first block's LayerNorm
+    OTAS_LAUNCH(K_LN, launch_layer_norm_widen(x0, c->layers[0].ln1_g, c->layers[0].ln1_b, hbuf, x_buf[0], T0, D,
+                                              d.ln_eps, s));
     x_cur = x_buf[0];
     cur = 0;
+    ln1_done = true;
   }
   for (int l = 0; l < L; ++l) {
     const otas_layer_weights& wl = c->layers[l];
@@ -770,7 +773,8 @@ otas_status otas_encoder_forward_deep(otas_ctx* c, const void* x0, const int32_t
                                                   n_lead, false, s));
       }
     }
-    OTAS_LAUNCH(K_LN, launch_layer_norm(dt, true, x_cur, wl.ln1_g, wl.ln1_b, hbuf, T, D, d.ln_eps, s));
+    if (!ln1_done) OTAS_LAUNCH(K_LN, launch_layer_norm(dt, true, x_cur, wl.ln1_g, wl.ln1_b, hbuf, T, D, d.ln_eps, s));
+    ln1_done = false;
     OTAS_LAUNCH(K_QKV, launch_linear(dt, hbuf, wl.w_qkv, wl.b_qkv, nullptr, qkv, T, 3 * D, D, EPI_NONE, s));
     OTAS_LAUNCH(K_ATTN, launch_attention(dt, qkv, nullptr, off_l, B, max_n[l], D, H, false, hbuf, s));
     if (cur < 0) cur = 0;   // the caller's x0 is never written: layer 0 of an f32 model writes into the workspace
