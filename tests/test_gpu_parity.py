@@ -829,3 +829,36 @@ def test_many_short_queries_plan_larger_than_a_staging_slot(torch_cuda, lib):
     for q in range(cfg.B):
         assert hz.rel_err(gpu["x"][q], ref[q]["x"]) <= F32_TOL
     ctx.close()
+
+
+def test_bench_prints_one_json_line_with_the_contract_keys(torch_cuda, lib):
+    """bench.py as the driver runs it (a child process, few steps, a two-query oracle sample): exactly one
+    JSON line on stdout with the agreed keys, a roofline object for the dominant kernel and the oracle baseline;
+    more than one GPU is refused with a message."""
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "3", "--warmup", "1", "--others", "",
+                        "--cpu-queries", "2"], capture_output=True, text=True, timeout=110, cwd=root)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    b = json.loads(lines[0])
+    for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+              "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert k in b, k
+    assert b["n_gpus"] == 1 and b["steps"] == 3 and b["warmup"] == 1 and b["higher_is_better"] is True
+    assert b["unit"] == "images/s" and b["dtype"] == "bf16" and b["data"] == "synthetic" and b["vs_baseline"] is None
+    assert "workload" in b["config"] and "model" not in b["config"]
+    assert b["value"] == pytest.approx(64 / (b["ms_per_step"] * 1e-3), rel=1e-3)
+    rf = b["roofline"]
+    assert rf["bound"] == "mfma" and rf["unit"] == "TFLOP/s" and rf["peak"] == 2500.0
+    assert rf["frac"] == pytest.approx(rf["achieved"] / rf["peak"], abs=1e-3) and 0.0 < rf["frac"] < 1.0
+    assert rf["traffic"] is None or rf["traffic"] > 0
+    cb = b["cpu_baseline"]
+    assert cb["kind"] == "oracle" and cb["unit"] == "images/s" and cb["value"] > 0 and cb["cores"] >= 1 and cb["sample"]
+    r2 = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                        timeout=60, cwd=root)
+    assert r2.returncode != 0 and "ONE GPU" in (r2.stderr + r2.stdout)
