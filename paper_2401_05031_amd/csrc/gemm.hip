@@ -134,17 +134,21 @@ __device__ inline void mfma_epilogue(const floatx16 (&acc)[TM][TN], float* stage
   const bool n_ok = n < N;         // N % 8 == 0: a 4-column group is inside or outside as a whole
   bf16x4 bb = {(bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f, (bf16_t)0.f};
   if (EPI != EPI_PARTIAL) bb = *reinterpret_cast<const bf16x4*>(bias + (n_ok ? n : 0));
+  // The residual rows of slab i + 1 are requested before slab i goes through LDS, so their latency
+  // is covered by a whole slab's work instead of being waited for once per slab.
+  floatx4 rr[2][NIT];
+  auto load_res = [&](int i) {
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int64_t m = m_wave + i * 32 + it * RPI + rrow;
+      rr[i & 1][it] = *reinterpret_cast<const floatx4*>(res + (size_t)(m < M ? m : M - 1) * N + (n_ok ? n : 0));
+    }
+  };
+  if (EPI == EPI_RESIDUAL) load_res(0);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int64_t m_slab = m_wave + i * 32;
-    floatx4 rr[NIT];
-    if (EPI == EPI_RESIDUAL) {
-#pragma unroll
-      for (int it = 0; it < NIT; ++it) {
-        const int64_t m = m_slab + it * RPI + rrow;
-        rr[it] = *reinterpret_cast<const floatx4*>(res + (size_t)(m < M ? m : M - 1) * N + (n_ok ? n : 0));
-      }
-    }
+    if (EPI == EPI_RESIDUAL && i + 1 < TM) load_res(i + 1);
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -167,7 +171,7 @@ __device__ inline void mfma_epilogue(const floatx16 (&acc)[TM][TN], float* stage
       if (m < M && n_ok) {
         const size_t idx = (size_t)m * N + n;
         if (EPI == EPI_RESIDUAL) {
-          floatx4 o = {v[0] + rr[it][0], v[1] + rr[it][1], v[2] + rr[it][2], v[3] + rr[it][3]};
+          floatx4 o = {v[0] + rr[i & 1][it][0], v[1] + rr[i & 1][it][1], v[2] + rr[i & 1][it][2], v[3] + rr[i & 1][it][3]};
           *reinterpret_cast<floatx4*>(reinterpret_cast<float*>(Y) + idx) = o;
         } else if (EPI == EPI_PARTIAL) {
           floatx4 o = {v[0], v[1], v[2], v[3]};
