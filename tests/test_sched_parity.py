@@ -219,3 +219,59 @@ def test_token_adaptation_beats_a_fixed_gamma_under_fluctuating_load():
     fixed = serve.replay_trace(otas.Scheduler([0], lat[:, i0:i0 + 1], acc[:, i0:i0 + 1]), trace,
                                serve.ProfileEngine(lat[:, i0:i0 + 1]), acc[:, i0:i0 + 1])
     assert adaptive["utility"] > fixed["utility"]
+
+
+@pytest.mark.parametrize("params", [dict(delta=0.1, epsilon=4, eta=0.05, mu=0.1, beta=2, kappa=0.25),
+                                    dict(delta=2.0, epsilon=200, eta=5.0, mu=5.0, beta=0, kappa=0.0)])
+def test_other_thresholds_match_the_oracle(params):
+    """Thresholds far from the paper's: tiny batches split on every criterion, and one where nearly everything
+    joins one batch and the dynamic program runs on every pass (beta = 0)."""
+    _ensure_built()
+    lat, acc = tables(31)
+    rate_table = serve.rate_table_from_latency(GAMMAS, lat)
+    lib = otas.Scheduler(GAMMAS, lat, acc, rate_table, **params)
+    orc = OracleScheduler(GAMMAS, lat, acc, rate_table, **params)
+    trace = synth.poisson_trace(33, 3, 150, 400)
+    rng = random.Random(7)
+    for i, (s, l, u, task) in enumerate(trace):
+        assert lib.otas_sched_add_query(i, s, l, u, task) == orc.otas_sched_add_query(i, s, l, u, task)
+        if i % 97 == 96:
+            T = s + rng.uniform(0.0, 0.2)
+            a, o = lib.otas_sched_allocate(T, 300.0, False), orc.otas_sched_allocate(T, 300.0, False)
+            assert (math.isnan(a) and math.isnan(o)) or a == o
+            same_queue(lib, orc)
+            for _ in range(min(3, lib.otas_sched_num_batches())):
+                lib.otas_sched_remove(0), orc.otas_sched_remove(0)
+    same_queue(lib, orc, check_gamma=False)
+    sizes = [lib.otas_sched_batch_info(b)["size"] for b in range(lib.otas_sched_num_batches())]
+    assert max(sizes) <= params["epsilon"]
+
+
+def test_allocator_scales_to_long_queues():
+    """2000 queued batches, 8 gammas: one pass of the dynamic program stays in the milliseconds (it is linear in the
+    queue length) and returns a feasible plan."""
+    import time
+    _ensure_built()
+    lat, acc = tables(41)
+    lib = otas.Scheduler(GAMMAS, lat, acc, delta=0.0, epsilon=1)        # every request its own batch
+    rng = np.random.default_rng(5)
+    t = 0.0
+    for i in range(2000):
+        t += rng.exponential(1 / 2000.0)
+        lib.otas_sched_add_query(i, t, float(rng.uniform(0.5, 3.0)), float(rng.choice([0.01, 0.2, 0.3, 1.0])), int(rng.integers(3)))
+    assert lib.otas_sched_num_batches() == 2000
+    t0 = time.perf_counter()
+    best = lib.otas_sched_allocate(t, 2000.0, False)
+    dt = time.perf_counter() - t0
+    assert dt < 0.25 and best > 0
+    clock, total = t, 0.0
+    for b in range(2000):
+        info = lib.otas_sched_batch_info(b)
+        if b:
+            assert info["d_b"] >= lib.otas_sched_batch_info(b - 1)["d_b"]
+        if info["gamma_index"] >= 0:
+            th, U = lib.otas_sched_estimate(b, info["gamma_index"])
+            clock += th
+            assert clock < info["d_b"]
+            total += U
+    assert total == pytest.approx(best, rel=1e-9)
