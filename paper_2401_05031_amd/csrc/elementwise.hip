@@ -279,21 +279,54 @@ __global__ __launch_bounds__(256) void merge_apply_ln_kernel(
       }
     }
   } else {
-    for (int e = beg; e < end; ++e) {
-      const int srow = src_list[e];
-      const int sz = sizes ? sizes[srow] : 1;
-      const float w = (float)sz;
-      tot += sz;
-      const float* xr = x + (size_t)srow * D;
+    // Every lane fetches one list entry and its size, so the rows' addresses are in registers before
+    // the first row is requested; the rows are then loaded two at a time and accumulated in list order.
+    for (int e0 = beg; e0 < end; e0 += 64) {
+      const int cnt = min(64, end - e0);
+      const int my_src = lane < cnt ? src_list[e0 + lane] : 0;
+      const int my_sz = lane < cnt ? (sizes ? sizes[my_src] : 1) : 0;
+      for (int e = 0; e < cnt; e += 2) {
+        const bool two = e + 1 < cnt;   // the same for the whole wave
+        const int s0 = __shfl(my_src, e, kWave), s1 = __shfl(my_src, two ? e + 1 : e, kWave);
+        const int z0 = __shfl(my_sz, e, kWave), z1 = __shfl(my_sz, two ? e + 1 : e, kWave);
+        const float* x0r = x + (size_t)s0 * D;
+        const float* x1r = x + (size_t)s1 * D;
+        Vec<float> a[NCH][2], b[NCH][2];
 #pragma unroll
-      for (int i = 0; i < NCH; ++i) {
-        const int c = lane + 64 * i;
-        if (c < chunks) {
-          const Vec<float> lo = load_vec<float>(xr + c * V), hi = load_vec<float>(xr + c * V + 4);
+        for (int i = 0; i < NCH; ++i) {
+          const int c = lane + 64 * i;
+          if (c < chunks) {
+            a[i][0] = load_vec<float>(x0r + c * V);
+            a[i][1] = load_vec<float>(x0r + c * V + 4);
+            if (two) {
+              b[i][0] = load_vec<float>(x1r + c * V);
+              b[i][1] = load_vec<float>(x1r + c * V + 4);
+            }
+          }
+        }
+        const float w0 = (float)z0, w1 = (float)z1;
+        tot += z0;
 #pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            v[i][k] = fmaf(w, lo.get(k), v[i][k]);
-            v[i][4 + k] = fmaf(w, hi.get(k), v[i][4 + k]);
+        for (int i = 0; i < NCH; ++i) {
+          if (lane + 64 * i < chunks) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              v[i][k] = fmaf(w0, a[i][0].get(k), v[i][k]);
+              v[i][4 + k] = fmaf(w0, a[i][1].get(k), v[i][4 + k]);
+            }
+          }
+        }
+        if (two) {
+          tot += z1;
+#pragma unroll
+          for (int i = 0; i < NCH; ++i) {
+            if (lane + 64 * i < chunks) {
+#pragma unroll
+              for (int k = 0; k < 4; ++k) {
+                v[i][k] = fmaf(w1, b[i][0].get(k), v[i][k]);
+                v[i][4 + k] = fmaf(w1, b[i][1].get(k), v[i][4 + k]);
+              }
+            }
           }
         }
       }
