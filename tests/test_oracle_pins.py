@@ -495,3 +495,191 @@ def test_task_head_matches_library_norm_and_linear():
     # only the first token counts
     x2 = x.copy(); x2[1:] += 1.0
     assert np.array_equal(orc.task_head(x2, g, bb, w, b, 1e-6), got)
+
+
+# ------------------------------------------------------------------ merge metric and where the merge sits
+def _independent_adapted_encoder(x0, layers, r, D, H, F, n_lead, eps=1e-6, metric_from="K",
+                                 head_layout="H_dh", keys_of="this_layer", merge_at="after_attention_residual"):
+    """Sec. III-B stated independently of the oracle: per block, torch's own pre-norm pieces
+    (norm1, self_attn, out_proj residual, norm2, linear1, GELU, linear2 residual), the metric from
+    torch layer_norm + linear with ONLY the key rows D..2D of w_qkv, the head mean written as explicit
+    Python loops, edges by the brute-force enumeration, the weighted average by explicit loops over
+    rows, and the merge between the attention residual and the MLP.  The keyword arguments switch in
+    the plausible misreadings (metric from Q or V, heads and head width swapped, the previous layer's
+    keys, merging at another point of the block) so that a test can show they give other results.
+    (Merging the stream and the attention branch separately and adding them afterwards is NOT another
+    result: the size-weighted average is linear, so it equals merging their sum; the placements that
+    can be told apart are in front of the attention and behind the MLP.)"""
+    F_ = torch.nn.functional
+    dh = D // H
+    x = torch.from_numpy(np.asarray(x0, dtype=np.float64))
+    sizes = [1] * x.shape[0]
+    traces = []
+    prev_metric = None
+
+    def plan(metric_rows, n_now):
+        r_eff = max(0, min(r, (n_now - n_lead) // 2))
+        return _brute_force_edges(np.asarray(metric_rows, dtype=np.float64)[:n_now], r_eff, n_lead)
+
+    def apply(x, sizes, edges):
+        n_now = x.shape[0]
+        rows = [x[i].clone() for i in range(n_now)]
+        new_sizes = list(sizes)
+        for b in sorted({b for _, b in edges}):
+            tot = sizes[b]
+            acc = sizes[b] * x[b]
+            for a in sorted(a for a, bb in edges if bb == b):
+                acc = acc + sizes[a] * x[a]
+                tot += sizes[a]
+            rows[b] = acc / tot
+            new_sizes[b] = tot
+        gone = {a for a, _ in edges}
+        keep = [i for i in range(n_now) if i not in gone]
+        return torch.stack([rows[i] for i in keep]), [new_sizes[i] for i in keep]
+
+    with torch.no_grad():
+        for m, w in zip(_torch_encoder(layers, D, H, F, eps), layers):
+            n_now = x.shape[0]
+            h = F_.layer_norm(x, (D,), torch.from_numpy(w["ln1_g"]), torch.from_numpy(w["ln1_b"]), eps)
+            third = {"Q": 0, "K": 1, "V": 2}[metric_from]
+            wk = torch.from_numpy(np.asarray(w["w_qkv"], dtype=np.float64))[third * D:(third + 1) * D]
+            bk = torch.from_numpy(np.asarray(w["b_qkv"], dtype=np.float64))[third * D:(third + 1) * D]
+            keys = F_.linear(h, wk, bk).numpy()                        # [n, D], heads side by side
+            metric = [[0.0] * dh for _ in range(n_now)]
+            for i in range(n_now):
+                for hd in range(H):
+                    for j in range(dh):
+                        col = hd * dh + j if head_layout == "H_dh" else j * H + hd
+                        metric[i][j] += keys[i][col] / H
+            use = metric if (keys_of == "this_layer" or prev_metric is None) else prev_metric
+            prev_metric = metric
+            if merge_at == "before_attention":
+                edges = plan(use, n_now)
+                x, sizes = apply(x, sizes, edges)
+                traces.append(edges)
+                x = x + m.self_attn(m.norm1(x)[None], m.norm1(x)[None], m.norm1(x)[None], need_weights=False)[0][0]
+            else:
+                attn = m.self_attn(m.norm1(x)[None], m.norm1(x)[None], m.norm1(x)[None], need_weights=False)[0][0]
+                x = x + attn
+                if merge_at == "after_attention_residual":
+                    edges = plan(use, n_now)
+                    x, sizes = apply(x, sizes, edges)
+                    traces.append(edges)
+            x = x + m.linear2(F_.gelu(m.linear1(m.norm2(x))))
+            if merge_at == "after_mlp":
+                edges = plan(use, n_now)
+                x, sizes = apply(x, sizes, edges)
+                traces.append(edges)
+    return x.numpy(), sizes, traces
+
+
+@pytest.mark.parametrize("L,n,r,n_lead", [(1, 13, 3, 1), (2, 17, 4, 1), (2, 12, 5, 0), (3, 21, 2, 1)])
+def test_merge_metric_and_placement_against_independent_blocks(L, n, r, n_lead):
+    """Sec. III-B: the similarity comes from the layer's own multi-head attention (head-averaged keys,
+    R3) and the merging module sits between the attention residual and the MLP.  The oracle's trace,
+    sizes and output must equal the independent statement above; every misreading must not."""
+    rng = np.random.default_rng(100 + L * 7 + n)
+    D, H, F = 24, 4, 40                                  # d_h = 6 != H, so a swapped reshape shows
+    layers = _rand_layers(rng, L, D, F, scale=0.35)
+    x0 = rng.standard_normal((n, D))
+    got = orc.encoder_forward_query(x0, layers, r, H=H, ln_eps=1e-6, n_lead=n_lead)
+    ref_x, ref_s, ref_tr = _independent_adapted_encoder(x0, layers, r, D, H, F, n_lead)
+    assert [list(zip(s.tolist(), d.tolist())) for s, d in got["trace"]] == ref_tr
+    assert got["sizes"].tolist() == ref_s
+    assert got["x"].shape == ref_x.shape
+    assert np.max(np.abs(got["x"] - ref_x)) <= 1e-11 * max(1.0, np.max(np.abs(ref_x)))
+    assert any(len(t) for t in ref_tr)
+    # the misreadings give something else, so an oracle that had taken one would fail the lines above
+    wrong = [dict(metric_from="Q"), dict(metric_from="V"), dict(head_layout="dh_H"),
+             dict(merge_at="before_attention"), dict(merge_at="after_mlp")]
+    if L > 1:
+        wrong += [dict(keys_of="previous_layer")]
+    for kw in wrong:
+        bad_x, bad_s, bad_tr = _independent_adapted_encoder(x0, layers, r, D, H, F, n_lead, **kw)
+        same_trace = [list(zip(s.tolist(), d.tolist())) for s, d in got["trace"]] == bad_tr
+        same_x = bad_x.shape == got["x"].shape and np.max(np.abs(got["x"] - bad_x)) <= 1e-9
+        assert not (same_trace and same_x), kw
+
+
+def test_merge_metric_hand_example():
+    """Two heads of width three: the key third of a row is [1 2 3 | 4 5 6], its head mean is
+    (2.5, 3.5, 4.5) by hand.  Taking the Q or V third, or reading the row as three heads of two, gives
+    other numbers."""
+    row = np.array([[10., 20., 30., 40., 50., 60., 1., 2., 3., 4., 5., 6., -1., -2., -3., -4., -5., -6.],
+                    [0., 0., 0., 0., 0., 0., 2., 0., -2., 4., 2., 0., 9., 9., 9., 9., 9., 9.]])
+    m = orc.merge_metric_from_keys(row, 2)
+    assert m.shape == (2, 3)
+    assert m.tolist() == [[2.5, 3.5, 4.5], [3.0, 1.0, -1.0]]
+
+
+def test_pins_catch_planted_metric_mistakes(monkeypatch):
+    """Plant the slips in the oracle itself and check the independent-block pin notices each one."""
+    rng = np.random.default_rng(31)
+    L, n, r, D, H, F = 2, 15, 3, 24, 4, 40
+    layers = _rand_layers(rng, L, D, F, scale=0.35)
+    x0 = rng.standard_normal((n, D))
+    ref_x, ref_s, ref_tr = _independent_adapted_encoder(x0, layers, r, D, H, F, 1)
+
+    def oracle_agrees():
+        try:
+            got = orc.encoder_forward_query(x0, layers, r, H=H, ln_eps=1e-6, n_lead=1)
+        except Exception:
+            return False
+        return ([list(zip(s.tolist(), d.tolist())) for s, d in got["trace"]] == ref_tr
+                and got["x"].shape == ref_x.shape and np.max(np.abs(got["x"] - ref_x)) <= 1e-9)
+
+    assert oracle_agrees()
+    dh = D // H
+    state = {}
+
+    def from_q(qkv, H_):
+        return qkv[:, 0:D].reshape(qkv.shape[0], H_, dh).mean(axis=1)
+
+    def from_v(qkv, H_):
+        return qkv[:, 2 * D:3 * D].reshape(qkv.shape[0], H_, dh).mean(axis=1)
+
+    def swapped(qkv, H_):
+        return qkv[:, D:2 * D].reshape(qkv.shape[0], dh, H_).mean(axis=2)
+
+    def no_head_mean(qkv, H_):
+        return qkv[:, D:D + dh]                          # first head only
+
+    good = orc.merge_metric_from_keys
+
+    def previous_layer(qkv, H_):
+        now = good(qkv, H_)
+        old = state.get("m")
+        state["m"] = now
+        return now if old is None else old[:now.shape[0]]
+
+    for slip in (from_q, from_v, swapped, no_head_mean, previous_layer):
+        state.clear()
+        monkeypatch.setattr(orc, "merge_metric_from_keys", slip)
+        assert not oracle_agrees(), slip.__name__
+    monkeypatch.setattr(orc, "merge_metric_from_keys", good)
+    assert oracle_agrees()
+
+
+def test_edge_deficit_hand_example():
+    """Six unit vectors from 3-4-5 triangles, so every cosine is a short decimal.  A = positions 0, 2, 4
+    = (0.8, 0.6), (0.6, 0.8), (-0.6, 0.8); B = positions 1, 3, 5 = (1, 0), (0, 1), (0.6, 0.8).
+    Similarities by hand:      b=1    b=3    b=5
+                        a=0    0.8    0.6    0.96
+                        a=2    0.6    0.8    1.0
+                        a=4   -0.6    0.8    0.28
+    best = (0.96, 1.0, 0.8); with two edges kept the second best edge has 0.96.  The deficit of an
+    edge (a, b) is how much its similarity falls short of a's best and of the last kept edge."""
+    m = np.array([[0.8, 0.6], [1.0, 0.0], [0.6, 0.8], [0.0, 1.0], [-0.6, 0.8], [0.6, 0.8]])
+    src, dst, info = orc.merge_plan(m, 2, 0)
+    assert list(zip(src.tolist(), dst.tolist())) == [(2, 5), (0, 5)]
+    assert np.allclose(info["sim"], [[0.8, 0.6, 0.96], [0.6, 0.8, 1.0], [-0.6, 0.8, 0.28]], atol=1e-15)
+    assert np.allclose(info["best"], [0.96, 1.0, 0.8], atol=1e-15) and abs(info["kth"] - 0.96) < 1e-15
+    assert abs(info["rank_margin"] - 0.16) < 1e-12 and abs(info["argmax_margin"] - 0.16) < 1e-12
+    want = {(2, 5): 0.0, (0, 5): 0.0, (4, 3): 0.16, (0, 1): 0.16, (2, 1): 0.4, (4, 5): 0.68,
+            (4, 1): 1.56, (0, 3): 0.36, (2, 3): 0.2}
+    for (a, b), d in want.items():
+        assert abs(orc.edge_deficit(info, a, b) - d) < 1e-12, (a, b)
+    # with a protected lead token row 0 cannot merge: the kept edges become (2,5) and (4,3), kth = 0.8
+    src, dst, info = orc.merge_plan(m, 2, 1)
+    assert list(zip(src.tolist(), dst.tolist())) == [(2, 5), (4, 3)]
+    assert abs(orc.edge_deficit(info, 4, 1) - 1.4) < 1e-12 and orc.edge_deficit(info, 4, 3) == 0.0
