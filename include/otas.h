@@ -153,6 +153,23 @@ otas_status otas_token_merge(otas_ctx *ctx, const void *x, const void *metric, i
                              int32_t *sizes_out, int32_t *offsets_out, int32_t *trace_src,
                              int32_t *trace_dst);
 
+/* otas_token_merge for callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).  Same arguments,
+ * same kernels and bit-identical results, without the workspace: the merge lists live in a static
+ * device array of the library (one copy per GPU, about 0.5 MB, held until the process ends), and the
+ * call itself allocates nothing on the device or the host.
+ * Limits: B <= OTAS_STATIC_MERGE_MAX_QUERIES and offsets[B] <= OTAS_STATIC_MERGE_MAX_ROWS, else
+ * OTAS_ENOMEM before any launch.  All calls on one GPU share the one array: calls that overlap in time
+ * on the same GPU (different contexts or streams) race on it; calls in stream order on one context
+ * are safe, and nothing from an earlier call is read (every list entry a call reads it has written).
+ * Launches of this entry point are not recorded by otas_timing_*. */
+#define OTAS_STATIC_MERGE_MAX_ROWS 65536
+#define OTAS_STATIC_MERGE_MAX_QUERIES 1024
+otas_status otas_token_merge_static(otas_ctx *ctx, const void *x, const void *metric, int32_t dm,
+                                    const int32_t *sizes, const int32_t *offsets, const int32_t *r,
+                                    int32_t B, void *x_out, int32_t *sizes_out, int32_t *offsets_out,
+                                    int32_t *trace_src, int32_t *trace_dst);
+
 /* Token-adapted encoder forward (Sec. III-B unified model; the ServeModel.forward of Sec. IV
  * without the task heads).  Per layer and query:
  *   x += Proj(Attention(LN1(x)));  merge r_eff tokens using the cosine similarity of the

@@ -15,6 +15,7 @@ import numpy as np
 OTAS_F32, OTAS_BF16 = 0, 1
 OTAS_FLAG_SIZE_BIAS, OTAS_FLAG_TRACE = 1, 2
 OTAS_PROMPT_REPLACE, OTAS_PROMPT_GROW = 1, 2
+OTAS_STATIC_MERGE_MAX_ROWS, OTAS_STATIC_MERGE_MAX_QUERIES = 65536, 1024
 _WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
                   "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 
@@ -76,6 +77,7 @@ def load_library():
         "otas_merge_workspace_bytes": (sz, [i32, i64]),
         "otas_prompt_prepend": (i32, [vp, vp, _I32P, vp, _I32P, i32, vp, _I32P]),
         "otas_token_merge": (i32, [vp, vp, vp, i32, vp, _I32P, _I32P, i32, vp, sz, vp, vp, _I32P, vp, vp]),
+        "otas_token_merge_static": (i32, [vp, vp, vp, i32, vp, _I32P, _I32P, i32, vp, vp, _I32P, vp, vp]),
         "otas_encoder_forward": (i32, [vp, vp, _I32P, _I32P, i32, u32, vp, sz, vp, vp, _I32P, vp, vp]),
         "otas_encoder_layers": (i32, [vp, i32, i32, vp, vp, _I32P, _I32P, i32, u32, vp, sz, vp, vp, _I32P, vp, vp]),
         "otas_encoder_forward_deep": (i32, [vp, vp, _I32P, i32, i32, vp, _I32P, vp, sz, vp, vp, _I32P]),
@@ -113,7 +115,7 @@ def load_library():
 
 
 EXPORTED = ("otas_create", "otas_destroy", "otas_schedule", "otas_workspace_bytes",
-            "otas_merge_workspace_bytes", "otas_prompt_prepend", "otas_token_merge",
+            "otas_merge_workspace_bytes", "otas_prompt_prepend", "otas_token_merge", "otas_token_merge_static",
             "otas_encoder_forward", "otas_encoder_layers", "otas_encoder_forward_deep", "otas_patch_embed_workspace_bytes", "otas_patch_embed", "otas_task_heads", "otas_layer_norm", "otas_linear", "otas_attention", "otas_strerror",
             "otas_timing_enable", "otas_timing_kinds", "otas_timing_kind_name", "otas_timing_read",
             "otas_timing_read_launches", "otas_timing_overhead_ms", "otas_set_lanes", "otas_splitk_factor",
@@ -218,6 +220,17 @@ class Context:
                                           _ptr(workspace), workspace.numel() * workspace.element_size(),
                                           _ptr(x_out), _ptr(sizes_out), oo.ctypes.data_as(_I32P),
                                           _ptr(trace_src), _ptr(trace_dst)), "otas_token_merge")
+        return oo
+
+    def otas_token_merge_static(self, x, metric, dm, sizes, offsets, r, x_out, sizes_out,
+                                trace_src=None, trace_dst=None) -> np.ndarray:
+        B = len(offsets) - 1
+        oa, op = _i32(offsets)
+        ra, rp = _i32(r)
+        oo = np.zeros(B + 1, dtype=np.int32)
+        _check(self._lib.otas_token_merge_static(self._h, _ptr(x), _ptr(metric), dm, _ptr(sizes), op, rp, B,
+                                                 _ptr(x_out), _ptr(sizes_out), oo.ctypes.data_as(_I32P),
+                                                 _ptr(trace_src), _ptr(trace_dst)), "otas_token_merge_static")
         return oo
 
     def otas_encoder_forward(self, x0, offsets, r, flags, workspace, x_out, sizes_out,

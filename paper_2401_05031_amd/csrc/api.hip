@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -27,9 +28,39 @@ constexpr size_t kSlotInts = kPlanInts / kStageSlots;
 constexpr int kMaxLanes = 8;
 constexpr int kPartRows = 2;   // split-K workspace: this many float rows of width D per token row
 
+// Scratch of otas_token_merge_static: the merge lists of one call (src_list [rows] | row_ptr [rows + 64]).
+// One copy per GPU, held until the process ends; every call on a GPU shares it.
+constexpr int64_t kStaticMergeRows = OTAS_STATIC_MERGE_MAX_ROWS;
+constexpr int kStaticMergeQueries = OTAS_STATIC_MERGE_MAX_QUERIES;
+constexpr size_t kStaticRowPtrAt = (size_t)kStaticMergeRows;
+constexpr size_t kStaticScratchInts = 2 * (size_t)kStaticMergeRows + 64;
+constexpr int kMaxDevices = 64;
+
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int removal_count(int n, int r, int n_lead) { return std::max(0, std::min(r, (n - n_lead) / 2)); }
 
+}  // namespace
+
+static __device__ __align__(256) int32_t scratch[kStaticScratchInts];
+
+namespace {
+// Device address of `scratch` on each GPU (the array's name is only a host-side handle: every use of
+// its memory from the host goes through the address looked up here, with that GPU current).
+std::mutex g_scratch_mu;
+int32_t* g_scratch_ptr[kMaxDevices] = {};
+
+// Looks the address up once per device; `device` must be the current device.
+otas_status scratch_address(int device, int32_t** out) {
+  if (device < 0 || device >= kMaxDevices) return OTAS_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[device]) {
+    int32_t* p = nullptr;
+    if (hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return OTAS_EDEVICE;
+    g_scratch_ptr[device] = p;
+  }
+  *out = g_scratch_ptr[device];
+  return OTAS_OK;
+}
 }  // namespace
 
 struct otas_ctx {
@@ -38,6 +69,7 @@ struct otas_ctx {
   hipStream_t stream;
   int device;
   int32_t* d_plan;        // device plan buffer [kPlanInts]
+  int32_t* d_scratch;     // this device's copy of the static scratch array (otas_token_merge_static)
   // Pinned host staging for the plan: a ring of kStageSlots slots of kSlotInts entries, so that the host
   // can enqueue that many calls ahead of the device (a host thread that is descheduled for tens of
   // milliseconds then costs nothing as long as the queue holds work).  Slot i may be overwritten once
@@ -79,15 +111,15 @@ bool offsets_ok(const int32_t* off, int B) {
 }
 
 // Copies `count` ints to the device plan buffer at entry `at` through pinned staging.
-otas_status upload_plan(otas_ctx* c, const std::vector<int32_t>& host) {
-  if (host.size() > kPlanInts) return OTAS_ENOMEM;
-  const size_t bytes = host.size() * sizeof(int32_t);
-  if (host.size() > kSlotInts) {
+otas_status upload_plan(otas_ctx* c, const int32_t* host, size_t count) {
+  if (count > kPlanInts) return OTAS_ENOMEM;
+  const size_t bytes = count * sizeof(int32_t);
+  if (count > kSlotInts) {
     for (int j = 0; j < kStageSlots; ++j) {
       if (c->h_used[j] && hipEventSynchronize(c->h_done[j]) != hipSuccess) return OTAS_EDEVICE;
       c->h_used[j] = false;
     }
-    std::memcpy(c->h_plan, host.data(), bytes);
+    std::memcpy(c->h_plan, host, bytes);
     if (hipMemcpyAsync(c->d_plan, c->h_plan, bytes, hipMemcpyHostToDevice, c->stream) != hipSuccess ||
         hipStreamSynchronize(c->stream) != hipSuccess)
       return OTAS_EDEVICE;
@@ -97,11 +129,14 @@ otas_status upload_plan(otas_ctx* c, const std::vector<int32_t>& host) {
   c->h_next = (c->h_next + 1) % kStageSlots;
   if (c->h_used[i] && hipEventSynchronize(c->h_done[i]) != hipSuccess) return OTAS_EDEVICE;
   int32_t* slot = c->h_plan + (size_t)i * kSlotInts;
-  std::memcpy(slot, host.data(), bytes);
+  std::memcpy(slot, host, bytes);
   if (hipMemcpyAsync(c->d_plan, slot, bytes, hipMemcpyHostToDevice, c->stream) != hipSuccess) return OTAS_EDEVICE;
   if (hipEventRecord(c->h_done[i], c->stream) != hipSuccess) return OTAS_EDEVICE;
   c->h_used[i] = true;
   return OTAS_OK;
+}
+otas_status upload_plan(otas_ctx* c, const std::vector<int32_t>& host) {
+  return upload_plan(c, host.data(), host.size());
 }
 
 struct WorkspaceLayout {
@@ -243,6 +278,7 @@ otas_status otas_create(otas_ctx** out, const otas_model_desc* desc, const otas_
   c->layers.assign(layers, layers + d.L);
   c->stream = (hipStream_t)hip_stream;
   c->d_plan = nullptr;
+  c->d_scratch = nullptr;
   c->h_plan = nullptr;
   for (int i = 0; i < kStageSlots; ++i) { c->h_done[i] = nullptr; c->h_used[i] = false; }
   c->h_next = 0;
@@ -254,6 +290,7 @@ otas_status otas_create(otas_ctx** out, const otas_model_desc* desc, const otas_
   c->lanes_ready = 0;
   if (const char* e = std::getenv("OTAS_LANES")) c->lanes = std::max(0, std::min(kMaxLanes, std::atoi(e)));
   bool ok = hipGetDevice(&c->device) == hipSuccess;
+  ok = ok && scratch_address(c->device, &c->d_scratch) == OTAS_OK;   // the current device is c->device
   ok = ok && hipMalloc((void**)&c->d_plan, kPlanInts * sizeof(int32_t)) == hipSuccess;
   ok = ok && hipHostMalloc((void**)&c->h_plan, kPlanInts * sizeof(int32_t), hipHostMallocDefault) == hipSuccess;
   for (int i = 0; i < kStageSlots && ok; ++i)
@@ -326,23 +363,19 @@ otas_status otas_prompt_prepend(otas_ctx* c, const void* tokens, const int32_t* 
   return OTAS_OK;
 }
 
-otas_status otas_token_merge(otas_ctx* c, const void* x, const void* metric, int32_t dm, const int32_t* sizes,
-                             const int32_t* offsets, const int32_t* r, int32_t B, void* workspace,
-                             size_t workspace_bytes, void* x_out, int32_t* sizes_out, int32_t* offsets_out,
-                             int32_t* trace_src, int32_t* trace_dst) {
-  if (!c || !x || !metric || !offsets || !r || !workspace || !x_out || !sizes_out || !offsets_out || B <= 0)
-    return OTAS_EINVAL;
-  if ((trace_src == nullptr) != (trace_dst == nullptr)) return OTAS_EINVAL;
-  if (dm <= 0 || dm % 4 != 0 || dm > 128) return OTAS_EUNSUPPORTED;
-  if (!offsets_ok(offsets, B)) return OTAS_EINVAL;
-  if (x_out == x || (const void*)sizes_out == (const void*)sizes) return OTAS_EINVAL;
-  if (((uintptr_t)workspace) % kAlign != 0) return OTAS_EINVAL;
+}  // extern "C"
+
+namespace {
+// Body of otas_token_merge and otas_token_merge_static.  plan: host array of 4 B + 2 entries to fill
+// (in_off [B+1] | out_off [B+1] | r_eff [B] | trace_off [B]); src_list / row_ptr: device lists of
+// at least T and T + 1 entries; timed: bracket the launches with timing events when timing is on
+// (creating events allocates, so the static entry point never does).
+otas_status token_merge_impl(otas_ctx* c, const void* x, const void* metric, int32_t dm, const int32_t* sizes,
+                             const int32_t* offsets, const int32_t* r, int32_t B, int32_t* plan, int32_t* src_list,
+                             int32_t* row_ptr, void* x_out, int32_t* sizes_out, int32_t* offsets_out,
+                             int32_t* trace_src, int32_t* trace_dst, bool timed) {
   const int64_t T = offsets[B];
-  if (T <= 0) return OTAS_EINVAL;
-  if (workspace_bytes < otas_merge_workspace_bytes(B, T)) return OTAS_ENOMEM;
   const int n_lead = c->desc.n_lead;
-  // plan: in_off [B+1] | out_off [B+1] | r_eff [B] | trace_off [B]
-  std::vector<int32_t> plan(4 * (size_t)B + 2);
   int32_t* in_off = &plan[0];
   int32_t* out_off = &plan[B + 1];
   int32_t* reff = &plan[2 * (B + 1)];
@@ -366,17 +399,69 @@ otas_status otas_token_merge(otas_ctx* c, const void* x, const void* metric, int
   std::memcpy(offsets_out, out_off, (B + 1) * sizeof(int32_t));
   const int64_t T_out = out_off[B];
   if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
-  otas_status st = upload_plan(c, plan);
+  otas_status st = upload_plan(c, plan, 4 * (size_t)B + 2);
   if (st != OTAS_OK) return st;
-  char* ws = (char*)workspace;
-  int32_t* src_list = (int32_t*)ws;
-  int32_t* row_ptr = (int32_t*)((char*)src_list + align_up((size_t)T * 4, kAlign));
   const int32_t* dp = c->d_plan;
-  OTAS_LAUNCH(K_PLAN, launch_merge_plan(c->desc.dtype, metric, dm, 0, 1, dm, dp, dp + (B + 1), dp + 2 * (B + 1), dp + 2 * (B + 1) + B, B, max_n, n_lead,
-                             src_list, row_ptr, trace_src, trace_dst, c->stream));
-  OTAS_LAUNCH(K_APPLY, launch_merge_apply(c->desc.dtype, x, sizes, src_list, row_ptr, T, T_out, c->desc.D, x_out, sizes_out,
-                              c->stream));
+  const bool was_timing = c->timing;
+  if (!timed) c->timing = false;
+  st = [&]() -> otas_status {
+    OTAS_LAUNCH(K_PLAN, launch_merge_plan(c->desc.dtype, metric, dm, 0, 1, dm, dp, dp + (B + 1), dp + 2 * (B + 1),
+                                          dp + 2 * (B + 1) + B, B, max_n, n_lead, src_list, row_ptr, trace_src,
+                                          trace_dst, c->stream));
+    OTAS_LAUNCH(K_APPLY, launch_merge_apply(c->desc.dtype, x, sizes, src_list, row_ptr, T, T_out, c->desc.D, x_out,
+                                            sizes_out, c->stream));
+    return OTAS_OK;
+  }();
+  c->timing = was_timing;
+  return st;
+}
+
+otas_status token_merge_args_ok(otas_ctx* c, const void* x, const void* metric, int32_t dm, const int32_t* sizes,
+                                const int32_t* offsets, const int32_t* r, int32_t B, void* x_out,
+                                int32_t* sizes_out, int32_t* offsets_out, int32_t* trace_src, int32_t* trace_dst) {
+  if (!c || !x || !metric || !offsets || !r || !x_out || !sizes_out || !offsets_out || B <= 0) return OTAS_EINVAL;
+  if ((trace_src == nullptr) != (trace_dst == nullptr)) return OTAS_EINVAL;
+  if (dm <= 0 || dm % 4 != 0 || dm > 128) return OTAS_EUNSUPPORTED;
+  if (!offsets_ok(offsets, B)) return OTAS_EINVAL;
+  if (x_out == x || (const void*)sizes_out == (const void*)sizes) return OTAS_EINVAL;
+  if (offsets[B] <= 0) return OTAS_EINVAL;
   return OTAS_OK;
+}
+}  // namespace
+
+extern "C" {
+
+otas_status otas_token_merge(otas_ctx* c, const void* x, const void* metric, int32_t dm, const int32_t* sizes,
+                             const int32_t* offsets, const int32_t* r, int32_t B, void* workspace,
+                             size_t workspace_bytes, void* x_out, int32_t* sizes_out, int32_t* offsets_out,
+                             int32_t* trace_src, int32_t* trace_dst) {
+  otas_status st = token_merge_args_ok(c, x, metric, dm, sizes, offsets, r, B, x_out, sizes_out, offsets_out,
+                                       trace_src, trace_dst);
+  if (st != OTAS_OK) return st;
+  if (!workspace || ((uintptr_t)workspace) % kAlign != 0) return OTAS_EINVAL;
+  const int64_t T = offsets[B];
+  if (workspace_bytes < otas_merge_workspace_bytes(B, T)) return OTAS_ENOMEM;
+  std::vector<int32_t> plan(4 * (size_t)B + 2);
+  int32_t* src_list = (int32_t*)workspace;
+  int32_t* row_ptr = (int32_t*)((char*)workspace + align_up((size_t)T * 4, kAlign));
+  return token_merge_impl(c, x, metric, dm, sizes, offsets, r, B, plan.data(), src_list, row_ptr, x_out, sizes_out,
+                          offsets_out, trace_src, trace_dst, true);
+}
+
+otas_status otas_token_merge_static(otas_ctx* c, const void* x, const void* metric, int32_t dm,
+                                    const int32_t* sizes, const int32_t* offsets, const int32_t* r, int32_t B,
+                                    void* x_out, int32_t* sizes_out, int32_t* offsets_out, int32_t* trace_src,
+                                    int32_t* trace_dst) {
+  otas_status st = token_merge_args_ok(c, x, metric, dm, sizes, offsets, r, B, x_out, sizes_out, offsets_out,
+                                       trace_src, trace_dst);
+  if (st != OTAS_OK) return st;
+  if (B > kStaticMergeQueries || (int64_t)offsets[B] > kStaticMergeRows) return OTAS_ENOMEM;
+  if (!c->d_scratch) return OTAS_EDEVICE;
+  int32_t plan[4 * kStaticMergeQueries + 2];   // on the stack: no host allocation either
+  // Nothing in the lists has to start at zero: the plan kernel writes every entry of src_list [0, T)
+  // and row_ptr [0, T_out) that the apply kernel reads, whatever an earlier call left there.
+  return token_merge_impl(c, x, metric, dm, sizes, offsets, r, B, plan, c->d_scratch,
+                          c->d_scratch + kStaticRowPtrAt, x_out, sizes_out, offsets_out, trace_src, trace_dst, false);
 }
 
 namespace {
