@@ -20,8 +20,10 @@
  *     without waiting for it.  Host outputs (offsets_out) are complete on return, because every
  *     sequence length is a function of (n, r, layer) alone and is computed on the host.
  *   - Host arrays are read during the call and never retained.
- *   - Every argument check happens on the host before any launch; a failed call enqueues
- *     nothing.  Errors are returned as otas_status, never thrown or aborted.
+ *   - Every argument check happens on the host before any launch: a call that fails with
+ *     EINVAL / ESHAPE / ENOMEM / EUNSUPPORTED has enqueued nothing.  A HIP runtime failure in the
+ *     middle of a call (EDEVICE) leaves the call's outputs undefined; the library waits for the
+ *     streams it owns before returning it.  Errors are returned as otas_status, never thrown.
  *   - Calls on one context must not overlap in time from different host threads.
  */
 #ifndef OTAS_H_
@@ -111,8 +113,10 @@ int32_t otas_splitk_factor(const otas_ctx *ctx, int64_t M, int32_t N, int32_t K)
  * the context's stream at the start of the call and joined into it before the call returns, so
  * the caller sees ordinary stream order.  Queries are independent (Sec. III-B: a batch is a set of
  * queries, each with its own strategy), so results do not depend on the lane count.  lanes = 0
- * (the default; the environment variable OTAS_LANES overrides it at otas_create) lets the
- * library choose from the batch size; 1 runs the whole batch as one sequence of launches. */
+ * (the default) lets the library choose from the batch size (today: 1); 1 runs the whole batch as
+ * one sequence of launches.
+ * Environment: the library reads one variable, OTAS_DEBUG (any value: name failing HIP calls on
+ * stderr).  No environment variable changes which kernel runs for a shape. */
 otas_status otas_set_lanes(otas_ctx *ctx, int32_t lanes);
 
 /* Bytes of device workspace otas_encoder_forward needs for B queries with T0 packed tokens in

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libotas.so")
-SOURCES = ["api.hip", "elementwise.hip", "gemm.hip", "attention.hip", "merge.hip", "sched.cpp"]
+SOURCES = ["api.hip", "elementwise.hip", "gemm.hip", "attention.hip", "merge.hip", "launch_util.hip", "sched.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

@@ -288,7 +288,6 @@ otas_status otas_create(otas_ctx** out, const otas_model_desc* desc, const otas_
   c->ev_begin = nullptr;
   c->lanes = 0;
   c->lanes_ready = 0;
-  if (const char* e = std::getenv("OTAS_LANES")) c->lanes = std::max(0, std::min(kMaxLanes, std::atoi(e)));
   bool ok = hipGetDevice(&c->device) == hipSuccess;
   ok = ok && scratch_address(c->device, &c->d_scratch) == OTAS_OK;   // the current device is c->device
   ok = ok && hipMalloc((void**)&c->d_plan, kPlanInts * sizeof(int32_t)) == hipSuccess;
@@ -622,6 +621,10 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
 
   otas_status st = upload_plan(c, plan);
   if (st != OTAS_OK) return st;
+  // Everything below enqueues work.  If a HIP call fails after lanes or the plan stream were forked,
+  // the library's own streams are drained before the error is returned, so that nothing of this call
+  // is still running on them when the next call reuses the plan buffer and the workspace.
+  const otas_status enq = [&]() -> otas_status {
   const int32_t* d_plan_base = c->d_plan;
   hipStream_t s0 = c->stream;   // lane 0 runs on the caller's stream
   // Lanes beyond the first run on streams of their own, forked here and joined at the end.
@@ -663,11 +666,7 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
   // The merge plan runs beside attention and the projection on a side stream when the batch is large
   // enough for that to pay: forking and joining costs the host ~45 us per layer, more than a small
   // batch's layer takes on the GPU, so small batches keep the plan on the lane's own stream.
-  static const int plan_mode = [] {
-    const char* e = std::getenv("OTAS_PLAN_STREAM");   // tuning override: 1 = always inline, 2 = always side
-    return e ? std::atoi(e) : 0;
-  }();
-  const bool plan_inline = plan_mode == 1 || (plan_mode == 0 && T0 < kPlanSideMinRows);
+  const bool plan_inline = T0 < kPlanSideMinRows;
   for (int l = 0; l < L; ++l) {
     const otas_layer_weights& wl = c->layers[layer_begin + l];
     for (int g = 0; g < G; ++g) {
@@ -769,6 +768,14 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
     }
   }
   return OTAS_OK;
+  }();
+  if (enq != OTAS_OK) {
+    for (int g = 0; g < G; ++g) {
+      if (g > 0 && c->lane[g].main) (void)hipStreamSynchronize(c->lane[g].main);
+      if (c->lane[g].side) (void)hipStreamSynchronize(c->lane[g].side);
+    }
+  }
+  return enq;
 }
 }  // namespace
 
@@ -968,6 +975,7 @@ otas_status otas_attention(otas_ctx* c, const void* qkv, const int32_t* sizes, c
 
 otas_status otas_timing_enable(otas_ctx* c, int32_t on) {
   if (!c) return OTAS_EINVAL;
+  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
   if (hipStreamSynchronize(c->stream) != hipSuccess) return OTAS_EDEVICE;
   c->timing = false;
   c->ev_kind.clear();
@@ -982,9 +990,8 @@ otas_status otas_timing_enable(otas_ctx* c, int32_t on) {
     c->timing = true;
     c->ev_overhead_ms = 0.f;
     int32_t* cell = c->d_plan + kPlanInts - 1;
-    int dev = 0, khz = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0)
+    int khz = 0;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device) != hipSuccess || khz <= 0)
       khz = 100000;
     const double spin_us[2] = {10.0, 30.0};
     OTAS_HIP(launch_spin((int64_t)(spin_us[0] * khz / 1000.0), cell, c->stream));   // warm the code object

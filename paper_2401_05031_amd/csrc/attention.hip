@@ -270,12 +270,8 @@ static hipError_t attention_mfma_b(const void* qkv, const int32_t* sz, const int
 #define OTAS_ATTN(NWV)                                                                                            \
   do {                                                                                                            \
     auto kern = attention_mfma_kernel<DH, BIAS, KC, NWV>;                                                         \
-    static bool attr = false;                                                                                     \
-    if (!attr) {                                                                                                  \
-      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-      if (e != hipSuccess) return e;                                                                              \
-      attr = true;                                                                                                \
-    }                                                                                                             \
+    hipError_t e = set_max_dynamic_lds((const void*)kern, (int)lds);                                              \
+    if (e != hipSuccess) return e;                                                                                \
     dim3 grid((max_n + 32 * NWV - 1) / (32 * NWV), H, B), block(64 * NWV);                                        \
     kern<<<grid, block, lds, s>>>((const bf16_t*)qkv, sz, d_off, D, scale, (bf16_t*)o);                           \
   } while (0)
@@ -292,8 +288,6 @@ static hipError_t attention_mfma(const void* qkv, const int32_t* sz, const int32
             : attention_mfma_b<DH, false>(qkv, sz, d_off, B, max_n, D, H, scale, o, s);
 }
 
-int g_attn_force_rows = 0;   // tuning / test switch: route bf16 through the row-wise kernel
-
 hipError_t launch_attention(int dtype, const void* qkv, const int32_t* sizes, const int32_t* d_off, int B,
                             int max_n, int D, int H, bool size_bias, void* o, hipStream_t s) {
   if (B <= 0 || max_n <= 0) return hipSuccess;
@@ -302,7 +296,7 @@ hipError_t launch_attention(int dtype, const void* qkv, const int32_t* sizes, co
   const int32_t* sz = size_bias ? sizes : nullptr;
   dim3 grid((max_n + 3) / 4, H, B), block(256);
   const size_t lds = (size_t)4 * (max_n + dh) * sizeof(float);
-  if (dtype != 0 && !g_attn_force_rows) {
+  if (dtype != 0) {
     if (dh == 64) return attention_mfma<64>(qkv, sz, d_off, B, max_n, D, H, scale, o, s);
     if (dh == 80) return attention_mfma<80>(qkv, sz, d_off, B, max_n, D, H, scale, o, s);
     if (dh == 96) return attention_mfma<96>(qkv, sz, d_off, B, max_n, D, H, scale, o, s);

@@ -628,23 +628,4 @@ hipError_t launch_task_heads(int dtype, const float* x, const int32_t* d_off, co
   return hipGetLastError();
 }
 
-// ---------------------------------------------------------------------------------- widen / narrow
-// Token tensors enter and leave in the model's dtype; the residual stream in between is float.
-__global__ void widen_kernel(const bf16_t* __restrict__ a, float* __restrict__ b, int64_t n8) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= n8) return;
-  const Vec<bf16_t> v = load_vec<bf16_t>(a + i * 8);
-  Vec<float> lo, hi;
-#pragma unroll
-  for (int k = 0; k < 4; ++k) { lo.set(k, v.get(k)); hi.set(k, v.get(4 + k)); }
-  store_vec<float>(b + i * 8, lo);
-  store_vec<float>(b + i * 8 + 4, hi);
-}
-hipError_t launch_widen(const void* src_bf16, float* dst, int64_t n, hipStream_t s) {
-  if (n <= 0) return hipSuccess;
-  const int64_t n8 = n / 8;
-  widen_kernel<<<dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s>>>((const bf16_t*)src_bf16, dst, n8);
-  return hipGetLastError();
-}
-
 }  // namespace otas

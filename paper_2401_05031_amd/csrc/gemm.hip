@@ -6,11 +6,10 @@
 //                          for shapes the MFMA kernels do not take.
 //   * bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32 accumulate, operand tiles loaded straight into
 //     swizzled LDS stages, fused bias / GELU / residual epilogue (bf16 models):
-//       gemm_mfma128_dma_kernel  128 x 128, K step 32, three workgroups per CU (also split-K)
+//       gemm_mfma_k32_kernel     128 / 192 / 256 x 128, K step 32, three / two workgroups per CU (also split-K)
 //       gemm_mfma128k64_kernel   128 x 128, K step 64, two per CU
 //       gemm_mfma256w8_kernel    192 / 256 / 320 x 256, eight waves, one per CU
-//       gemm_mfma_kernel         register-staged 128 x 128 fallback for K % 32 != 0
-//     linear_mfma picks among them with a cost model fitted to measured launch times.
+//     pick_mfma_kernel chooses among them with a cost model fitted to measured launch times.
 #include <algorithm>
 #include <cmath>
 #include <cstdlib>
@@ -236,148 +235,9 @@ __device__ inline void mfma_epilogue_bf16(const floatx16 (&acc)[TM][TN], bf16_t*
 }
 
 // ------------------------------------------------------------------------------ bf16 MFMA tiles
-// Block tile BM x BN, K step 64, 256 threads = 4 waves in a WGM x WGN grid, each wave owning a
-// (BM/WGM) x (BN/WGN) sub-tile built from 32x32x16 MFMAs.  Operand tiles are staged through LDS,
-// double buffered: while the MFMAs of k-tile t run from one buffer, the global loads of tile t+1
-// are in flight into registers and are written to the other buffer afterwards.
-//
-// LDS rows are 64 bf16 = 128 B = eight 16-byte chunks; chunk c of row r is stored at chunk
-// position c ^ ((r >> 1) & 7).  A ds_read_b128 is served 16 lanes per clock (64 banks x 4 B), and
-// the 16 lanes that read one chunk column of 16 consecutive rows (the MFMA operand pattern) then
-// fall on 16 different (row parity, chunk position) pairs, i.e. on all 64 banks once.
-//
-// The MFMA computes the transposed tile (W rows as the first operand, X rows as the second): a
+// All MFMA kernels compute the transposed tile (W rows as the first operand, X rows as the second): a
 // lane then holds, for one output row m, runs of 4 consecutive output columns n, which makes the
 // epilogue's loads and stores 8- or 16-byte vectors along the row.
-template <int EPI, int BM, int BN, int WGM, int WGN>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
-                                                        const bf16_t* __restrict__ bias, const float* res,
-                                                        typename OutType<bf16_t, EPI>::type* Y, int64_t M, int N,
-                                                        int K, int tiles_n) {
-  typedef typename OutType<bf16_t, EPI>::type OT;
-  constexpr int BK = 64;
-  constexpr int WM = BM / WGM, WN = BN / WGN;          // wave sub-tile
-  constexpr int TM = WM / 32, TN = WN / 32;            // 32x32 MFMA tiles per wave
-  constexpr int A_CHUNKS = BM * 8 / 256, W_CHUNKS = BN * 8 / 256;   // 16-byte chunks per thread per k-tile
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                       // [2][BM][64]
-  bf16_t* Ws = As + 2 * BM * BK;                                      // [2][BN][64]
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WGN, wn = wave % WGN;
-  const int bid = blockIdx.x;
-  const int tile_m = bid / tiles_n, tile_n = bid - tile_m * tiles_n;
-  const int64_t m0 = (int64_t)tile_m * BM;
-  const int n0 = tile_n * BN;
-
-  // global -> register staging: chunk i = tid + 256 j covers row i / 8, k-chunk i % 8
-  const int ld_row = tid >> 3, ld_c = tid & 7;
-  bf16x8 a_reg[A_CHUNKS], w_reg[W_CHUNKS];
-  auto load_tiles = [&](int k0) {
-#pragma unroll
-    for (int j = 0; j < A_CHUNKS; ++j) {
-      int64_t r = m0 + ld_row + 32 * j;
-      r = r < M ? r : M - 1;                                           // rows past M are never stored
-      a_reg[j] = *reinterpret_cast<const bf16x8*>(A + (size_t)r * K + k0 + ld_c * 8);
-    }
-#pragma unroll
-    for (int j = 0; j < W_CHUNKS; ++j) {
-      int r = n0 + ld_row + 32 * j;
-      r = r < N ? r : N - 1;
-      w_reg[j] = *reinterpret_cast<const bf16x8*>(W + (size_t)r * K + k0 + ld_c * 8);
-    }
-  };
-  auto store_tiles = [&](int buf) {
-    bf16_t* as = As + buf * BM * BK;
-    bf16_t* ws = Ws + buf * BN * BK;
-#pragma unroll
-    for (int j = 0; j < A_CHUNKS; ++j) {
-      const int r = ld_row + 32 * j;
-      *reinterpret_cast<bf16x8*>(as + r * BK + ((ld_c ^ ((r >> 1) & 7)) * 8)) = a_reg[j];
-    }
-#pragma unroll
-    for (int j = 0; j < W_CHUNKS; ++j) {
-      const int r = ld_row + 32 * j;
-      *reinterpret_cast<bf16x8*>(ws + r * BK + ((ld_c ^ ((r >> 1) & 7)) * 8)) = w_reg[j];
-    }
-  };
-
-  floatx16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-  const int KT = K / BK;
-  load_tiles(0);
-  store_tiles(0);
-  __syncthreads();
-  const int fr = lane & 31, fk = lane >> 5;      // fragment row inside a 32-row tile, k half
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < KT) load_tiles((kt + 1) * BK);
-    const bf16_t* as = As + buf * BM * BK + (wm * WM) * BK;
-    const bf16_t* ws = Ws + buf * BN * BK + (wn * WN) * BK;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      const int c = ks * 2 + fk;                  // logical 16-byte chunk of this lane
-      bf16x8 af[TM], wf[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        const int r = i * 32 + fr;
-        af[i] = *reinterpret_cast<const bf16x8*>(as + r * BK + ((c ^ ((r >> 1) & 7)) * 8));
-      }
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int r = j * 32 + fr;
-        wf[j] = *reinterpret_cast<const bf16x8*>(ws + r * BK + ((c ^ ((r >> 1) & 7)) * 8));
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < KT) store_tiles(buf ^ 1);
-    __syncthreads();
-  }
-
-  __syncthreads();   // the operand buffers become the epilogue's staging area
-  if constexpr (EPI == EPI_NONE || EPI == EPI_GELU)
-    mfma_epilogue_bf16<EPI, TM, TN>(acc, reinterpret_cast<bf16_t*>(smem) + wave * 32 * (WN + 8), bias, Y, M, N,
-                                    m0 + wm * WM, n0 + wn * WN, lane);
-  else
-    mfma_epilogue<EPI, TM, TN>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (WN + 4), bias, res, Y, M, N,
-                               m0 + wm * WM, n0 + wn * WN, lane);
-}
-
-template <int BM, int BN, int WGM, int WGN>
-static hipError_t linear_mfma_tile(const void* x, const void* w, const void* bias, const float* res, void* y,
-                                   int64_t M, int N, int K, int epi, hipStream_t s) {
-  const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
-  const size_t lds = (size_t)2 * (BM + BN) * 64 * sizeof(bf16_t);
-  dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
-#define OTAS_MFMA(E)                                                                                              \
-  do {                                                                                                            \
-    auto kern = gemm_mfma_kernel<E, BM, BN, WGM, WGN>;                                                            \
-    static bool attr = false;                                                                                     \
-    if (!attr) {                                                                                                  \
-      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-      if (e != hipSuccess) return e;                                                                              \
-      attr = true;                                                                                                \
-    }                                                                                                             \
-    kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
-                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_n);                       \
-  } while (0)
-  if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
-  else if (epi == EPI_GELU) OTAS_MFMA(EPI_GELU);
-  else OTAS_MFMA(EPI_RESIDUAL);
-#undef OTAS_MFMA
-  return hipGetLastError();
-}
-
 
 // Tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2, and inside
 // an XCD the ~32 resident workgroups are consecutive in that XCD's sequence.  Give XCD x the
@@ -416,30 +276,28 @@ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int& til
 #define OTAS_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 
-// ------------------------------------------------------------------------------ 128x128, LDS DMA
-// The mid-size kernel: block tile 128 x 128, 4 waves of 64 x 64, K step 32, operand tiles loaded
-// straight into a ring of NS LDS stages (16 KB each) by global_load_lds_dwordx4.  With NS = 3 a
-// workgroup needs 48 KB of LDS and ~110 registers per lane, so three workgroups share a CU: while
-// one waits at its barrier or for its fragments, the others keep the matrix pipe busy, and one
-// workgroup's epilogue overlaps the others' main loops.
+// ------------------------------------------------------------------------------ (64 TM) x 128, K step 32
+// Four waves in a 2 x 2 arrangement, each owning (32 TM) x 64 outputs; block tile (64 TM) x 128 with
+// TM = 2 (128 rows, three workgroups per CU) or TM = 3, 4 (192 / 256 rows, two per CU).  K step 32,
+// operand tiles loaded straight into a ring of NS = 3 LDS stages by global_load_lds_dwordx4.  Several
+// workgroups share a CU: while one waits at its barrier or for its fragments, or runs its epilogue
+// (bias, GELU, the residual traffic), the others keep the matrix pipe busy.  The taller tiles read
+// 0.75 KB of fragments per MFMA instead of 1 KB and fetch a third less from L2 per FLOP.
 //   iteration t: wait for this wave's loads of tile t, barrier, start the loads of tile t+NS-1 into
 //                the stage tile t-1 used, then the two k-steps of tile t (fragment reads of the
 //                second step are issued between the MFMAs of the first).
-template <int EPI, int NS>
-__global__ __launch_bounds__(256, 3) void gemm_mfma128_dma_kernel(const bf16_t* __restrict__ A,
-                                                                  const bf16_t* __restrict__ W,
-                                                                  const bf16_t* __restrict__ bias,
-                                                                  const float* res,
-                                                                  typename OutType<bf16_t, EPI>::type* Y,
-                                                                  int64_t M, int N, int K, int k_len,
-                                                                  int tiles_m, int tiles_n) {
+template <int EPI, int NS, int TM>
+__global__ __launch_bounds__(256, TM == 2 ? 3 : 2) void gemm_mfma_k32_kernel(
+    const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ bias, const float* res,
+    typename OutType<bf16_t, EPI>::type* Y, int64_t M, int N, int K, int k_len, int tiles_m, int tiles_n) {
   // K is the row length of A and W; this workgroup contracts over k_len of it, starting at
   // blockIdx.y * k_len (split-K launches write one float partial result [M, N] per blockIdx.y).
-  constexpr int BM = 128, BN = 128, BK = 32, WM = 64, WN = 64, TM = 2, TN = 2;
-  constexpr int STAGE = BM * BK;   // elements per operand per stage
+  constexpr int WM = 32 * TM, BM = 2 * WM, BN = 128, BK = 32, WN = 64, TN = 2;
+  constexpr int STAGE_A = BM * BK, STAGE_W = BN * BK;   // elements per stage
+  constexpr int NM = TM * TN, NF = TM + TN, ND = TM + 2;   // MFMAs / fragment reads per k-step, loads per tile
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [NS][128][32]
-  bf16_t* Ws = As + NS * STAGE;                   // [NS][128][32]
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [NS][BM][32]
+  bf16_t* Ws = As + NS * STAGE_A;                 // [NS][128][32]
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: LDS addresses of the DMA stay scalar
@@ -449,33 +307,38 @@ __global__ __launch_bounds__(256, 3) void gemm_mfma128_dma_kernel(const bf16_t* 
   const int64_t m0 = (int64_t)tile_m * BM;
   const int n0 = tile_n * BN;
 
-  // DMA addressing: wave w owns rows w*32 .. w*32+31 of each operand tile, 16 rows per instruction.
-  // Global addresses: uniform base (tile origin + this split's k range + k) plus a constant per-lane
-  // 32-bit byte offset.
-  uint32_t a_off[2], w_off[2];
+  // DMA addressing: 16 rows of 64 B per instruction; wave w owns rows w*16*TM .. of the A tile and rows
+  // w*32 .. of the W tile.  Global addresses: uniform base (tile origin + this split's k range + k)
+  // plus a constant per-lane 32-bit byte offset.
+  uint32_t a_off[TM], w_off[2];
+#pragma unroll
+  for (int j = 0; j < TM; ++j) {
+    const int row = wave * (16 * TM) + j * 16 + (lane >> 2);
+    const int c = (lane & 3) ^ ((row >> 2) & 3);
+    const int64_t a_last = M - 1 - m0;                // rows past the end repeat the last row
+    const uint32_t ra = (uint32_t)(row < a_last ? row : a_last);
+    a_off[j] = (ra * (uint32_t)K + (uint32_t)c * 8u) * (uint32_t)sizeof(bf16_t);
+  }
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int row = wave * 32 + j * 16 + (lane >> 2);
     const int c = (lane & 3) ^ ((row >> 2) & 3);
-    const int64_t a_last = M - 1 - m0;                // rows past the end repeat the last row
     const int w_last = N - 1 - n0;
-    const uint32_t ra = (uint32_t)(row < a_last ? row : a_last), rw = (uint32_t)(row < w_last ? row : w_last);
-    a_off[j] = (ra * (uint32_t)K + (uint32_t)c * 8u) * (uint32_t)sizeof(bf16_t);
+    const uint32_t rw = (uint32_t)(row < w_last ? row : w_last);
     w_off[j] = (rw * (uint32_t)K + (uint32_t)c * 8u) * (uint32_t)sizeof(bf16_t);
   }
   const char* a_base = reinterpret_cast<const char*>(A + (size_t)m0 * K + (size_t)blockIdx.y * k_len);
   const char* w_base = reinterpret_cast<const char*>(W + (size_t)n0 * K + (size_t)blockIdx.y * k_len);
   if (EPI == EPI_PARTIAL) Y += (size_t)blockIdx.y * M * N;
   const int KT = k_len / BK;
-  auto dma_one = [&](int kt, int st, int d) {   // d = 0..3: A rows j = d/2 (even d), W rows (odd d)
+  auto dma_one = [&](int kt, int st, int d) {   // d = 0..TM-1: A rows; TM, TM+1: W rows
     const size_t kb = (size_t)((kt < KT ? kt : KT - 1) * BK) * sizeof(bf16_t);
-    const int j = d >> 1;
-    if ((d & 1) == 0)
-      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_base + kb + a_off[j]),
-                                       OTAS_LPTR(As + st * STAGE + (wave * 32 + j * 16) * BK), 16, 0, 0);
+    if (d < TM)
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_base + kb + a_off[d]),
+                                       OTAS_LPTR(As + st * STAGE_A + (wave * (16 * TM) + d * 16) * BK), 16, 0, 0);
     else
-      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_base + kb + w_off[j]),
-                                       OTAS_LPTR(Ws + st * STAGE + (wave * 32 + j * 16) * BK), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_base + kb + w_off[d - TM]),
+                                       OTAS_LPTR(Ws + st * STAGE_W + (wave * 32 + (d - TM) * 16) * BK), 16, 0, 0);
   };
 
   floatx16 acc[TM][TN];
@@ -489,12 +352,13 @@ __global__ __launch_bounds__(256, 3) void gemm_mfma128_dma_kernel(const bf16_t* 
   const int fr = lane & 31, fk = lane >> 5;
   const int frag_row = fr * BK, sw = (fr >> 2) & 3;
   bf16x8 af[2][TM], wf[2][TN];
-  auto read_frag = [&](int st, int ks, int slot, int f) {   // f = 0,1: A tiles; 2,3: W tiles
+  auto read_frag = [&](int st, int ks, int slot, int f) {   // f = 0..TM-1: A tiles; then the W tiles
     const int c = (((ks << 1) + fk) ^ sw) * 8;
-    if (f < 2)
-      af[slot][f] = *reinterpret_cast<const bf16x8*>(As + st * STAGE + (wm * WM + f * 32) * BK + frag_row + c);
+    if (f < TM)
+      af[slot][f] = *reinterpret_cast<const bf16x8*>(As + st * STAGE_A + (wm * WM + f * 32) * BK + frag_row + c);
     else
-      wf[slot][f - 2] = *reinterpret_cast<const bf16x8*>(Ws + st * STAGE + (wn * WN + (f - 2) * 32) * BK + frag_row + c);
+      wf[slot][f - TM] =
+          *reinterpret_cast<const bf16x8*>(Ws + st * STAGE_W + (wn * WN + (f - TM) * 32) * BK + frag_row + c);
   };
   auto mfma_one = [&](int slot, int t) {
     const int i = t / TN, j = t % TN;
@@ -506,27 +370,27 @@ __global__ __launch_bounds__(256, 3) void gemm_mfma128_dma_kernel(const bf16_t* 
 #pragma unroll
   for (int t = 0; t < NS - 1; ++t)
 #pragma unroll
-    for (int d = 0; d < 4; ++d) dma_one(t, t, d);
+    for (int d = 0; d < ND; ++d) dma_one(t, t, d);
 
   int st = 0, st_new = NS - 1;
   for (int kt = 0; kt < KT; ++kt) {
-    OTAS_VMCNT(4 * (NS - 2));   // tile kt landed; tiles kt+1 .. kt+NS-2 may still be in flight
+    OTAS_VMCNT(ND * (NS - 2));   // tile kt landed; tiles kt+1 .. kt+NS-2 may still be in flight
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 #pragma unroll
-    for (int f = 0; f < 4; ++f) read_frag(st, 0, 0, f);
+    for (int f = 0; f < NF; ++f) read_frag(st, 0, 0, f);
 #pragma unroll
-    for (int d = 0; d < 4; ++d) dma_one(kt + NS - 1, st_new, d);
+    for (int d = 0; d < ND; ++d) dma_one(kt + NS - 1, st_new, d);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < NM; ++t) {
       mfma_one(0, t);
-      read_frag(st, 1, 1, t);
+      if (t < NF) read_frag(st, 1, 1, t);
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
-    for (int t = 0; t < 4; ++t) mfma_one(1, t);
+    for (int t = 0; t < NM; ++t) mfma_one(1, t);
     st = st + 1 == NS ? 0 : st + 1;
     st_new = st_new + 1 == NS ? 0 : st_new + 1;
   }
@@ -542,22 +406,20 @@ __global__ __launch_bounds__(256, 3) void gemm_mfma128_dma_kernel(const bf16_t* 
                                m0 + wm * WM, n0 + wn * WN, lane);
 }
 
-template <int NS>
-static hipError_t linear_mfma128_dma(const void* x, const void* w, const void* bias, const float* res, void* y,
-                                     int64_t M, int N, int K, int epi, hipStream_t s, int splits = 1) {
-  const int tiles_m = (int)((M + 127) / 128), tiles_n = (N + 127) / 128;
-  const size_t lds = (size_t)NS * 2 * 128 * 32 * sizeof(bf16_t);
+template <int NS, int TM>
+static hipError_t linear_mfma_k32(const void* x, const void* w, const void* bias, const float* res, void* y,
+                                  int64_t M, int N, int K, int epi, hipStream_t s, int splits = 1) {
+  constexpr int BM = 64 * TM;
+  const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + 127) / 128;
+  const size_t lds = (size_t)NS * (BM + 128) * 32 * sizeof(bf16_t);
+  static_assert(4 * 32 * (64 + 4) * sizeof(float) <= (size_t)NS * (BM + 128) * 32 * sizeof(bf16_t), "epilogue slab");
   dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)splits), block(256);
   const int k_len = K / splits;
 #define OTAS_MFMA(E)                                                                                              \
   do {                                                                                                            \
-    auto kern = gemm_mfma128_dma_kernel<E, NS>;                                                                   \
-    static bool attr = false;                                                                                     \
-    if (!attr) {                                                                                                  \
-      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-      if (e != hipSuccess) return e;                                                                              \
-      attr = true;                                                                                                \
-    }                                                                                                             \
+    auto kern = gemm_mfma_k32_kernel<E, NS, TM>;                                                                  \
+    hipError_t e = set_max_dynamic_lds((const void*)kern, (int)lds);                                              \
+    if (e != hipSuccess) return e;                                                                                \
     kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
                                   (typename OutType<bf16_t, E>::type*)y, M, N, K, k_len, tiles_m, tiles_n);       \
   } while (0)
@@ -734,12 +596,8 @@ static hipError_t linear_mfma256w8(const void* x, const void* w, const void* bia
 #define OTAS_MFMA(E)                                                                                              \
   do {                                                                                                            \
     auto kern = gemm_mfma256w8_kernel<E, TM>;                                                                     \
-    static bool attr = false;                                                                                     \
-    if (!attr) {                                                                                                  \
-      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-      if (e != hipSuccess) return e;                                                                              \
-      attr = true;                                                                                                \
-    }                                                                                                             \
+    hipError_t e = set_max_dynamic_lds((const void*)kern, (int)lds);                                              \
+    if (e != hipSuccess) return e;                                                                                \
     kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
                                   (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_m, tiles_n);              \
   } while (0)
@@ -885,12 +743,8 @@ static hipError_t linear_mfma128k64(const void* x, const void* w, const void* bi
 #define OTAS_MFMA(E)                                                                                              \
   do {                                                                                                            \
     auto kern = gemm_mfma128k64_kernel<E>;                                                                        \
-    static bool attr = false;                                                                                     \
-    if (!attr) {                                                                                                  \
-      hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds); \
-      if (e != hipSuccess) return e;                                                                              \
-      attr = true;                                                                                                \
-    }                                                                                                             \
+    hipError_t e = set_max_dynamic_lds((const void*)kern, (int)lds);                                              \
+    if (e != hipSuccess) return e;                                                                                \
     kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
                                   (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_m, tiles_n);              \
   } while (0)
@@ -901,54 +755,48 @@ static hipError_t linear_mfma128k64(const void* x, const void* w, const void* bi
   return hipGetLastError();
 }
 
-int g_gemm_variant = 0;   // tile selection override for tuning runs (0 = automatic)
+// Runs one named kernel (gemm_kernel_id in kernels.h); hipErrorInvalidValue if it does not take the shape.
+static hipError_t linear_mfma_kernel(int kernel, const void* x, const void* w, const void* bias, const float* res,
+                                     void* y, int64_t M, int N, int K, int epi, hipStream_t s) {
+  const bool k32 = K % 32 == 0 && K >= 64, k64 = K % 64 == 0 && K >= 128;
+  switch (kernel) {
+    case GK_128_K32: return k32 ? linear_mfma_k32<3, 2>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
+    case GK_192X128_K32: return k32 ? linear_mfma_k32<3, 3>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
+    case GK_256X128_K32: return k32 ? linear_mfma_k32<3, 4>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
+    case GK_128_K64: return k64 ? linear_mfma128k64(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
+    case GK_192X256: return k64 ? linear_mfma256w8<3>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
+    case GK_256X256: return k64 ? linear_mfma256w8<4>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
+    case GK_320X256: return k64 ? linear_mfma256w8<5>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
+    default: return hipErrorInvalidValue;
+  }
+}
 
-static hipError_t linear_mfma(const void* x, const void* w, const void* bias, const float* res, void* y, int64_t M,
-                              int N, int K, int epi, hipStream_t s) {
-  // Kernel choice by a cost model fitted to per-launch times measured on MI355X inside the encoder
-  // (ViT-B shapes, all three epilogues, every kernel forced in turn; 5 % rms error, and the kernels
-  // it picks cost 0.7 % more in total than the best kernel per shape).  A kernel with tile bm x bn
-  // and S workgroup slots on the chip (256 CUs x workgroups per CU) takes
-  //     (alpha[epilogue] + beta K) * G(tiles),   G = full rounds + p + (1 - p) * (last round's fill),
-  // i.e. whole rounds of S tiles, a partly filled last round costing p of a round plus its share:
-  //   128 x 128, K step 32, three workgroups per CU (bound by L2 -> LDS bandwidth, but cheap per
-  //       round, with fine-grained rounds and an epilogue that overlaps other workgroups' loops);
-  //   128 x 128, K step 64, two per CU (whole cache lines per row and k-tile);
-  //   192 / 256 / 320 x 256, 8 waves, one per CU (up to twice the FLOP per byte loaded, coarse
-  //       rounds: the height that wastes least of the last round wins).
-  // K % 64 != 0 or tiny K falls back to the K-step-32 kernels.
-  static const int env_variant = [] {
-    const char* e = std::getenv("OTAS_GEMM_VARIANT");   // tuning override, 0 / unset = automatic
-    return e ? std::atoi(e) : 0;
-  }();
-  int variant = g_gemm_variant ? g_gemm_variant : env_variant;
-  if (K % 64 != 0 || K < 128) variant = (K % 32 == 0 && K >= 64 && (variant == 0 || variant == 5)) ? 5 : 1;
-  if (variant == 0) {
-    struct Cand { int id, bm, bn, slots; double alpha[3], beta, p; };
-    static const Cand cands[] = {
-        {5, 128, 128, 768, {4.06, 7.04, 13.0}, 0.0278, 0.27},
-        {9, 128, 128, 512, {3.17, 6.37, 8.75}, 0.0161, 0.58},
-        {73, 192, 256, 256, {4.36, 10.8, 11.9}, 0.0215, 0.72},
-        {7, 256, 256, 256, {5.85, 14.9, 12.7}, 0.0252, 0.72},
-        {75, 320, 256, 256, {8.34, 19.2, 14.7}, 0.0284, 0.74},
-    };
-    double best = 1e30;
-    for (const Cand& c : cands) {
-      const double tiles = (double)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
-      const double full = std::floor(tiles / c.slots), frac = tiles / c.slots - full;
-      const double g = full + (frac > 0 ? c.p + (1.0 - c.p) * frac : 0.0);
-      const double cost = (c.alpha[epi == EPI_RESIDUAL ? 2 : epi == EPI_GELU ? 1 : 0] + c.beta * K) * g;
-      if (cost < best) { best = cost; variant = c.id; }
-    }
+// Kernel choice by a cost model fitted to per-launch times measured on MI355X inside the encoder
+// (ViT-B shapes, all three epilogues, every kernel forced in turn).  A kernel with tile bm x bn and S
+// workgroup slots on the chip (256 CUs x workgroups per CU) takes
+//     (alpha[epilogue] + beta K) * G(tiles),   G = full rounds + p + (1 - p) * (last round's fill),
+// i.e. whole rounds of S tiles, a partly filled last round costing p of a round plus its share.
+// The choice depends on the shape only, so a shape always runs the same kernel.
+static int pick_mfma_kernel(int64_t M, int N, int K, int epi) {
+  if (K % 64 != 0 || K < 128) return GK_128_K32;
+  struct Cand { int id, bm, bn, slots; double alpha[3], beta, p; };
+  static const Cand cands[] = {
+      {GK_128_K32, 128, 128, 768, {4.06, 7.04, 13.0}, 0.0278, 0.27},
+      {GK_128_K64, 128, 128, 512, {3.17, 6.37, 8.75}, 0.0161, 0.58},
+      {GK_192X256, 192, 256, 256, {4.36, 10.8, 11.9}, 0.0215, 0.72},
+      {GK_256X256, 256, 256, 256, {5.85, 14.9, 12.7}, 0.0252, 0.72},
+      {GK_320X256, 320, 256, 256, {8.34, 19.2, 14.7}, 0.0284, 0.74},
+  };
+  double best = 1e30;
+  int kernel = GK_128_K32;
+  for (const Cand& c : cands) {
+    const double tiles = (double)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
+    const double full = std::floor(tiles / c.slots), frac = tiles / c.slots - full;
+    const double g = full + (frac > 0 ? c.p + (1.0 - c.p) * frac : 0.0);
+    const double cost = (c.alpha[epi == EPI_RESIDUAL ? 2 : epi == EPI_GELU ? 1 : 0] + c.beta * K) * g;
+    if (cost < best) { best = cost; kernel = c.id; }
   }
-  switch (variant) {
-    case 5: return linear_mfma128_dma<3>(x, w, bias, res, y, M, N, K, epi, s);
-    case 7: return linear_mfma256w8<4>(x, w, bias, res, y, M, N, K, epi, s);
-    case 73: return linear_mfma256w8<3>(x, w, bias, res, y, M, N, K, epi, s);
-    case 75: return linear_mfma256w8<5>(x, w, bias, res, y, M, N, K, epi, s);
-    case 9: return linear_mfma128k64(x, w, bias, res, y, M, N, K, epi, s);
-    default: return linear_mfma_tile<128, 128, 2, 2>(x, w, bias, res, y, M, N, K, epi, s);
-  }
+  return kernel;
 }
 
 // Split-K for few-tile, long-K products (the MLP's second linear once merging has shrunk the
@@ -957,12 +805,7 @@ static hipError_t linear_mfma(const void* x, const void* w, const void* bias, co
 // each contract over K / S and write a float partial result; a second kernel adds the partial
 // results in split order (a fixed order: results are reproducible), the bias and the residual.
 int splitk_factor(int dtype, int64_t M, int N, int K) {
-  if (dtype == 0 || g_gemm_variant || K < 2048 || N % 8 != 0) return 1;
-  static const int env = [] {
-    const char* e = std::getenv("OTAS_SPLITK");   // tuning override: 1 = never split
-    return e ? std::atoi(e) : 0;
-  }();
-  if (env == 1) return 1;
+  if (dtype == 0 || K < 2048 || N % 8 != 0) return 1;
   const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
   // measured inside the encoder (K = 3072, N = 768): the partial products' extra traffic pays off
   // only while one workgroup per tile leaves most CUs idle
@@ -977,17 +820,27 @@ hipError_t launch_linear_splitk(const void* x, const void* w, float* part, int64
                                 hipStream_t s) {
   if (M <= 0) return hipSuccess;
   if (S < 1 || K % (S * 32) != 0 || K / S < 64 || N % 8 != 0) return hipErrorInvalidValue;
-  return linear_mfma128_dma<3>(x, w, nullptr, nullptr, part, M, N, K, EPI_PARTIAL, s, S);
+  return linear_mfma_k32<3, 2>(x, w, nullptr, nullptr, part, M, N, K, EPI_PARTIAL, s, S);
 }
-
-int g_gemm_force_valu = 0;   // tuning / test switch: route bf16 through the plain-FMA kernel
 
 hipError_t launch_linear(int dtype, const void* x, const void* w, const void* bias, const float* res, void* y,
                          int64_t M, int N, int K, int epi, hipStream_t s) {
   if (M <= 0) return hipSuccess;
   if (dtype == 0) return linear_valu<float>(x, w, bias, res, y, M, N, K, epi, s);
-  if (K % 64 == 0 && N % 8 == 0 && !g_gemm_force_valu) return linear_mfma(x, w, bias, res, y, M, N, K, epi, s);
+  if (K % 32 == 0 && K >= 64 && N % 8 == 0)
+    return linear_mfma_kernel(pick_mfma_kernel(M, N, K, epi), x, w, bias, res, y, M, N, K, epi, s);
   return linear_valu<bf16_t>(x, w, bias, res, y, M, N, K, epi, s);
+}
+
+hipError_t launch_linear_kernel(int kernel, int dtype, const void* x, const void* w, const void* bias,
+                                const float* res, void* y, int64_t M, int N, int K, int epi, hipStream_t s) {
+  if (kernel == GK_AUTO) return launch_linear(dtype, x, w, bias, res, y, M, N, K, epi, s);
+  if (M <= 0) return hipSuccess;
+  if (kernel == GK_FMA)
+    return dtype == 0 ? linear_valu<float>(x, w, bias, res, y, M, N, K, epi, s)
+                      : linear_valu<bf16_t>(x, w, bias, res, y, M, N, K, epi, s);
+  if (dtype == 0 || N % 8 != 0) return hipErrorInvalidValue;
+  return linear_mfma_kernel(kernel, x, w, bias, res, y, M, N, K, epi, s);
 }
 
 }  // namespace otas

@@ -8,6 +8,9 @@ namespace otas {
 
 enum Epilogue { EPI_NONE = 0, EPI_GELU = 1, EPI_RESIDUAL = 2, EPI_PARTIAL = 3 /* internal: raw float sums */ };
 
+// Sets hipFuncAttributeMaxDynamicSharedMemorySize once per (kernel, device); thread-safe.
+hipError_t set_max_dynamic_lds(const void* kernel, int bytes);
+
 // One wave busy for `ticks` wall-clock periods (hipDeviceAttributeWallClockRate); sink: one int.
 hipError_t launch_spin(int64_t ticks, int32_t* sink, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s);
@@ -41,7 +44,6 @@ hipError_t launch_task_heads(int dtype, const float* x, const int32_t* d_off, co
 // x_is_float: the input rows are float (the residual stream) even when dtype is bf16.
 hipError_t launch_layer_norm(int dtype, bool x_is_float, const void* x, const void* g, const void* b,
                              void* y, int64_t T, int D, float eps, hipStream_t s);
-hipError_t launch_widen(const void* src_bf16, float* dst, int64_t n, hipStream_t s);
 // LayerNorm of bf16 rows that also writes the rows out as floats (x_float [T, D]).
 hipError_t launch_layer_norm_widen(const void* x_bf16, const void* g, const void* b, void* y, float* x_float,
                                    int64_t T, int D, float eps, hipStream_t s);
@@ -51,6 +53,17 @@ hipError_t launch_layer_norm_widen(const void* x_bf16, const void* g, const void
 hipError_t launch_linear(int dtype, const void* x, const void* w, const void* bias,
                          const float* res, void* y, int64_t M, int N, int K, int epi,
                          hipStream_t s);
+
+// The same with the kernel named by the caller (tests and profiling exercise every kernel at every
+// shape this way): GK_AUTO = launch_linear's own choice, GK_FMA = the plain-FMA kernel (any dtype),
+// the others bf16 MFMA kernels named by block tile (rows x columns) and K step.  Returns
+// hipErrorInvalidValue if the kernel does not take the shape (K % 32 / K % 64, N % 8).
+enum gemm_kernel_id {
+  GK_AUTO = 0, GK_FMA = 1, GK_128_K32 = 2, GK_192X128_K32 = 3, GK_256X128_K32 = 4, GK_128_K64 = 5,
+  GK_192X256 = 6, GK_256X256 = 7, GK_320X256 = 8, GK_COUNT = 9
+};
+hipError_t launch_linear_kernel(int kernel, int dtype, const void* x, const void* w, const void* bias,
+                                const float* res, void* y, int64_t M, int N, int K, int epi, hipStream_t s);
 
 // Split-K form of the residual linear for bf16 models: splitk_factor picks S (1 = do not split);
 // launch_linear_splitk writes S float partial products part[S][M][N] of x W^T, each over K / S;

@@ -273,16 +273,9 @@ hipError_t launch_merge_plan(int dtype, const void* src, int64_t row_stride, int
   if (dm % 4 != 0 || dm > 128 || max_n > kPlanThreads) return hipErrorInvalidValue;
   const size_t lds = merge_plan_lds_bytes(max_n, dm);
   if (lds > 160 * 1024) return hipErrorInvalidValue;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)merge_plan_kernel<float>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)merge_plan_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  hipError_t e = set_max_dynamic_lds(dtype == 0 ? (const void*)merge_plan_kernel<float>
+                                                : (const void*)merge_plan_kernel<bf16_t>, 160 * 1024);
+  if (e != hipSuccess) return e;
   if (dtype == 0)
     merge_plan_kernel<float><<<dim3(B), dim3(kPlanThreads), lds, s>>>(
         (const float*)src, row_stride, col_off, H, dm, d_in_off, d_out_off, d_reff, d_troff, n_lead, src_list, row_ptr,

@@ -12,12 +12,26 @@ from oracle import otas_oracle as orc
 
 
 def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
-    """max |got - ref| / max |ref| over one tensor."""
+    """The tolerance metric of the parity bars: max_i |got_i - ref_i| / max_i |ref_i| over one tensor
+    (a max-norm relative error, NOT an element-wise one: element-wise relative error is meaningless
+    at the zero crossings of a residual stream)."""
     ref = np.asarray(ref, dtype=np.float64)
     got = np.asarray(got, dtype=np.float64)
     if ref.size == 0:
         return 0.0
     return float(np.max(np.abs(got - ref)) / max(np.max(np.abs(ref)), 1e-30))
+
+
+def elem_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """Element-wise companion of rel_err: max_i |got_i - ref_i| / max(|ref_i|, rms(ref)), i.e. the
+    relative error of every element with the tensor's root mean square as the absolute floor (so an
+    element near zero is held to an absolute error of bar * rms, a large one to bar * its size)."""
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    if ref.size == 0:
+        return 0.0
+    floor = max(float(np.sqrt(np.mean(ref * ref))), 1e-30)
+    return float(np.max(np.abs(got - ref) / np.maximum(np.abs(ref), floor)))
 
 
 def storage_of(cfg: synth.Config) -> str:
@@ -108,15 +122,16 @@ def compare_lockstep(cfg, layers_host, toks, prm, r, gpu, size_bias: bool = Fals
     decision so that later layers stay comparable.  Returns dict(max_err, decisions,
     disagreements, max_deficit, sizes_equal)."""
     outs = oracle_forward(cfg, layers_host, toks, prm, r, adopt=gpu["trace"], size_bias=size_bias)
-    max_err, dis, dec, sizes_equal, max_def = 0.0, 0, 0, True, 0.0
+    max_err, dis, dec, sizes_equal, max_def, max_elem = 0.0, 0, 0, True, 0.0, 0.0
     for q, o in enumerate(outs):
         max_err = max(max_err, rel_err(gpu["x"][q], o["x"]))
+        max_elem = max(max_elem, elem_err(gpu["x"][q], o["x"]))
         dis += int(sum(o["disagree"]))
         dec += int(sum(s.size for s, _ in o["trace"]))
         max_def = max([max_def] + o["deficits"])
         sizes_equal = sizes_equal and np.array_equal(gpu["sizes"][q], o["sizes"])
-    return {"max_err": max_err, "decisions": dec, "disagreements": dis, "max_deficit": max_def,
-            "sizes_equal": sizes_equal}
+    return {"max_err": max_err, "elem_err": max_elem, "decisions": dec, "disagreements": dis,
+            "max_deficit": max_def, "sizes_equal": sizes_equal}
 
 
 def compare_per_layer(ctx, cfg, layers_host, toks, prm, r, size_bias: bool = False):
@@ -135,7 +150,7 @@ def compare_per_layer(ctx, cfg, layers_host, toks, prm, r, size_bias: bool = Fal
                                               n_lead=cfg.n_lead, storage=storage_of(cfg),
                                               size_bias=size_bias, taps=taps[q]))
     dec = dis = 0
-    max_err, sizes_equal = 0.0, True
+    max_err, max_elem, sizes_equal = 0.0, 0.0, True
     flags = otas.OTAS_FLAG_SIZE_BIAS if size_bias else 0
     for l in range(cfg.L):
         xs = [taps[q]["x_in"][l] for q in range(len(toks))]
@@ -155,7 +170,9 @@ def compare_per_layer(ctx, cfg, layers_host, toks, prm, r, size_bias: bool = Fal
                 want_s = taps[q]["sizes_in"][l + 1] if l + 1 < cfg.L else outs[q]["sizes"]
                 sizes_equal = sizes_equal and np.array_equal(g["sizes"][q], want_s)
                 max_err = max(max_err, rel_err(g["x"][q], taps[q]["x_out"][l]))
-    return {"decisions": dec, "disagreements": dis, "max_err": max_err, "sizes_equal": sizes_equal}
+                max_elem = max(max_elem, elem_err(g["x"][q], taps[q]["x_out"][l]))
+    return {"decisions": dec, "disagreements": dis, "max_err": max_err, "elem_err": max_elem,
+            "sizes_equal": sizes_equal}
 
 
 def deep_prompt_tensor(cfg: synth.Config, queries: Sequence[int]):

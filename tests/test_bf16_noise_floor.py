@@ -13,7 +13,7 @@ import numpy as np
 import otas_synth as synth
 from oracle import otas_oracle as orc
 
-NEAR_TIE = 8e-3
+NEAR_TIE = 4e-3   # measured: CPU self-disagreement 0.8e-3, GPU end to end <= 1.7e-3
 
 
 def test_one_ulp_input_change_moves_decisions_only_at_near_ties():
@@ -39,4 +39,4 @@ def test_one_ulp_input_change_moves_decisions_only_at_near_ties():
     assert max(errs) > 1e-3                  # the trajectories really did decorrelate ...
     assert max(errs) < 2e-2                  # ... to the bf16 noise floor, not beyond
     assert max(deficits, default=0.0) <= NEAR_TIE
-    assert dis <= 0.02 * dec
+    assert dis <= 0.015 * dec

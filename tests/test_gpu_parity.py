@@ -1,7 +1,13 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
-inputs.  Bars: f32 -- merge edges and sizes bit-exact, values <= 1e-4 (max abs diff / max abs
-ref); bf16 -- values <= 2e-2 and < 0.1 % of merge decisions differing (near-ties), with the oracle
-rounding at the same storage points and adopting the GPU's decisions layer by layer."""
+inputs.  Error metric of every value bar: max |got - ref| / max |ref| over a query's output tensor
+(harness.rel_err); beside it harness.elem_err, the element-wise relative error with the tensor's rms
+as the absolute floor, is asserted against bars of its own.
+Bars: f32 -- merge edges and sizes bit-exact, values <= 1e-4.  bf16 -- the target is values <= 2e-2
+and < 0.1 % of merge decisions differing; the tests hold the kernels to what they deliver, which is
+tighter on values (<= 1e-2) and, for decisions, the 0.1 % bar block by block on identical inputs
+(no slack; >= 1000 decisions per case) and the oracle's own noise floor end to end (<= 1.5 % of
+decisions, every differing edge within NEAR_TIE), with the oracle rounding at the same storage
+points and adopting the GPU's decisions layer by layer."""
 import numpy as np
 import pytest
 
@@ -12,8 +18,11 @@ from tests import harness as hz
 pytestmark = pytest.mark.gpu
 
 F32_TOL = 1e-4
-BF16_TOL = 2e-2
-BF16_DECISION_TOL = 1e-3
+BF16_TOL = 1e-2                 # the target is 2e-2; measured <= 5.4e-3
+BF16_ELEM_TOL = 5e-2            # element-wise, floor = rms of the tensor (harness.elem_err); measured <= 2.6e-2
+F32_ELEM_TOL = 1e-5             # measured 4.5e-7
+BF16_DECISION_TOL = 1e-3        # block by block, identical inputs
+BF16_E2E_DECISION_TOL = 1.5e-2  # end to end, the oracle's own noise floor (tests/test_bf16_noise_floor.py)
 
 
 @pytest.fixture(scope="module")
@@ -45,6 +54,9 @@ def test_tiny_f32_encoder_bit_exact_decisions(torch_cuda, lib):
             margins.append((ref[q]["margins"][l]["argmax_margin"], ref[q]["margins"][l]["rank_margin"]))
         assert gpu["x"][q].shape == ref[q]["x"].shape == (185, cfg.D)
         assert hz.rel_err(gpu["x"][q], ref[q]["x"]) <= F32_TOL
+        assert hz.elem_err(gpu["x"][q], ref[q]["x"]) <= F32_ELEM_TOL
+        print("tiny f32 query", q, "rel_err %.2e elem_err %.2e" % (hz.rel_err(gpu["x"][q], ref[q]["x"]),
+                                                                  hz.elem_err(gpu["x"][q], ref[q]["x"])))
     print("min decision margins (argmax, rank):", np.min(np.array(margins), axis=0))
     assert gpu["offsets"].tolist() == [0, 185, 370]
     ctx.close()
@@ -258,12 +270,15 @@ def _bf16_case(cfg, queries):
     return rep, per
 
 
+# Queries per case: enough that 0.1 % of the case's merge decisions is at least one decision
+# (186 per vitb_r16 query, 96 per vitb_p10_r8 query), four of every (P, r) group of vitl_ragged and one
+# query of each of the eight (P, r) pairs of vith_mixed: (0,0) (0,4) (0,8) (0,12) (10,0) (10,4) (10,8) (10,12).
 BF16_CASES = [
     ("vitb_plain", [0, 1]),
-    ("vitb_r16", [0, 1, 2, 3]),
-    ("vitb_p10_r8", [0, 1, 2, 3]),
-    ("vitl_ragged", [0, 1, 32, 33, 64, 65, 96, 97]),           # two queries of each of the 4 groups
-    ("vith_mixed", list(range(8))),
+    ("vitb_r16", [0, 1, 2, 3, 4, 5]),
+    ("vitb_p10_r8", list(range(11))),
+    ("vitl_ragged", [0, 1, 2, 3, 32, 33, 34, 35, 64, 65, 66, 67, 96, 97, 98, 99]),
+    ("vith_mixed", [6, 3, 7, 4, 5, 0, 2, 12]),
 ]
 
 
@@ -277,21 +292,29 @@ def test_bf16_encoder_parity(torch_cuda, lib, name, queries):
     # differing edge a near-tie in the oracle's own similarities
     assert rep["sizes_equal"]
     assert rep["max_err"] <= BF16_TOL
+    assert rep["elem_err"] <= BF16_ELEM_TOL
     assert rep["max_deficit"] <= NEAR_TIE
-    assert rep["disagreements"] <= 0.02 * max(rep["decisions"], 1)
-    # per layer on identical inputs: < 0.1 % of merge decisions differ, values within tolerance
+    assert rep["disagreements"] <= BF16_E2E_DECISION_TOL * rep["decisions"]
+    # per layer on identical inputs: < 0.1 % of merge decisions differ (no slack: every case that
+    # merges has at least 1000 decisions), values within tolerance
+    assert per["decisions"] == 0 or per["decisions"] >= 1000
     assert per["sizes_equal"]
     assert per["max_err"] <= BF16_TOL
-    assert per["disagreements"] <= BF16_DECISION_TOL * per["decisions"] + (1 if per["decisions"] < 2000 else 0)
+    assert per["elem_err"] <= BF16_ELEM_TOL
+    assert per["disagreements"] <= BF16_DECISION_TOL * per["decisions"]
+    print(name, "block-by-block decision disagreement: %d of %d = %.3f %% (bar 0.1 %%)"
+          % (per["disagreements"], per["decisions"], 100.0 * per["disagreements"] / max(per["decisions"], 1)))
 
 
 # ------------------------------------------------------------------ full batches, as bench.py launches them
+# Samples: every 4th query of the ViT-B batches (>= 1500 decisions where the strategy merges), four
+# queries of every (P, r) group of vitl_ragged, two of each of vith_mixed's eight (P, r) pairs.
 FULL_CASES = [
     ("vitb_plain", [0, 63]),
-    ("vitb_r16", [0, 31, 63]),
-    ("vitb_p10_r8", [0, 31, 63]),
-    ("vitl_ragged", [0, 33, 66, 127]),            # one query of every (P, r) group
-    ("vith_mixed", [0, 100, 255]),
+    ("vitb_r16", list(range(0, 64, 4))),
+    ("vitb_p10_r8", list(range(0, 64, 4))),
+    ("vitl_ragged", [0, 9, 18, 31, 32, 41, 50, 63, 64, 73, 82, 95, 96, 105, 114, 127]),
+    ("vith_mixed", [6, 10, 3, 38, 7, 9, 4, 15, 5, 11, 0, 1, 2, 14, 12, 23]),
 ]
 
 
@@ -316,8 +339,33 @@ def test_full_batch_sampled_queries(torch_cuda, lib, name, sample):
     print(name, "full batch, sampled", sample, rep)
     assert rep["sizes_equal"]
     assert rep["max_err"] <= BF16_TOL
+    assert rep["elem_err"] <= BF16_ELEM_TOL
     assert rep["max_deficit"] <= NEAR_TIE
-    assert rep["disagreements"] <= 0.02 * max(rep["decisions"], 1) + 1
+    assert rep["decisions"] == 0 or rep["decisions"] >= 1500
+    assert rep["disagreements"] <= BF16_E2E_DECISION_TOL * rep["decisions"]
+    ctx.close()
+
+
+def test_bf16_path_against_the_unrounded_oracle(torch_cuda, lib):
+    """The absolute error of the bf16 path: the plain ViT-B encoder (no merging, so no decisions to
+    adopt) against the oracle in float64 WITHOUT storage rounding.  This is the error of computing in
+    bf16 at all, not a parity bar of the kernels (those are held to the bf16-storage oracle above);
+    measured 2.3e-3 for the GPU and for the bf16-storage oracle alike."""
+    cfg = synth.config("vitb_plain")
+    ctx, layers = hz.make_context(cfg)
+    qs = [0, 17, 40, 63]
+    toks, prm, P, R = synth.batch(cfg, qs)
+    x0, off = hz.gpu_prepend(ctx, toks, prm)
+    gpu = hz.gpu_forward(ctx, x0, off, R)
+    exact = hz.oracle_forward(cfg, layers, toks, prm, R, storage="f64")
+    stored = hz.oracle_forward(cfg, layers, toks, prm, R, storage="bf16")
+    e_gpu = max(hz.rel_err(gpu["x"][i], exact[i]["x"]) for i in range(len(qs)))
+    e_orc = max(hz.rel_err(stored[i]["x"], exact[i]["x"]) for i in range(len(qs)))
+    e_par = max(hz.rel_err(gpu["x"][i], stored[i]["x"]) for i in range(len(qs)))
+    print("vitb_plain bf16 vs float64 without rounding: GPU %.3e, bf16-storage oracle %.3e; GPU vs bf16-storage oracle %.3e"
+          % (e_gpu, e_orc, e_par))
+    assert e_par <= BF16_TOL
+    assert e_gpu <= 1e-2 and e_gpu <= 2.0 * e_orc + 1e-3    # the kernels add nothing beyond the storage rounding
     ctx.close()
 
 
@@ -491,8 +539,8 @@ def test_lanes_bit_identical_full_batch_bf16(torch_cuda, lib):
     (1344, 768, 3072, 2), (67, 2304, 768, 0), (12608, 768, 3072, 2)])
 def test_linear_bf16_every_kernel_ragged_rows(torch_cuda, lib, M, N, K, epi):
     """otas_linear at the encoder's own shapes, chosen so that every MFMA kernel and tile height the
-    dispatch knows is exercised, with row counts that leave ragged last tiles.  Checked on sampled
-    rows (first, last, around every tile boundary, random) against float64."""
+    dispatch knows is exercised, with row counts that leave ragged last tiles.  The WHOLE output is
+    compared with a float64 product."""
     torch = torch_cuda
     cfg = synth.config("vitb_plain")
     cfg.L = 1
@@ -508,16 +556,12 @@ def test_linear_bf16_every_kernel_ragged_rows(torch_cuda, lib, M, N, K, epi):
                     _t(torch, res, torch.float32) if epi == 2 else None, M, N, K, epi, out)
     got = out.to(torch.float32).cpu().numpy()
     assert np.isfinite(got).all()
-    rows = {0, 1, M - 1, M - 2, M // 2}
-    for t in (128, 192, 256, 320):
-        for k in range(1, M // t + 1):
-            if k in (1, 2, M // t):
-                rows.update({k * t - 1, k * t})
-    rows.update(rng.integers(0, M, 40).tolist())
-    rows = sorted(r for r in rows if 0 <= r < M)
-    lin = x[rows].astype(np.float64) @ w.astype(np.float64).T + b
-    lin = orc.gelu(lin) if epi == 1 else (lin + res[rows] if epi == 2 else lin)
-    assert hz.rel_err(got[rows], lin) <= 1e-2
+    lin = x.astype(np.float64) @ w.astype(np.float64).T + b
+    lin = orc.gelu(lin) if epi == 1 else (lin + res if epi == 2 else lin)
+    if epi == 2:      # float output: only the fp32 accumulation order separates the two
+        assert hz.rel_err(got, lin) <= 1e-5 and hz.elem_err(got, lin) <= 1e-4
+    else:             # bf16 output: one rounding of the float64 value, up to the last place
+        assert hz.rel_err(got, lin) <= 2.0 ** -8 and hz.elem_err(got, lin) <= 2.0 ** -7
     ctx.close()
 
 
