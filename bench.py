@@ -128,6 +128,23 @@ class Strategy:
         torch.cuda.synchronize()
         self.ms_step = (time.perf_counter() - t0) / steps * 1e3
 
+    def time_single_forwards(self, runs=21):
+        """Latency of ONE forward pass (prompt prepend included) as a serving batch sees it: the GPU is
+        idle when the call starts and the pass is waited for; HIP events on the stream the library works
+        on (the context was created on torch's current stream); median of `runs`."""
+        import torch
+        t = []
+        for _ in range(runs):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            self.step()
+            e1.record()
+            e1.synchronize()
+            t.append(e0.elapsed_time(e1))
+        self.latency_ms = float(np.median(t))
+        self.latency_runs = runs
+
     def time_launches(self, timing_steps):
         """Per-kernel durations: the same steps again with an event pair around every launch."""
         import torch
@@ -152,6 +169,7 @@ class Strategy:
         work = algorithmic_work(cfg, self.lengths0, self.R, otas, ctx)
         assert torch.isfinite(self.x_out.float()).all()
         return {"name": self.name, "cfg": cfg, "ms": self.ms_step, "img_s": cfg.B / (self.ms_step * 1e-3),
+                "latency_ms": self.latency_ms, "latency_runs": self.latency_runs,
                 "kernels": per_step, "launches": per_launch, "work": work, "ev_overhead_us": ev_overhead_us}
 
 
@@ -220,7 +238,8 @@ def rooflines(res):
 
 
 def cpu_baseline(name, n_queries):
-    """The oracle, as it stands, on the host cores over a bounded sample of the same workload."""
+    """The oracle, as it stands, on the host cores over a bounded sample of the same workload: float64
+    arithmetic (the value), and the same sample again with float32 arithmetic (second figure)."""
     from oracle import otas_oracle as orc
     cfg = synth.config(name)
     layers = synth.all_weights(cfg)
@@ -231,14 +250,19 @@ def cpu_baseline(name, n_queries):
     except Exception:
         threads = len(os.sched_getaffinity(0))
     storage = "bf16" if cfg.dtype == "bf16" else "f64"
-    t0 = time.perf_counter()
-    for q in range(n_queries):
-        x0, _ = orc.prompt_prepend(toks[q], prm[q], cfg.n_lead)
-        orc.encoder_forward_query(x0, layers, R[q], H=cfg.H, ln_eps=cfg.ln_eps, n_lead=cfg.n_lead, storage=storage)
-    dt = time.perf_counter() - t0
-    return {"value": round(n_queries / dt, 3), "unit": "images/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{n_queries} of {cfg.B} queries of {name} (float64 NumPy oracle with bf16 storage rounding), "
-                      f"{dt:.1f} s; host has {len(os.sched_getaffinity(0))} usable cores"}
+    dts = {}
+    for arith in ("f64", "f32"):
+        t0 = time.perf_counter()
+        for q in range(n_queries):
+            x0, _ = orc.prompt_prepend(toks[q], prm[q], cfg.n_lead)
+            orc.encoder_forward_query(x0, layers, R[q], H=cfg.H, ln_eps=cfg.ln_eps, n_lead=cfg.n_lead,
+                                      storage=storage, arith=arith)
+        dts[arith] = time.perf_counter() - t0
+    return {"value": round(n_queries / dts["f64"], 3), "unit": "images/s", "cores": int(threads), "kind": "oracle",
+            "value_f32_arithmetic": round(n_queries / dts["f32"], 3),
+            "sample": f"{n_queries} of {cfg.B} queries of {name}, NumPy oracle with bf16 storage rounding: float64 "
+                      f"arithmetic {dts['f64']:.1f} s (the value), float32 arithmetic {dts['f32']:.1f} s; host has "
+                      f"{len(os.sched_getaffinity(0))} usable cores"}
 
 
 def main():
@@ -247,8 +271,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="vitb_r16", choices=list(synth.CONFIG_NAMES))
-    ap.add_argument("--others", default="vitb_plain,vitb_p10_r8,vitb_deep10_replace,vitb_deep2_grow", help="further strategies reported per strategy")
-    ap.add_argument("--cpu-queries", type=int, default=64)
+    ap.add_argument("--others", default="vitb_plain,vitb_p10_r8,vitb_deep10_replace,vitb_deep2_grow,vitl_ragged,vith_mixed",
+                    help="further workloads reported per strategy (the two large ragged ones run few steps)")
+    ap.add_argument("--cpu-queries", type=int, default=32)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run one plain device copy of 256 MiB (torch) so that a rocprofv3 --pmc run of this "
@@ -282,7 +307,11 @@ def main():
     gc.collect()
     gc.freeze()
     for i, st in enumerate(strategies):
-        st.time_steps(args.steps if i == 0 else max(5, args.steps // 2), args.warmup)
+        big = st.cfg.L * st.cfg.D * st.cfg.B > 12 * 768 * 64 * 2      # ViT-L / ViT-H batches: 12 / 73 ms a step
+        st.time_steps(args.steps if i == 0 else (max(5, args.steps // 8) if big else max(5, args.steps // 2)),
+                      args.warmup if not big else min(args.warmup, 3))
+    for st in strategies:
+        st.time_single_forwards(21)
     all_res = [st.time_launches(max(3, min(10, args.steps)) if i == 0 else 3) for i, st in enumerate(strategies)]
     for st in strategies:
         st.ctx.close()
@@ -296,6 +325,8 @@ def main():
             "strategy": "mixed" if mixed else ({"prompts": P, "r": R, "per_layer": r["cfg"].deep} if r["cfg"].deep
                                                else {"prompts": P, "r": R}),
             "images_per_s": round(r["img_s"], 1), "ms_per_step": round(r["ms"], 4),
+            "single_forward_ms_median": round(r["latency_ms"], 4), "single_forward_runs": r["latency_runs"],
+            "single_forward_images_per_s": round(r["cfg"].B / (r["latency_ms"] * 1e-3), 1),
             "gemm_tflops": rf["gemm"]["achieved"],
             "merge_apply_gbs": rf.get("merge_apply", {}).get("achieved"),
             "attention_tflops": rf.get("attention", {}).get("achieved"),
@@ -310,6 +341,7 @@ def main():
         "config": {"workload": f"{cfg.name}: L={cfg.L} D={cfg.D} H={cfg.H} F={cfg.F}, batch {cfg.B} x {cfg.n0} tokens, "
                                f"strategy (P, r) = {'mixed' if len(set(cfg.strategies)) > 1 else cfg.strategies[0]}",
                    "global_batch": cfg.B, "seq_len": cfg.n0, "parallelism": "single GPU"},
+        "single_forward_ms_median": round(head["latency_ms"], 4),
         "roofline": {k: rf["gemm"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},
         "rooflines": rf,
         "per_strategy": per_strategy,

@@ -273,6 +273,18 @@ otas_status otas_linear(otas_ctx *ctx, const void *x, const void *w, const void 
 otas_status otas_attention(otas_ctx *ctx, const void *qkv, const int32_t *sizes,
                            const int32_t *offsets, int32_t B, uint32_t flags, void *o);
 
+/* otas_linear with the kernel named by the caller, so that tests and profiles can run every GEMM
+ * kernel of the library at every shape (otas_linear and the encoder choose by shape alone).
+ * kernel: 0 the library's own choice, 1 plain fp32-FMA tiles (any dtype), and for bf16 models the
+ * MFMA kernels named by block tile (rows x columns) and K step: 2 128x128 k32, 3 128x128 k64,
+ * 4 192x256 k64, 5 256x256 k64, 6 320x256 k64.
+ * OTAS_EUNSUPPORTED if the kernel does not take the shape (k32 kernels need K % 32 == 0 and K >= 64,
+ * k64 kernels K % 64 == 0 and K >= 128) or the dtype. */
+#define OTAS_LINEAR_KERNELS 7
+otas_status otas_linear_kernel(otas_ctx *ctx, int32_t kernel, const void *x, const void *w,
+                               const void *b, const void *res, int64_t T, int32_t N, int32_t K,
+                               int32_t epilogue, void *y);
+
 /* Per-launch timing for benchmarks (callers that want the time of each kernel kind measured with
  * HIP events on the context's stream).  otas_timing_enable(ctx, 1) waits for the stream, then makes
  * every later launch of this context record an event before and after itself;

@@ -330,8 +330,12 @@ def encoder_forward_query(x0: np.ndarray, layers: Sequence[Dict[str, np.ndarray]
                           size_bias: bool = False, adopt: Optional[Sequence] = None,
                           taps: Optional[dict] = None, sizes0: Optional[np.ndarray] = None,
                           deep_prompts: Optional[Sequence[Optional[np.ndarray]]] = None,
-                          deep_mode: Optional[str] = None):
+                          deep_mode: Optional[str] = None, arith: str = "f64"):
     """Token-adapted encoder for ONE query (prompts already prepended).
+
+    arith: "f64" (the oracle proper) or "f32": the same steps with NumPy float32 arithmetic for the
+    normalisations, linear layers, attention and the weighted average (merge decisions are still
+    taken on float64 copies of the float32 metric).  Only the benchmark's second CPU figure uses it.
 
     deep_prompts / deep_mode (R13): per-layer prompting; deep_prompts[l] ([P, D]) is applied in
     front of layer l for l >= 1 (entry 0 is not used: layer 0's prompts are part of x0); needs
@@ -343,6 +347,11 @@ def encoder_forward_query(x0: np.ndarray, layers: Sequence[Dict[str, np.ndarray]
     (edge_deficit).  sizes0: sizes entering the first given layer (default all 1); taps: dict that
     receives per-layer intermediate states.  Returns dict(x, sizes, trace=[(src,dst) per layer],
     disagree=[per layer], margins=[per layer], lengths, deficits)."""
+    if arith not in ("f64", "f32"):
+        raise ValueError(arith)
+    if arith == "f32":
+        return _encoder_forward_query_f32(x0, layers, r, H=H, ln_eps=ln_eps, n_lead=n_lead, storage=storage,
+                                          size_bias=size_bias)
     st = storage
     rs = "f32" if storage == "bf16" else storage          # storage of the residual stream
     x = round_storage(np.asarray(x0, dtype=np.float64), rs)
@@ -401,6 +410,38 @@ def encoder_forward_query(x0: np.ndarray, layers: Sequence[Dict[str, np.ndarray]
             taps.setdefault("x_out", []).append(x.copy())
     return {"x": x, "sizes": sizes, "trace": trace, "disagree": disagree,
             "margins": margins, "lengths": lengths, "deficits": deficits}
+
+
+def _encoder_forward_query_f32(x0, layers, r, *, H, ln_eps, n_lead, storage, size_bias):
+    """The block sequence of encoder_forward_query with float32 NumPy arithmetic (no lock-step, taps
+    or per-layer prompting): normalisation -> attention -> residual -> merge -> normalisation -> MLP
+    -> residual, rounding at the same storage points."""
+    f = np.float32
+    rs = "f32" if storage == "bf16" else storage
+
+    def rnd(a, how):
+        return round_storage(a, how).astype(f)
+
+    x = rnd(np.asarray(x0, dtype=np.float64), rs)
+    sizes = np.ones(x.shape[0], dtype=np.int64)
+    trace, lengths = [], [x.shape[0]]
+    for w in layers:
+        W = {k: np.asarray(v, dtype=f) for k, v in w.items()}
+        h = rnd(layer_norm(x, W["ln1_g"], W["ln1_b"], f(ln_eps)), storage)
+        qkv = rnd(qkv_project(h, W["w_qkv"], W["b_qkv"]), storage)
+        o = rnd(attention_heads(qkv, H, sizes, size_bias).astype(f), storage)
+        x = rnd(x + o @ W["w_proj"].T + W["b_proj"], rs)
+        r_eff = removal_count(x.shape[0], r, n_lead)
+        src, dst, _ = merge_plan(merge_metric_from_keys(qkv, H).astype(np.float64), r_eff, n_lead)
+        if r_eff > 0:
+            x2, sizes = merge_apply(x, sizes, src, dst)
+            x = rnd(x2, rs)
+        trace.append((src, dst))
+        h2 = rnd(layer_norm(x, W["ln2_g"], W["ln2_b"], f(ln_eps)), storage)
+        hid = rnd(gelu(h2 @ W["w_fc1"].T + W["b_fc1"]).astype(f), storage)
+        x = rnd(x + hid @ W["w_fc2"].T + W["b_fc2"], rs)
+        lengths.append(x.shape[0])
+    return {"x": x.astype(np.float64), "sizes": sizes, "trace": trace, "lengths": lengths}
 
 
 def encoder_forward(x0_list: Sequence[np.ndarray], layers, r_list: Sequence[int], *, H: int,

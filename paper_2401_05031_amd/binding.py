@@ -16,6 +16,7 @@ OTAS_F32, OTAS_BF16 = 0, 1
 OTAS_FLAG_SIZE_BIAS, OTAS_FLAG_TRACE = 1, 2
 OTAS_PROMPT_REPLACE, OTAS_PROMPT_GROW = 1, 2
 OTAS_STATIC_MERGE_MAX_ROWS, OTAS_STATIC_MERGE_MAX_QUERIES = 65536, 1024
+OTAS_LINEAR_KERNELS = 7
 _WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
                   "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 
@@ -87,6 +88,7 @@ def load_library():
         "otas_layer_norm": (i32, [vp, vp, vp, vp, i64, vp]),
         "otas_linear": (i32, [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]),
         "otas_attention": (i32, [vp, vp, vp, _I32P, i32, u32, vp]),
+        "otas_linear_kernel": (i32, [vp, i32, vp, vp, vp, vp, i64, i32, i32, i32, vp]),
         "otas_strerror": (C.c_char_p, [i32]),
         "otas_timing_enable": (i32, [vp, i32]),
         "otas_timing_kinds": (i32, []),
@@ -116,7 +118,7 @@ def load_library():
 
 EXPORTED = ("otas_create", "otas_destroy", "otas_schedule", "otas_workspace_bytes",
             "otas_merge_workspace_bytes", "otas_prompt_prepend", "otas_token_merge", "otas_token_merge_static",
-            "otas_encoder_forward", "otas_encoder_layers", "otas_encoder_forward_deep", "otas_patch_embed_workspace_bytes", "otas_patch_embed", "otas_task_heads", "otas_layer_norm", "otas_linear", "otas_attention", "otas_strerror",
+            "otas_encoder_forward", "otas_encoder_layers", "otas_encoder_forward_deep", "otas_patch_embed_workspace_bytes", "otas_patch_embed", "otas_task_heads", "otas_layer_norm", "otas_linear", "otas_attention", "otas_linear_kernel", "otas_strerror",
             "otas_timing_enable", "otas_timing_kinds", "otas_timing_kind_name", "otas_timing_read",
             "otas_timing_read_launches", "otas_timing_overhead_ms", "otas_set_lanes", "otas_splitk_factor",
             "otas_sched_create", "otas_sched_destroy", "otas_sched_add_query", "otas_sched_allocate",
@@ -300,6 +302,10 @@ class Context:
     def otas_linear(self, x, w, b, res, T, N, K, epilogue, y) -> None:
         _check(self._lib.otas_linear(self._h, _ptr(x), _ptr(w), _ptr(b), _ptr(res), T, N, K, epilogue, _ptr(y)),
                "otas_linear")
+
+    def otas_linear_kernel(self, kernel, x, w, b, res, T, N, K, epilogue, y) -> None:
+        _check(self._lib.otas_linear_kernel(self._h, int(kernel), _ptr(x), _ptr(w), _ptr(b), _ptr(res), T, N, K,
+                                            epilogue, _ptr(y)), "otas_linear_kernel")
 
     def otas_attention(self, qkv, sizes, offsets, flags, o) -> None:
         B = len(offsets) - 1

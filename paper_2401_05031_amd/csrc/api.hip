@@ -955,6 +955,19 @@ otas_status otas_linear(otas_ctx* c, const void* x, const void* w, const void* b
   return OTAS_OK;
 }
 
+otas_status otas_linear_kernel(otas_ctx* c, int32_t kernel, const void* x, const void* w, const void* b,
+                               const void* res, int64_t T, int32_t N, int32_t K, int32_t epilogue, void* y) {
+  if (!c || !x || !w || !b || !y || T < 0 || N <= 0 || K <= 0) return OTAS_EINVAL;
+  if (epilogue < 0 || epilogue > 2 || (epilogue == EPI_RESIDUAL && !res)) return OTAS_EINVAL;
+  if (kernel < 0 || kernel >= GK_COUNT) return OTAS_EINVAL;
+  if (N % 8 != 0 || K % 8 != 0) return OTAS_EUNSUPPORTED;
+  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
+  const hipError_t e = launch_linear_kernel(kernel, c->desc.dtype, x, w, b, (const float*)res, y, T, N, K, epilogue,
+                                            c->stream);
+  if (e == hipErrorInvalidValue) return OTAS_EUNSUPPORTED;   // the kernel does not take this shape / dtype
+  return hip_ok(e, "launch_linear_kernel") ? OTAS_OK : OTAS_EDEVICE;
+}
+
 otas_status otas_attention(otas_ctx* c, const void* qkv, const int32_t* sizes, const int32_t* offsets, int32_t B,
                            uint32_t flags, void* o) {
   if (!c || !qkv || !offsets || !o || B <= 0) return OTAS_EINVAL;

@@ -6,7 +6,7 @@
 //                          for shapes the MFMA kernels do not take.
 //   * bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32 accumulate, operand tiles loaded straight into
 //     swizzled LDS stages, fused bias / GELU / residual epilogue (bf16 models):
-//       gemm_mfma_k32_kernel     128 / 192 / 256 x 128, K step 32, three / two workgroups per CU (also split-K)
+//       gemm_mfma_k32_kernel     128 x 128, K step 32, three workgroups per CU (also split-K)
 //       gemm_mfma128k64_kernel   128 x 128, K step 64, two per CU
 //       gemm_mfma256w8_kernel    192 / 256 / 320 x 256, eight waves, one per CU
 //     pick_mfma_kernel chooses among them with a cost model fitted to measured launch times.
@@ -277,12 +277,15 @@ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int& til
 
 
 // ------------------------------------------------------------------------------ (64 TM) x 128, K step 32
-// Four waves in a 2 x 2 arrangement, each owning (32 TM) x 64 outputs; block tile (64 TM) x 128 with
-// TM = 2 (128 rows, three workgroups per CU) or TM = 3, 4 (192 / 256 rows, two per CU).  K step 32,
-// operand tiles loaded straight into a ring of NS = 3 LDS stages by global_load_lds_dwordx4.  Several
-// workgroups share a CU: while one waits at its barrier or for its fragments, or runs its epilogue
-// (bias, GELU, the residual traffic), the others keep the matrix pipe busy.  The taller tiles read
-// 0.75 KB of fragments per MFMA instead of 1 KB and fetch a third less from L2 per FLOP.
+// Four waves in a 2 x 2 arrangement, each owning (32 TM) x 64 outputs; block tile (64 TM) x 128.  The
+// library runs TM = 2 (128 rows, three workgroups per CU); TM = 3 and 4 (192 / 256 rows, two per CU)
+// were measured on MI355X and lose to the 256-wide kernels on every large shape (60 us against 50 us
+// for 12608 x 2304 x 768) and win by less than 10 % on a handful of mid-size ones, so they are not
+// dispatched.  K step 32, operand tiles loaded straight into a ring of NS = 3 LDS stages by
+// global_load_lds_dwordx4 (deeper rings, NS = 4 .. 8, change nothing: a lone workgroup is bound by what
+// one CU can stream from L2, about 50 GB/s, not by load latency).  Several workgroups share a CU:
+// while one waits at its barrier or for its fragments, or runs its epilogue (bias, GELU, the residual
+// traffic), the others keep the matrix pipe busy.
 //   iteration t: wait for this wave's loads of tile t, barrier, start the loads of tile t+NS-1 into
 //                the stage tile t-1 used, then the two k-steps of tile t (fragment reads of the
 //                second step are issued between the MFMAs of the first).
@@ -761,8 +764,6 @@ static hipError_t linear_mfma_kernel(int kernel, const void* x, const void* w, c
   const bool k32 = K % 32 == 0 && K >= 64, k64 = K % 64 == 0 && K >= 128;
   switch (kernel) {
     case GK_128_K32: return k32 ? linear_mfma_k32<3, 2>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
-    case GK_192X128_K32: return k32 ? linear_mfma_k32<3, 3>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
-    case GK_256X128_K32: return k32 ? linear_mfma_k32<3, 4>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
     case GK_128_K64: return k64 ? linear_mfma128k64(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
     case GK_192X256: return k64 ? linear_mfma256w8<3>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
     case GK_256X256: return k64 ? linear_mfma256w8<4>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;

@@ -59,8 +59,8 @@ hipError_t launch_linear(int dtype, const void* x, const void* w, const void* bi
 // the others bf16 MFMA kernels named by block tile (rows x columns) and K step.  Returns
 // hipErrorInvalidValue if the kernel does not take the shape (K % 32 / K % 64, N % 8).
 enum gemm_kernel_id {
-  GK_AUTO = 0, GK_FMA = 1, GK_128_K32 = 2, GK_192X128_K32 = 3, GK_256X128_K32 = 4, GK_128_K64 = 5,
-  GK_192X256 = 6, GK_256X256 = 7, GK_320X256 = 8, GK_COUNT = 9
+  GK_AUTO = 0, GK_FMA = 1, GK_128_K32 = 2, GK_128_K64 = 3, GK_192X256 = 4, GK_256X256 = 5, GK_320X256 = 6,
+  GK_COUNT = 7
 };
 hipError_t launch_linear_kernel(int kernel, int dtype, const void* x, const void* w, const void* bias,
                                 const float* res, void* y, int64_t M, int N, int K, int epi, hipStream_t s);

@@ -565,6 +565,50 @@ def test_linear_bf16_every_kernel_ragged_rows(torch_cuda, lib, M, N, K, epi):
     ctx.close()
 
 
+@pytest.mark.parametrize("kernel", range(1, 7))
+def test_linear_every_named_kernel_whole_output(torch_cuda, lib, kernel):
+    """Every GEMM kernel of the library forced by name (otas_linear_kernel) on shapes with ragged row
+    and column tiles, all three epilogues, the whole output against a float64 product; a K that a
+    kernel does not take is refused, not mangled."""
+    torch = torch_cuda
+    cfg = synth.config("vitb_plain")
+    cfg.L = 1
+    ctx, layers = hz.make_context(cfg)
+    dt = torch.bfloat16
+    for M, N, K, epi in [(1345, 776, 768, 2), (701, 2304, 256, 0), (523, 1000, 768, 1), (389, 768, 3072, 2), (33, 8, 128, 0)]:
+        rng = np.random.default_rng(M + N + K + epi + kernel)
+        x = synth.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+        w = synth.round_to_bf16((rng.standard_normal((N, K)) * 0.03).astype(np.float32))
+        b = synth.round_to_bf16((rng.standard_normal(N) * 0.1).astype(np.float32))
+        res = rng.standard_normal((M, N)).astype(np.float32)
+        out = torch.full((M, N), float("nan"), dtype=torch.float32 if epi == 2 else dt, device="cuda")
+        ctx.otas_linear_kernel(kernel, _t(torch, x, dt), _t(torch, w, dt), _t(torch, b, dt),
+                               _t(torch, res, torch.float32) if epi == 2 else None, M, N, K, epi, out)
+        got = out.to(torch.float32).cpu().numpy()
+        lin = x.astype(np.float64) @ w.astype(np.float64).T + b
+        lin = orc.gelu(lin) if epi == 1 else (lin + res if epi == 2 else lin)
+        assert np.isfinite(got).all(), (kernel, M, N, K, epi)
+        if epi == 2:
+            assert hz.rel_err(got, lin) <= 1e-5 and hz.elem_err(got, lin) <= 1e-4, (kernel, M, N, K, epi)
+        else:
+            assert hz.rel_err(got, lin) <= 2.0 ** -8 and hz.elem_err(got, lin) <= 2.0 ** -7, (kernel, M, N, K, epi)
+    if kernel >= 2:     # MFMA kernels: K = 96 suits only the K-step-32 kernel, K = 40 none of them
+        x = torch.zeros((64, 96), dtype=dt, device="cuda")
+        w = torch.zeros((64, 96), dtype=dt, device="cuda")
+        b = torch.zeros(64, dtype=dt, device="cuda")
+        y = torch.zeros((64, 64), dtype=dt, device="cuda")
+        if kernel == 2:
+            ctx.otas_linear_kernel(kernel, x, w, b, None, 64, 64, 96, 0, y)
+        else:
+            with pytest.raises(lib.OtasError) as e:
+                ctx.otas_linear_kernel(kernel, x, w, b, None, 64, 64, 96, 0, y)
+            assert e.value.status == 5
+        with pytest.raises(lib.OtasError):
+            ctx.otas_linear_kernel(kernel, x[:, :40].contiguous(), w[:, :40].contiguous(), b, None, 64, 64, 40, 0, y)
+    torch.cuda.synchronize()
+    ctx.close()
+
+
 def test_longest_sequences_f32(torch_cuda, lib):
     """The longest query that can merge (554 tokens at d_h = 64: the plan kernel keeps every unit
     metric vector of a query in LDS) next to a short one, fp32, r larger than half the tokens:

@@ -683,3 +683,23 @@ def test_edge_deficit_hand_example():
     src, dst, info = orc.merge_plan(m, 2, 1)
     assert list(zip(src.tolist(), dst.tolist())) == [(2, 5), (4, 3)]
     assert abs(orc.edge_deficit(info, 4, 1) - 1.4) < 1e-12 and orc.edge_deficit(info, 4, 3) == 0.0
+
+
+def test_float32_arithmetic_mode_follows_the_float64_oracle():
+    """The benchmark's second CPU figure runs the oracle's steps in float32 arithmetic: without merging
+    it must agree with the float64 oracle to float32 accuracy, and with merging it must obey the same
+    shape law and size conservation."""
+    rng = np.random.default_rng(41)
+    D, H, F, n, L = 32, 4, 64, 19, 3
+    layers = _rand_layers(rng, L, D, F, 0.2)
+    x0 = rng.standard_normal((n, D))
+    a = orc.encoder_forward_query(x0, layers, 0, H=H, ln_eps=1e-6, n_lead=1)
+    b = orc.encoder_forward_query(x0, layers, 0, H=H, ln_eps=1e-6, n_lead=1, arith="f32")
+    assert np.max(np.abs(a["x"] - b["x"])) / np.max(np.abs(a["x"])) < 1e-5
+    c = orc.encoder_forward_query(x0, layers, 3, H=H, ln_eps=1e-6, n_lead=1, arith="f32")
+    assert c["lengths"] == orc.length_schedule(n, 0, 3, 1, L) and int(c["sizes"].sum()) == n
+    d = orc.encoder_forward_query(x0, layers, 3, H=H, ln_eps=1e-6, n_lead=1)
+    if all(np.array_equal(s1, s2) and np.array_equal(d1, d2) for (s1, d1), (s2, d2) in zip(c["trace"], d["trace"])):
+        assert np.max(np.abs(c["x"] - d["x"])) / np.max(np.abs(d["x"])) < 1e-4
+    with pytest.raises(ValueError):
+        orc.encoder_forward_query(x0, layers, 0, H=H, ln_eps=1e-6, n_lead=1, arith="f16")
