@@ -47,7 +47,11 @@ def algorithmic_work(cfg, lengths0, r, otas, ctx):
     Tm = T[:L] if cfg.deep else T[1:]           # rows of layer l behind its merging module (MLP rows)
     w = {"gemm_qkv": 0.0, "gemm_proj": 0.0, "gemm_fc1": 0.0, "gemm_fc2": 0.0, "attention": 0.0,
          "merge_apply_bytes": 0.0, "layer_norm_bytes": 0.0, "splitk_reduce_bytes": 0.0,
-         "merge_apply_bytes_per_layer": [], "splits": []}
+         "merge_apply_bytes_per_layer": [], "splits": [],
+         # the same three passes priced as if the residual stream were stored in the model's dtype (what the
+         # method itself needs: token rows in and out, the metric rows, sizes in and out)
+         "merge_apply_method_bytes": 0.0, "merge_apply_method_bytes_per_layer": [],
+         "layer_norm_method_bytes": 0.0, "splitk_reduce_method_bytes": 0.0}
     ln1_fused = False
     for l in range(L):
         w["gemm_qkv"] += 2.0 * T[l] * D * 3 * D
@@ -57,19 +61,25 @@ def algorithmic_work(cfg, lengths0, r, otas, ctx):
         w["attention"] += float(np.sum(4.0 * sched[:, l].astype(np.float64) ** 2 * D))
         if not ln1_fused:
             w["layer_norm_bytes"] += T[l] * D * (4.0 + e)            # LN1: float residual row in, operand row out
+            w["layer_norm_method_bytes"] += T[l] * D * 2.0 * e
         if Tm[l] != T[l]:
             # merge-apply fused with LN2: float rows in and out, a size and a list entry per row, operand row out
             b = (T[l] + Tm[l]) * (D * 4.0 + 8.0) + Tm[l] * D * e
             w["merge_apply_bytes"] += b
             w["merge_apply_bytes_per_layer"].append(b)
+            bm = (T[l] + Tm[l]) * D * e + T[l] * (D // H) * e + 4.0 * (T[l] + Tm[l])
+            w["merge_apply_method_bytes"] += bm
+            w["merge_apply_method_bytes_per_layer"].append(bm)
         else:
             w["layer_norm_bytes"] += Tm[l] * D * (4.0 + e)           # LN2 on its own
+            w["layer_norm_method_bytes"] += Tm[l] * D * 2.0 * e
         S = min(ctx.otas_splitk_factor(int(Tm[l]), D, F), int(2 * T[0] // max(Tm[l], 1))) if e == 2 and not cfg.deep else 1
         S = S if S > 1 and F % (S * 32) == 0 else 1
         w["splits"].append(S)
         ln1_fused = S > 1 and l + 1 < L
         if S > 1:   # S float partial rows + residual row in, residual row out, next block's operand row out
             w["splitk_reduce_bytes"] += Tm[l] * D * (4.0 * (S + 2) + (e if l + 1 < L else 0))
+            w["splitk_reduce_method_bytes"] += Tm[l] * D * (e * 2 + (e if l + 1 < L else 0))   # residual in/out, operand out
     w["T"] = T.tolist()
     return w
 
@@ -211,6 +221,8 @@ def rooflines(res):
         out["merge_apply"] = {"bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                               "frac": round(a / PEAK_HBM_GBS, 4), "traffic": traffic.get("merge_apply"),
                               "algorithmic_bytes_per_launch": round(w["merge_apply_bytes"] / max(k["merge_apply"][1], 1)),
+                              "method_bytes_per_launch": round(w["merge_apply_method_bytes"] / max(k["merge_apply"][1], 1)),
+                              "frac_on_method_bytes": round(w["merge_apply_method_bytes"] / (k["merge_apply"][0] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                               "avg_launch_us": round(k["merge_apply"][0] * 1e3 / max(k["merge_apply"][1], 1), 2)}
     if k["merge_apply"][0] > 0 and w["merge_apply_bytes_per_layer"]:
         # the largest launch (the first merging layer): later layers shrink until launch latency dominates
@@ -218,20 +230,28 @@ def rooflines(res):
         a = b0 / (t0 * 1e-3) / 1e9
         out["merge_apply_first_layer"] = {"bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                           "frac": round(a / PEAK_HBM_GBS, 4), "algorithmic_bytes": round(b0),
+                                          "method_bytes": round(w["merge_apply_method_bytes_per_layer"][0]),
+                                          "frac_on_method_bytes": round(w["merge_apply_method_bytes_per_layer"][0] / (t0 * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                                           "launch_us": round(t0 * 1e3, 2)}
     if k.get("splitk_reduce_ln", (0, 0))[0] > 0:
         a = w["splitk_reduce_bytes"] / (k["splitk_reduce_ln"][0] * 1e-3) / 1e9
         out["splitk_reduce_ln"] = {"bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                    "frac": round(a / PEAK_HBM_GBS, 4), "launches_per_step": k["splitk_reduce_ln"][1],
+                                   "frac_on_method_bytes": round(w["splitk_reduce_method_bytes"] / (k["splitk_reduce_ln"][0] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                                    "avg_launch_us": round(k["splitk_reduce_ln"][0] * 1e3 / k["splitk_reduce_ln"][1], 2)}
     if k["layer_norm"][0] > 0:
         a = w["layer_norm_bytes"] / (k["layer_norm"][0] * 1e-3) / 1e9
         out["layer_norm"] = {"bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                              "frac": round(a / PEAK_HBM_GBS, 4), "traffic": traffic.get("layer_norm"),
+                             "frac_on_method_bytes": round(w["layer_norm_method_bytes"] / (k["layer_norm"][0] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                              "avg_launch_us": round(k["layer_norm"][0] * 1e3 / max(k["layer_norm"][1], 1), 2)}
     for n in ("merge_plan", "prompt_prepend"):
         if k[n][1] > 0:
             out[n] = {"avg_launch_us": round(k[n][0] * 1e3 / k[n][1], 2), "launches_per_step": k[n][1]}
+    out["note_hbm_kernels"] = ("achieved / frac count the bytes these kernels move with the float residual stream "
+                               "(4 B per element of a token row); frac_on_method_bytes prices the same launches at "
+                               "what the method needs with rows in the model's dtype (2 B): the gap is the cost of "
+                               "keeping the residual in float")
     out["kernel_ms_per_step"] = {n: round(v[0], 4) for n, v in k.items()}
     out["event_pair_overhead_us_subtracted"] = round(res["ev_overhead_us"], 2)
     return out

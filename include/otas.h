@@ -136,6 +136,15 @@ otas_status otas_prompt_prepend(otas_ctx *ctx, const void *tokens, const int32_t
                                 const void *prompts, const int32_t *prompt_offsets, int32_t B,
                                 void *out, int32_t *out_offsets);
 
+/* The same with the prompts taken from a prompt repository (Sec. III-B: the trained prompts of every
+ * task are kept in a repository and a query takes those of its task): query q takes rows
+ * prompt_first[q] .. prompt_first[q] + prompt_count[q] - 1 of pool, dev [pool_rows, D]; several queries
+ * may take the same rows.  prompt_first / prompt_count host [B]; a range outside the pool is EINVAL. */
+otas_status otas_prompt_prepend_pool(otas_ctx *ctx, const void *tokens, const int32_t *tok_offsets,
+                                     const void *pool, int64_t pool_rows, const int32_t *prompt_first,
+                                     const int32_t *prompt_count, int32_t B, void *out,
+                                     int32_t *out_offsets);
+
 /* Merging module (Sec. II-C) applied once to every query of a packed batch.
  * Tokens at even positions of a query form set A, odd positions set B.  Every A token picks the
  * B token whose metric vector has the highest cosine similarity (ties: lowest position); the

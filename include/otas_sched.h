@@ -46,6 +46,16 @@ int otas_sched_create(const otas_sched_params* params, int32_t n_gamma, const in
                       const int32_t* rate_gamma, otas_sched** out);
 void otas_sched_destroy(otas_sched* s);
 
+/* The projection f of Alg. 3 built from a latency profile (Sec. III-D; Table I is the paper's instance for
+ * its own machine): walking the selection list from the largest gamma down, a gamma serves every request
+ * rate up to its own throughput 1 / (mean over tasks of the per-sample latency); a gamma whose throughput
+ * does not exceed the previous row's gets no row; the smallest gamma gets none either (rates above the
+ * table take it).  latency as in otas_sched_create.  Outputs: rate_max[*n_rate] ascending and
+ * rate_gamma[*n_rate] (indices into gammas), arrays of at least n_gamma - 1 entries, ready for
+ * otas_sched_create.  Pure host function. */
+int otas_sched_rate_table(int32_t n_gamma, const int32_t* gammas, int32_t n_tasks, const double* latency,
+                          double* rate_max, int32_t* rate_gamma, int32_t* n_rate);
+
 /* Alg. 1: puts request `id` (arrival time s_r, latency requirement l_r, utility u_r, task) into the newest
  * acceptable batch of the queue, walking from its last batch towards its first, or opens a new batch at
  * the end.  *batch (may be NULL) receives the queue position of the batch that took it. */

@@ -115,6 +115,24 @@ def profile(batch: Batch, g: int, latency: Sequence[Sequence[float]], accuracy: 
     return t, U
 
 
+def rate_table_from_latency(gammas: Sequence[int], latency: Sequence[Sequence[float]]) -> List[Tuple[float, int]]:
+    """The projection f of Alg. 3 built from a latency profile (Sec. III-D; Table I is the paper's own
+    instance): the gammas from the largest down; a gamma serves every rate up to its throughput
+    1 / (mean per-sample latency over the tasks); a gamma that is no faster than the row before it, and
+    the smallest gamma (what rates beyond the table get), have no row."""
+    n_tasks = len(latency)
+    order = sorted(range(len(gammas)), key=lambda i: -gammas[i])
+    rows: List[Tuple[float, int]] = []
+    for gi in order[:-1]:
+        total = 0.0
+        for k in range(n_tasks):
+            total += latency[k][gi]
+        thr = 1.0 / (total / n_tasks)
+        if not rows or thr > rows[-1][0]:
+            rows.append((thr, gi))
+    return rows
+
+
 def f_of_rate(q: float, table: Sequence[Tuple[float, int]], smallest: int) -> int:
     """S7: selection-list index for request rate q."""
     for q_max, g in table:

@@ -77,6 +77,7 @@ def load_library():
         "otas_workspace_bytes": (sz, [vp, i32, i64]),
         "otas_merge_workspace_bytes": (sz, [i32, i64]),
         "otas_prompt_prepend": (i32, [vp, vp, _I32P, vp, _I32P, i32, vp, _I32P]),
+        "otas_prompt_prepend_pool": (i32, [vp, vp, _I32P, vp, i64, _I32P, _I32P, i32, vp, _I32P]),
         "otas_token_merge": (i32, [vp, vp, vp, i32, vp, _I32P, _I32P, i32, vp, sz, vp, vp, _I32P, vp, vp]),
         "otas_token_merge_static": (i32, [vp, vp, vp, i32, vp, _I32P, _I32P, i32, vp, vp, _I32P, vp, vp]),
         "otas_encoder_forward": (i32, [vp, vp, _I32P, _I32P, i32, u32, vp, sz, vp, vp, _I32P, vp, vp]),
@@ -101,6 +102,7 @@ def load_library():
         "otas_sched_create": (i32, [C.POINTER(_SchedParams), i32, _I32P, i32, _F64P, _F64P, i32, _F64P, _I32P,
                                     C.POINTER(vp)]),
         "otas_sched_destroy": (None, [vp]),
+        "otas_sched_rate_table": (i32, [i32, _I32P, i32, _F64P, _F64P, _I32P, _I32P]),
         "otas_sched_add_query": (i32, [vp, i64, C.c_double, C.c_double, C.c_double, i32, _I32P]),
         "otas_sched_allocate": (i32, [vp, C.c_double, C.c_double, i32, _F64P]),
         "otas_sched_num_batches": (i32, [vp]),
@@ -117,11 +119,11 @@ def load_library():
 
 
 EXPORTED = ("otas_create", "otas_destroy", "otas_schedule", "otas_workspace_bytes",
-            "otas_merge_workspace_bytes", "otas_prompt_prepend", "otas_token_merge", "otas_token_merge_static",
+            "otas_merge_workspace_bytes", "otas_prompt_prepend", "otas_prompt_prepend_pool", "otas_token_merge", "otas_token_merge_static",
             "otas_encoder_forward", "otas_encoder_layers", "otas_encoder_forward_deep", "otas_patch_embed_workspace_bytes", "otas_patch_embed", "otas_task_heads", "otas_layer_norm", "otas_linear", "otas_attention", "otas_linear_kernel", "otas_strerror",
             "otas_timing_enable", "otas_timing_kinds", "otas_timing_kind_name", "otas_timing_read",
             "otas_timing_read_launches", "otas_timing_overhead_ms", "otas_set_lanes", "otas_splitk_factor",
-            "otas_sched_create", "otas_sched_destroy", "otas_sched_add_query", "otas_sched_allocate",
+            "otas_sched_create", "otas_sched_destroy", "otas_sched_rate_table", "otas_sched_add_query", "otas_sched_allocate",
             "otas_sched_num_batches", "otas_sched_batch_info", "otas_sched_batch_queries", "otas_sched_estimate",
             "otas_sched_remove")
 
@@ -210,6 +212,17 @@ class Context:
         oo = np.zeros(B + 1, dtype=np.int32)
         _check(self._lib.otas_prompt_prepend(self._h, _ptr(tokens), tp, _ptr(prompts), pp, B, _ptr(out),
                                              oo.ctypes.data_as(_I32P)), "otas_prompt_prepend")
+        return oo
+
+    def otas_prompt_prepend_pool(self, tokens, tok_offsets, pool, prompt_first, prompt_count, out) -> np.ndarray:
+        B = len(tok_offsets) - 1
+        ta, tp = _i32(tok_offsets)
+        fa, fp = _i32(prompt_first)
+        ca, cp = _i32(prompt_count)
+        oo = np.zeros(B + 1, dtype=np.int32)
+        _check(self._lib.otas_prompt_prepend_pool(self._h, _ptr(tokens), tp, _ptr(pool),
+                                                  0 if pool is None else int(pool.shape[0]), fp, cp, B, _ptr(out),
+                                                  oo.ctypes.data_as(_I32P)), "otas_prompt_prepend_pool")
         return oo
 
     def otas_token_merge(self, x, metric, dm, sizes, offsets, r, workspace, x_out, sizes_out,
@@ -358,6 +371,22 @@ class Context:
         flat = reff.reshape(-1)
         troff = np.concatenate([[0], np.cumsum(flat)[:-1]]).reshape(nl, B)
         return reff, troff
+
+
+def otas_sched_rate_table(gammas: Sequence[int], latency) -> List[Tuple[float, int]]:
+    """otas_sched_rate_table: rows (largest request rate, index into gammas) of the projection f of Alg. 3
+    from a latency profile [n_tasks][len(gammas)]."""
+    lat = np.ascontiguousarray(np.asarray(latency, dtype=np.float64))
+    if lat.ndim != 2 or lat.shape[1] != len(gammas):
+        raise ValueError("latency must be [n_tasks][len(gammas)]")
+    ga, gp = _i32(gammas)
+    rm = np.zeros(max(len(gammas), 1), dtype=np.float64)
+    rg = np.zeros(max(len(gammas), 1), dtype=np.int32)
+    n = C.c_int32()
+    _check(load_library().otas_sched_rate_table(len(gammas), gp, lat.shape[0], lat.ctypes.data_as(_F64P),
+                                                rm.ctypes.data_as(_F64P), rg.ctypes.data_as(_I32P), C.byref(n)),
+           "otas_sched_rate_table")
+    return [(float(rm[i]), int(rg[i])) for i in range(n.value)]
 
 
 class Scheduler:

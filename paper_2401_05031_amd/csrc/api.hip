@@ -336,30 +336,59 @@ size_t otas_merge_workspace_bytes(int32_t B, int64_t T) {
   return align_up((size_t)T * 4, kAlign) + align_up((size_t)(T + 1) * 4, kAlign);
 }
 
+}  // extern "C"
+
+namespace {
+// Body of otas_prompt_prepend and otas_prompt_prepend_pool: query q takes rows prm_beg[q] .. +prm_cnt[q]-1
+// of `prompts` (prm_rows rows in all).
+otas_status prepend_impl(otas_ctx* c, const void* tokens, const int32_t* tok_off, const void* prompts,
+                         int64_t prm_rows, const int32_t* prm_beg, const int32_t* prm_cnt, int32_t B, void* out,
+                         int32_t* out_off) {
+  if (out == tokens || (prompts && out == prompts)) return OTAS_EINVAL;
+  int max_n = 0;
+  // plan: tok_off [B+1] | prm_beg [B] | prm_cnt [B] | out_off [B+1]
+  std::vector<int32_t> plan(4 * (size_t)B + 2);
+  out_off[0] = 0;
+  for (int q = 0; q < B; ++q) {
+    const int n = tok_off[q + 1] - tok_off[q], P = prm_cnt[q];
+    if (n < c->desc.n_lead || P < 0) return OTAS_EINVAL;
+    if (P > 0 && (!prompts || prm_beg[q] < 0 || (int64_t)prm_beg[q] + P > prm_rows)) return OTAS_EINVAL;
+    out_off[q + 1] = out_off[q] + n + P;
+    max_n = std::max(max_n, n + P);
+  }
+  std::memcpy(&plan[0], tok_off, (B + 1) * sizeof(int32_t));
+  std::memcpy(&plan[B + 1], prm_beg, B * sizeof(int32_t));
+  std::memcpy(&plan[2 * B + 1], prm_cnt, B * sizeof(int32_t));
+  std::memcpy(&plan[3 * B + 1], out_off, (B + 1) * sizeof(int32_t));
+  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
+  otas_status st = upload_plan(c, plan);
+  if (st != OTAS_OK) return st;
+  const int32_t* dp = c->d_plan;
+  OTAS_LAUNCH(K_PREPEND, launch_prepend(c->desc.dtype, tokens, prompts, out, dp, dp + (B + 1), dp + (2 * B + 1),
+                                        dp + (3 * B + 1), B, max_n, c->desc.D, c->desc.n_lead, c->stream));
+  return OTAS_OK;
+}
+}  // namespace
+
+extern "C" {
+
 otas_status otas_prompt_prepend(otas_ctx* c, const void* tokens, const int32_t* tok_off, const void* prompts,
                                 const int32_t* prm_off, int32_t B, void* out, int32_t* out_off) {
   if (!c || !tokens || !tok_off || !prm_off || !out || !out_off || B <= 0) return OTAS_EINVAL;
   if (!offsets_ok(tok_off, B) || !offsets_ok(prm_off, B)) return OTAS_EINVAL;
   if (prm_off[B] > 0 && !prompts) return OTAS_EINVAL;
-  if (out == tokens || (prompts && out == prompts)) return OTAS_EINVAL;
-  int max_n = 0;
-  std::vector<int32_t> plan(3 * (size_t)(B + 1));
-  out_off[0] = 0;
-  for (int q = 0; q < B; ++q) {
-    const int n = tok_off[q + 1] - tok_off[q], P = prm_off[q + 1] - prm_off[q];
-    if (n < c->desc.n_lead) return OTAS_EINVAL;
-    out_off[q + 1] = out_off[q] + n + P;
-    max_n = std::max(max_n, n + P);
-  }
-  std::memcpy(&plan[0], tok_off, (B + 1) * sizeof(int32_t));
-  std::memcpy(&plan[B + 1], prm_off, (B + 1) * sizeof(int32_t));
-  std::memcpy(&plan[2 * (B + 1)], out_off, (B + 1) * sizeof(int32_t));
-  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
-  otas_status st = upload_plan(c, plan);
-  if (st != OTAS_OK) return st;
-  OTAS_LAUNCH(K_PREPEND, launch_prepend(c->desc.dtype, tokens, prompts, out, c->d_plan, c->d_plan + (B + 1),
-                          c->d_plan + 2 * (B + 1), B, max_n, c->desc.D, c->desc.n_lead, c->stream));
-  return OTAS_OK;
+  std::vector<int32_t> cnt(B);
+  for (int q = 0; q < B; ++q) cnt[q] = prm_off[q + 1] - prm_off[q];
+  return prepend_impl(c, tokens, tok_off, prompts, prm_off[B], prm_off, cnt.data(), B, out, out_off);
+}
+
+otas_status otas_prompt_prepend_pool(otas_ctx* c, const void* tokens, const int32_t* tok_off, const void* pool,
+                                     int64_t pool_rows, const int32_t* prompt_first, const int32_t* prompt_count,
+                                     int32_t B, void* out, int32_t* out_off) {
+  if (!c || !tokens || !tok_off || !prompt_first || !prompt_count || !out || !out_off || B <= 0 || pool_rows < 0)
+    return OTAS_EINVAL;
+  if (!offsets_ok(tok_off, B)) return OTAS_EINVAL;
+  return prepend_impl(c, tokens, tok_off, pool, pool_rows, prompt_first, prompt_count, B, out, out_off);
 }
 
 }  // extern "C"

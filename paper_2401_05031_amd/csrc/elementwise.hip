@@ -46,12 +46,12 @@ hipError_t launch_copy_i32(const int32_t* a, int32_t* b, int64_t n, hipStream_t 
 template <typename T>
 __global__ void prepend_kernel(const T* __restrict__ tokens, const T* __restrict__ prompts,
                                T* __restrict__ out, const int32_t* __restrict__ tok_off,
-                               const int32_t* __restrict__ prm_off,
+                               const int32_t* __restrict__ prm_beg, const int32_t* __restrict__ prm_cnt,
                                const int32_t* __restrict__ out_off, int D, int n_lead) {
   constexpr int V = Vec<T>::N;
   const int q = blockIdx.y;
   const int o0 = out_off[q], n_out = out_off[q + 1] - o0;
-  const int t0 = tok_off[q], p0 = prm_off[q], P = prm_off[q + 1] - p0;
+  const int t0 = tok_off[q], p0 = prm_beg[q], P = prm_cnt[q];   // the query's rows of the prompt tensor
   const int chunks = D / V;
   const int total = n_out * chunks;
   for (int t = blockIdx.x * blockDim.x + threadIdx.x; t < total; t += gridDim.x * blockDim.x) {
@@ -65,7 +65,7 @@ __global__ void prepend_kernel(const T* __restrict__ tokens, const T* __restrict
 }
 
 hipError_t launch_prepend(int dtype, const void* tokens, const void* prompts, void* out,
-                          const int32_t* d_tok_off, const int32_t* d_prm_off,
+                          const int32_t* d_tok_off, const int32_t* d_prm_beg, const int32_t* d_prm_cnt,
                           const int32_t* d_out_off, int B, int max_n_out, int D, int n_lead,
                           hipStream_t s) {
   if (B <= 0 || max_n_out <= 0) return hipSuccess;
@@ -76,10 +76,10 @@ hipError_t launch_prepend(int dtype, const void* tokens, const void* prompts, vo
   dim3 grid(gx, B), block(256);
   if (dtype == 0)
     prepend_kernel<float><<<grid, block, 0, s>>>((const float*)tokens, (const float*)prompts, (float*)out,
-                                                 d_tok_off, d_prm_off, d_out_off, D, n_lead);
+                                                 d_tok_off, d_prm_beg, d_prm_cnt, d_out_off, D, n_lead);
   else
     prepend_kernel<bf16_t><<<grid, block, 0, s>>>((const bf16_t*)tokens, (const bf16_t*)prompts,
-                                                  (bf16_t*)out, d_tok_off, d_prm_off, d_out_off, D, n_lead);
+                                                  (bf16_t*)out, d_tok_off, d_prm_beg, d_prm_cnt, d_out_off, D, n_lead);
   return hipGetLastError();
 }
 

@@ -16,8 +16,9 @@ hipError_t launch_spin(int64_t ticks, int32_t* sink, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s);
 hipError_t launch_copy_i32(const int32_t* src, int32_t* dst, int64_t n, hipStream_t s);
 
+// Query q takes rows d_prm_beg[q] .. + d_prm_cnt[q] - 1 of the prompt tensor.
 hipError_t launch_prepend(int dtype, const void* tokens, const void* prompts, void* out,
-                          const int32_t* d_tok_off, const int32_t* d_prm_off,
+                          const int32_t* d_tok_off, const int32_t* d_prm_beg, const int32_t* d_prm_cnt,
                           const int32_t* d_out_off, int B, int max_n_out, int D, int n_lead,
                           hipStream_t s);
 

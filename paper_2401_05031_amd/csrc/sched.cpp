@@ -266,6 +266,31 @@ int otas_sched_estimate(const otas_sched* s, int32_t b, int32_t gamma_index, dou
   return OTAS_OK;
 }
 
+int otas_sched_rate_table(int32_t n_gamma, const int32_t* gammas, int32_t n_tasks, const double* latency,
+                          double* rate_max, int32_t* rate_gamma, int32_t* n_rate) {
+  if (!gammas || !latency || !rate_max || !rate_gamma || !n_rate || n_gamma <= 0 || n_tasks <= 0) return OTAS_EINVAL;
+  for (int32_t i = 0; i < n_tasks * n_gamma; ++i)
+    if (!(latency[i] > 0.0)) return OTAS_EINVAL;
+  // gamma indices from the largest gamma down (stable: equal gammas keep their list order)
+  std::vector<int32_t> order(n_gamma);
+  for (int32_t i = 0; i < n_gamma; ++i) order[i] = i;
+  std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return gammas[a] > gammas[b]; });
+  int32_t rows = 0;
+  for (int32_t k = 0; k + 1 < n_gamma; ++k) {   // the smallest gamma needs no row
+    const int32_t gi = order[k];
+    double sum = 0.0;
+    for (int32_t t = 0; t < n_tasks; ++t) sum += latency[(size_t)t * n_gamma + gi];   // tasks in ascending order
+    const double thr = 1.0 / (sum / (double)n_tasks);
+    if (rows == 0 || thr > rate_max[rows - 1]) {
+      rate_max[rows] = thr;
+      rate_gamma[rows] = gi;
+      ++rows;
+    }
+  }
+  *n_rate = rows;
+  return OTAS_OK;
+}
+
 int otas_sched_remove(otas_sched* s, int32_t b) {
   if (!s || b < 0 || b >= (int32_t)s->queue.size()) return OTAS_EINVAL;
   s->queue.erase(s->queue.begin() + b);

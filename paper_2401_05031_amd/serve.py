@@ -26,7 +26,7 @@ from typing import Dict, List, Sequence, Tuple
 
 import numpy as np
 
-from .binding import OTAS_BF16, Context, Scheduler  # noqa: F401
+from .binding import OTAS_BF16, Context, Scheduler, otas_sched_rate_table  # noqa: F401
 
 
 def gamma_to_strategy(gamma: int) -> Tuple[int, int]:
@@ -64,7 +64,8 @@ class GpuEngine:
         g = torch.Generator(device="cpu").manual_seed(seed)
         dt = ctx.torch_dtype
         self.tokens = torch.randn((pool * n_tokens, D), generator=g).to("cuda").to(dt)
-        self.prompts = [(0.02 * torch.randn((max_prompts, D), generator=g)).to("cuda").to(dt) for _ in task_classes]
+        # the prompt repository: task k's trained prompts are rows k * max_prompts .. of one device tensor
+        self.prompt_pool = (0.02 * torch.randn((len(task_classes) * max_prompts, D), generator=g)).to("cuda").to(dt)
         self.heads = [((0.02 * torch.randn((k, D), generator=g)).to("cuda").to(dt).contiguous(),
                        torch.zeros(k).to("cuda").to(dt)) for k in task_classes]
         self.lnf_g = torch.ones(D).to("cuda").to(dt)
@@ -74,7 +75,6 @@ class GpuEngine:
         self.x0 = torch.empty((T_max, D), dtype=dt, device="cuda")
         self.x_out = torch.empty((T_max, D), dtype=torch.float32, device="cuda")
         self.sizes_out = torch.empty(T_max, dtype=torch.int32, device="cuda")
-        self.prm = torch.empty((pool * max_prompts, D), dtype=dt, device="cuda")
         self.ws = torch.empty(ctx.otas_workspace_bytes(pool, T_max), dtype=torch.uint8, device="cuda")
         self.logits = torch.empty((pool, max(task_classes)), dtype=torch.float32, device="cuda")
 
@@ -89,12 +89,9 @@ class GpuEngine:
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         tok_off = np.arange(B + 1, dtype=np.int32) * self.n
-        prm_off = np.arange(B + 1, dtype=np.int32) * P
-        prm = None
-        if P:
-            prm = self.prm[:B * P]
-            prm.view(B, P, -1).copy_(torch.stack([self.prompts[k][:P] for k in tasks]))
-        off = self.ctx.otas_prompt_prepend(self.tokens[:B * self.n], tok_off, prm, prm_off, self.x0)
+        first = [k * self.max_prompts for k in tasks]           # every query takes the first P rows of its task
+        off = self.ctx.otas_prompt_prepend_pool(self.tokens[:B * self.n], tok_off, self.prompt_pool, first, [P] * B,
+                                                self.x0)
         out_off = self.ctx.otas_encoder_forward(self.x0, off, [r] * B, 0, self.ws, self.x_out, self.sizes_out)
         self.ctx.otas_task_heads(self.x_out, out_off, list(tasks), self.heads, self.lnf_g, self.lnf_b, self.logits[:B])
         torch.cuda.synchronize()
@@ -113,18 +110,8 @@ class GpuEngine:
 
 
 def rate_table_from_latency(gammas: Sequence[int], latency) -> List[Tuple[float, int]]:
-    """The projection f of Alg. 3 profiled from throughput (Sec. III-D; Table I is the paper's instance):
-    walking the gammas from the largest down, gamma serves every rate up to its own throughput
-    1 / (mean per-sample latency over tasks); rows whose throughput does not exceed the previous row's
-    are left out.  The smallest gamma needs no row: it is what rates above the table get."""
-    lat = np.asarray(latency, dtype=np.float64).mean(axis=0)
-    order = sorted(range(len(gammas)), key=lambda i: -gammas[i])
-    rows: List[Tuple[float, int]] = []
-    for gi in order[:-1]:
-        thr = 1.0 / lat[gi]
-        if not rows or thr > rows[-1][0]:
-            rows.append((thr, gi))
-    return rows
+    """The projection f of Alg. 3 profiled from throughput: otas_sched_rate_table of the library."""
+    return otas_sched_rate_table(gammas, latency)
 
 
 def replay_trace(sched, trace: Sequence[Tuple[float, float, float, int]], engine, accuracy, initial_stage: float = 2.0,

@@ -112,6 +112,40 @@ def test_prompt_prepend_ragged(torch_cuda, lib, dtype):
     ctx.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_prompt_prepend_from_a_prompt_pool(torch_cuda, lib, dtype):
+    """otas_prompt_prepend_pool: every query takes a row range of one prompt repository (shared ranges,
+    empty ranges, the last rows of the pool); bit-exact against the oracle's prepend; ranges outside the
+    pool are refused."""
+    torch = torch_cuda
+    cfg = synth.config("tiny")
+    cfg.dtype = dtype
+    ctx, _ = hz.make_context(cfg)
+    rng = np.random.default_rng(77)
+    rnd = synth.round_to_bf16 if dtype == "bf16" else (lambda a: a.astype(np.float32))
+    ns = [197, 1, 5, 64, 33, 2]
+    pool = rnd(rng.standard_normal((24, cfg.D)).astype(np.float32))
+    first = [0, 8, 8, 20, 3, 16]
+    count = [8, 4, 4, 4, 0, 8]
+    toks = [rnd(rng.standard_normal((n, cfg.D)).astype(np.float32)) for n in ns]
+    tp, toff = synth.pack(toks, cfg.D)
+    out = torch.full((sum(ns) + sum(count), cfg.D), float("nan"), dtype=ctx.torch_dtype, device="cuda")
+    off = ctx.otas_prompt_prepend_pool(_t(torch, tp, ctx.torch_dtype), toff, _t(torch, pool, ctx.torch_dtype), first,
+                                       count, out)
+    torch.cuda.synchronize()
+    got = out.to(torch.float32).cpu().numpy()
+    assert off.tolist() == np.concatenate([[0], np.cumsum(np.array(ns) + np.array(count))]).tolist()
+    for q in range(len(ns)):
+        ref, _ = orc.prompt_prepend(toks[q], pool[first[q]:first[q] + count[q]], cfg.n_lead)
+        assert np.array_equal(got[off[q]:off[q + 1]], ref.astype(np.float32))
+    for bad_first, bad_count in (([0, 8, 8, 21, 3, 16], count), ([-1, 8, 8, 20, 3, 16], count), (first, [8, 4, -1, 4, 0, 8])):
+        with pytest.raises(lib.OtasError) as e:
+            ctx.otas_prompt_prepend_pool(_t(torch, tp, ctx.torch_dtype), toff, _t(torch, pool, ctx.torch_dtype),
+                                         bad_first, bad_count, out)
+        assert e.value.status == 1
+    ctx.close()
+
+
 def _merge_case(torch, ctx, cfg, ns, rs, dm, seed, sizes_hi=1, dup=False):
     rng = np.random.default_rng(seed)
     rnd = synth.round_to_bf16 if cfg.dtype == "bf16" else (lambda a: a.astype(np.float32))
@@ -714,6 +748,55 @@ def test_per_layer_prompting_bf16_full_batch(torch_cuda, lib, name):
     ctx.close()
 
 
+@pytest.mark.parametrize("name,queries", [("vitl_ragged", [0, 40, 70, 100, 33, 99, 71]),
+                                          ("vith_mixed", [12, 4, 2, 7, 23, 15])])
+def test_size_bias_on_the_ragged_bf16_workloads(torch_cuda, lib, name, queries):
+    """OTAS_FLAG_SIZE_BIAS on the selective batches of ViT-L and ViT-H (queries that merge most, next to
+    one that only prompts): block by block on identical inputs the decisions must agree to 0.1 %, end
+    to end in lock-step every differing edge must be a near-tie; and the flag must matter."""
+    cfg = synth.config(name)
+    ctx, layers = hz.make_context(cfg)
+    toks, prm, P, R = synth.batch(cfg, queries)
+    x0, off = hz.gpu_prepend(ctx, toks, prm)
+    gpu = hz.gpu_forward(ctx, x0, off, R, flags=lib.OTAS_FLAG_SIZE_BIAS)
+    plain = hz.gpu_forward(ctx, x0, off, R)
+    rep = hz.compare_lockstep(cfg, layers, toks, prm, R, gpu, size_bias=True)
+    per = hz.compare_per_layer(ctx, cfg, layers, toks, prm, R, size_bias=True)
+    print(name, "size bias end to end:", rep)
+    print(name, "size bias per layer:", per)
+    assert rep["sizes_equal"] and rep["max_err"] <= BF16_TOL and rep["elem_err"] <= BF16_ELEM_TOL
+    assert rep["max_deficit"] <= NEAR_TIE
+    assert rep["decisions"] >= 1000 and rep["disagreements"] <= BF16_E2E_DECISION_TOL * rep["decisions"]
+    assert per["sizes_equal"] and per["max_err"] <= BF16_TOL
+    assert per["decisions"] >= 1000 and per["disagreements"] <= BF16_DECISION_TOL * per["decisions"]
+    merging = [i for i, r in enumerate(R) if r > 0]
+    assert any(hz.rel_err(gpu["x"][i], plain["x"][i]) > 1e-3 for i in merging)
+    ctx.close()
+
+
+@pytest.mark.parametrize("shape,mode", [("vitl_ragged", "replace"), ("vitl_ragged", "grow"),
+                                        ("vith_mixed", "replace"), ("vith_mixed", "grow")])
+def test_per_layer_prompting_on_the_large_models_ragged_prompts(torch_cuda, lib, shape, mode):
+    """Per-layer prompting at the ViT-L and ViT-H shapes with a different prompt count per query
+    (0, 2, 5, 10 rows; sequences grow to 197 + 24 * 10 and 257 + 32 * 5 rows) in one launch."""
+    base = synth.config(shape)
+    Ps = [0, 2, 10, 5] if shape == "vitl_ragged" else [5, 0, 2, 3]
+    cfg = synth.Config(shape + "_deep_" + mode, base.L, base.D, base.H, base.F, "bf16", len(Ps), base.n0,
+                       [(p, 0) for p in Ps], seed=base.seed + 40, deep=mode)
+    ctx, layers = hz.make_context(cfg)
+    qs = list(range(cfg.B))
+    gpu = hz.gpu_forward_deep(ctx, cfg, qs, mode)
+    ref = hz.oracle_forward_deep(cfg, layers, qs, mode)
+    for q in qs:
+        want = orc.deep_length_schedule(cfg.n0, Ps[q], cfg.L, mode)[-1]
+        assert gpu["x"][q].shape == ref[q]["x"].shape == (want, cfg.D)
+        assert gpu["sizes"][q].tolist() == [1] * want
+        err, eerr = hz.rel_err(gpu["x"][q], ref[q]["x"]), hz.elem_err(gpu["x"][q], ref[q]["x"])
+        print(cfg.name, "query", q, "P", Ps[q], "rel err %.2e elem err %.2e" % (err, eerr))
+        assert err <= BF16_TOL and eerr <= BF16_ELEM_TOL
+    ctx.close()
+
+
 def test_per_layer_prompting_argument_errors(torch_cuda, lib):
     torch = torch_cuda
     cfg = synth.config("tiny")
@@ -867,7 +950,7 @@ def test_serving_engine_batches_match_oracle_and_loop_accounts(torch_cuda, lib):
         lg = eng.logits[:3].cpu().numpy()
         P, r = serve.gamma_to_strategy(g)
         for q, task in enumerate(tasks):
-            prm = eng.prompts[task][:P].float().cpu().numpy()
+            prm = eng.prompt_pool[task * eng.max_prompts:task * eng.max_prompts + P].float().cpu().numpy()
             xq, _ = orc.prompt_prepend(toks[q], prm, cfg.n_lead)
             out = orc.encoder_forward_query(xq, layers, r, H=cfg.H, ln_eps=cfg.ln_eps, n_lead=cfg.n_lead)
             w, b = eng.heads[task]

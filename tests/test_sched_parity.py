@@ -171,6 +171,30 @@ def test_argument_errors():
     assert s.otas_sched_batch_queries(0) == ([7], [1])
 
 
+def test_rate_table_library_equals_oracle_exactly():
+    """otas_sched_rate_table against the oracle's statement of the projection: identical rows (exact
+    doubles), also with unsorted gamma lists, a gamma no faster than its neighbour (no row) and one task."""
+    _ensure_built()
+    from oracle import otas_sched_oracle as so
+    rng = np.random.default_rng(3)
+    for n_tasks in (1, 3, 6):
+        for gl in (GAMMAS, [0], [-5, 8, 0, -20, 4], list(reversed(GAMMAS))):
+            lat = rng.uniform(1e-4, 2e-3, size=(n_tasks, len(gl)))
+            if len(gl) > 2:
+                lat[:, 1] = lat[:, 0]                 # equal throughput: the later one gets no row
+            want = so.rate_table_from_latency(gl, lat.tolist())
+            got = otas.otas_sched_rate_table(gl, lat)
+            assert got == want
+    # the paper's Table I is such a projection: throughputs 279, 319, ... give its rows back
+    gl = [8, 4, 2, 0, -5, -10, -15, -20]
+    thr = [279.0, 319.0, 348.0, 379.0, 449.0, 519.0, 999.0, 5000.0]
+    lat = np.array([[1.0 / t for t in thr]])
+    rows = otas.otas_sched_rate_table(gl, lat)
+    assert [g for _, g in rows] == list(range(7)) and [round(r) for r, _ in rows] == [279, 319, 348, 379, 449, 519, 999]
+    with pytest.raises(otas.OtasError):
+        otas.otas_sched_rate_table(gl, np.zeros((1, 8)))
+
+
 def test_rate_table_from_latency_orders_gammas_by_throughput():
     lat, _ = tables(6)
     rows = serve.rate_table_from_latency(GAMMAS, lat)
