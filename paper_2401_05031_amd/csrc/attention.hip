@@ -85,7 +85,7 @@ typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef short short8_t __attribute__((ext_vector_type(8)));
 
 template <int DH, bool BIAS, int KC, int NW>
-__global__ __launch_bounds__(64 * NW, (DH <= 64 ? 16 : 8) / NW) void attention_mfma_kernel(const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(64 * NW, DH <= 64 ? 4 : 2) void attention_mfma_kernel(const bf16_t* __restrict__ qkv,
                                                              const int32_t* __restrict__ sizes,
                                                              const int32_t* __restrict__ off, int D, float scale,
                                                              bf16_t* __restrict__ o) {
@@ -165,9 +165,11 @@ __global__ __launch_bounds__(64 * NW, (DH <= 64 ? 16 : 8) / NW) void attention_m
     __syncthreads();
     if (!wave_active) continue;
 
-    for (int kb = 0; kb < nc_pad; kb += 32) {
-      // S^T block
-      floatx16 sacc;
+    // The key blocks are software-pipelined inside the wave: the MFMA chain of block b + 1's logits is
+    // issued before the softmax arithmetic of block b starts, so the matrix pipe works under the VALU
+    // instructions of the same wave (the kernel runs at two to four waves per SIMD and is bound by
+    // these dependency waits, not by VALU or MFMA throughput).
+    auto s_block = [&](floatx16& sacc, int kb) {   // S^T block: logits of keys kb .. kb + 31
 #pragma unroll
       for (int e = 0; e < 16; ++e) sacc[e] = 0.f;
 #pragma unroll
@@ -175,6 +177,8 @@ __global__ __launch_bounds__(64 * NW, (DH <= 64 ? 16 : 8) / NW) void attention_m
         const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + (kb + fr) * LD + ks * 16 + fk * 8);
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
       }
+    };
+    auto softmax_pv = [&](floatx16& sacc, int kb) {
       // Logits in base-2 units, t = s * (scale * log2 e) [+ log2(size)], so that exp(s - m) is one
       // v_exp_f32.  Without the size bias the scaling is folded into the exponent's argument,
       // exp2(fma(s, scale2, -m)): the maximum is taken over the raw products (scale2 > 0) and scaled
@@ -235,6 +239,19 @@ __global__ __launch_bounds__(64 * NW, (DH <= 64 ? 16 : 8) / NW) void attention_m
           __builtin_memcpy(&vf, &both, 16);
           oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[t], 0, 0, 0);
         }
+      }
+    };
+    const int nblk = nc_pad >> 5;
+    floatx16 s_even, s_odd;
+    s_block(s_even, 0);
+    for (int b = 0; b < nblk; b += 2) {
+      if (b + 1 < nblk) s_block(s_odd, (b + 1) * 32);
+      __builtin_amdgcn_sched_barrier(0);
+      softmax_pv(s_even, b * 32);
+      if (b + 1 < nblk) {
+        if (b + 2 < nblk) s_block(s_even, (b + 2) * 32);
+        __builtin_amdgcn_sched_barrier(0);
+        softmax_pv(s_odd, (b + 1) * 32);
       }
     }
   }
