@@ -81,6 +81,7 @@ def algorithmic_work(cfg, lengths0, r, otas, ctx):
             w["splitk_reduce_bytes"] += Tm[l] * D * (4.0 * (S + 2) + (e if l + 1 < L else 0))
             w["splitk_reduce_method_bytes"] += Tm[l] * D * (e * 2 + (e if l + 1 < L else 0))   # residual in/out, operand out
     w["T"] = T.tolist()
+    w["Tm"] = [int(v) for v in Tm]
     return w
 
 
@@ -178,7 +179,7 @@ class Strategy:
             per_step[kind] = (float(sum(v)), len(v))
         work = algorithmic_work(cfg, self.lengths0, self.R, otas, ctx)
         assert torch.isfinite(self.x_out.float()).all()
-        return {"name": self.name, "cfg": cfg, "ms": self.ms_step, "img_s": cfg.B / (self.ms_step * 1e-3),
+        return {"name": self.name, "cfg": cfg, "ctx": ctx, "ms": self.ms_step, "img_s": cfg.B / (self.ms_step * 1e-3),
                 "latency_ms": self.latency_ms, "latency_runs": self.latency_runs,
                 "kernels": per_step, "launches": per_launch, "work": work, "ev_overhead_us": ev_overhead_us}
 
@@ -245,6 +246,25 @@ def rooflines(res):
                              "frac": round(a / PEAK_HBM_GBS, 4), "traffic": traffic.get("layer_norm"),
                              "frac_on_method_bytes": round(w["layer_norm_method_bytes"] / (k["layer_norm"][0] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                              "avg_launch_us": round(k["layer_norm"][0] * 1e3 / max(k["layer_norm"][1], 1), 2)}
+    # one row per GEMM launch of a forward pass: rows, the kernel the library picks (block tile, workgroup
+    # slots on 256 CUs), tiles, rounds of those slots, microseconds, TFLOP/s
+    tiles_of = {1: (64, 64, 2048), 2: (128, 128, 768), 3: (128, 128, 512), 4: (192, 256, 256), 5: (256, 256, 256),
+                6: (320, 256, 256)}
+    cfg, ctx = res["cfg"], res.get("ctx")
+    if ctx is not None and not cfg.deep:
+        table = []
+        shapes = {"gemm_qkv": (w["T"][:cfg.L], 3 * cfg.D, cfg.D, 0), "gemm_proj": (w["T"][:cfg.L], cfg.D, cfg.D, 2),
+                  "gemm_fc1": (w["Tm"], cfg.F, cfg.D, 1), "gemm_fc2": (w["Tm"], cfg.D, cfg.F, 2)}
+        for kind, (rows, N, K, epi) in shapes.items():
+            for l, (M, ms) in enumerate(zip(rows, res["launches"].get(kind, []))):
+                S = w["splits"][l] if kind == "gemm_fc2" else 1
+                kid = 2 if S > 1 else ctx.otas_linear_choice(M, N, K, epi)
+                bm, bn, slots = tiles_of.get(kid, (0, 0, 1))
+                tiles = -(-M // bm) * -(-N // bn) * S if bm else 0
+                table.append({"kind": kind, "layer": l, "M": int(M), "N": N, "K": K, "kernel": kid, "tile": f"{bm}x{bn}",
+                              "split_k": S, "tiles": int(tiles), "rounds": round(tiles / slots, 2), "us": round(ms * 1e3, 1),
+                              "tflops": round(2.0 * M * N * K / (ms * 1e-3) / 1e12, 1)})
+        out["gemm_per_launch"] = table
     for n in ("merge_plan", "prompt_prepend"):
         if k[n][1] > 0:
             out[n] = {"avg_launch_us": round(k[n][0] * 1e3 / k[n][1], 2), "launches_per_step": k[n][1]}
@@ -333,14 +353,13 @@ def main():
     for st in strategies:
         st.time_single_forwards(21)
     all_res = [st.time_launches(max(3, min(10, args.steps)) if i == 0 else 3) for i, st in enumerate(strategies)]
-    for st in strategies:
-        st.ctx.close()
     head = all_res[0]
     per_strategy = {}
     for r in all_res:
         P, R = r["cfg"].strategies[0]
         mixed = len(set(r["cfg"].strategies)) > 1
         rf = rooflines(r)
+        rf.pop("gemm_per_launch", None)
         per_strategy[r["name"]] = {
             "strategy": "mixed" if mixed else ({"prompts": P, "r": R, "per_layer": r["cfg"].deep} if r["cfg"].deep
                                                else {"prompts": P, "r": R}),
@@ -366,6 +385,8 @@ def main():
         "rooflines": rf,
         "per_strategy": per_strategy,
     }
+    for st in strategies:
+        st.ctx.close()
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(args.workload, args.cpu_queries)
     print(json.dumps(out))

@@ -290,6 +290,9 @@ otas_status otas_attention(otas_ctx *ctx, const void *qkv, const int32_t *sizes,
  * OTAS_EUNSUPPORTED if the kernel does not take the shape (k32 kernels need K % 32 == 0 and K >= 64,
  * k64 kernels K % 64 == 0 and K >= 128) or the dtype. */
 #define OTAS_LINEAR_KERNELS 7
+/* The kernel (numbering above, never 0) that otas_linear and the encoder run for this shape; pure host
+ * function, -1 on invalid arguments.  Lets a benchmark report tiles and rounds per launch. */
+int32_t otas_linear_choice(const otas_ctx *ctx, int64_t T, int32_t N, int32_t K, int32_t epilogue);
 otas_status otas_linear_kernel(otas_ctx *ctx, int32_t kernel, const void *x, const void *w,
                                const void *b, const void *res, int64_t T, int32_t N, int32_t K,
                                int32_t epilogue, void *y);

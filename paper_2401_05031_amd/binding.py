@@ -89,6 +89,7 @@ def load_library():
         "otas_layer_norm": (i32, [vp, vp, vp, vp, i64, vp]),
         "otas_linear": (i32, [vp, vp, vp, vp, vp, i64, i32, i32, i32, vp]),
         "otas_attention": (i32, [vp, vp, vp, _I32P, i32, u32, vp]),
+        "otas_linear_choice": (i32, [vp, i64, i32, i32, i32]),
         "otas_linear_kernel": (i32, [vp, i32, vp, vp, vp, vp, i64, i32, i32, i32, vp]),
         "otas_strerror": (C.c_char_p, [i32]),
         "otas_timing_enable": (i32, [vp, i32]),
@@ -120,7 +121,7 @@ def load_library():
 
 EXPORTED = ("otas_create", "otas_destroy", "otas_schedule", "otas_workspace_bytes",
             "otas_merge_workspace_bytes", "otas_prompt_prepend", "otas_prompt_prepend_pool", "otas_token_merge", "otas_token_merge_static",
-            "otas_encoder_forward", "otas_encoder_layers", "otas_encoder_forward_deep", "otas_patch_embed_workspace_bytes", "otas_patch_embed", "otas_task_heads", "otas_layer_norm", "otas_linear", "otas_attention", "otas_linear_kernel", "otas_strerror",
+            "otas_encoder_forward", "otas_encoder_layers", "otas_encoder_forward_deep", "otas_patch_embed_workspace_bytes", "otas_patch_embed", "otas_task_heads", "otas_layer_norm", "otas_linear", "otas_attention", "otas_linear_kernel", "otas_linear_choice", "otas_strerror",
             "otas_timing_enable", "otas_timing_kinds", "otas_timing_kind_name", "otas_timing_read",
             "otas_timing_read_launches", "otas_timing_overhead_ms", "otas_set_lanes", "otas_splitk_factor",
             "otas_sched_create", "otas_sched_destroy", "otas_sched_rate_table", "otas_sched_add_query", "otas_sched_allocate",
@@ -319,6 +320,9 @@ class Context:
     def otas_linear_kernel(self, kernel, x, w, b, res, T, N, K, epilogue, y) -> None:
         _check(self._lib.otas_linear_kernel(self._h, int(kernel), _ptr(x), _ptr(w), _ptr(b), _ptr(res), T, N, K,
                                             epilogue, _ptr(y)), "otas_linear_kernel")
+
+    def otas_linear_choice(self, T, N, K, epilogue) -> int:
+        return int(self._lib.otas_linear_choice(self._h, int(T), int(N), int(K), int(epilogue)))
 
     def otas_attention(self, qkv, sizes, offsets, flags, o) -> None:
         B = len(offsets) - 1

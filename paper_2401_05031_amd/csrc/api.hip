@@ -997,6 +997,11 @@ otas_status otas_linear_kernel(otas_ctx* c, int32_t kernel, const void* x, const
   return hip_ok(e, "launch_linear_kernel") ? OTAS_OK : OTAS_EDEVICE;
 }
 
+int32_t otas_linear_choice(const otas_ctx* c, int64_t T, int32_t N, int32_t K, int32_t epilogue) {
+  if (!c || T < 0 || N <= 0 || K <= 0 || epilogue < 0 || epilogue > 2) return -1;
+  return linear_kernel_choice(c->desc.dtype, T, N, K, epilogue);
+}
+
 otas_status otas_attention(otas_ctx* c, const void* qkv, const int32_t* sizes, const int32_t* offsets, int32_t B,
                            uint32_t flags, void* o) {
   if (!c || !qkv || !offsets || !o || B <= 0) return OTAS_EINVAL;

@@ -833,6 +833,12 @@ hipError_t launch_linear(int dtype, const void* x, const void* w, const void* bi
   return linear_valu<bf16_t>(x, w, bias, res, y, M, N, K, epi, s);
 }
 
+int linear_kernel_choice(int dtype, int64_t M, int N, int K, int epi) {
+  if (dtype == 0) return GK_FMA;
+  if (K % 32 == 0 && K >= 64 && N % 8 == 0) return pick_mfma_kernel(M, N, K, epi);
+  return GK_FMA;
+}
+
 hipError_t launch_linear_kernel(int kernel, int dtype, const void* x, const void* w, const void* bias,
                                 const float* res, void* y, int64_t M, int N, int K, int epi, hipStream_t s) {
   if (kernel == GK_AUTO) return launch_linear(dtype, x, w, bias, res, y, M, N, K, epi, s);

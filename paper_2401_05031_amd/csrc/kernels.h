@@ -63,6 +63,7 @@ enum gemm_kernel_id {
   GK_AUTO = 0, GK_FMA = 1, GK_128_K32 = 2, GK_128_K64 = 3, GK_192X256 = 4, GK_256X256 = 5, GK_320X256 = 6,
   GK_COUNT = 7
 };
+int linear_kernel_choice(int dtype, int64_t M, int N, int K, int epi);   // the id launch_linear runs for this shape
 hipError_t launch_linear_kernel(int kernel, int dtype, const void* x, const void* w, const void* bias,
                                 const float* res, void* y, int64_t M, int N, int K, int epi, hipStream_t s);
 
