@@ -49,10 +49,14 @@ Readings taken where the paper is silent (each is also listed in the design note
 Parity pins (tests/test_oracle_pins.py): gamma = 0 against torch.nn.TransformerEncoderLayer in
 float64; length schedule closed forms; size conservation; size-weighted mean conservation;
 brute-force edge selection on tiny inputs; closed-form tie cases; planted duplicate pairs;
-identity cases; per-layer prompting against the torch layer applied block by block with the rows
-replaced / inserted by hand, closed forms with the residual branches switched off, and the
-replacement of the prompt rows by their own values being a no-op.  The paper prints no worked numeric example for this path, so nothing here is
-pinned to a paper-printed value.
+identity cases; the merge metric (head-averaged keys of the same layer) and the merge's place in the
+block (between the attention residual and the MLP) against an independent statement built from torch's
+own block pieces, explicit loops and brute-force edges, with every misreading shown to differ; a
+hand-worked head mean; a hand-worked edge_deficit case; per-layer prompting against the torch layer
+applied block by block with the rows replaced / inserted by hand, closed forms with the residual
+branches switched off, and the replacement of the prompt rows by their own values being a no-op.
+No function here is without a pin.  The paper prints no worked numeric example for this path, so
+nothing is pinned to a paper-printed value.
 
 Storage modes.  storage="f64" computes everything in float64.  storage="bf16" keeps float64
 arithmetic but rounds at the points where the HIP path of a bf16 model stores a tensor: to bf16
