@@ -381,7 +381,10 @@ def main():
                                f"strategy (P, r) = {'mixed' if len(set(cfg.strategies)) > 1 else cfg.strategies[0]}",
                    "global_batch": cfg.B, "seq_len": cfg.n0, "parallelism": "single GPU"},
         "single_forward_ms_median": round(head["latency_ms"], 4),
-        "roofline": {k: rf["gemm"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},
+        "roofline": dict({k: rf["gemm"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},
+                         traffic_source="rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, stored in "
+                                        "paper_2401_05031_amd/hbm_traffic.json (profiles/hbm_traffic_vitb_r16_pmc.md); "
+                                        "not re-measured by this run"),
         "rooflines": rf,
         "per_strategy": per_strategy,
     }
