@@ -53,4 +53,18 @@ def test_host_side_argument_errors():
     assert lib.otas_encoder_forward(None, None, None, None, 1, 0, None, 0, None, None, None, None, None) == 1
     assert lib.otas_token_merge(None, None, None, 64, None, None, None, 1, None, 0, None, None, None, None, None) == 1
     assert lib.otas_prompt_prepend(None, None, None, None, None, 1, None, None) == 1
+    assert lib.otas_prompt_prepend_pool(None, None, None, None, 0, None, None, 1, None, None) == 1
+    assert lib.otas_token_merge_static(None, None, None, 64, None, None, None, 1, None, None, None, None, None) == 1
+    assert lib.otas_linear_kernel(None, 2, None, None, None, None, 1, 8, 64, 0, None) == 1
+    assert lib.otas_linear_choice(None, 128, 768, 768, 0) == -1
     assert lib.otas_create(None, None, None, None) == 1
+
+
+def test_rate_table_host_function_rejects_bad_input():
+    _ensure_built()
+    import numpy as np
+    with pytest.raises(otas.OtasError):
+        otas.otas_sched_rate_table([0, -5], np.array([[1e-3, -1e-3]]))       # a non-positive latency
+    with pytest.raises(ValueError):
+        otas.otas_sched_rate_table([0, -5], np.array([[1e-3]]))              # wrong table shape
+    assert otas.otas_sched_rate_table([0], np.array([[1e-3]])) == []         # one gamma: it is the overflow row
