@@ -27,6 +27,7 @@ import otas_synth as synth  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+RATED_MHZ = 2400.0             # the clock the data-sheet peaks are quoted at
 BASELINE_METRIC = "images/sec per (prompts, r) strategy, ViT-B/16 batch 64 bf16; merge-kernel HBM GB/s"
 
 
@@ -156,6 +157,28 @@ class Strategy:
         self.latency_ms = float(np.median(t))
         self.latency_runs = runs
 
+    def measure_clock(self, steps):
+        """Shader clock while this workload runs back to back: the library's one-wave probe samples it (every
+        32512 clocks) beside `steps` steps; it is sized to end before they do even if the clock never drops."""
+        import torch
+        torch.cuda.synchronize()
+        n = int(max(64, min(60000, 0.45 * steps * self.ms_step / 0.01355)))
+        self.ctx.otas_clock_probe_start(n)
+        for _ in range(steps):
+            self.step()
+        mhz = np.asarray(self.ctx.otas_clock_probe_read(), dtype=np.float64)
+        torch.cuda.synchronize()
+        mhz = mhz[len(mhz) // 10:]          # the first tenth covers the launch ramp
+        self.clock = {"median": round(float(np.median(mhz)), 0), "p10": round(float(np.percentile(mhz, 10)), 0),
+                      "p90": round(float(np.percentile(mhz, 90)), 0), "samples": int(len(mhz)), "steps": steps}
+
+    def idle_clock(self):
+        import torch
+        torch.cuda.synchronize()
+        self.ctx.otas_clock_probe_start(400)
+        mhz = np.asarray(self.ctx.otas_clock_probe_read(), dtype=np.float64)
+        return round(float(np.median(mhz[40:])), 0)
+
     def time_launches(self, timing_steps):
         """Per-kernel durations: the same steps again with an event pair around every launch."""
         import torch
@@ -180,7 +203,7 @@ class Strategy:
         work = algorithmic_work(cfg, self.lengths0, self.R, otas, ctx)
         assert torch.isfinite(self.x_out.float()).all()
         return {"name": self.name, "cfg": cfg, "ctx": ctx, "ms": self.ms_step, "img_s": cfg.B / (self.ms_step * 1e-3),
-                "latency_ms": self.latency_ms, "latency_runs": self.latency_runs,
+                "latency_ms": self.latency_ms, "latency_runs": self.latency_runs, "clock": self.clock,
                 "kernels": per_step, "launches": per_launch, "work": work, "ev_overhead_us": ev_overhead_us}
 
 
@@ -352,6 +375,10 @@ def main():
                       args.warmup if not big else min(args.warmup, 3))
     for st in strategies:
         st.time_single_forwards(21)
+    idle_mhz = strategies[0].idle_clock()
+    for i, st in enumerate(strategies):
+        big = st.cfg.L * st.cfg.D * st.cfg.B > 12 * 768 * 64 * 2
+        st.measure_clock(4 if big else 20)
     all_res = [st.time_launches(max(3, min(10, args.steps)) if i == 0 else 3) for i, st in enumerate(strategies)]
     head = all_res[0]
     per_strategy = {}
@@ -366,7 +393,7 @@ def main():
             "images_per_s": round(r["img_s"], 1), "ms_per_step": round(r["ms"], 4),
             "single_forward_ms_median": round(r["latency_ms"], 4), "single_forward_runs": r["latency_runs"],
             "single_forward_images_per_s": round(r["cfg"].B / (r["latency_ms"] * 1e-3), 1),
-            "gemm_tflops": rf["gemm"]["achieved"],
+            "gemm_tflops": rf["gemm"]["achieved"], "shader_clock_mhz_median": r["clock"]["median"],
             "merge_apply_gbs": rf.get("merge_apply", {}).get("achieved"),
             "attention_tflops": rf.get("attention", {}).get("achieved"),
         }
@@ -385,6 +412,14 @@ def main():
                          traffic_source="rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, stored in "
                                         "paper_2401_05031_amd/hbm_traffic.json (profiles/hbm_traffic_vitb_r16_pmc.md); "
                                         "not re-measured by this run"),
+        "shader_clock": {"rated_mhz": RATED_MHZ, "idle_mhz": idle_mhz, "under_load_mhz": head["clock"],
+                         "peak_at_measured_clock": round(PEAK_BF16_TFLOPS * head["clock"]["median"] / RATED_MHZ, 1),
+                         "gemm_frac_of_peak_at_measured_clock":
+                             round(rf["gemm"]["achieved"] / (PEAK_BF16_TFLOPS * head["clock"]["median"] / RATED_MHZ), 4),
+                         "note": "the data-sheet peak (roofline.peak) is 256 CUs x 4 matrix cores x 1024 FLOP per clock at "
+                                 "2400 MHz; under sustained matrix work on random operands the chip lowers its clock "
+                                 "(measured here by a one-wave probe beside the timed steps), so the same cycles-per-"
+                                 "tile efficiency yields a smaller fraction of that peak"},
         "rooflines": rf,
         "per_strategy": per_strategy,
     }

@@ -316,6 +316,20 @@ float otas_timing_overhead_ms(const otas_ctx *ctx);
  * to cap launches into the host arrays; returns the number of records held (-1 on error). */
 int32_t otas_timing_read_launches(otas_ctx *ctx, int32_t cap, int32_t *kinds, float *ms);
 
+/* Shader clock under load, for benchmarks (MI355X lowers its clock under sustained matrix work, by an amount that
+ * depends on the operand data; a roofline fraction against the data-sheet peak therefore needs the clock that the
+ * measured kernels actually ran at).  otas_clock_probe_start enqueues, on a stream of the context's own (created at
+ * first use, default priority, with a sample buffer that otas_destroy frees), one wave that `samples` times sleeps
+ * 32512 shader clocks and stores how many periods of the device's constant-rate wall clock that took; it returns
+ * at once, and whatever the caller launches next runs beside the probe.  A sample lasts 13.5 us at 2.4 GHz.
+ * otas_clock_probe_read waits for the probe to end and writes the shader clock of each sample in MHz, in
+ * order, into mhz[0 .. *n), *n = min(samples, cap); *n = 0 if no probe was started since the last read.
+ * samples: 1 .. OTAS_CLOCK_PROBE_MAX_SAMPLES, else OTAS_EINVAL.  One probe at a time per context: a second start
+ * waits for the first to end and discards its samples. */
+#define OTAS_CLOCK_PROBE_MAX_SAMPLES 65536
+otas_status otas_clock_probe_start(otas_ctx *ctx, int32_t samples);
+otas_status otas_clock_probe_read(otas_ctx *ctx, float *mhz /* host [cap] */, int32_t cap, int32_t *n);
+
 const char *otas_strerror(otas_status s);
 
 #ifdef __cplusplus

@@ -17,6 +17,7 @@ OTAS_FLAG_SIZE_BIAS, OTAS_FLAG_TRACE = 1, 2
 OTAS_PROMPT_REPLACE, OTAS_PROMPT_GROW = 1, 2
 OTAS_STATIC_MERGE_MAX_ROWS, OTAS_STATIC_MERGE_MAX_QUERIES = 65536, 1024
 OTAS_LINEAR_KERNELS = 7
+OTAS_CLOCK_PROBE_MAX_SAMPLES = 65536
 _WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
                   "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
 
@@ -99,6 +100,8 @@ def load_library():
         "otas_timing_read_launches": (i32, [vp, i32, _I32P, C.POINTER(C.c_float)]),
         "otas_timing_overhead_ms": (C.c_float, [vp]),
         "otas_set_lanes": (i32, [vp, i32]),
+        "otas_clock_probe_start": (i32, [vp, i32]),
+        "otas_clock_probe_read": (i32, [vp, C.POINTER(C.c_float), i32, _I32P]),
         "otas_splitk_factor": (i32, [vp, C.c_int64, i32, i32]),
         "otas_sched_create": (i32, [C.POINTER(_SchedParams), i32, _I32P, i32, _F64P, _F64P, i32, _F64P, _I32P,
                                     C.POINTER(vp)]),
@@ -124,6 +127,7 @@ EXPORTED = ("otas_create", "otas_destroy", "otas_schedule", "otas_workspace_byte
             "otas_encoder_forward", "otas_encoder_layers", "otas_encoder_forward_deep", "otas_patch_embed_workspace_bytes", "otas_patch_embed", "otas_task_heads", "otas_layer_norm", "otas_linear", "otas_attention", "otas_linear_kernel", "otas_linear_choice", "otas_strerror",
             "otas_timing_enable", "otas_timing_kinds", "otas_timing_kind_name", "otas_timing_read",
             "otas_timing_read_launches", "otas_timing_overhead_ms", "otas_set_lanes", "otas_splitk_factor",
+            "otas_clock_probe_start", "otas_clock_probe_read",
             "otas_sched_create", "otas_sched_destroy", "otas_sched_rate_table", "otas_sched_add_query", "otas_sched_allocate",
             "otas_sched_num_batches", "otas_sched_batch_info", "otas_sched_batch_queries", "otas_sched_estimate",
             "otas_sched_remove")
@@ -348,6 +352,16 @@ class Context:
 
     def otas_set_lanes(self, lanes: int) -> None:
         _check(self._lib.otas_set_lanes(self._h, int(lanes)), "otas_set_lanes")
+
+    def otas_clock_probe_start(self, samples: int) -> None:
+        _check(self._lib.otas_clock_probe_start(self._h, int(samples)), "otas_clock_probe_start")
+
+    def otas_clock_probe_read(self, cap: int = 65536) -> List[float]:
+        """Shader clock in MHz of every sample of the probe started last, in order (waits for the probe)."""
+        mhz = (C.c_float * cap)()
+        n = C.c_int32(0)
+        _check(self._lib.otas_clock_probe_read(self._h, mhz, cap, C.byref(n)), "otas_clock_probe_read")
+        return [float(mhz[i]) for i in range(n.value)]
 
     def otas_timing_overhead_ms(self) -> float:
         return float(self._lib.otas_timing_overhead_ms(self._h))

@@ -97,6 +97,10 @@ struct otas_ctx {
   float ev_overhead_ms;   // what an event pair reads around an empty launch (subtracted from every record)
   std::vector<hipEvent_t> ev_pool;
   std::vector<int> ev_kind;   // kind of the launch bracketed by ev_pool[2i], ev_pool[2i+1]
+  // optional shader-clock probe (otas_clock_probe_start): its own stream and sample buffer, made at first use
+  hipStream_t probe_stream;
+  uint32_t* d_probe;      // [kProbeMaxSamples]
+  int32_t probe_samples;  // samples of the probe in flight or finished and unread, 0 = none
 };
 
 namespace {
@@ -288,6 +292,9 @@ otas_status otas_create(otas_ctx** out, const otas_model_desc* desc, const otas_
   c->ev_begin = nullptr;
   c->lanes = 0;
   c->lanes_ready = 0;
+  c->probe_stream = nullptr;
+  c->d_probe = nullptr;
+  c->probe_samples = 0;
   bool ok = hipGetDevice(&c->device) == hipSuccess;
   ok = ok && scratch_address(c->device, &c->d_scratch) == OTAS_OK;   // the current device is c->device
   ok = ok && hipMalloc((void**)&c->d_plan, kPlanInts * sizeof(int32_t)) == hipSuccess;
@@ -320,6 +327,8 @@ otas_status otas_destroy(otas_ctx* c) {
     if (c->h_done[i]) (void)hipEventDestroy(c->h_done[i]);
   if (c->h_plan) (void)hipHostFree(c->h_plan);
   for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+  if (c->probe_stream) { (void)hipStreamSynchronize(c->probe_stream); (void)hipStreamDestroy(c->probe_stream); }
+  if (c->d_probe) (void)hipFree(c->d_probe);
   if (c->d_plan) (void)hipFree(c->d_plan);
   delete c;
   return OTAS_OK;
@@ -1075,6 +1084,35 @@ int32_t otas_splitk_factor(const otas_ctx* c, int64_t M, int32_t N, int32_t K) {
 }
 
 float otas_timing_overhead_ms(const otas_ctx* c) { return c ? c->ev_overhead_ms : 0.f; }
+
+otas_status otas_clock_probe_start(otas_ctx* c, int32_t samples) {
+  if (!c || samples <= 0 || samples > OTAS_CLOCK_PROBE_MAX_SAMPLES) return OTAS_EINVAL;
+  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
+  if (!c->probe_stream) OTAS_HIP(hipStreamCreateWithFlags(&c->probe_stream, hipStreamNonBlocking));
+  if (!c->d_probe) OTAS_HIP(hipMalloc((void**)&c->d_probe, (size_t)OTAS_CLOCK_PROBE_MAX_SAMPLES * sizeof(uint32_t)));
+  OTAS_HIP(hipStreamSynchronize(c->probe_stream));   // an earlier probe has finished with the buffer
+  OTAS_HIP(launch_clock_probe(c->d_probe, samples, c->probe_stream));
+  c->probe_samples = samples;
+  return OTAS_OK;
+}
+
+otas_status otas_clock_probe_read(otas_ctx* c, float* mhz, int32_t cap, int32_t* n) {
+  if (!c || !mhz || !n || cap < 0) return OTAS_EINVAL;
+  *n = 0;
+  if (!c->probe_samples) return OTAS_OK;
+  if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
+  OTAS_HIP(hipStreamSynchronize(c->probe_stream));
+  const int32_t m = c->probe_samples < cap ? c->probe_samples : cap;
+  std::vector<uint32_t> ticks((size_t)m);
+  if (m) OTAS_HIP(hipMemcpy(ticks.data(), c->d_probe, (size_t)m * sizeof(uint32_t), hipMemcpyDeviceToHost));
+  int khz = 0;
+  if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device) != hipSuccess || khz <= 0) khz = 100000;
+  for (int32_t i = 0; i < m; ++i)
+    mhz[i] = ticks[i] ? (float)((double)kClockProbeClocks * (double)khz / 1000.0 / (double)ticks[i]) : 0.f;
+  *n = m;
+  c->probe_samples = 0;
+  return OTAS_OK;
+}
 
 int32_t otas_timing_kinds(void) { return K_COUNT; }
 

@@ -28,6 +28,22 @@ hipError_t launch_spin(int64_t ticks, int32_t* sink, hipStream_t s) {
   spin_kernel<<<dim3(1), dim3(64), 0, s>>>(ticks, sink);
   return hipGetLastError();
 }
+// One wave that `samples` times sleeps 4 x 8128 shader clocks (s_sleep 127 = 127 x 64 clocks; a sleeping wave
+// needs no issue slots, so the waves it shares a SIMD with do not stretch it) and stores how many periods of the
+// constant-rate wall clock that took: 4 * 8128 / ticks[s] = shader clocks per wall-clock period while whatever else
+// is in flight on the chip runs.  Ends by itself after `samples` samples.
+__global__ void clock_probe_kernel(uint32_t* ticks, int32_t samples) {
+  for (int32_t s = 0; s < samples; ++s) {
+    const uint64_t t0 = wall_clock64();
+    asm volatile("s_sleep 127\n s_sleep 127\n s_sleep 127\n s_sleep 127");
+    const uint64_t t1 = wall_clock64();
+    if (threadIdx.x == 0) ticks[s] = (uint32_t)(t1 - t0);
+  }
+}
+hipError_t launch_clock_probe(uint32_t* ticks, int32_t samples, hipStream_t s) {
+  clock_probe_kernel<<<dim3(1), dim3(64), 0, s>>>(ticks, samples);
+  return hipGetLastError();
+}
 hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   fill_i32_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(p, v, n);

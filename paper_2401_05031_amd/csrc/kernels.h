@@ -13,6 +13,9 @@ hipError_t set_max_dynamic_lds(const void* kernel, int bytes);
 
 // One wave busy for `ticks` wall-clock periods (hipDeviceAttributeWallClockRate); sink: one int.
 hipError_t launch_spin(int64_t ticks, int32_t* sink, hipStream_t s);
+// One wave sampling the shader clock against the wall clock; ticks: device [samples]; shader clocks per sample: kClockProbeClocks.
+constexpr int kClockProbeClocks = 4 * 127 * 64;
+hipError_t launch_clock_probe(uint32_t* ticks, int32_t samples, hipStream_t s);
 hipError_t launch_fill_i32(int32_t* p, int32_t v, int64_t n, hipStream_t s);
 hipError_t launch_copy_i32(const int32_t* src, int32_t* dst, int64_t n, hipStream_t s);
 

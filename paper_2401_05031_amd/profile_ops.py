@@ -5,6 +5,8 @@ measured with HIP events.
 
     attention --n N [--batch 64] [--D 768] [--H 12] [--size-bias]
     linear    --M M --N N --K K [--epilogue 0|1|2] [--kernel ID]      (ID as in otas_linear_kernel, 0 = the library's choice)
+    clock     --M M --N N --K K [--kernel ID] [--zero-data]           (the linear product back to back with the library's
+                                                                       shader-clock probe running beside it)
 """
 from __future__ import annotations
 
@@ -17,7 +19,7 @@ def main(argv=None) -> None:
     import torch
     from . import OTAS_BF16, OTAS_FLAG_SIZE_BIAS, Context
     ap = argparse.ArgumentParser()
-    ap.add_argument("op", choices=["attention", "linear"])
+    ap.add_argument("op", choices=["attention", "linear", "clock"])
     ap.add_argument("--n", type=int, default=197)
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--D", type=int, default=768)
@@ -29,6 +31,7 @@ def main(argv=None) -> None:
     ap.add_argument("--epilogue", type=int, default=0)
     ap.add_argument("--kernel", type=int, default=0)
     ap.add_argument("--iters", type=int, default=3)
+    ap.add_argument("--zero-data", action="store_true", help="all-zero operands (clock: the matrix cores then toggle no bits)")
     a = ap.parse_args(argv)
     dev, bf = "cuda", torch.bfloat16
     g = torch.Generator(device="cpu").manual_seed(0)
@@ -48,6 +51,8 @@ def main(argv=None) -> None:
     else:
         x = torch.randn((a.M, a.K), generator=g).to(dev).to(bf)
         w = (0.03 * torch.randn((a.N, a.K), generator=g)).to(dev).to(bf)
+        if a.zero_data:
+            x.zero_(), w.zero_()
         b = torch.zeros(a.N, dtype=bf, device=dev)
         res = torch.zeros((a.M, a.N), dtype=torch.float32, device=dev) if a.epilogue == 2 else None
         y = torch.empty((a.M, a.N), dtype=torch.float32 if a.epilogue == 2 else bf, device=dev)
@@ -56,12 +61,29 @@ def main(argv=None) -> None:
     run()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if a.op == "clock":
+        ctx.otas_clock_probe_start(400)
+        idle = float(np.median(ctx.otas_clock_probe_read()[40:]))
+        e0.record()
+        for _ in range(a.iters):
+            run()
+        e1.record()
+        e1.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / a.iters
+        ctx.otas_clock_probe_start(int(max(64, min(60000, 0.45 * a.iters * us / 13.55))))
     e0.record()
     for _ in range(a.iters):
         run()
     e1.record()
     e1.synchronize()
-    print(f"{what}: {e0.elapsed_time(e1) * 1e3 / a.iters:.1f} us per launch over {a.iters} launches")
+    us = e0.elapsed_time(e1) * 1e3 / a.iters
+    print(f"{what}{' zero data' if a.zero_data else ''}: {us:.1f} us per launch over {a.iters} launches"
+          + (f", {2.0 * a.M * a.N * a.K / us / 1e6:.1f} TFLOP/s" if a.op != "attention" else ""))
+    if a.op == "clock":
+        mhz = np.asarray(ctx.otas_clock_probe_read())
+        mhz = mhz[len(mhz) // 10:]
+        print(f"shader clock: idle {idle:.0f} MHz; beside the launches median {np.median(mhz):.0f} MHz, "
+              f"10th / 90th percentile {np.percentile(mhz, 10):.0f} / {np.percentile(mhz, 90):.0f} MHz over {len(mhz)} samples")
     ctx.close()
 
 

@@ -57,6 +57,8 @@ def test_host_side_argument_errors():
     assert lib.otas_token_merge_static(None, None, None, 64, None, None, None, 1, None, None, None, None, None) == 1
     assert lib.otas_linear_kernel(None, 2, None, None, None, None, 1, 8, 64, 0, None) == 1
     assert lib.otas_linear_choice(None, 128, 768, 768, 0) == -1
+    assert lib.otas_clock_probe_start(None, 16) == 1
+    assert lib.otas_clock_probe_read(None, None, 0, None) == 1
     assert lib.otas_create(None, None, None, None) == 1
 
 

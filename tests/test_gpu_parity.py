@@ -1002,6 +1002,27 @@ def test_many_short_queries_plan_larger_than_a_staging_slot(torch_cuda, lib):
     ctx.close()
 
 
+def test_clock_probe_samples_a_plausible_shader_clock(torch_cuda, lib):
+    """The benchmark's shader-clock probe: every sample of a run on an idle GPU reads a clock between 0.3 and
+    3 GHz, the samples agree with each other, a second probe reuses the buffer, a read without a probe is empty
+    and bad sample counts are refused."""
+    import paper_2401_05031_amd as otas
+    cfg = synth.config("tiny")
+    ctx, _ = hz.make_context(cfg)
+    for n in (64, 200):
+        ctx.otas_clock_probe_start(n)
+        mhz = np.asarray(ctx.otas_clock_probe_read())
+        assert mhz.shape == (n,)
+        assert (mhz > 300).all() and (mhz < 3000).all(), (mhz.min(), mhz.max())
+        body = mhz[n // 4:]
+        assert body.max() - body.min() <= 0.2 * np.median(body)
+    assert ctx.otas_clock_probe_read() == []
+    for bad in (0, -1, otas.OTAS_CLOCK_PROBE_MAX_SAMPLES + 1):
+        with pytest.raises(otas.OtasError):
+            ctx.otas_clock_probe_start(bad)
+    ctx.close()
+
+
 def test_bench_prints_one_json_line_with_the_contract_keys(torch_cuda, lib):
     """bench.py as the driver runs it (a child process, few steps, a two-query oracle sample): exactly one
     JSON line on stdout with the agreed keys, a roofline object for the dominant kernel and the oracle baseline;
@@ -1028,6 +1049,9 @@ def test_bench_prints_one_json_line_with_the_contract_keys(torch_cuda, lib):
     assert rf["bound"] == "mfma" and rf["unit"] == "TFLOP/s" and rf["peak"] == 2500.0
     assert rf["frac"] == pytest.approx(rf["achieved"] / rf["peak"], abs=1e-3) and 0.0 < rf["frac"] < 1.0
     assert rf["traffic"] is None or rf["traffic"] > 0
+    sc = b["shader_clock"]
+    assert 300 < sc["under_load_mhz"]["median"] <= sc["idle_mhz"] * 1.05 and sc["rated_mhz"] == 2400.0
+    assert sc["peak_at_measured_clock"] == pytest.approx(2500.0 * sc["under_load_mhz"]["median"] / 2400.0, rel=1e-3)
     cb = b["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["unit"] == "images/s" and cb["value"] > 0 and cb["cores"] >= 1 and cb["sample"]
     r2 = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
