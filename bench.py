@@ -230,6 +230,11 @@ def rooflines(res):
                    "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": traffic.get("gemm"),
                    "launches_per_step": gemm_launches, "avg_launch_us": round(gemm_ms * 1e3 / max(gemm_launches, 1), 2),
                    "flops_per_launch": gemm_flops / max(gemm_launches, 1)}
+    # the same with nothing subtracted from the event readings (each launch then also carries what its event pair adds)
+    raw_ms = gemm_ms + gemm_launches * res["ev_overhead_us"] * 1e-3
+    if raw_ms > 0:
+        out["gemm"]["achieved_without_overhead_subtraction"] = round(gemm_flops / (raw_ms * 1e-3) / 1e12, 2)
+        out["gemm"]["frac_without_overhead_subtraction"] = round(gemm_flops / (raw_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)
     for n in ("gemm_qkv", "gemm_proj", "gemm_fc1", "gemm_fc2"):
         if k[n][0] > 0:
             a = w[n] / (k[n][0] * 1e-3) / 1e12
