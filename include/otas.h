@@ -55,10 +55,11 @@ enum {
 
 /* Limits of this build: D % H == 0, head width d_h in {64, 80, 96, 128} for bf16 and any
  * multiple of 4 up to 128 for f32, D % 8 == 0, F % 8 == 0, sequence length per query <= 1024,
- * n_lead in {0, 1}.  A query that merges tokens in a layer (r_eff > 0) must also fit the plan
- * kernel, which keeps the unit metric vector of every token of the query in LDS:
- * 4 (n (d_m + 8) + 1064) <= 163840 bytes, i.e. n <= 554 at metric width d_m = 64, n <= 453 at 80,
- * n <= 293 at 128; longer merging queries are refused with OTAS_EUNSUPPORTED before any launch. */
+ * n_lead in {0, 1}.  The plan kernel keeps the unit metric vector of every token of a query in LDS
+ * while 4 (n (d_m + 8) + 1064) <= 163840 bytes (n <= 554 at metric width d_m = 64, 453 at 80, 293 at
+ * 128); longer merging queries keep them in the workspace (same arithmetic and order, slower).  Only
+ * otas_token_merge_static, which has no workspace, refuses such a batch with OTAS_EUNSUPPORTED; the
+ * encoder needs F * sizeof(element) >= 4 (d_h + 8) for them (it borrows the MLP's hidden buffer). */
 #define OTAS_MAX_SEQ 1024
 
 typedef struct {
@@ -122,7 +123,8 @@ otas_status otas_set_lanes(otas_ctx *ctx, int32_t lanes);
 /* Bytes of device workspace otas_encoder_forward needs for B queries with T0 packed tokens in
  * total (pure host).  Returns 0 on invalid arguments. */
 size_t otas_workspace_bytes(const otas_ctx *ctx, int32_t B, int64_t T0);
-/* Same for otas_token_merge (plan arrays only). */
+/* Same for otas_token_merge: the plan arrays, plus 528 bytes per token once T > 293 (room for the unit metric
+ * rows of queries too long for the plan kernel's LDS, at the widest metric). */
 size_t otas_merge_workspace_bytes(int32_t B, int64_t T);
 
 /* Prompting module (Sec. II-B, Sec. III-B): for every query, put its P_q prompt rows in front of

@@ -38,6 +38,12 @@ constexpr int kMaxDevices = 64;
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int removal_count(int n, int r, int n_lead) { return std::max(0, std::min(r, (n - n_lead) / 2)); }
+// Workspace of otas_token_merge for the plan kernel's metric rows: none while no query of T tokens can
+// overflow the kernel's LDS at any metric width.
+inline size_t merge_rows_bytes(int64_t T) {
+  return merge_plan_lds_bytes((int)std::min<int64_t>(T, OTAS_MAX_SEQ), 128) <= 160 * 1024
+             ? 0 : align_up(merge_plan_rows_bytes(T, 128), kAlign);
+}
 
 }  // namespace
 
@@ -341,8 +347,9 @@ size_t otas_workspace_bytes(const otas_ctx* c, int32_t B, int64_t T0) {
 
 size_t otas_merge_workspace_bytes(int32_t B, int64_t T) {
   if (B <= 0 || T <= 0) return 0;
-  // src_list [T], row_ptr [T+1]
-  return align_up((size_t)T * 4, kAlign) + align_up((size_t)(T + 1) * 4, kAlign);
+  // src_list [T], row_ptr [T+1], and -- once a query can be too long for the plan kernel's LDS -- the
+  // unit metric rows of all tokens at the widest metric (128)
+  return align_up((size_t)T * 4, kAlign) + align_up((size_t)(T + 1) * 4, kAlign) + merge_rows_bytes(T);
 }
 
 }  // extern "C"
@@ -409,7 +416,7 @@ namespace {
 // (creating events allocates, so the static entry point never does).
 otas_status token_merge_impl(otas_ctx* c, const void* x, const void* metric, int32_t dm, const int32_t* sizes,
                              const int32_t* offsets, const int32_t* r, int32_t B, int32_t* plan, int32_t* src_list,
-                             int32_t* row_ptr, void* x_out, int32_t* sizes_out, int32_t* offsets_out,
+                             int32_t* row_ptr, float* rows, void* x_out, int32_t* sizes_out, int32_t* offsets_out,
                              int32_t* trace_src, int32_t* trace_dst, bool timed) {
   const int64_t T = offsets[B];
   const int n_lead = c->desc.n_lead;
@@ -432,7 +439,7 @@ otas_status token_merge_impl(otas_ctx* c, const void* x, const void* metric, int
     max_n = std::max(max_n, n);
   }
   in_off[B] = offsets[B];
-  if (merge_plan_lds_bytes(max_n, dm) > 160 * 1024) return OTAS_EUNSUPPORTED;
+  if (merge_plan_lds_bytes(max_n, dm) > 160 * 1024 && !rows) return OTAS_EUNSUPPORTED;   // no room for the metric rows
   std::memcpy(offsets_out, out_off, (B + 1) * sizeof(int32_t));
   const int64_t T_out = out_off[B];
   if (hipSetDevice(c->device) != hipSuccess) return OTAS_EDEVICE;
@@ -444,7 +451,7 @@ otas_status token_merge_impl(otas_ctx* c, const void* x, const void* metric, int
   st = [&]() -> otas_status {
     OTAS_LAUNCH(K_PLAN, launch_merge_plan(c->desc.dtype, metric, dm, 0, 1, dm, dp, dp + (B + 1), dp + 2 * (B + 1),
                                           dp + 2 * (B + 1) + B, B, max_n, n_lead, src_list, row_ptr, trace_src,
-                                          trace_dst, c->stream));
+                                          trace_dst, rows, c->stream));
     OTAS_LAUNCH(K_APPLY, launch_merge_apply(c->desc.dtype, x, sizes, src_list, row_ptr, T, T_out, c->desc.D, x_out,
                                             sizes_out, c->stream));
     return OTAS_OK;
@@ -481,8 +488,9 @@ otas_status otas_token_merge(otas_ctx* c, const void* x, const void* metric, int
   std::vector<int32_t> plan(4 * (size_t)B + 2);
   int32_t* src_list = (int32_t*)workspace;
   int32_t* row_ptr = (int32_t*)((char*)workspace + align_up((size_t)T * 4, kAlign));
-  return token_merge_impl(c, x, metric, dm, sizes, offsets, r, B, plan.data(), src_list, row_ptr, x_out, sizes_out,
-                          offsets_out, trace_src, trace_dst, true);
+  float* rows = merge_rows_bytes(T) ? (float*)((char*)row_ptr + align_up((size_t)(T + 1) * 4, kAlign)) : nullptr;
+  return token_merge_impl(c, x, metric, dm, sizes, offsets, r, B, plan.data(), src_list, row_ptr, rows, x_out,
+                          sizes_out, offsets_out, trace_src, trace_dst, true);
 }
 
 otas_status otas_token_merge_static(otas_ctx* c, const void* x, const void* metric, int32_t dm,
@@ -497,8 +505,10 @@ otas_status otas_token_merge_static(otas_ctx* c, const void* x, const void* metr
   int32_t plan[4 * kStaticMergeQueries + 2];   // on the stack: no host allocation either
   // Nothing in the lists has to start at zero: the plan kernel writes every entry of src_list [0, T)
   // and row_ptr [0, T_out) that the apply kernel reads, whatever an earlier call left there.
+  // (no room for metric rows here: a query too long for the plan kernel's LDS is refused, EUNSUPPORTED)
   return token_merge_impl(c, x, metric, dm, sizes, offsets, r, B, plan, c->d_scratch,
-                          c->d_scratch + kStaticRowPtrAt, x_out, sizes_out, offsets_out, trace_src, trace_dst, false);
+                          c->d_scratch + kStaticRowPtrAt, nullptr, x_out, sizes_out, offsets_out, trace_src,
+                          trace_dst, false);
 }
 
 namespace {
@@ -595,7 +605,11 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
       mx = std::max(mx, n);
       len[(size_t)(l + 1) * B + q] = n - k;
     }
-    if (any && merge_plan_lds_bytes(mx, dh) > 160 * 1024) return OTAS_EUNSUPPORTED;
+    // a query too long for the plan kernel's LDS keeps its metric rows in the (then unused) MLP hidden buffer,
+    // F elements per token: that has to hold a metric row
+    if (any && merge_plan_lds_bytes(mx, dh) > 160 * 1024 &&
+        (size_t)d.F * elem_size(d.dtype) * 64 < merge_plan_rows_bytes(64, dh))
+      return OTAS_EUNSUPPORTED;
   }
   offsets_out[0] = 0;
   for (int q = 0; q < B; ++q) offsets_out[q + 1] = offsets_out[q] + len[(size_t)L * B + q];
@@ -742,7 +756,7 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
         OTAS_LAUNCH_ON(K_PLAN, ps,
                        launch_merge_plan(dt, qkv, 3 * (int64_t)D, D, H, dh, off_l, off_n, d_reff, d_tr, Bg,
                                          ln.max_n[l], n_lead, src_list, row_ptr, trace ? trace_src : nullptr,
-                                         trace ? trace_dst : nullptr, ps));
+                                         trace ? trace_dst : nullptr, (float*)hid, ps));
         if (!plan_inline) OTAS_HIP(hipEventRecord(hw.ev_join, hw.side));
       }
       OTAS_LAUNCH_ON(K_ATTN, s,

@@ -86,12 +86,16 @@ hipError_t launch_attention(int dtype, const void* qkv, const int32_t* sizes,
                             void* o, hipStream_t s);
 
 // The metric of token i is the mean over H heads of src[i * row_stride + col_off + h * dm + c]
-// (dtype = type of src), normalised to unit length inside the kernel.
+// (dtype = type of src), normalised to unit length inside the kernel.  The kernel keeps a query's unit
+// metric rows in LDS when merge_plan_lds_bytes(max_n, dm) <= 160 KB; otherwise in `rows`, a device
+// buffer of merge_plan_rows_bytes(T, dm) bytes for the T packed tokens (16-byte aligned; may be NULL
+// when every query fits LDS, else the launch fails with hipErrorInvalidValue).
 hipError_t launch_merge_plan(int dtype, const void* src, int64_t row_stride, int col_off, int H, int dm,
                              const int32_t* d_in_off, const int32_t* d_out_off, const int32_t* d_reff,
                              const int32_t* d_troff, int B, int max_n, int n_lead, int32_t* src_list,
-                             int32_t* row_ptr, int32_t* trace_src, int32_t* trace_dst, hipStream_t s);
+                             int32_t* row_ptr, int32_t* trace_src, int32_t* trace_dst, float* rows, hipStream_t s);
 size_t merge_plan_lds_bytes(int max_n, int dm);
+size_t merge_plan_rows_bytes(int64_t T, int dm);
 
 // dtype: type of x and x_out (0 = float, 1 = bf16).
 hipError_t launch_merge_apply(int dtype, const void* x, const int32_t* sizes,

@@ -25,21 +25,29 @@ template <typename T> struct alignas(4 * sizeof(T)) Quad { T x[4]; };   // 4 con
 // Floats per metric row in LDS: the even and the odd columns each padded to a multiple of 4, plus 4.
 static inline int plan_row_floats(int dm) { return 2 * (((dm >> 1) + 3) & ~3) + 4; }
 
-size_t merge_plan_lds_bytes(int max_n, int dm) {
+// Everything but the metric rows.
+static inline size_t plan_small_lds_bytes(int max_n) {
   const size_t nA = (max_n + 1) / 2, nB = max_n / 2;
-  return sizeof(float) * ((size_t)max_n * plan_row_floats(dm) + 3 * nA + nB + 2 * (size_t)max_n + 32 + 8 + 2 * 512);
+  return sizeof(float) * (3 * nA + nB + 2 * (size_t)max_n + 32 + 8 + 2 * 512);
 }
+size_t merge_plan_lds_bytes(int max_n, int dm) {
+  return sizeof(float) * (size_t)max_n * plan_row_floats(dm) + plan_small_lds_bytes(max_n);
+}
+size_t merge_plan_rows_bytes(int64_t T, int dm) { return sizeof(float) * (size_t)T * plan_row_floats(dm); }
 
 // One workgroup of 1024 threads per query.  src: the vectors the similarity is taken on; the metric
 // of token i is the mean over H heads of src[(i0 + i) * row_stride + col_off + h * dm + c] (H = 1 for
 // a caller-supplied metric, H heads of the attention keys inside the encoder), normalised to unit
 // length with fp32 arithmetic.
-template <typename T>
+// ROWS_IN_LDS = false: the metric rows of the query live in global memory (rows + i0 * ldm: the
+// query's own rows of a [T][ldm] float buffer; written and read by this workgroup only, between its
+// barriers) instead of LDS, for queries whose rows do not fit the 160 KB; same arithmetic, same order.
+template <typename T, bool ROWS_IN_LDS>
 __global__ __launch_bounds__(kPlanThreads) void merge_plan_kernel(
     const T* __restrict__ src, int64_t row_stride, int col_off, int H, int dm, const int32_t* __restrict__ in_off,
     const int32_t* __restrict__ out_off, const int32_t* __restrict__ reff_arr, const int32_t* __restrict__ troff,
     int n_lead, int32_t* __restrict__ src_list, int32_t* __restrict__ row_ptr, int32_t* __restrict__ trace_src,
-    int32_t* __restrict__ trace_dst) {
+    int32_t* __restrict__ trace_dst, float* rows) {
   extern __shared__ float lds[];
   const int q = blockIdx.x, tid = threadIdx.x;
   const int i0 = in_off[q], n = in_off[q + 1] - i0, o0 = out_off[q];
@@ -61,8 +69,15 @@ __global__ __launch_bounds__(kPlanThreads) void merge_plan_kernel(
   // column c sits at (c & 1) * hp + c / 2, so
   // the two halves of a wave (which feed the even and the odd k of every fp32 MFMA) each read
   // consecutive floats.
-  float* mh = lds;
-  float* best = mh + (size_t)n * ldm;
+  float* mh;
+  float* best;
+  if constexpr (ROWS_IN_LDS) {
+    mh = lds;
+    best = mh + (size_t)n * ldm;
+  } else {
+    mh = rows + (size_t)i0 * ldm;
+    best = lds;
+  }
   int* bcol = (int*)(best + nA);
   int* merged = bcol + nA;
   int* cnt = merged + nA;
@@ -268,22 +283,27 @@ __global__ __launch_bounds__(kPlanThreads) void merge_plan_kernel(
 hipError_t launch_merge_plan(int dtype, const void* src, int64_t row_stride, int col_off, int H, int dm,
                              const int32_t* d_in_off, const int32_t* d_out_off, const int32_t* d_reff,
                              const int32_t* d_troff, int B, int max_n, int n_lead, int32_t* src_list,
-                             int32_t* row_ptr, int32_t* trace_src, int32_t* trace_dst, hipStream_t s) {
+                             int32_t* row_ptr, int32_t* trace_src, int32_t* trace_dst, float* rows, hipStream_t s) {
   if (B <= 0 || max_n <= 0) return hipSuccess;
   if (dm % 4 != 0 || dm > 128 || max_n > kPlanThreads) return hipErrorInvalidValue;
-  const size_t lds = merge_plan_lds_bytes(max_n, dm);
-  if (lds > 160 * 1024) return hipErrorInvalidValue;
-  hipError_t e = set_max_dynamic_lds(dtype == 0 ? (const void*)merge_plan_kernel<float>
-                                                : (const void*)merge_plan_kernel<bf16_t>, 160 * 1024);
-  if (e != hipSuccess) return e;
-  if (dtype == 0)
-    merge_plan_kernel<float><<<dim3(B), dim3(kPlanThreads), lds, s>>>(
-        (const float*)src, row_stride, col_off, H, dm, d_in_off, d_out_off, d_reff, d_troff, n_lead, src_list, row_ptr,
-        trace_src, trace_dst);
-  else
-    merge_plan_kernel<bf16_t><<<dim3(B), dim3(kPlanThreads), lds, s>>>(
-        (const bf16_t*)src, row_stride, col_off, H, dm, d_in_off, d_out_off, d_reff, d_troff, n_lead, src_list,
-        row_ptr, trace_src, trace_dst);
+  const bool in_lds = merge_plan_lds_bytes(max_n, dm) <= 160 * 1024;
+  if (!in_lds && !rows) return hipErrorInvalidValue;
+  const size_t lds = in_lds ? merge_plan_lds_bytes(max_n, dm) : plan_small_lds_bytes(max_n);
+#define OTAS_PLAN(TYPE, IN_LDS)                                                                                  \
+  do {                                                                                                           \
+    auto kern = merge_plan_kernel<TYPE, IN_LDS>;                                                                 \
+    hipError_t e = set_max_dynamic_lds((const void*)kern, 160 * 1024);                                           \
+    if (e != hipSuccess) return e;                                                                               \
+    kern<<<dim3(B), dim3(kPlanThreads), lds, s>>>((const TYPE*)src, row_stride, col_off, H, dm, d_in_off,        \
+                                                  d_out_off, d_reff, d_troff, n_lead, src_list, row_ptr,         \
+                                                  trace_src, trace_dst, rows);                                   \
+  } while (0)
+  if (dtype == 0) {
+    if (in_lds) OTAS_PLAN(float, true); else OTAS_PLAN(float, false);
+  } else {
+    if (in_lds) OTAS_PLAN(bf16_t, true); else OTAS_PLAN(bf16_t, false);
+  }
+#undef OTAS_PLAN
   return hipGetLastError();
 }
 

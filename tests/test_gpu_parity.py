@@ -212,6 +212,21 @@ def test_token_merge_ragged_and_edge_cases(torch_cuda, lib, dtype):
     ctx.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_token_merge_queries_longer_than_the_plan_kernels_lds(torch_cuda, lib, dtype):
+    """Queries whose unit metric rows do not fit the plan kernel's 160 KB of LDS (more than 554 tokens at metric
+    width 64, 293 at 128) keep them in the workspace instead: same decisions (bit-exact against the oracle), up to
+    OTAS_MAX_SEQ = 1024 tokens, mixed with short queries in one call."""
+    torch = torch_cuda
+    cfg = synth.config("tiny")
+    cfg.dtype = dtype
+    ctx, _ = hz.make_context(cfg)
+    _merge_case(torch, ctx, cfg, [555, 40, 1024, 577, 3], [16, 8, 600, 100, 1], 64, seed=11)
+    _merge_case(torch, ctx, cfg, [294, 1000, 9], [50, 24, 2], 128, seed=12, sizes_hi=4)
+    _merge_case(torch, ctx, cfg, [700], [350], 80, seed=13)
+    ctx.close()
+
+
 @pytest.mark.parametrize("dtype,tol", [("f32", 2e-6), ("bf16", 1e-2)])
 def test_layer_norm_linear_attention_steps(torch_cuda, lib, dtype, tol):
     torch = torch_cuda
@@ -644,32 +659,28 @@ def test_linear_every_named_kernel_whole_output(torch_cuda, lib, kernel):
 
 
 def test_longest_sequences_f32(torch_cuda, lib):
-    """The longest query that can merge (554 tokens at d_h = 64: the plan kernel keeps every unit
-    metric vector of a query in LDS) next to a short one, fp32, r larger than half the tokens:
-    decisions checked against the oracle in lock-step (bit-exact unless the oracle itself sees an
-    exact tie).  One token more is refused; without merging 1024 tokens (OTAS_MAX_SEQ) run."""
+    """Long merging queries next to a short one, fp32, r larger than half the tokens: 554 tokens (the longest
+    whose unit metric vectors fit the plan kernel's LDS at d_h = 64), 577 (a 384-pixel image at patch 16: the
+    metric rows then live in the workspace) and 1024 (OTAS_MAX_SEQ).  Decisions checked against the oracle in
+    lock-step (bit-exact unless the oracle itself sees an exact tie); 1025 tokens are refused."""
     torch = torch_cuda
     cfg = synth.config("tiny")
     cfg.n0 = 1020
     cfg.strategies = [(4, 600), (0, 3)]
     ctx, layers = hz.make_context(cfg)
     long_tok = synth.query_tokens(cfg, 0)
-    toks = [long_tok[:550], synth.query_tokens(cfg, 1)[:9]]
     prm = [synth.query_prompts(cfg, 0), synth.query_prompts(cfg, 1)]
     R = [600, 3]
-    x0, off = hz.gpu_prepend(ctx, toks, prm)
-    assert off.tolist() == [0, 554, 563]
-    gpu = hz.gpu_forward(ctx, x0, off, R)
-    rep = hz.compare_lockstep(cfg, layers, toks, prm, R, gpu)
-    print("n = 554:", rep)
-    assert rep["sizes_equal"] and rep["max_err"] <= F32_TOL
-    assert rep["disagreements"] == 0 or rep["max_deficit"] <= 1e-6
-    assert gpu["offsets"].tolist() == [0, 140, 144]   # 554 -> 278 -> 140 ; 9 -> 6 -> 4 (r clamps to 2)
-    # 556 merging tokens do not fit the plan kernel
-    x1, off1 = hz.gpu_prepend(ctx, [long_tok[:552]], [prm[0]])
-    with pytest.raises(lib.OtasError) as e:
-        hz.gpu_forward(ctx, x1, off1, [1])
-    assert e.value.status == 5
+    for n_long, want in ((554, [0, 140, 144]), (577, [0, 145, 149]), (1024, [0, 257, 261])):
+        toks = [long_tok[:n_long - 4], synth.query_tokens(cfg, 1)[:9]]
+        x0, off = hz.gpu_prepend(ctx, toks, prm)
+        assert off.tolist() == [0, n_long, n_long + 9]
+        gpu = hz.gpu_forward(ctx, x0, off, R)
+        rep = hz.compare_lockstep(cfg, layers, toks, prm, R, gpu)
+        print(f"n = {n_long}:", rep)
+        assert rep["sizes_equal"] and rep["max_err"] <= F32_TOL
+        assert rep["disagreements"] == 0 or rep["max_deficit"] <= 1e-6
+        assert gpu["offsets"].tolist() == want   # n -> ceil(n / 2) + ... twice; 9 -> 6 -> 4 (r clamps to 2)
     # no merging: the full 1024 tokens
     x2, off2 = hz.gpu_prepend(ctx, [long_tok], [prm[0]])
     assert off2.tolist() == [0, 1024]

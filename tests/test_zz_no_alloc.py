@@ -79,6 +79,11 @@ def test_static_scratch_merge_equals_workspace_merge_twice_in_a_row(dtype):
     with pytest.raises(otas.OtasError) as e:
         ctx.otas_token_merge_static(x, m, 64, None, np.arange(Bq + 1) * 2, [0] * Bq, xo, so)
     assert e.value.status == 3
+    # a query too long for the plan kernel's LDS would need workspace for its metric rows: refused here
+    # (otas_token_merge takes it), with or without merging in it
+    with pytest.raises(otas.OtasError) as e:
+        ctx.otas_token_merge_static(x[:700], m[:700], 64, None, [0, 700], [4], xo[:700], so[:700])
+    assert e.value.status == 5
     # and a third, ordinary call still works after the refused ones
     _both(torch, ctx, cfg, [197, 197], [16, 8], 64, seed=23, sizes_hi=2)
     ctx.close()
