@@ -343,6 +343,8 @@ def main():
                     help="further workloads reported per strategy (the two large ragged ones run few steps)")
     ap.add_argument("--cpu-queries", type=int, default=32)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-clock", action="store_true",
+                    help="skip the shader-clock pass (profiler runs: the probe is a kernel that lasts as long as the steps)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run one plain device copy of 256 MiB (torch) so that a rocprofv3 --pmc run of this "
                          "command holds a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -380,10 +382,13 @@ def main():
                       args.warmup if not big else min(args.warmup, 3))
     for st in strategies:
         st.time_single_forwards(21)
-    idle_mhz = strategies[0].idle_clock()
+    idle_mhz = None if args.no_clock else strategies[0].idle_clock()
     for i, st in enumerate(strategies):
         big = st.cfg.L * st.cfg.D * st.cfg.B > 12 * 768 * 64 * 2
-        st.measure_clock(4 if big else 20)
+        if args.no_clock:
+            st.clock = None
+        else:
+            st.measure_clock(4 if big else 20)
     all_res = [st.time_launches(max(3, min(10, args.steps)) if i == 0 else 3) for i, st in enumerate(strategies)]
     head = all_res[0]
     per_strategy = {}
@@ -398,7 +403,8 @@ def main():
             "images_per_s": round(r["img_s"], 1), "ms_per_step": round(r["ms"], 4),
             "single_forward_ms_median": round(r["latency_ms"], 4), "single_forward_runs": r["latency_runs"],
             "single_forward_images_per_s": round(r["cfg"].B / (r["latency_ms"] * 1e-3), 1),
-            "gemm_tflops": rf["gemm"]["achieved"], "shader_clock_mhz_median": r["clock"]["median"],
+            "gemm_tflops": rf["gemm"]["achieved"],
+            "shader_clock_mhz_median": r["clock"]["median"] if r["clock"] else None,
             "merge_apply_gbs": rf.get("merge_apply", {}).get("achieved"),
             "attention_tflops": rf.get("attention", {}).get("achieved"),
         }
@@ -417,14 +423,15 @@ def main():
                          traffic_source="rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, stored in "
                                         "paper_2401_05031_amd/hbm_traffic.json (profiles/hbm_traffic_vitb_r16_pmc.md); "
                                         "not re-measured by this run"),
-        "shader_clock": {"rated_mhz": RATED_MHZ, "idle_mhz": idle_mhz, "under_load_mhz": head["clock"],
-                         "peak_at_measured_clock": round(PEAK_BF16_TFLOPS * head["clock"]["median"] / RATED_MHZ, 1),
-                         "gemm_frac_of_peak_at_measured_clock":
-                             round(rf["gemm"]["achieved"] / (PEAK_BF16_TFLOPS * head["clock"]["median"] / RATED_MHZ), 4),
-                         "note": "the data-sheet peak (roofline.peak) is 256 CUs x 4 matrix cores x 1024 FLOP per clock at "
-                                 "2400 MHz; under sustained matrix work on random operands the chip lowers its clock "
-                                 "(measured here by a one-wave probe beside the timed steps), so the same cycles-per-"
-                                 "tile efficiency yields a smaller fraction of that peak"},
+        "shader_clock": None if head["clock"] is None else {
+            "rated_mhz": RATED_MHZ, "idle_mhz": idle_mhz, "under_load_mhz": head["clock"],
+            "peak_at_measured_clock": round(PEAK_BF16_TFLOPS * head["clock"]["median"] / RATED_MHZ, 1),
+            "gemm_frac_of_peak_at_measured_clock":
+                round(rf["gemm"]["achieved"] / (PEAK_BF16_TFLOPS * head["clock"]["median"] / RATED_MHZ), 4),
+            "note": "the data-sheet peak (roofline.peak) is 256 CUs x 4 matrix cores x 1024 FLOP per clock at 2400 MHz; "
+                    "under sustained matrix work on random operands the chip lowers its clock (measured here by a "
+                    "one-wave probe beside the timed steps), so the same cycles-per-tile efficiency yields a smaller "
+                    "fraction of that peak"},
         "rooflines": rf,
         "per_strategy": per_strategy,
     }

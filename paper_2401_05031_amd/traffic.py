@@ -49,7 +49,7 @@ def main(argv):
     wscale = CAL_BYTES / (wcal * 1024.0)
     res = {"workload": workload, "unit": "bytes per launch (fetch + write), averaged over the launches of one forward",
            "fetch_scale": round(fscale, 4), "write_scale": round(wscale, 4),
-           "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE over `bench.py --steps 2 --warmup 1 --no-cpu --others '' "
+           "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE over `bench.py --steps 2 --warmup 1 --no-cpu --no-clock --others '' "
                      "--calibrate`, each scaled by the counter's reading for the 256 MiB device copy in the same run",
            "families": {}}
     for fam in FAMILIES:
