@@ -277,7 +277,7 @@ def rooflines(res):
     # one row per GEMM launch of a forward pass: rows, the kernel the library picks (block tile, workgroup
     # slots on 256 CUs), tiles, rounds of those slots, microseconds, TFLOP/s
     tiles_of = {1: (64, 64, 2048), 2: (128, 128, 768), 3: (128, 128, 512), 4: (192, 256, 256), 5: (256, 256, 256),
-                6: (320, 256, 256)}
+                6: (320, 256, 256), 7: (64, 64, 1280)}
     cfg, ctx = res["cfg"], res.get("ctx")
     if ctx is not None and not cfg.deep:
         table = []

@@ -288,10 +288,10 @@ otas_status otas_attention(otas_ctx *ctx, const void *qkv, const int32_t *sizes,
  * kernel of the library at every shape (otas_linear and the encoder choose by shape alone).
  * kernel: 0 the library's own choice, 1 plain fp32-FMA tiles (any dtype), and for bf16 models the
  * MFMA kernels named by block tile (rows x columns) and K step: 2 128x128 k32, 3 128x128 k64,
- * 4 192x256 k64, 5 256x256 k64, 6 320x256 k64.
+ * 4 192x256 k64, 5 256x256 k64, 6 320x256 k64, 7 64x64 k32.
  * OTAS_EUNSUPPORTED if the kernel does not take the shape (k32 kernels need K % 32 == 0 and K >= 64,
  * k64 kernels K % 64 == 0 and K >= 128) or the dtype. */
-#define OTAS_LINEAR_KERNELS 7
+#define OTAS_LINEAR_KERNELS 8
 /* The kernel (numbering above, never 0) that otas_linear and the encoder run for this shape; pure host
  * function, -1 on invalid arguments.  Lets a benchmark report tiles and rounds per launch. */
 int32_t otas_linear_choice(const otas_ctx *ctx, int64_t T, int32_t N, int32_t K, int32_t epilogue);

@@ -16,7 +16,7 @@ OTAS_F32, OTAS_BF16 = 0, 1
 OTAS_FLAG_SIZE_BIAS, OTAS_FLAG_TRACE = 1, 2
 OTAS_PROMPT_REPLACE, OTAS_PROMPT_GROW = 1, 2
 OTAS_STATIC_MERGE_MAX_ROWS, OTAS_STATIC_MERGE_MAX_QUERIES = 65536, 1024
-OTAS_LINEAR_KERNELS = 7
+OTAS_LINEAR_KERNELS = 8
 OTAS_CLOCK_PROBE_MAX_SAMPLES = 65536
 _WEIGHT_FIELDS = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_proj", "b_proj",
                   "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")

@@ -9,6 +9,7 @@
 //       gemm_mfma_k32_kernel     128 x 128, K step 32, three workgroups per CU (also split-K)
 //       gemm_mfma128k64_kernel   128 x 128, K step 64, two per CU
 //       gemm_mfma256w8_kernel    192 / 256 / 320 x 256, eight waves, one per CU
+//       gemm_mfma64_kernel       64 x 64, K step 32, for products of very few rows
 //     pick_mfma_kernel chooses among them with a cost model fitted to measured launch times.
 #include <algorithm>
 #include <cmath>
@@ -434,6 +435,105 @@ static hipError_t linear_mfma_k32(const void* x, const void* w, const void* bias
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------ 64 x 64, K step 32
+// For products of so few rows that 128 x 128 tiles leave most CUs without a workgroup (small serving batches: a
+// ViT-B query is 197 rows): block tile 64 x 64, four waves of 32 x 32 in a 2 x 2 arrangement, the same
+// direct-to-LDS ring as gemm_mfma_k32_kernel with NS = 4 stages of 8 KB (up to five workgroups per CU).  Four times
+// the workgroups of the 128 x 128 tiling at twice the operand bytes per FLOP: it wins while the launch is bound by
+// the serial k-loop of a lone workgroup per CU, not by what the CUs can load.
+template <int EPI>
+__global__ __launch_bounds__(256, 4) void gemm_mfma64_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
+                                                             const bf16_t* __restrict__ bias, const float* res,
+                                                             typename OutType<bf16_t, EPI>::type* Y, int64_t M, int N,
+                                                             int K, int tiles_m, int tiles_n) {
+  constexpr int BM = 64, BN = 64, BK = 32, NS = 4, ND = 2;
+  constexpr int STAGE_A = BM * BK, STAGE_W = BN * BK;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);   // [NS][64][32]
+  bf16_t* Ws = As + NS * STAGE_A;                 // [NS][64][32]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  const int64_t m0 = (int64_t)tile_m * BM;
+  const int n0 = tile_n * BN;
+  // DMA: 16 rows of 64 B per instruction; wave w loads rows 16 w .. of the A tile and of the W tile
+  uint32_t a_off, w_off;
+  {
+    const int row = wave * 16 + (lane >> 2);
+    const int c = (lane & 3) ^ ((row >> 2) & 3);
+    const int64_t a_last = M - 1 - m0;
+    const int w_last = N - 1 - n0;
+    const uint32_t ra = (uint32_t)(row < a_last ? row : a_last), rw = (uint32_t)(row < w_last ? row : w_last);
+    a_off = (ra * (uint32_t)K + (uint32_t)c * 8u) * (uint32_t)sizeof(bf16_t);
+    w_off = (rw * (uint32_t)K + (uint32_t)c * 8u) * (uint32_t)sizeof(bf16_t);
+  }
+  const char* a_base = reinterpret_cast<const char*>(A + (size_t)m0 * K);
+  const char* w_base = reinterpret_cast<const char*>(W + (size_t)n0 * K);
+  const int KT = K / BK;
+  auto dma = [&](int kt, int st) {
+    const size_t kb = (size_t)((kt < KT ? kt : KT - 1) * BK) * sizeof(bf16_t);
+    __builtin_amdgcn_global_load_lds(OTAS_GPTR(a_base + kb + a_off), OTAS_LPTR(As + st * STAGE_A + wave * 16 * BK), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds(OTAS_GPTR(w_base + kb + w_off), OTAS_LPTR(Ws + st * STAGE_W + wave * 16 * BK), 16, 0, 0);
+  };
+  floatx16 acc[1][1];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[0][0][e] = 0.f;
+  const int fr = lane & 31, fk = lane >> 5;
+  const int frag_row = fr * BK, sw = (fr >> 2) & 3;
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t) dma(t, t);
+  int st = 0, st_new = NS - 1;
+  for (int kt = 0; kt < KT; ++kt) {
+    OTAS_VMCNT(ND * (NS - 2));
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    bf16x8 af[2], wf[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const int c = (((ks << 1) + fk) ^ sw) * 8;
+      af[ks] = *reinterpret_cast<const bf16x8*>(As + st * STAGE_A + (wm * 32) * BK + frag_row + c);
+      wf[ks] = *reinterpret_cast<const bf16x8*>(Ws + st * STAGE_W + (wn * 32) * BK + frag_row + c);
+    }
+    dma(kt + NS - 1, st_new);
+    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0], af[0], acc[0][0], 0, 0, 0);
+    acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[1], af[1], acc[0][0], 0, 0, 0);
+    st = st + 1 == NS ? 0 : st + 1;
+    st_new = st_new + 1 == NS ? 0 : st_new + 1;
+  }
+  OTAS_VMCNT(0);
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+  if constexpr (EPI == EPI_NONE || EPI == EPI_GELU)
+    mfma_epilogue_bf16<EPI, 1, 1>(acc, reinterpret_cast<bf16_t*>(smem) + wave * 32 * (32 + 8), bias, Y, M, N,
+                                  m0 + wm * 32, n0 + wn * 32, lane);
+  else
+    mfma_epilogue<EPI, 1, 1>(acc, reinterpret_cast<float*>(smem) + wave * 32 * (32 + 4), bias, res, Y, M, N,
+                             m0 + wm * 32, n0 + wn * 32, lane);
+}
+
+static hipError_t linear_mfma64(const void* x, const void* w, const void* bias, const float* res, void* y, int64_t M,
+                                int N, int K, int epi, hipStream_t s) {
+  const int tiles_m = (int)((M + 63) / 64), tiles_n = (N + 63) / 64;
+  const size_t lds = (size_t)4 * (64 + 64) * 32 * sizeof(bf16_t);
+  static_assert(4 * 32 * (32 + 4) * sizeof(float) <= (size_t)4 * (64 + 64) * 32 * sizeof(bf16_t), "epilogue slab");
+  dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
+#define OTAS_MFMA(E)                                                                                              \
+  do {                                                                                                            \
+    gemm_mfma64_kernel<E><<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,  \
+                                                   (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_m,       \
+                                                   tiles_n);                                                      \
+  } while (0)
+  if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
+  else if (epi == EPI_GELU) OTAS_MFMA(EPI_GELU);
+  else OTAS_MFMA(EPI_RESIDUAL);
+#undef OTAS_MFMA
+  return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------ 256x256, 8 waves
 // The large-shape kernel: block tile 256 x 256, 8 waves of 128 x 64 (2 x 4 arrangement), two LDS
 // stages of K step 64 (128 KB; rows of 128 B, i.e. whole cache lines per row and k-tile: streaming
@@ -768,6 +868,7 @@ static hipError_t linear_mfma_kernel(int kernel, const void* x, const void* w, c
     case GK_192X256: return k64 ? linear_mfma256w8<3>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
     case GK_256X256: return k64 ? linear_mfma256w8<4>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
     case GK_320X256: return k64 ? linear_mfma256w8<5>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
+    case GK_64X64: return k32 ? linear_mfma64(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }
 }
@@ -779,6 +880,10 @@ static hipError_t linear_mfma_kernel(int kernel, const void* x, const void* w, c
 // i.e. whole rounds of S tiles, a partly filled last round costing p of a round plus its share.
 // The choice depends on the shape only, so a shape always runs the same kernel.
 static int pick_mfma_kernel(int64_t M, int N, int K, int epi) {
+  // So few outputs that even 64 x 64 tiles do not fill the chip twice: the small-tile kernel (measured on MI355X
+  // at K = 768: 197 x 2304 8.3 -> 5.9 us, 788 x 768 9.6 -> 6.4, 2368 x 768 12.1 -> 9.8; from ~470 tiles on it loses,
+  // 788 x 3072 11.1 -> 12.9, 3392 x 768 13.2 -> 14.6: it loads twice the operand bytes per FLOP)
+  if (((M + 63) / 64) * ((N + 63) / 64) <= 450) return GK_64X64;
   if (K % 64 != 0 || K < 128) return GK_128_K32;
   struct Cand { int id, bm, bn, slots; double alpha[3], beta, p; };
   static const Cand cands[] = {

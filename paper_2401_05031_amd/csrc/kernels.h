@@ -64,7 +64,7 @@ hipError_t launch_linear(int dtype, const void* x, const void* w, const void* bi
 // hipErrorInvalidValue if the kernel does not take the shape (K % 32 / K % 64, N % 8).
 enum gemm_kernel_id {
   GK_AUTO = 0, GK_FMA = 1, GK_128_K32 = 2, GK_128_K64 = 3, GK_192X256 = 4, GK_256X256 = 5, GK_320X256 = 6,
-  GK_COUNT = 7
+  GK_64X64 = 7, GK_COUNT = 8
 };
 int linear_kernel_choice(int dtype, int64_t M, int N, int K, int epi);   // the id launch_linear runs for this shape
 hipError_t launch_linear_kernel(int kernel, int dtype, const void* x, const void* w, const void* bias,

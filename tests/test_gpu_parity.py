@@ -614,7 +614,7 @@ def test_linear_bf16_every_kernel_ragged_rows(torch_cuda, lib, M, N, K, epi):
     ctx.close()
 
 
-@pytest.mark.parametrize("kernel", range(1, 7))
+@pytest.mark.parametrize("kernel", range(1, 8))
 def test_linear_every_named_kernel_whole_output(torch_cuda, lib, kernel):
     """Every GEMM kernel of the library forced by name (otas_linear_kernel) on shapes with ragged row
     and column tiles, all three epilogues, the whole output against a float64 product; a K that a
@@ -641,12 +641,12 @@ def test_linear_every_named_kernel_whole_output(torch_cuda, lib, kernel):
             assert hz.rel_err(got, lin) <= 1e-5 and hz.elem_err(got, lin) <= 1e-4, (kernel, M, N, K, epi)
         else:
             assert hz.rel_err(got, lin) <= 2.0 ** -8 and hz.elem_err(got, lin) <= 2.0 ** -7, (kernel, M, N, K, epi)
-    if kernel >= 2:     # MFMA kernels: K = 96 suits only the K-step-32 kernel, K = 40 none of them
+    if kernel >= 2:     # MFMA kernels: K = 96 suits only the K-step-32 kernels, K = 40 none of them
         x = torch.zeros((64, 96), dtype=dt, device="cuda")
         w = torch.zeros((64, 96), dtype=dt, device="cuda")
         b = torch.zeros(64, dtype=dt, device="cuda")
         y = torch.zeros((64, 64), dtype=dt, device="cuda")
-        if kernel == 2:
+        if kernel in (2, 7):
             ctx.otas_linear_kernel(kernel, x, w, b, None, 64, 64, 96, 0, y)
         else:
             with pytest.raises(lib.OtasError) as e:
