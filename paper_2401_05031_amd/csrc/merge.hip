@@ -18,6 +18,7 @@ namespace otas {
 constexpr int kPlanThreads = 1024;
 
 template <typename T> struct alignas(4 * sizeof(T)) Quad { T x[4]; };   // 4 consecutive elements, one load
+template <typename T> struct alignas(8 * sizeof(T)) Oct { T x[8]; };    // 8 consecutive elements, one load
 
 // LDS layout of the plan kernel (4-byte words), n = query length, nA = ceil(n/2), nB = floor(n/2):
 //   mh [n][dm+4] normalised metric rows | best [nA] | bcol [nA] | merged [nA] | cnt [nB] |
@@ -86,27 +87,50 @@ __global__ __launch_bounds__(kPlanThreads) void merge_plan_kernel(
   int* wave_tot = ent_pos + n;   // [2][16]
   auto row_of = [&](int i) { return mh + (size_t)((i & 1) ? nA + (i >> 1) : (i >> 1)) * ldm; };
 
-  // Phase 0: head-mean metric rows, 4 columns per thread (one 8- or 16-byte load per head), heads
-  // summed in ascending order.  (This phase is bound by instruction issue on the one CU that runs
-  // the query, not by load latency: deeper load batches made it slower.)
-  const int c4n = dm >> 2;
+  // Phase 0: head-mean metric rows, heads summed in ascending order.  A thread takes 8 columns of a token when the
+  // source is 16-bit and 16-byte aligned with dm % 8 == 0 (one 16-byte load per head, two 16-byte LDS stores: this phase is bound by
+  // instruction issue on the one CU that runs the query), else 4 columns.
   const float inv_h = 1.0f / (float)H;
-  for (int t = tid; t < n * c4n; t += kPlanThreads) {
-    const int i = t / c4n, c = (t - i * c4n) * 4;
-    const T* p = src + (size_t)(i0 + i) * row_stride + col_off + c;
-    float m0 = 0.f, m1 = 0.f, m2 = 0.f, m3 = 0.f;
+  if (sizeof(T) == 2 && (dm & 7) == 0 && (row_stride & 7) == 0 && (col_off & 7) == 0 &&
+      (reinterpret_cast<uintptr_t>(src) & 15) == 0) {
+    const int c8n = dm >> 3;
+    for (int t = tid; t < n * c8n; t += kPlanThreads) {
+      const int i = t / c8n, c = (t - i * c8n) * 8;
+      const T* p = src + (size_t)(i0 + i) * row_stride + col_off + c;
+      float m[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) m[e] = 0.f;
 #pragma unroll 4
-    for (int h = 0; h < H; ++h) {
-      const Quad<T> v = *reinterpret_cast<const Quad<T>*>(p);
-      m0 += to_float(v.x[0]); m1 += to_float(v.x[1]); m2 += to_float(v.x[2]); m3 += to_float(v.x[3]);
-      p += dm;
+      for (int h = 0; h < H; ++h) {
+        const Oct<T> v = *reinterpret_cast<const Oct<T>*>(p);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) m[e] += to_float(v.x[e]);
+        p += dm;
+      }
+      float* r = row_of(i);
+      const int ce = c >> 1;   // columns c, c+2, c+4, c+6 are even ones, the others odd ones
+      *reinterpret_cast<floatx4*>(r + ce) = floatx4{m[0] * inv_h, m[2] * inv_h, m[4] * inv_h, m[6] * inv_h};
+      *reinterpret_cast<floatx4*>(r + hp + ce) = floatx4{m[1] * inv_h, m[3] * inv_h, m[5] * inv_h, m[7] * inv_h};
     }
-    float* r = row_of(i);
-    const int ce = c >> 1;   // columns c, c+2 are even ones, c+1, c+3 odd ones
-    r[ce] = m0 * inv_h;
-    r[ce + 1] = m2 * inv_h;
-    r[hp + ce] = m1 * inv_h;
-    r[hp + ce + 1] = m3 * inv_h;
+  } else {
+    const int c4n = dm >> 2;
+    for (int t = tid; t < n * c4n; t += kPlanThreads) {
+      const int i = t / c4n, c = (t - i * c4n) * 4;
+      const T* p = src + (size_t)(i0 + i) * row_stride + col_off + c;
+      float m0 = 0.f, m1 = 0.f, m2 = 0.f, m3 = 0.f;
+#pragma unroll 4
+      for (int h = 0; h < H; ++h) {
+        const Quad<T> v = *reinterpret_cast<const Quad<T>*>(p);
+        m0 += to_float(v.x[0]); m1 += to_float(v.x[1]); m2 += to_float(v.x[2]); m3 += to_float(v.x[3]);
+        p += dm;
+      }
+      float* r = row_of(i);
+      const int ce = c >> 1;   // columns c, c+2 are even ones, c+1, c+3 odd ones
+      r[ce] = m0 * inv_h;
+      r[ce + 1] = m2 * inv_h;
+      r[hp + ce] = m1 * inv_h;
+      r[hp + ce + 1] = m3 * inv_h;
+    }
   }
   if (hp != half)   // the padding columns take part in the contraction: zero
     for (int t = tid; t < n * 2 * (hp - half); t += kPlanThreads) {
@@ -114,18 +138,31 @@ __global__ __launch_bounds__(kPlanThreads) void merge_plan_kernel(
       row_of(i)[(c & 1) * hp + half + (c >> 1)] = 0.f;
     }
   __syncthreads();
-  // Phase 1: unit length.  4 consecutive lanes share a row: lane j sums the squares of columns
-  // j, j+4, ... in ascending order, the four partial sums are added by a fixed butterfly.
-  for (int i0r = 0; i0r < n; i0r += kPlanThreads / 4) {
-    const int i = i0r + (tid >> 2), j = tid & 3;
-    float ss = 0.f;
-    float* r = row_of(min(i, n - 1)) + (j & 1) * hp + (j >> 1);   // column c = j + 4 m sits at (j & 1) hp + (j >> 1) + 2 m
-    for (int m = 0; m < c4n; ++m) ss = fmaf(r[2 * m], r[2 * m], ss);
-    ss += __shfl_xor(ss, 1, kWave);
-    ss += __shfl_xor(ss, 2, kWave);
-    const float rn = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
-    if (i < n)
-      for (int m = 0; m < c4n; ++m) r[2 * m] *= rn;
+  // Phase 1: unit length.  16 consecutive lanes share a row of 2 hp floats (the zero padding adds nothing): lane j
+  // sums the squares of the 16-byte pieces j, j + 16, ... in ascending order, the sixteen partial sums are added by
+  // a fixed butterfly, and every lane scales its own pieces.
+  {
+    const int q4 = (2 * hp) >> 2;   // 16-byte pieces per row
+    for (int i0r = 0; i0r < n; i0r += kPlanThreads / 16) {
+      const int i = i0r + (tid >> 4), j = tid & 15;
+      float* r = row_of(min(i, n - 1));
+      float ss = 0.f;
+      for (int m = j; m < q4; m += 16) {
+        const floatx4 v = *reinterpret_cast<const floatx4*>(r + 4 * m);
+        ss = fmaf(v[0], v[0], ss); ss = fmaf(v[1], v[1], ss); ss = fmaf(v[2], v[2], ss); ss = fmaf(v[3], v[3], ss);
+      }
+      ss += __shfl_xor(ss, 1, kWave);
+      ss += __shfl_xor(ss, 2, kWave);
+      ss += __shfl_xor(ss, 4, kWave);
+      ss += __shfl_xor(ss, 8, kWave);
+      const float rn = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
+      if (i < n)
+        for (int m = j; m < q4; m += 16) {
+          floatx4 v = *reinterpret_cast<const floatx4*>(r + 4 * m);
+          v[0] *= rn; v[1] *= rn; v[2] *= rn; v[3] *= rn;
+          *reinterpret_cast<floatx4*>(r + 4 * m) = v;
+        }
+    }
   }
   __syncthreads();
 
