@@ -15,7 +15,8 @@
  *     unless a parameter says "float": inside the encoder the residual stream is always float
  *     (bf16 is used for the GEMM and attention operands), and the encoder returns it as float.
  *   - The caller owns every buffer.  The library allocates device memory only in otas_create
- *     (a small plan buffer) and frees it in otas_destroy.
+ *     (a small plan buffer) and, if the optional benchmark probe otas_clock_probe_start is used, at its
+ *     first call (256 KB of samples), and frees both in otas_destroy.
  *   - All device work is enqueued on the HIP stream given to otas_create and the calls return
  *     without waiting for it.  Host outputs (offsets_out) are complete on return, because every
  *     sequence length is a function of (n, r, layer) alone and is computed on the host.
