@@ -22,7 +22,7 @@ namespace {
 constexpr size_t kAlign = 256;
 constexpr int64_t kRowPad = 256;              // activation buffers are padded to this many rows
 constexpr size_t kPlanInts = (size_t)1 << 20;  // capacity of the device plan buffer (int32 entries)
-constexpr int64_t kPlanSideMinRows = 4096;   // batches below this many rows plan inline (see run_layers)
+constexpr int64_t kPlanSideMinRows = 32768;  // batches below this many rows plan inline (see run_layers)
 constexpr int kStageSlots = 32;
 constexpr size_t kSlotInts = kPlanInts / kStageSlots;
 constexpr int kMaxLanes = 8;
@@ -715,9 +715,12 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
       ln.ln1_done = true;
     }
   }
-  // The merge plan runs beside attention and the projection on a side stream when the batch is large
-  // enough for that to pay: forking and joining costs the host ~45 us per layer, more than a small
-  // batch's layer takes on the GPU, so small batches keep the plan on the lane's own stream.
+  // The merge plan needs only this layer's keys, so it may run beside attention and the projection on a side
+  // stream.  Measured on MI355X that pays only for the largest batches (ViT-H, 256 queries, 67 k rows: +0.9 %):
+  // at ViT-B batch 64 and ViT-L batch 128 the plan's workgroups slow attention and the GEMMs next to them by as
+  // much as hiding the plan saves (same images/s either way), a single forward pass is ~1 % quicker with the
+  // plan inline, and every fork / join costs the host ~45 us per layer.  So smaller batches keep the plan on
+  // the lane's own stream.
   const bool plan_inline = T0 < kPlanSideMinRows;
   for (int l = 0; l < L; ++l) {
     const otas_layer_weights& wl = c->layers[layer_begin + l];
