@@ -382,13 +382,20 @@ def main():
                       args.warmup if not big else min(args.warmup, 3))
     for st in strategies:
         st.time_single_forwards(21)
-    idle_mhz = None if args.no_clock else strategies[0].idle_clock()
+    # The clock figures are an extra: if the probe fails, the line is still printed without them.
+    idle_mhz = None
     for i, st in enumerate(strategies):
         big = st.cfg.L * st.cfg.D * st.cfg.B > 12 * 768 * 64 * 2
+        st.clock = None
         if args.no_clock:
-            st.clock = None
-        else:
+            continue
+        try:
+            if idle_mhz is None:
+                idle_mhz = st.idle_clock()
             st.measure_clock(4 if big else 20)
+        except Exception as e:      # noqa: BLE001
+            print(f"bench.py: shader-clock probe failed for {st.name}: {e}", file=sys.stderr)
+            st.clock = None
     all_res = [st.time_launches(max(3, min(10, args.steps)) if i == 0 else 3) for i, st in enumerate(strategies)]
     head = all_res[0]
     per_strategy = {}
