@@ -118,6 +118,35 @@ def test_rate_projection_reproduces_table1():
     assert GAMMAS[so.f_of_rate(1000, f_table, smallest)] == -20
 
 
+def test_rate_table_from_latency_gives_table1_back():
+    """Table I read as the projection built from a latency profile: a model whose gamma serves `hi` requests per
+    second (per-sample latency 1 / hi, two tasks of different speed with that mean) gets the table's rows back,
+    the smallest gamma has no row, a gamma that is no faster than the one before it has none either, and the
+    order of the selection list does not matter."""
+    rows = table1()
+    finite = [(hi, g) for _, hi, g in rows if math.isfinite(hi)]
+    gammas = [g for _, g in finite] + [-20]                     # 8, 4, 2, 0, -5, -10, -15, -20
+    mean_lat = [1.0 / hi for hi, _ in finite] + [1.0 / 5000.0]
+    latency = [[0.5 * m for m in mean_lat], [1.5 * m for m in mean_lat]]      # mean over the tasks = 1 / hi
+    got = so.rate_table_from_latency(gammas, latency)
+    assert [gammas[i] for _, i in got] == [g for _, g in finite]
+    assert [round(q, 6) for q, _ in got] == [hi for hi, _ in finite]
+    for lo, hi, g in rows:
+        for q in (lo, hi if math.isfinite(hi) else 5000.0):
+            assert gammas[so.f_of_rate(q, got, gammas.index(-20))] == g
+    # shuffled selection list: same rows (indices follow the list)
+    perm = [3, 7, 0, 5, 1, 6, 2, 4]
+    g2 = [gammas[i] for i in perm]
+    lat2 = [[row[i] for i in perm] for row in latency]
+    got2 = so.rate_table_from_latency(g2, lat2)
+    assert [(round(q, 6), g2[i]) for q, i in got2] == [(round(q, 6), gammas[i]) for q, i in got]
+    # gamma 2 made no faster than gamma 4: it loses its row
+    slow = [list(r) for r in latency]
+    for r in slow:
+        r[2] = r[1]
+    assert [gammas[i] for _, i in so.rate_table_from_latency(gammas, slow)] == [8, 4, 0, -5, -10, -15]
+
+
 # ------------------------------------------------------------------------------------------- profile
 def test_profile_counts_per_task_and_weights_utility():
     lat = [[0.001, 0.002], [0.010, 0.020]]
