@@ -748,22 +748,33 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
         OTAS_LAUNCH_ON(K_LN, s, launch_layer_norm(dt, true, ln.x_cur, wl.ln1_g, wl.ln1_b, hbuf, T, D, d.ln_eps, s));
       ln.ln1_done = false;
       OTAS_LAUNCH_ON(K_QKV, s, launch_linear(dt, hbuf, wl.w_qkv, wl.b_qkv, nullptr, qkv, T, 3 * D, D, EPI_NONE, s));
-      if (ln.any_merge[l]) {
-        // fork: the merge plan reads only the keys just written; the lists it writes were last read by
-        // the previous layer's merge-apply, which precedes this point on the lane's stream
-        hipStream_t ps = plan_inline ? s : hw.side;
-        if (!plan_inline) {
-          OTAS_HIP(hipEventRecord(hw.ev_fork, s));
-          OTAS_HIP(hipStreamWaitEvent(hw.side, hw.ev_fork, 0));
+      // Attention and the merge plan both read only the QKV projection.  On one stream two kernels never overlap,
+      // so where the plan stays on this stream and one kernel can hold both (bf16, head width 64), they go out
+      // as ONE launch whose first workgroups are the plan's; it is recorded as an attention launch.
+      const bool fuse = ln.any_merge[l] && plan_inline && attention_plan_takes(dt, ln.max_n[l], D, H);
+      if (fuse) {
+        OTAS_LAUNCH_ON(K_ATTN, s,
+                       launch_attention_plan(qkv, ln.sizes_now, off_l, off_n, d_reff, d_tr, Bg, ln.max_n[l], D, H,
+                                             size_bias, n_lead, hbuf, src_list, row_ptr,
+                                             trace ? trace_src : nullptr, trace ? trace_dst : nullptr, s));
+      } else {
+        if (ln.any_merge[l]) {
+          // fork: the merge plan reads only the keys just written; the lists it writes were last read by
+          // the previous layer's merge-apply, which precedes this point on the lane's stream
+          hipStream_t ps = plan_inline ? s : hw.side;
+          if (!plan_inline) {
+            OTAS_HIP(hipEventRecord(hw.ev_fork, s));
+            OTAS_HIP(hipStreamWaitEvent(hw.side, hw.ev_fork, 0));
+          }
+          OTAS_LAUNCH_ON(K_PLAN, ps,
+                         launch_merge_plan(dt, qkv, 3 * (int64_t)D, D, H, dh, off_l, off_n, d_reff, d_tr, Bg,
+                                           ln.max_n[l], n_lead, src_list, row_ptr, trace ? trace_src : nullptr,
+                                           trace ? trace_dst : nullptr, (float*)hid, ps));
+          if (!plan_inline) OTAS_HIP(hipEventRecord(hw.ev_join, hw.side));
         }
-        OTAS_LAUNCH_ON(K_PLAN, ps,
-                       launch_merge_plan(dt, qkv, 3 * (int64_t)D, D, H, dh, off_l, off_n, d_reff, d_tr, Bg,
-                                         ln.max_n[l], n_lead, src_list, row_ptr, trace ? trace_src : nullptr,
-                                         trace ? trace_dst : nullptr, (float*)hid, ps));
-        if (!plan_inline) OTAS_HIP(hipEventRecord(hw.ev_join, hw.side));
+        OTAS_LAUNCH_ON(K_ATTN, s,
+                       launch_attention(dt, qkv, ln.sizes_now, off_l, Bg, ln.max_n[l], D, H, size_bias, hbuf, s));
       }
-      OTAS_LAUNCH_ON(K_ATTN, s,
-                     launch_attention(dt, qkv, ln.sizes_now, off_l, Bg, ln.max_n[l], D, H, size_bias, hbuf, s));
       // in-place residual is safe (each element is read then written by the same thread); the
       // caller's x0 is never written, so layer 0 writes into the workspace.
       void* x_attn = ln.x_owned ? const_cast<void*>(ln.x_cur) : (void*)x_free[0];

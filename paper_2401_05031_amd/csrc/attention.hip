@@ -9,6 +9,7 @@
 
 #include "common.h"
 #include "kernels.h"
+#include "merge_plan_body.h"
 
 namespace otas {
 
@@ -84,25 +85,27 @@ __global__ __launch_bounds__(256) void attention_rows_kernel(const T* __restrict
 typedef short short4_t __attribute__((ext_vector_type(4)));
 typedef short short8_t __attribute__((ext_vector_type(8)));
 
+// One (query q, head h, block xblk of 32 NW query rows) on NW waves: tid = thread index among those 64 NW
+// threads, smem = their LDS region.  Every __syncthreads() below is reached by all threads of the workgroup
+// that share q and xblk (the trip counts depend on the query's length and xblk only), so a workgroup may run
+// several heads of one query side by side, each on its own NW waves and LDS region.
 template <int DH, bool BIAS, int KC, int NW>
-__global__ __launch_bounds__(64 * NW, DH <= 64 ? 4 : 2) void attention_mfma_kernel(const bf16_t* __restrict__ qkv,
-                                                             const int32_t* __restrict__ sizes,
-                                                             const int32_t* __restrict__ off, int D, float scale,
-                                                             bf16_t* __restrict__ o) {
+__device__ __forceinline__ void attention_mfma_body(const bf16_t* __restrict__ qkv, const int32_t* __restrict__ sizes,
+                                                    const int32_t* __restrict__ off, int D, float scale,
+                                                    bf16_t* __restrict__ o, const int q, const int h, const int xblk,
+                                                    unsigned char* smem, const int tid) {
   constexpr int KS = DH / 16;             // k-steps of Q K^T
   constexpr int DT = (DH + 31) / 32;      // 32-row tiles of O^T
   constexpr int LD = DH + 8;              // LDS row stride in elements (16 bytes of padding)
   constexpr int VROWS = KC + 4;           // V^T reads of the last d tile may run past DH: keep them in bounds
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem);           // [KC][LD]
   bf16_t* Vs = Ks + KC * LD;                              // [VROWS][LD]
   float* lnsz = reinterpret_cast<float*>(Vs + VROWS * LD);  // [KC] log2(size) of the chunk's keys
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int q = blockIdx.z, h = blockIdx.y;
+  const int lane = tid & 63, wave = tid >> 6;
   const int base = off[q], n = off[q + 1] - base;
   constexpr int NT = 64 * NW;             // threads: NW waves of 32 query rows each
-  const int row0 = blockIdx.x * (32 * NW);
+  const int row0 = xblk * (32 * NW);
   if (row0 >= n) return;
   const size_t ld = (size_t)3 * D;
   const int fr = lane & 31, fk = lane >> 5;
@@ -274,6 +277,47 @@ __global__ __launch_bounds__(64 * NW, DH <= 64 ? 4 : 2) void attention_mfma_kern
   }
 }
 
+template <int DH, bool BIAS, int KC, int NW>
+__global__ __launch_bounds__(64 * NW, DH <= 64 ? 4 : 2) void attention_mfma_kernel(const bf16_t* __restrict__ qkv,
+                                                             const int32_t* __restrict__ sizes,
+                                                             const int32_t* __restrict__ off, int D, float scale,
+                                                             bf16_t* __restrict__ o) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  attention_mfma_body<DH, BIAS, KC, NW>(qkv, sizes, off, D, scale, o, (int)blockIdx.z, (int)blockIdx.y, (int)blockIdx.x,
+                                        smem, (int)threadIdx.x);
+}
+
+// Attention and the merge plan of a layer in ONE launch (both only read the layer's QKV projection, and
+// kernels of one stream do not overlap): workgroups 0 .. B-1 of 1024 threads run the plan of query 0 .. B-1
+// (merge_plan_body), the others run attention, each on 16 / NW heads of one (query, row block) side by side.
+// The plan workgroups come first in dispatch order, so their long serial chains start at once and the attention
+// workgroups fill the other CUs.  Head width 64 only (a 1024-thread workgroup leaves 128 registers per lane).
+// grid.x = B + xblks * (H / G) * B with G = 16 / NW.
+template <bool BIAS, int KC, int NW>
+__global__ __launch_bounds__(1024) void attention_plan_kernel(
+    const bf16_t* __restrict__ qkv, const int32_t* __restrict__ sizes, const int32_t* __restrict__ off, int D, int H,
+    float scale, bf16_t* __restrict__ o, int B, int xblks, const int32_t* __restrict__ out_off,
+    const int32_t* __restrict__ reff_arr, const int32_t* __restrict__ troff, int n_lead,
+    int32_t* __restrict__ src_list, int32_t* __restrict__ row_ptr, int32_t* __restrict__ trace_src,
+    int32_t* __restrict__ trace_dst, int unit_lds) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int DH = 64, G = 16 / NW;
+  if ((int)blockIdx.x < B) {   // workgroup-uniform
+    merge_plan_body<bf16_t, true>(qkv, 3 * (int64_t)D, D, H, DH, off, out_off, reff_arr, troff, n_lead, src_list, row_ptr,
+                                  trace_src, trace_dst, nullptr, reinterpret_cast<float*>(smem), (int)blockIdx.x,
+                                  (int)threadIdx.x);
+    return;
+  }
+  int id = (int)blockIdx.x - B;
+  const int hg = H / G;
+  const int xblk = id % xblks;
+  id /= xblks;
+  const int hgrp = id % hg, q = id / hg;
+  const int unit = (int)threadIdx.x / (64 * NW), tid = (int)threadIdx.x % (64 * NW);
+  attention_mfma_body<DH, BIAS, KC, NW>(qkv, sizes, off, D, scale, o, q, hgrp * G + unit, xblk, smem + (size_t)unit * unit_lds,
+                                        tid);
+}
+
 template <int DH, bool BIAS>
 static hipError_t attention_mfma_b(const void* qkv, const int32_t* sz, const int32_t* d_off, int B, int max_n, int D,
                                  int H, float scale, void* o, hipStream_t s) {
@@ -305,6 +349,52 @@ static hipError_t attention_mfma(const void* qkv, const int32_t* sz, const int32
                                  int H, float scale, void* o, hipStream_t s) {
   return sz ? attention_mfma_b<DH, true>(qkv, sz, d_off, B, max_n, D, H, scale, o, s)
             : attention_mfma_b<DH, false>(qkv, sz, d_off, B, max_n, D, H, scale, o, s);
+}
+
+// Whether launch_attention_plan takes this case (pure host).
+bool attention_plan_takes(int dtype, int max_n, int D, int H) {
+  if (dtype == 0 || H <= 0 || D != 64 * H || max_n <= 0 || max_n > kPlanThreads) return false;
+  if (merge_plan_lds_bytes(max_n, 64) > 160 * 1024) return false;
+  const int G = (max_n > 128 && max_n <= 256) ? 2 : 4;   // heads per workgroup: 16 waves / (8 or 4 waves per head)
+  return H % G == 0;
+}
+
+// Attention of a layer together with the layer's merge plan (bf16, head width 64, H a multiple of the heads a
+// workgroup takes, every query's metric rows in LDS); hipErrorInvalidValue otherwise -- the caller then launches
+// the two kernels one after the other.
+hipError_t launch_attention_plan(const void* qkv, const int32_t* sizes, const int32_t* d_off, const int32_t* d_out_off,
+                                 const int32_t* d_reff, const int32_t* d_troff, int B, int max_n, int D, int H,
+                                 bool size_bias, int n_lead, void* o, int32_t* src_list, int32_t* row_ptr,
+                                 int32_t* trace_src, int32_t* trace_dst, hipStream_t s) {
+  if (B <= 0 || max_n <= 0) return hipSuccess;
+  if (H <= 0 || D != 64 * H || max_n > kPlanThreads) return hipErrorInvalidValue;
+  const size_t plan_lds = merge_plan_lds_bytes(max_n, 64);
+  if (plan_lds > 160 * 1024) return hipErrorInvalidValue;
+  const float scale = 1.0f / sqrtf(64.0f);
+  const int32_t* sz = size_bias ? sizes : nullptr;
+  constexpr int LD = 64 + 8;
+#define OTAS_FUSED(BIASV, KC, NWV)                                                                                \
+  do {                                                                                                            \
+    constexpr int G = 16 / NWV;                                                                                   \
+    if (H % G != 0) return hipErrorInvalidValue;                                                                  \
+    const size_t unit = ((size_t)(KC + KC + 4) * LD * sizeof(bf16_t) + KC * sizeof(float) + 15) & ~(size_t)15;    \
+    const size_t lds = unit * G > plan_lds ? unit * G : plan_lds;                                                 \
+    if (lds > 160 * 1024) return hipErrorInvalidValue;                                                            \
+    auto kern = attention_plan_kernel<BIASV, KC, NWV>;                                                            \
+    hipError_t e = set_max_dynamic_lds((const void*)kern, 160 * 1024);                                            \
+    if (e != hipSuccess) return e;                                                                                \
+    const int xblks = (max_n + 32 * NWV - 1) / (32 * NWV);                                                        \
+    dim3 grid((unsigned)(B + xblks * (H / G) * B)), block(1024);                                                  \
+    kern<<<grid, block, lds, s>>>((const bf16_t*)qkv, sz, d_off, D, H, scale, (bf16_t*)o, B, xblks, d_out_off,    \
+                                  d_reff, d_troff, n_lead, src_list, row_ptr, trace_src, trace_dst, (int)unit);   \
+  } while (0)
+  if (max_n > 128 && max_n <= 256) {
+    if (sz) OTAS_FUSED(true, 256, 8); else OTAS_FUSED(false, 256, 8);
+  } else {
+    if (sz) OTAS_FUSED(true, 128, 4); else OTAS_FUSED(false, 128, 4);
+  }
+#undef OTAS_FUSED
+  return hipGetLastError();
 }
 
 hipError_t launch_attention(int dtype, const void* qkv, const int32_t* sizes, const int32_t* d_off, int B,

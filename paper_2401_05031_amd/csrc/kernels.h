@@ -85,6 +85,15 @@ hipError_t launch_attention(int dtype, const void* qkv, const int32_t* sizes,
                             const int32_t* d_off, int B, int max_n, int D, int H, bool size_bias,
                             void* o, hipStream_t s);
 
+// Attention and the merge plan of one layer in a single launch (bf16 models of head width 64 whose queries all
+// fit the plan's LDS form; the plan's metric is the head mean of the keys in qkv).  Returns
+// hipErrorInvalidValue, having launched nothing, for every other case.
+bool attention_plan_takes(int dtype, int max_n, int D, int H);
+hipError_t launch_attention_plan(const void* qkv, const int32_t* sizes, const int32_t* d_off, const int32_t* d_out_off,
+                                 const int32_t* d_reff, const int32_t* d_troff, int B, int max_n, int D, int H,
+                                 bool size_bias, int n_lead, void* o, int32_t* src_list, int32_t* row_ptr,
+                                 int32_t* trace_src, int32_t* trace_dst, hipStream_t s);
+
 // The metric of token i is the mean over H heads of src[i * row_stride + col_off + h * dm + c]
 // (dtype = type of src), normalised to unit length inside the kernel.  The kernel keeps a query's unit
 // metric rows in LDS when merge_plan_lds_bytes(max_n, dm) <= 160 KB; otherwise in `rows`, a device

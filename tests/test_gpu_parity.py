@@ -1060,6 +1060,8 @@ def test_bench_prints_one_json_line_with_the_contract_keys(torch_cuda, lib):
     assert rf["bound"] == "mfma" and rf["unit"] == "TFLOP/s" and rf["peak"] == 2500.0
     assert rf["frac"] == pytest.approx(rf["achieved"] / rf["peak"], abs=1e-3) and 0.0 < rf["frac"] < 1.0
     assert rf["traffic"] is None or rf["traffic"] > 0
+    # head width 64, bf16: attention and the merge plan of a layer go out as one launch, recorded as attention
+    assert b["rooflines"]["attention"].get("includes_merge_plan") is True and "merge_plan" not in b["rooflines"]
     sc = b["shader_clock"]
     assert 300 < sc["under_load_mhz"]["median"] <= sc["idle_mhz"] * 1.05 and sc["rated_mhz"] == 2400.0
     assert sc["peak_at_measured_clock"] == pytest.approx(2500.0 * sc["under_load_mhz"]["median"] / 2400.0, rel=1e-3)
