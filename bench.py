@@ -74,8 +74,7 @@ def algorithmic_work(cfg, lengths0, r, otas, ctx):
         else:
             w["layer_norm_bytes"] += Tm[l] * D * (4.0 + e)           # LN2 on its own
             w["layer_norm_method_bytes"] += Tm[l] * D * 2.0 * e
-        S = min(ctx.otas_splitk_factor(int(Tm[l]), D, F), int(2 * T[0] // max(Tm[l], 1))) if e == 2 and not cfg.deep else 1
-        S = S if S > 1 and F % (S * 32) == 0 else 1
+        S = ctx.otas_splitk_factor(int(Tm[l]), D, F, min(8, int(2 * T[0] // max(Tm[l], 1)))) if e == 2 and not cfg.deep else 1
         w["splits"].append(S)
         ln1_fused = S > 1 and l + 1 < L
         if S > 1:   # S float partial rows + residual row in, residual row out, next block's operand row out
@@ -294,7 +293,8 @@ def rooflines(res):
         for kind, (rows, N, K, epi) in shapes.items():
             for l, (M, ms) in enumerate(zip(rows, res["launches"].get(kind, []))):
                 S = w["splits"][l] if kind == "gemm_fc2" else 1
-                kid = 2 if S > 1 else ctx.otas_linear_choice(M, N, K, epi)
+                # split products run the partial-output form of the 128 x 128 kernels: K step 64 where K / S allows it
+                kid = (3 if K % (S * 64) == 0 and K // S >= 128 else 2) if S > 1 else ctx.otas_linear_choice(M, N, K, epi)
                 bm, bn, slots = tiles_of.get(kid, (0, 0, 1))
                 tiles = -(-M // bm) * -(-N // bn) * S if bm else 0
                 table.append({"kind": kind, "layer": l, "M": int(M), "N": N, "K": K, "kernel": kid, "tile": f"{bm}x{bn}",

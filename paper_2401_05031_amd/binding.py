@@ -102,7 +102,7 @@ def load_library():
         "otas_set_lanes": (i32, [vp, i32]),
         "otas_clock_probe_start": (i32, [vp, i32]),
         "otas_clock_probe_read": (i32, [vp, C.POINTER(C.c_float), i32, _I32P]),
-        "otas_splitk_factor": (i32, [vp, C.c_int64, i32, i32]),
+        "otas_splitk_factor": (i32, [vp, C.c_int64, i32, i32, i32]),
         "otas_sched_create": (i32, [C.POINTER(_SchedParams), i32, _I32P, i32, _F64P, _F64P, i32, _F64P, _I32P,
                                     C.POINTER(vp)]),
         "otas_sched_destroy": (None, [vp]),
@@ -347,8 +347,8 @@ class Context:
     def otas_timing_kind_names(self) -> List[str]:
         return [self._lib.otas_timing_kind_name(i).decode() for i in range(self._lib.otas_timing_kinds())]
 
-    def otas_splitk_factor(self, M: int, N: int, K: int) -> int:
-        return int(self._lib.otas_splitk_factor(self._h, int(M), int(N), int(K)))
+    def otas_splitk_factor(self, M: int, N: int, K: int, max_split: int = 8) -> int:
+        return int(self._lib.otas_splitk_factor(self._h, int(M), int(N), int(K), int(max_split)))
 
     def otas_set_lanes(self, lanes: int) -> None:
         _check(self._lib.otas_set_lanes(self._h, int(lanes)), "otas_set_lanes")

@@ -799,9 +799,8 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
       // MLP + residual
       OTAS_LAUNCH_ON(K_FC1, s, launch_linear(dt, hbuf, wl.w_fc1, wl.b_fc1, nullptr, hid, Tn, F, D, EPI_GELU, s));
       void* x_next = (l == L - 1) ? (void*)((float*)x_out + (size_t)ln.rowL * D) : x_mlp;
-      int S = splitk_factor(dt, Tn, D, F);
-      S = (int)std::min<int64_t>(S, kPartRows * ln.T[0] / std::max<int64_t>(Tn, 1));
-      if (S > 1 && F % (S * 32) == 0) {
+      const int S = splitk_factor(dt, Tn, D, F, (int)std::min<int64_t>(8, kPartRows * ln.T[0] / std::max<int64_t>(Tn, 1)));
+      if (S > 1) {
         // few tiles, long K: S partial products, then one pass that adds them, the bias and the
         // residual and already applies the next block's first LayerNorm to the row in registers
         float* part = (float*)(ws + w.part) + (size_t)kPartRows * ln.row0 * D;
@@ -1107,8 +1106,8 @@ otas_status otas_set_lanes(otas_ctx* c, int32_t lanes) {
   return OTAS_OK;
 }
 
-int32_t otas_splitk_factor(const otas_ctx* c, int64_t M, int32_t N, int32_t K) {
-  return c ? splitk_factor(c->desc.dtype, M, N, K) : 1;
+int32_t otas_splitk_factor(const otas_ctx* c, int64_t M, int32_t N, int32_t K, int32_t max_split) {
+  return c ? splitk_factor(c->desc.dtype, M, N, K, max_split) : 1;
 }
 
 float otas_timing_overhead_ms(const otas_ctx* c) { return c ? c->ev_overhead_ms : 0.f; }

@@ -721,7 +721,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma128k64_kernel(const bf16_t* _
                                                                  const bf16_t* __restrict__ W,
                                                                  const bf16_t* __restrict__ bias, const float* res,
                                                                  typename OutType<bf16_t, EPI>::type* Y, int64_t M,
-                                                                 int N, int K, int tiles_m, int tiles_n) {
+                                                                 int N, int K, int k_len, int tiles_m, int tiles_n) {
   constexpr int BM = 128, BN = 128, BK = 64, WM = 64, WN = 64, TM = 2, TN = 2;
   constexpr int STAGE = BM * BK;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -749,9 +749,12 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma128k64_kernel(const bf16_t* _
     a_off[j] = (ra * (uint32_t)K + (uint32_t)c * 8u) * (uint32_t)sizeof(bf16_t);
     w_off[j] = (rw * (uint32_t)K + (uint32_t)c * 8u) * (uint32_t)sizeof(bf16_t);
   }
-  const char* a_base = reinterpret_cast<const char*>(A + (size_t)m0 * K);
-  const char* w_base = reinterpret_cast<const char*>(W + (size_t)n0 * K);
-  const int KT = K / BK;
+  // split-K launches: workgroup row blockIdx.y contracts over k_len columns from blockIdx.y * k_len and writes the
+  // float partial result [M, N] number blockIdx.y
+  const char* a_base = reinterpret_cast<const char*>(A + (size_t)m0 * K + (size_t)blockIdx.y * k_len);
+  const char* w_base = reinterpret_cast<const char*>(W + (size_t)n0 * K + (size_t)blockIdx.y * k_len);
+  if (EPI == EPI_PARTIAL) Y += (size_t)blockIdx.y * M * N;
+  const int KT = k_len / BK;
   auto dma_one = [&](int kt, int st, int d) {   // d = 0..7
     const size_t kb = (size_t)((kt < KT ? kt : KT - 1) * BK) * sizeof(bf16_t);
     const int j = d >> 1;
@@ -839,20 +842,22 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma128k64_kernel(const bf16_t* _
 }
 
 static hipError_t linear_mfma128k64(const void* x, const void* w, const void* bias, const float* res, void* y,
-                                    int64_t M, int N, int K, int epi, hipStream_t s) {
+                                    int64_t M, int N, int K, int epi, hipStream_t s, int splits = 1) {
   const int tiles_m = (int)((M + 127) / 128), tiles_n = (N + 127) / 128;
   const size_t lds = (size_t)2 * 2 * 128 * 64 * sizeof(bf16_t);
-  dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
+  dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)splits), block(256);
+  const int k_len = K / splits;
 #define OTAS_MFMA(E)                                                                                              \
   do {                                                                                                            \
     auto kern = gemm_mfma128k64_kernel<E>;                                                                        \
     hipError_t e = set_max_dynamic_lds((const void*)kern, (int)lds);                                              \
     if (e != hipSuccess) return e;                                                                                \
     kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
-                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_m, tiles_n);              \
+                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, k_len, tiles_m, tiles_n);       \
   } while (0)
   if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
   else if (epi == EPI_GELU) OTAS_MFMA(EPI_GELU);
+  else if (epi == EPI_PARTIAL) OTAS_MFMA(EPI_PARTIAL);
   else OTAS_MFMA(EPI_RESIDUAL);
 #undef OTAS_MFMA
   return hipGetLastError();
@@ -879,11 +884,17 @@ static hipError_t linear_mfma_kernel(int kernel, const void* x, const void* w, c
 //     (alpha[epilogue] + beta K) * G(tiles),   G = full rounds + p + (1 - p) * (last round's fill),
 // i.e. whole rounds of S tiles, a partly filled last round costing p of a round plus its share.
 // The choice depends on the shape only, so a shape always runs the same kernel.
-static int pick_mfma_kernel(int64_t M, int N, int K, int epi) {
+static double rounds_cost(double tiles, int slots, double p) {
+  const double full = std::floor(tiles / slots), frac = tiles / slots - full;
+  return full + (frac > 0 ? p + (1.0 - p) * frac : 0.0);
+}
+
+static int pick_mfma_kernel(int64_t M, int N, int K, int epi, double* cost_us = nullptr) {
+  if (cost_us) *cost_us = 0.0;
   // So few outputs that even 64 x 64 tiles do not fill the chip twice: the small-tile kernel (measured on MI355X
   // at K = 768: 197 x 2304 8.3 -> 5.9 us, 788 x 768 9.6 -> 6.4, 2368 x 768 12.1 -> 9.8; from ~470 tiles on it loses,
   // 788 x 3072 11.1 -> 12.9, 3392 x 768 13.2 -> 14.6: it loads twice the operand bytes per FLOP)
-  if (((M + 63) / 64) * ((N + 63) / 64) <= 450) return GK_64X64;
+  if (((M + 63) / 64) * ((N + 63) / 64) <= 450 && !cost_us) return GK_64X64;
   if (K % 64 != 0 || K < 128) return GK_128_K32;
   struct Cand { int id, bm, bn, slots; double alpha[3], beta, p; };
   static const Cand cands[] = {
@@ -897,35 +908,46 @@ static int pick_mfma_kernel(int64_t M, int N, int K, int epi) {
   int kernel = GK_128_K32;
   for (const Cand& c : cands) {
     const double tiles = (double)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
-    const double full = std::floor(tiles / c.slots), frac = tiles / c.slots - full;
-    const double g = full + (frac > 0 ? c.p + (1.0 - c.p) * frac : 0.0);
-    const double cost = (c.alpha[epi == EPI_RESIDUAL ? 2 : epi == EPI_GELU ? 1 : 0] + c.beta * K) * g;
+    const double cost =
+        (c.alpha[epi == EPI_RESIDUAL ? 2 : epi == EPI_GELU ? 1 : 0] + c.beta * K) * rounds_cost(tiles, c.slots, c.p);
     if (cost < best) { best = cost; kernel = c.id; }
   }
+  if (cost_us) *cost_us = best;
   return kernel;
 }
 
 // Split-K for few-tile, long-K products (the MLP's second linear once merging has shrunk the
-// batch): with M * N / 128^2 tiles far below the ~768 workgroups the chip holds, one workgroup per
+// batch): with M * N / 128^2 tiles below the 512 workgroups the chip holds, one workgroup per
 // tile walks the whole K alone and the launch is bound by that serial chain.  S workgroups per tile
 // each contract over K / S and write a float partial result; a second kernel adds the partial
-// results in split order (a fixed order: results are reproducible), the bias and the residual.
-int splitk_factor(int dtype, int64_t M, int N, int K) {
-  if (dtype == 0 || K < 2048 || N % 8 != 0) return 1;
-  const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
-  // measured inside the encoder (K = 3072, N = 768): the partial products' extra traffic pays off
-  // only while one workgroup per tile leaves most CUs idle
-  if (tiles > 170) return 1;
-  static const int cand[] = {8, 6, 4, 3, 2};
-  for (int S : cand)
-    if (K % (S * 64) == 0 && tiles * S <= 768) return S;
-  return 1;
+// results in split order (a fixed order: results are reproducible), the bias and the residual, and
+// applies the LayerNorm that follows -- so the split costs S + 1 more float passes over the
+// output than the one-kernel form followed by its LayerNorm.  S minimises the same cost model as
+// above (partial-output form of the 128 x 128 K-step-64 kernel, fitted to launches of 704 ... 7488
+// rows at N = 768, K = 3072 with S = 2 ... 12, 9 % rms) plus those passes at the rate the reduce
+// kernel reaches inside the encoder.  S never exceeds max_split.
+int splitk_factor(int dtype, int64_t M, int N, int K, int max_split) {
+  if (dtype == 0 || K < 2048 || K % 64 != 0 || N % 8 != 0 || M <= 0) return 1;
+  const double pass_us = (double)M * N * 4.0 / 6.0e6;   // one float pass over the output at 6 TB/s
+  double unsplit;
+  pick_mfma_kernel(M, N, K, EPI_RESIDUAL, &unsplit);
+  double best = unsplit + 1.5 * pass_us;                // + the LayerNorm pass: float in, 16-bit out
+  int S = 1;
+  const double tiles = (double)((M + 127) / 128) * ((N + 127) / 128);
+  static const int cand[] = {2, 3, 4, 6, 8};
+  for (int c : cand) {
+    if (c > max_split || K % (c * 64) != 0 || K / c < 128) continue;
+    const double cost = (6.5 + 0.0153 * (K / c)) * rounds_cost(tiles * c, 512, 0.556) + (c + 2.5) * pass_us;
+    if (cost < best) { best = cost; S = c; }
+  }
+  return S;
 }
 
 hipError_t launch_linear_splitk(const void* x, const void* w, float* part, int64_t M, int N, int K, int S,
                                 hipStream_t s) {
   if (M <= 0) return hipSuccess;
   if (S < 1 || K % (S * 32) != 0 || K / S < 64 || N % 8 != 0) return hipErrorInvalidValue;
+  if (K % (S * 64) == 0 && K / S >= 128) return linear_mfma128k64(x, w, nullptr, nullptr, part, M, N, K, EPI_PARTIAL, s, S);
   return linear_mfma_k32<3, 2>(x, w, nullptr, nullptr, part, M, N, K, EPI_PARTIAL, s, S);
 }
 

@@ -74,7 +74,7 @@ hipError_t launch_linear_kernel(int kernel, int dtype, const void* x, const void
 // launch_linear_splitk writes S float partial products part[S][M][N] of x W^T, each over K / S;
 // launch_splitk_reduce_ln then forms x_out = res + bias + sum_s part[s] (s ascending) and, when
 // y != nullptr, y = LayerNorm(x_out) with gamma g, beta b in bf16 (the next block's first norm).
-int splitk_factor(int dtype, int64_t M, int N, int K);
+int splitk_factor(int dtype, int64_t M, int N, int K, int max_split = 8);
 hipError_t launch_linear_splitk(const void* x, const void* w, float* part, int64_t M, int N, int K, int S,
                                 hipStream_t s);
 hipError_t launch_splitk_reduce_ln(const float* part, int S, const void* bias, const float* res, float* x_out,

@@ -557,28 +557,48 @@ def test_lanes_do_not_change_results(torch_cuda, lib):
 
 
 def test_lanes_bit_identical_full_batch_bf16(torch_cuda, lib):
-    """Full ViT-B batch without merging (no split-K at these row counts): every GEMM kernel variant
-    accumulates over K in the same order, so three lanes running side by side -- different tile
-    shapes per lane, kernels of different lanes sharing CUs -- must reproduce the single-lane result
-    bit for bit.  Guards the kernels' LDS stage reuse against co-resident workgroups."""
+    """Full ViT-B batch without merging.  A lane's kernels are chosen from the lane's row counts, so the
+    rows of every lane of a G-lane run -- different tile shapes per lane, kernels of different lanes
+    sharing CUs -- must equal, bit for bit, a single-lane call on that lane's queries alone; and where no
+    lane splits a product over K (1 and 2 lanes here) the whole result equals the single-lane one.
+    Guards the kernels' LDS stage reuse against co-resident workgroups."""
     import torch
     cfg = synth.config("vitb_plain")
     ctx, layers = hz.make_context(cfg)
     toks, prm, P, R = synth.batch(cfg)
     x0, off = hz.gpu_prepend(ctx, toks, prm)
-    T0 = int(off[-1])
-    assert all(ctx.otas_splitk_factor(T0 // g, cfg.D, cfg.F) == 1 for g in (1, 2, 3))
-    ws = torch.empty(ctx.otas_workspace_bytes(cfg.B, T0), dtype=torch.uint8, device="cuda")
-    outs = []
-    for lanes in (1, 3, 2, 3):
+    off = np.asarray(off, dtype=np.int64)
+    T0, B = int(off[-1]), cfg.B
+    ws = torch.empty(ctx.otas_workspace_bytes(B, T0), dtype=torch.uint8, device="cuda")
+
+    def run(q0, q1, lanes):
         ctx.otas_set_lanes(lanes)
-        x_out = torch.zeros((T0, cfg.D), dtype=torch.float32, device="cuda")
-        sz = torch.zeros(T0, dtype=torch.int32, device="cuda")
-        ctx.otas_encoder_forward(x0, off, R, 0, ws, x_out, sz)
+        r0, r1 = int(off[q0]), int(off[q1])
+        x_out = torch.zeros((r1 - r0, cfg.D), dtype=torch.float32, device="cuda")
+        sz = torch.zeros(r1 - r0, dtype=torch.int32, device="cuda")
+        ctx.otas_encoder_forward(x0[r0:r1].contiguous(), (off[q0:q1 + 1] - r0).astype(np.int32), R[q0:q1], 0, ws, x_out, sz)
         torch.cuda.synchronize()
-        outs.append(x_out)
-    for o in outs[1:]:
-        assert torch.equal(o, outs[0])
+        return x_out
+
+    def lane_ranges(G):   # the rule of otas_set_lanes: lane g ends where the token count reaches T0 (g + 1) / G
+        cuts, q = [0], 0
+        for g in range(G - 1):
+            goal = T0 * (g + 1) // G
+            q += 1
+            while q < B - (G - 1 - g) and off[q] < goal:
+                q += 1
+            cuts.append(q)
+        return list(zip(cuts, cuts[1:] + [B]))
+
+    whole = run(0, B, 1)
+    for G in (3, 2, 3):
+        got = run(0, B, G)
+        ranges = lane_ranges(G)
+        for q0, q1 in ranges:
+            assert torch.equal(got[int(off[q0]):int(off[q1])], run(q0, q1, 1)), (G, q0, q1)
+        if all(ctx.otas_splitk_factor(int(off[q1] - off[q0]), cfg.D, cfg.F, 2) == 1 for q0, q1 in ranges):
+            assert torch.equal(got, whole), G
+    assert ctx.otas_splitk_factor(T0, cfg.D, cfg.F, 2) == 1 and ctx.otas_splitk_factor(T0 // 2, cfg.D, cfg.F, 2) == 1
     ctx.close()
 
 
