@@ -251,7 +251,9 @@ def rooflines(res):
         if fused_plan:
             out["attention"]["includes_merge_plan"] = True
             out["attention"]["note"] = ("these launches also run the layer's merge plan (one kernel, the plan's "
-                                        "workgroups first): the time covers both, the FLOP count attention alone")
+                                        "workgroups first; its list-writing phases move into the projection's launch "
+                                        "where that has workgroup slots to spare): the time covers both, the FLOP "
+                                        "count attention alone")
     if k["merge_apply"][0] > 0:
         a = w["merge_apply_bytes"] / (k["merge_apply"][0] * 1e-3) / 1e9
         out["merge_apply"] = {"bound": "hbm", "achieved": round(a, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",

@@ -752,11 +752,19 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
       // so where the plan stays on this stream and one kernel can hold both (bf16, head width 64), they go out
       // as ONE launch whose first workgroups are the plan's; it is recorded as an attention launch.
       const bool fuse = ln.any_merge[l] && plan_inline && attention_plan_takes(dt, ln.max_n[l], D, H);
+      // Where the projection's launch below has workgroup slots to spare, the fused launch runs only the plan's
+      // selection (the long part: keys, similarities, best matches) and the lists, which need nothing else, are
+      // written by extra workgroups of the projection's launch: the plan's serial chain beside attention gets
+      // shorter by a quarter.  The selection's result waits in the split-K partial buffer, idle between two MLPs.
+      float* sel_best = (float*)(ws + w.part) + (size_t)kPartRows * ln.row0 * D;
+      int32_t* sel_bcol = (int32_t*)(sel_best + T);
+      const bool tail = fuse && linear_plan_tail_fits(T, D, D, Bg);
       if (fuse) {
         OTAS_LAUNCH_ON(K_ATTN, s,
                        launch_attention_plan(qkv, ln.sizes_now, off_l, off_n, d_reff, d_tr, Bg, ln.max_n[l], D, H,
                                              size_bias, n_lead, hbuf, src_list, row_ptr,
-                                             trace ? trace_src : nullptr, trace ? trace_dst : nullptr, s));
+                                             trace ? trace_src : nullptr, trace ? trace_dst : nullptr,
+                                             tail ? sel_best : nullptr, tail ? sel_bcol : nullptr, s));
       } else {
         if (ln.any_merge[l]) {
           // fork: the merge plan reads only the keys just written; the lists it writes were last read by
@@ -778,8 +786,15 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
       // in-place residual is safe (each element is read then written by the same thread); the
       // caller's x0 is never written, so layer 0 writes into the workspace.
       void* x_attn = ln.x_owned ? const_cast<void*>(ln.x_cur) : (void*)x_free[0];
-      OTAS_LAUNCH_ON(K_PROJ, s, launch_linear(dt, hbuf, wl.w_proj, wl.b_proj, (const float*)ln.x_cur, x_attn, T, D, D,
-                                              EPI_RESIDUAL, s));
+      if (tail) {
+        const PlanTail pt{off_l, off_n, d_reff, d_tr, src_list, row_ptr, trace ? trace_src : nullptr,
+                          trace ? trace_dst : nullptr, sel_best, sel_bcol, Bg};
+        OTAS_LAUNCH_ON(K_PROJ, s, launch_linear_plan_tail(hbuf, wl.w_proj, wl.b_proj, (const float*)ln.x_cur, x_attn, T,
+                                                          D, D, pt, ln.max_n[l], s));
+      } else {
+        OTAS_LAUNCH_ON(K_PROJ, s, launch_linear(dt, hbuf, wl.w_proj, wl.b_proj, (const float*)ln.x_cur, x_attn, T, D,
+                                                D, EPI_RESIDUAL, s));
+      }
       void* x_mlp = x_attn;
       // merging module
       if (ln.any_merge[l]) {

@@ -289,7 +289,8 @@ __global__ __launch_bounds__(64 * NW, DH <= 64 ? 4 : 2) void attention_mfma_kern
 
 // Attention and the merge plan of a layer in ONE launch (both only read the layer's QKV projection, and
 // kernels of one stream do not overlap): workgroups 0 .. B-1 of 1024 threads run the plan of query 0 .. B-1
-// (merge_plan_body), the others run attention, each on 16 / NW heads of one (query, row block) side by side.
+// (merge_plan_body; or only its selection, merge_plan_select, when sel_best is given: the lists are then
+// written beside the next launch), the others run attention, each on 16 / NW heads of one (query, row block) side by side.
 // The plan workgroups come first in dispatch order, so their long serial chains start at once and the attention
 // workgroups fill the other CUs.  Head width 64 only (a 1024-thread workgroup leaves 128 registers per lane).
 // grid.x = B + xblks * (H / G) * B with G = 16 / NW.
@@ -299,13 +300,18 @@ __global__ __launch_bounds__(1024) void attention_plan_kernel(
     float scale, bf16_t* __restrict__ o, int B, int xblks, const int32_t* __restrict__ out_off,
     const int32_t* __restrict__ reff_arr, const int32_t* __restrict__ troff, int n_lead,
     int32_t* __restrict__ src_list, int32_t* __restrict__ row_ptr, int32_t* __restrict__ trace_src,
-    int32_t* __restrict__ trace_dst, int unit_lds) {
+    int32_t* __restrict__ trace_dst, float* __restrict__ sel_best, int32_t* __restrict__ sel_bcol, int unit_lds) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int DH = 64, G = 16 / NW;
   if ((int)blockIdx.x < B) {   // workgroup-uniform
-    merge_plan_body<bf16_t, true>(qkv, 3 * (int64_t)D, D, H, DH, off, out_off, reff_arr, troff, n_lead, src_list, row_ptr,
-                                  trace_src, trace_dst, nullptr, reinterpret_cast<float*>(smem), (int)blockIdx.x,
-                                  (int)threadIdx.x);
+    if (sel_best)   // the selection only: the lists are written beside the output projection
+      merge_plan_select<bf16_t, true, true>(qkv, 3 * (int64_t)D, D, H, DH, off, reff_arr, n_lead, nullptr,
+                                            reinterpret_cast<float*>(smem), sel_best, sel_bcol, (int)blockIdx.x,
+                                            (int)threadIdx.x);
+    else
+      merge_plan_body<bf16_t, true>(qkv, 3 * (int64_t)D, D, H, DH, off, out_off, reff_arr, troff, n_lead, src_list,
+                                    row_ptr, trace_src, trace_dst, nullptr, reinterpret_cast<float*>(smem),
+                                    (int)blockIdx.x, (int)threadIdx.x);
     return;
   }
   int id = (int)blockIdx.x - B;
@@ -365,9 +371,11 @@ bool attention_plan_takes(int dtype, int max_n, int D, int H) {
 hipError_t launch_attention_plan(const void* qkv, const int32_t* sizes, const int32_t* d_off, const int32_t* d_out_off,
                                  const int32_t* d_reff, const int32_t* d_troff, int B, int max_n, int D, int H,
                                  bool size_bias, int n_lead, void* o, int32_t* src_list, int32_t* row_ptr,
-                                 int32_t* trace_src, int32_t* trace_dst, hipStream_t s) {
+                                 int32_t* trace_src, int32_t* trace_dst, float* sel_best, int32_t* sel_bcol,
+                                 hipStream_t s) {
   if (B <= 0 || max_n <= 0) return hipSuccess;
-  if (H <= 0 || D != 64 * H || max_n > kPlanThreads) return hipErrorInvalidValue;
+  if (H <= 0 || D != 64 * H || max_n > kPlanThreads || (sel_best == nullptr) != (sel_bcol == nullptr))
+    return hipErrorInvalidValue;
   const size_t plan_lds = merge_plan_lds_bytes(max_n, 64);
   if (plan_lds > 160 * 1024) return hipErrorInvalidValue;
   const float scale = 1.0f / sqrtf(64.0f);
@@ -386,7 +394,8 @@ hipError_t launch_attention_plan(const void* qkv, const int32_t* sizes, const in
     const int xblks = (max_n + 32 * NWV - 1) / (32 * NWV);                                                        \
     dim3 grid((unsigned)(B + xblks * (H / G) * B)), block(1024);                                                  \
     kern<<<grid, block, lds, s>>>((const bf16_t*)qkv, sz, d_off, D, H, scale, (bf16_t*)o, B, xblks, d_out_off,    \
-                                  d_reff, d_troff, n_lead, src_list, row_ptr, trace_src, trace_dst, (int)unit);   \
+                                  d_reff, d_troff, n_lead, src_list, row_ptr, trace_src, trace_dst, sel_best,     \
+                                  sel_bcol, (int)unit);                                                           \
   } while (0)
   if (max_n > 128 && max_n <= 256) {
     if (sz) OTAS_FUSED(true, 256, 8); else OTAS_FUSED(false, 256, 8);

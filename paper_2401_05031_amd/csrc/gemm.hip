@@ -17,6 +17,7 @@
 
 #include "common.h"
 #include "kernels.h"
+#include "merge_plan_body.h"
 
 namespace otas {
 
@@ -277,6 +278,25 @@ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int& til
 #define OTAS_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 
+// The list phases of the merge plan inside a GEMM launch (PLAN variants of the kernels below): the launch's first
+// pt.B workgroups each write the lists of one query and leave; the others compute tiles as if those did not exist.
+// The attention output projection runs this way: the lists depend on the selection made beside attention one
+// launch earlier, and the projection leaves CUs idle at the batch sizes this matters for.
+template <int NT>
+__device__ __forceinline__ void plan_tail_run(const PlanTail& pt, unsigned char* smem, int q, int tid) {
+  merge_plan_lists<NT, true>(reinterpret_cast<float*>(smem), pt.best, pt.bcol, pt.in_off, pt.out_off, pt.reff, pt.troff,
+                             pt.src_list, pt.row_ptr, pt.trace_src, pt.trace_dst, q, tid);
+}
+#define OTAS_PLAN_TAIL_OR_TILE(NT)                          \
+  int bid = (int)blockIdx.x;                                \
+  if constexpr (PLAN) {                                     \
+    if (bid < pt.B) {                                       \
+      plan_tail_run<NT>(pt, smem, bid, (int)threadIdx.x);   \
+      return;                                               \
+    }                                                       \
+    bid -= pt.B;                                            \
+  }
+
 // ------------------------------------------------------------------------------ (64 TM) x 128, K step 32
 // Four waves in a 2 x 2 arrangement, each owning (32 TM) x 64 outputs; block tile (64 TM) x 128.  The
 // library runs TM = 2 (128 rows, three workgroups per CU); TM = 3 and 4 (192 / 256 rows, two per CU)
@@ -290,10 +310,11 @@ __device__ inline void tile_of_block(int bid, int tiles_m, int tiles_n, int& til
 //   iteration t: wait for this wave's loads of tile t, barrier, start the loads of tile t+NS-1 into
 //                the stage tile t-1 used, then the two k-steps of tile t (fragment reads of the
 //                second step are issued between the MFMAs of the first).
-template <int EPI, int NS, int TM>
+template <int EPI, int NS, int TM, bool PLAN = false>
 __global__ __launch_bounds__(256, TM == 2 ? 3 : 2) void gemm_mfma_k32_kernel(
     const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, const bf16_t* __restrict__ bias, const float* res,
-    typename OutType<bf16_t, EPI>::type* Y, int64_t M, int N, int K, int k_len, int tiles_m, int tiles_n) {
+    typename OutType<bf16_t, EPI>::type* Y, int64_t M, int N, int K, int k_len, int tiles_m, int tiles_n,
+    PlanTail pt) {
   // K is the row length of A and W; this workgroup contracts over k_len of it, starting at
   // blockIdx.y * k_len (split-K launches write one float partial result [M, N] per blockIdx.y).
   constexpr int WM = 32 * TM, BM = 2 * WM, BN = 128, BK = 32, WN = 64, TN = 2;
@@ -307,7 +328,8 @@ __global__ __launch_bounds__(256, TM == 2 ? 3 : 2) void gemm_mfma_k32_kernel(
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: LDS addresses of the DMA stay scalar
   const int wm = wave >> 1, wn = wave & 1;
   int tile_m, tile_n;
-  tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  OTAS_PLAN_TAIL_OR_TILE(256)
+  tile_of_block(bid, tiles_m, tiles_n, tile_m, tile_n);
   const int64_t m0 = (int64_t)tile_m * BM;
   const int n0 = tile_n * BN;
 
@@ -412,22 +434,28 @@ __global__ __launch_bounds__(256, TM == 2 ? 3 : 2) void gemm_mfma_k32_kernel(
 
 template <int NS, int TM>
 static hipError_t linear_mfma_k32(const void* x, const void* w, const void* bias, const float* res, void* y,
-                                  int64_t M, int N, int K, int epi, hipStream_t s, int splits = 1) {
+                                  int64_t M, int N, int K, int epi, hipStream_t s, int splits = 1,
+                                  const PlanTail* pt = nullptr) {
   constexpr int BM = 64 * TM;
   const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + 127) / 128;
   const size_t lds = (size_t)NS * (BM + 128) * 32 * sizeof(bf16_t);
   static_assert(4 * 32 * (64 + 4) * sizeof(float) <= (size_t)NS * (BM + 128) * 32 * sizeof(bf16_t), "epilogue slab");
-  dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)splits), block(256);
+  static_assert(kPlanListsLdsMax <= (size_t)NS * (BM + 128) * 32 * sizeof(bf16_t), "plan lists");
+  dim3 grid((unsigned)(tiles_m * tiles_n + (pt ? pt->B : 0)), (unsigned)splits), block(256);
   const int k_len = K / splits;
-#define OTAS_MFMA(E)                                                                                              \
+#define OTAS_MFMA(E, ...)                                                                                         \
   do {                                                                                                            \
-    auto kern = gemm_mfma_k32_kernel<E, NS, TM>;                                                                  \
+    auto kern = gemm_mfma_k32_kernel<E, NS, TM, ##__VA_ARGS__>;                                                   \
     hipError_t e = set_max_dynamic_lds((const void*)kern, (int)lds);                                              \
     if (e != hipSuccess) return e;                                                                                \
     kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
-                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, k_len, tiles_m, tiles_n);       \
+                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, k_len, tiles_m, tiles_n,        \
+                                  pt ? *pt : PlanTail{});                                                         \
   } while (0)
-  if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
+  if (pt) {
+    if (epi != EPI_RESIDUAL || splits != 1) return hipErrorInvalidValue;
+    OTAS_MFMA(EPI_RESIDUAL, true);
+  } else if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
   else if (epi == EPI_GELU) OTAS_MFMA(EPI_GELU);
   else if (epi == EPI_PARTIAL) OTAS_MFMA(EPI_PARTIAL);
   else OTAS_MFMA(EPI_RESIDUAL);
@@ -441,11 +469,11 @@ static hipError_t linear_mfma_k32(const void* x, const void* w, const void* bias
 // direct-to-LDS ring as gemm_mfma_k32_kernel with NS = 4 stages of 8 KB (up to five workgroups per CU).  Four times
 // the workgroups of the 128 x 128 tiling at twice the operand bytes per FLOP: it wins while the launch is bound by
 // the serial k-loop of a lone workgroup per CU, not by what the CUs can load.
-template <int EPI>
+template <int EPI, bool PLAN = false>
 __global__ __launch_bounds__(256, 4) void gemm_mfma64_kernel(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W,
                                                              const bf16_t* __restrict__ bias, const float* res,
                                                              typename OutType<bf16_t, EPI>::type* Y, int64_t M, int N,
-                                                             int K, int tiles_m, int tiles_n) {
+                                                             int K, int tiles_m, int tiles_n, PlanTail pt) {
   constexpr int BM = 64, BN = 64, BK = 32, NS = 4, ND = 2;
   constexpr int STAGE_A = BM * BK, STAGE_W = BN * BK;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -455,7 +483,8 @@ __global__ __launch_bounds__(256, 4) void gemm_mfma64_kernel(const bf16_t* __res
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   int tile_m, tile_n;
-  tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  OTAS_PLAN_TAIL_OR_TILE(256)
+  tile_of_block(bid, tiles_m, tiles_n, tile_m, tile_n);
   const int64_t m0 = (int64_t)tile_m * BM;
   const int n0 = tile_n * BN;
   // DMA: 16 rows of 64 B per instruction; wave w loads rows 16 w .. of the A tile and of the W tile
@@ -516,18 +545,22 @@ __global__ __launch_bounds__(256, 4) void gemm_mfma64_kernel(const bf16_t* __res
 }
 
 static hipError_t linear_mfma64(const void* x, const void* w, const void* bias, const float* res, void* y, int64_t M,
-                                int N, int K, int epi, hipStream_t s) {
+                                int N, int K, int epi, hipStream_t s, const PlanTail* pt = nullptr) {
   const int tiles_m = (int)((M + 63) / 64), tiles_n = (N + 63) / 64;
   const size_t lds = (size_t)4 * (64 + 64) * 32 * sizeof(bf16_t);
   static_assert(4 * 32 * (32 + 4) * sizeof(float) <= (size_t)4 * (64 + 64) * 32 * sizeof(bf16_t), "epilogue slab");
-  dim3 grid((unsigned)(tiles_m * tiles_n)), block(256);
-#define OTAS_MFMA(E)                                                                                              \
+  static_assert(kPlanListsLdsMax <= (size_t)4 * (64 + 64) * 32 * sizeof(bf16_t), "plan lists");
+  dim3 grid((unsigned)(tiles_m * tiles_n + (pt ? pt->B : 0))), block(256);
+#define OTAS_MFMA(E, ...)                                                                                         \
   do {                                                                                                            \
-    gemm_mfma64_kernel<E><<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,  \
-                                                   (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_m,       \
-                                                   tiles_n);                                                      \
+    gemm_mfma64_kernel<E, ##__VA_ARGS__><<<grid, block, lds, s>>>(                                                \
+        (const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res, (typename OutType<bf16_t, E>::type*)y, M,   \
+        N, K, tiles_m, tiles_n, pt ? *pt : PlanTail{});                                                           \
   } while (0)
-  if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
+  if (pt) {
+    if (epi != EPI_RESIDUAL) return hipErrorInvalidValue;
+    OTAS_MFMA(EPI_RESIDUAL, true);
+  } else if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
   else if (epi == EPI_GELU) OTAS_MFMA(EPI_GELU);
   else OTAS_MFMA(EPI_RESIDUAL);
 #undef OTAS_MFMA
@@ -549,12 +582,12 @@ static hipError_t linear_mfma64(const void* x, const void* w, const void* bias, 
 // The tile height is a template parameter: BM = 64 TM rows (TM = 3, 4, 5: 192, 256, 320) by 256
 // columns.  Whole rounds of one workgroup per CU are what this kernel costs, so the launcher picks
 // the height whose tile count wastes the least of the last round.
-template <int EPI, int TM>
+template <int EPI, int TM, bool PLAN = false>
 __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __restrict__ A,
                                                                 const bf16_t* __restrict__ W,
                                                                 const bf16_t* __restrict__ bias, const float* res,
                                                                 typename OutType<bf16_t, EPI>::type* Y, int64_t M,
-                                                                int N, int K, int tiles_m, int tiles_n) {
+                                                                int N, int K, int tiles_m, int tiles_n, PlanTail pt) {
   constexpr int WM = 32 * TM, BM = 2 * WM, BN = 256, BK = 64, WN = 64, TN = 2, NS = 2;
   constexpr int STAGE_A = BM * BK, STAGE_W = BN * BK;
   constexpr int NA = BM / 64;   // DMA instructions per wave for the A tile (8 rows each), 4 for W
@@ -567,7 +600,8 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: LDS addresses of the DMA stay scalar
   const int wm = wave >> 2, wn = wave & 3;
   int tile_m, tile_n;
-  tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  OTAS_PLAN_TAIL_OR_TILE(512)
+  tile_of_block(bid, tiles_m, tiles_n, tile_m, tile_n);
   const int64_t m0 = (int64_t)tile_m * BM;
   const int n0 = tile_n * BN;
 
@@ -691,20 +725,24 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma256w8_kernel(const bf16_t* __
 
 template <int TM>
 static hipError_t linear_mfma256w8(const void* x, const void* w, const void* bias, const float* res, void* y,
-                                   int64_t M, int N, int K, int epi, hipStream_t s) {
+                                   int64_t M, int N, int K, int epi, hipStream_t s, const PlanTail* pt = nullptr) {
   constexpr int BM = 64 * TM;
   const int tiles_m = (int)((M + BM - 1) / BM), tiles_n = (N + 255) / 256;
   const size_t lds = (size_t)2 * (BM + 256) * 64 * sizeof(bf16_t);
-  dim3 grid((unsigned)(tiles_m * tiles_n)), block(512);
-#define OTAS_MFMA(E)                                                                                              \
+  dim3 grid((unsigned)(tiles_m * tiles_n + (pt ? pt->B : 0))), block(512);
+#define OTAS_MFMA(E, ...)                                                                                         \
   do {                                                                                                            \
-    auto kern = gemm_mfma256w8_kernel<E, TM>;                                                                     \
+    auto kern = gemm_mfma256w8_kernel<E, TM, ##__VA_ARGS__>;                                                      \
     hipError_t e = set_max_dynamic_lds((const void*)kern, (int)lds);                                              \
     if (e != hipSuccess) return e;                                                                                \
     kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
-                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_m, tiles_n);              \
+                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, tiles_m, tiles_n,               \
+                                  pt ? *pt : PlanTail{});                                                         \
   } while (0)
-  if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
+  if (pt) {
+    if (epi != EPI_RESIDUAL) return hipErrorInvalidValue;
+    OTAS_MFMA(EPI_RESIDUAL, true);
+  } else if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
   else if (epi == EPI_GELU) OTAS_MFMA(EPI_GELU);
   else OTAS_MFMA(EPI_RESIDUAL);
 #undef OTAS_MFMA
@@ -716,12 +754,13 @@ static hipError_t linear_mfma256w8(const void* x, const void* w, const void* bia
 // lines, 64 KB in all, two workgroups per CU).  Same per-tile protocol as gemm_mfma256w8_kernel:
 // k-steps 0..2, wait for the next tile + barrier, k-step 3 while the loads of the tile after next
 // are issued into the stage just freed.
-template <int EPI>
+template <int EPI, bool PLAN = false>
 __global__ __launch_bounds__(256, 2) void gemm_mfma128k64_kernel(const bf16_t* __restrict__ A,
                                                                  const bf16_t* __restrict__ W,
                                                                  const bf16_t* __restrict__ bias, const float* res,
                                                                  typename OutType<bf16_t, EPI>::type* Y, int64_t M,
-                                                                 int N, int K, int k_len, int tiles_m, int tiles_n) {
+                                                                 int N, int K, int k_len, int tiles_m, int tiles_n,
+                                                                 PlanTail pt) {
   constexpr int BM = 128, BN = 128, BK = 64, WM = 64, WN = 64, TM = 2, TN = 2;
   constexpr int STAGE = BM * BK;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -732,7 +771,8 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma128k64_kernel(const bf16_t* _
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: LDS addresses of the DMA stay scalar
   const int wm = wave >> 1, wn = wave & 1;
   int tile_m, tile_n;
-  tile_of_block(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  OTAS_PLAN_TAIL_OR_TILE(256)
+  tile_of_block(bid, tiles_m, tiles_n, tile_m, tile_n);
   const int64_t m0 = (int64_t)tile_m * BM;
   const int n0 = tile_n * BN;
 
@@ -842,20 +882,25 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma128k64_kernel(const bf16_t* _
 }
 
 static hipError_t linear_mfma128k64(const void* x, const void* w, const void* bias, const float* res, void* y,
-                                    int64_t M, int N, int K, int epi, hipStream_t s, int splits = 1) {
+                                    int64_t M, int N, int K, int epi, hipStream_t s, int splits = 1,
+                                    const PlanTail* pt = nullptr) {
   const int tiles_m = (int)((M + 127) / 128), tiles_n = (N + 127) / 128;
   const size_t lds = (size_t)2 * 2 * 128 * 64 * sizeof(bf16_t);
-  dim3 grid((unsigned)(tiles_m * tiles_n), (unsigned)splits), block(256);
+  dim3 grid((unsigned)(tiles_m * tiles_n + (pt ? pt->B : 0)), (unsigned)splits), block(256);
   const int k_len = K / splits;
-#define OTAS_MFMA(E)                                                                                              \
+#define OTAS_MFMA(E, ...)                                                                                         \
   do {                                                                                                            \
-    auto kern = gemm_mfma128k64_kernel<E>;                                                                        \
+    auto kern = gemm_mfma128k64_kernel<E, ##__VA_ARGS__>;                                                         \
     hipError_t e = set_max_dynamic_lds((const void*)kern, (int)lds);                                              \
     if (e != hipSuccess) return e;                                                                                \
     kern<<<grid, block, lds, s>>>((const bf16_t*)x, (const bf16_t*)w, (const bf16_t*)bias, res,                   \
-                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, k_len, tiles_m, tiles_n);       \
+                                  (typename OutType<bf16_t, E>::type*)y, M, N, K, k_len, tiles_m, tiles_n,        \
+                                  pt ? *pt : PlanTail{});                                                         \
   } while (0)
-  if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
+  if (pt) {
+    if (epi != EPI_RESIDUAL || splits != 1) return hipErrorInvalidValue;
+    OTAS_MFMA(EPI_RESIDUAL, true);
+  } else if (epi == EPI_NONE) OTAS_MFMA(EPI_NONE);
   else if (epi == EPI_GELU) OTAS_MFMA(EPI_GELU);
   else if (epi == EPI_PARTIAL) OTAS_MFMA(EPI_PARTIAL);
   else OTAS_MFMA(EPI_RESIDUAL);
@@ -865,15 +910,16 @@ static hipError_t linear_mfma128k64(const void* x, const void* w, const void* bi
 
 // Runs one named kernel (gemm_kernel_id in kernels.h); hipErrorInvalidValue if it does not take the shape.
 static hipError_t linear_mfma_kernel(int kernel, const void* x, const void* w, const void* bias, const float* res,
-                                     void* y, int64_t M, int N, int K, int epi, hipStream_t s) {
+                                     void* y, int64_t M, int N, int K, int epi, hipStream_t s,
+                                     const PlanTail* pt = nullptr) {
   const bool k32 = K % 32 == 0 && K >= 64, k64 = K % 64 == 0 && K >= 128;
   switch (kernel) {
-    case GK_128_K32: return k32 ? linear_mfma_k32<3, 2>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
-    case GK_128_K64: return k64 ? linear_mfma128k64(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
-    case GK_192X256: return k64 ? linear_mfma256w8<3>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
-    case GK_256X256: return k64 ? linear_mfma256w8<4>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
-    case GK_320X256: return k64 ? linear_mfma256w8<5>(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
-    case GK_64X64: return k32 ? linear_mfma64(x, w, bias, res, y, M, N, K, epi, s) : hipErrorInvalidValue;
+    case GK_128_K32: return k32 ? linear_mfma_k32<3, 2>(x, w, bias, res, y, M, N, K, epi, s, 1, pt) : hipErrorInvalidValue;
+    case GK_128_K64: return k64 ? linear_mfma128k64(x, w, bias, res, y, M, N, K, epi, s, 1, pt) : hipErrorInvalidValue;
+    case GK_192X256: return k64 ? linear_mfma256w8<3>(x, w, bias, res, y, M, N, K, epi, s, pt) : hipErrorInvalidValue;
+    case GK_256X256: return k64 ? linear_mfma256w8<4>(x, w, bias, res, y, M, N, K, epi, s, pt) : hipErrorInvalidValue;
+    case GK_320X256: return k64 ? linear_mfma256w8<5>(x, w, bias, res, y, M, N, K, epi, s, pt) : hipErrorInvalidValue;
+    case GK_64X64: return k32 ? linear_mfma64(x, w, bias, res, y, M, N, K, epi, s, pt) : hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }
 }
@@ -958,6 +1004,32 @@ hipError_t launch_linear(int dtype, const void* x, const void* w, const void* bi
   if (K % 32 == 0 && K >= 64 && N % 8 == 0)
     return linear_mfma_kernel(pick_mfma_kernel(M, N, K, epi), x, w, bias, res, y, M, N, K, epi, s);
   return linear_valu<bf16_t>(x, w, bias, res, y, M, N, K, epi, s);
+}
+
+// Whether the projection's launch has workgroup slots to spare for B list workgroups: they take a slot each (a
+// launch's dynamic LDS is the same for all its workgroups), so beside a launch that fills its last round they would
+// cost a round of their own (measured: + 5 us on such launches, what the selection-only plan saves beside attention).
+bool linear_plan_tail_fits(int64_t M, int N, int K, int B) {
+  if (M <= 0 || B <= 0 || !(K % 32 == 0 && K >= 64 && N % 8 == 0)) return false;
+  int bm = 128, bn = 128, slots = 768;
+  switch (pick_mfma_kernel(M, N, K, EPI_RESIDUAL)) {
+    case GK_128_K64: slots = 512; break;
+    case GK_192X256: bm = 192; bn = 256; slots = 256; break;
+    case GK_256X256: bm = 256; bn = 256; slots = 256; break;
+    case GK_320X256: bm = 320; bn = 256; slots = 256; break;
+    case GK_64X64: bm = 64; bn = 64; slots = 1024; break;
+    default: break;
+  }
+  const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn);
+  return tiles % slots + B <= slots && tiles % slots != 0;
+}
+
+hipError_t launch_linear_plan_tail(const void* x, const void* w, const void* bias, const float* res, void* y,
+                                   int64_t M, int N, int K, const PlanTail& tail, int max_n, hipStream_t s) {
+  if (M <= 0 || tail.B <= 0 || max_n > kPlanThreads || plan_lists_lds_bytes(max_n) > kPlanListsLdsMax ||
+      !(K % 32 == 0 && K >= 64 && N % 8 == 0))
+    return hipErrorInvalidValue;
+  return linear_mfma_kernel(pick_mfma_kernel(M, N, K, EPI_RESIDUAL), x, w, bias, res, y, M, N, K, EPI_RESIDUAL, s, &tail);
 }
 
 int linear_kernel_choice(int dtype, int64_t M, int N, int K, int epi) {

@@ -88,11 +88,31 @@ hipError_t launch_attention(int dtype, const void* qkv, const int32_t* sizes,
 // Attention and the merge plan of one layer in a single launch (bf16 models of head width 64 whose queries all
 // fit the plan's LDS form; the plan's metric is the head mean of the keys in qkv).  Returns
 // hipErrorInvalidValue, having launched nothing, for every other case.
+// With sel_best / sel_bcol (device, one entry per packed token row) the launch runs only the plan's selection
+// (every A token's best match) and leaves it there; the lists are then written by the first B workgroups of
+// launch_linear_plan_tail, beside the attention output projection.  With both NULL it runs the whole plan.
 bool attention_plan_takes(int dtype, int max_n, int D, int H);
 hipError_t launch_attention_plan(const void* qkv, const int32_t* sizes, const int32_t* d_off, const int32_t* d_out_off,
                                  const int32_t* d_reff, const int32_t* d_troff, int B, int max_n, int D, int H,
                                  bool size_bias, int n_lead, void* o, int32_t* src_list, int32_t* row_ptr,
-                                 int32_t* trace_src, int32_t* trace_dst, hipStream_t s);
+                                 int32_t* trace_src, int32_t* trace_dst, float* sel_best, int32_t* sel_bcol,
+                                 hipStream_t s);
+
+// What the list phases of the merge plan (merge_plan_lists) need when they run inside another kernel's launch.
+struct PlanTail {
+  const int32_t *in_off, *out_off, *reff, *troff;   // device: per-query offsets in / out, r_eff, trace offsets
+  int32_t *src_list, *row_ptr, *trace_src, *trace_dst;
+  const float* best;                                // the selection's result, one entry per packed token row
+  const int32_t* bcol;
+  int B;                                            // queries = leading workgroups that run the lists
+};
+// y = x W^T + bias + res (bf16 operands, float residual in and out) as launch_linear with EPI_RESIDUAL, and in
+// the same launch the list phases of the merge plan for tail.B queries of at most max_n tokens.
+// hipErrorInvalidValue, having launched nothing, when no MFMA kernel takes the shape.  linear_plan_tail_fits: whether
+// the launch's last round has B workgroup slots to spare (pure host); if not, the lists are better written elsewhere.
+bool linear_plan_tail_fits(int64_t M, int N, int K, int B);
+hipError_t launch_linear_plan_tail(const void* x, const void* w, const void* bias, const float* res, void* y,
+                                   int64_t M, int N, int K, const PlanTail& tail, int max_n, hipStream_t s);
 
 // The metric of token i is the mean over H heads of src[i * row_stride + col_off + h * dm + c]
 // (dtype = type of src), normalised to unit length inside the kernel.  The kernel keeps a query's unit

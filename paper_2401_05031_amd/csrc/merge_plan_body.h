@@ -1,6 +1,10 @@
-// The plan of the merging module (Sec. II-C) for one query, as a device function that a workgroup of
-// kPlanThreads threads executes: used by merge_plan_kernel (one workgroup per query) and by the kernel that
-// runs the plan beside attention in one launch.
+// The plan of the merging module (Sec. II-C) for one query, as device functions that a workgroup executes:
+//   merge_plan_select  phases 0-2: head-mean metric, unit length, every A token's most similar B token
+//                      (kPlanThreads threads)
+//   merge_plan_lists   phases 3-5: the r best edges, list slots, scans, the lists (any multiple of 64 threads)
+//   merge_plan_body    both, one after the other (kPlanThreads threads)
+// Used by merge_plan_kernel (one workgroup per query runs the whole plan), by the kernel that runs the selection
+// beside attention in one launch, and by the GEMM kernels that run the list phases beside the projection.
 #ifndef OTAS_MERGE_PLAN_BODY_H_
 #define OTAS_MERGE_PLAN_BODY_H_
 
@@ -16,8 +20,15 @@ template <typename T> struct alignas(8 * sizeof(T)) Oct { T x[8]; };    // 8 con
 // LDS layout of the plan kernel (4-byte words), n = query length, nA = ceil(n/2), nB = floor(n/2):
 //   mh [n][dm+4] normalised metric rows | best [nA] | bcol [nA] | merged [nA] | cnt [nB] |
 //   keep_pos [n] | ent_pos [n] | wave_tot [2][16] | part_v [512] | part_c [512]
+// (the list phases on their own use the part from best on, without part_v / part_c).
 // Floats per metric row in LDS: the even and the odd columns each padded to a multiple of 4, plus 4.
-static inline int plan_row_floats(int dm) { return 2 * (((dm >> 1) + 3) & ~3) + 4; }
+__host__ __device__ static inline int plan_row_floats(int dm) { return 2 * (((dm >> 1) + 3) & ~3) + 4; }
+// Bytes of LDS the list phases need for a query of up to max_n tokens, and that for the longest query there is.
+static inline size_t plan_lists_lds_bytes(int max_n) {
+  const size_t nA = (max_n + 1) / 2, nB = max_n / 2;
+  return 4 * (3 * nA + nB + 2 * (size_t)max_n + 32);
+}
+constexpr size_t kPlanListsLdsMax = 4 * (3 * 512 + 512 + 2 * 1024 + 32);
 
 // One workgroup of 1024 threads per query (q; tid = thread index in the workgroup; lds: its dynamic LDS).
 // src: the vectors the similarity is taken on; the metric of token i is the mean over H heads of src[(i0 + i) * row_stride + col_off + h * dm + c] (H = 1 for
@@ -26,23 +37,17 @@ static inline int plan_row_floats(int dm) { return 2 * (((dm >> 1) + 3) & ~3) + 
 // ROWS_IN_LDS = false: the metric rows of the query live in global memory (rows + i0 * ldm: the
 // query's own rows of a [T][ldm] float buffer; written and read by this workgroup only, between its
 // barriers) instead of LDS, for queries whose rows do not fit the 160 KB; same arithmetic, same order.
-template <typename T, bool ROWS_IN_LDS>
-__device__ __forceinline__ void merge_plan_body(
+// TO_GLOBAL = false: the result (best[a] = similarity of A token a's best match, -inf for a protected leading
+// token; bcol[a] = that B token) stays in LDS behind the metric rows, valid for every thread on return.
+// TO_GLOBAL = true: it goes to g_best[i0 + a], g_bcol[i0 + a] (a < nA) for merge_plan_lists in a later launch.
+// Queries with nothing to merge return at once.
+template <typename T, bool ROWS_IN_LDS, bool TO_GLOBAL>
+__device__ __forceinline__ void merge_plan_select(
     const T* __restrict__ src, int64_t row_stride, int col_off, int H, int dm, const int32_t* __restrict__ in_off,
-    const int32_t* __restrict__ out_off, const int32_t* __restrict__ reff_arr, const int32_t* __restrict__ troff,
-    int n_lead, int32_t* __restrict__ src_list, int32_t* __restrict__ row_ptr, int32_t* __restrict__ trace_src,
-    int32_t* __restrict__ trace_dst, float* rows, float* lds, const int q, const int tid) {
-
-  const int i0 = in_off[q], n = in_off[q + 1] - i0, o0 = out_off[q];
-  const int r_eff = reff_arr[q];
-  if (n <= 0) return;
-  if (r_eff <= 0) {  // nothing merges: every output row is its own single source
-    for (int i = tid; i < n; i += kPlanThreads) {
-      row_ptr[o0 + i] = i0 + i;
-      src_list[i0 + i] = i0 + i;
-    }
-    return;
-  }
+    const int32_t* __restrict__ reff_arr, int n_lead, float* rows, float* lds, float* __restrict__ g_best,
+    int32_t* __restrict__ g_bcol, const int q, const int tid) {
+  const int i0 = in_off[q], n = in_off[q + 1] - i0;
+  if (n <= 0 || reff_arr[q] <= 0) return;
   const int half = dm >> 1, hp = (half + 3) & ~3;   // columns per parity, and their padded count
   const int nA = (n + 1) >> 1, nB = n >> 1, ldm = 2 * hp + 4;
   // Metric rows in LDS: the A tokens (even positions) first, then the B tokens, one row of ldm
@@ -62,11 +67,7 @@ __device__ __forceinline__ void merge_plan_body(
     best = lds;
   }
   int* bcol = (int*)(best + nA);
-  int* merged = bcol + nA;
-  int* cnt = merged + nA;
-  int* keep_pos = cnt + nB;      // [n] exclusive scan of "row survives"
-  int* ent_pos = keep_pos + n;   // [n] exclusive scan of list lengths
-  int* wave_tot = ent_pos + n;   // [2][16]
+  int* wave_tot = bcol + 2 * nA + nB + 2 * n;   // behind merged, cnt, keep_pos, ent_pos of the list phases
   auto row_of = [&](int i) { return mh + (size_t)((i & 1) ? nA + (i >> 1) : (i >> 1)) * ldm; };
 
   // Phase 0: head-mean metric rows, heads summed in ascending order.  A thread takes 8 columns of a token when the
@@ -214,17 +215,61 @@ __device__ __forceinline__ void merge_plan_body(
       const int c = part_c[g * (nAb * 32) + a];
       if (v > bv || (v == bv && c < bc)) { bv = v; bc = c; }
     }
-    best[a] = (2 * a < n_lead) ? -INFINITY : bv;   // protected leading token: never a merge source
-    bcol[a] = bc;
+    const float v = (2 * a < n_lead) ? -INFINITY : bv;   // protected leading token: never a merge source
+    if constexpr (TO_GLOBAL) {
+      g_best[i0 + a] = v;
+      g_bcol[i0 + a] = bc;
+    } else {
+      best[a] = v;
+      bcol[a] = bc;
+    }
   }
-  __syncthreads();
+  if constexpr (!TO_GLOBAL) __syncthreads();
+}
+
+// The list phases for query q by a workgroup of NT threads (a multiple of 64, at most 1024).  small: LDS for
+// best [nA] | bcol [nA] | merged [nA] | cnt [nB] | keep_pos [n] | ent_pos [n] | wave_tot [32] (4-byte words).
+// FROM_GLOBAL = false: best / bcol are already there (merge_plan_select in the same workgroup);
+// true: they are read from g_best / g_bcol [i0 + a].  Integer work only, apart from comparisons of the
+// similarities: the result does not depend on NT.
+template <int NT, bool FROM_GLOBAL>
+__device__ __forceinline__ void merge_plan_lists(
+    float* small, const float* __restrict__ g_best, const int32_t* __restrict__ g_bcol,
+    const int32_t* __restrict__ in_off, const int32_t* __restrict__ out_off, const int32_t* __restrict__ reff_arr,
+    const int32_t* __restrict__ troff, int32_t* __restrict__ src_list, int32_t* __restrict__ row_ptr,
+    int32_t* __restrict__ trace_src, int32_t* __restrict__ trace_dst, const int q, const int tid) {
+  const int i0 = in_off[q], n = in_off[q + 1] - i0, o0 = out_off[q];
+  const int r_eff = reff_arr[q];
+  if (n <= 0) return;
+  if (r_eff <= 0) {  // nothing merges: every output row is its own single source
+    for (int i = tid; i < n; i += NT) {
+      row_ptr[o0 + i] = i0 + i;
+      src_list[i0 + i] = i0 + i;
+    }
+    return;
+  }
+  const int nA = (n + 1) >> 1, nB = n >> 1;
+  float* best = small;
+  int* bcol = (int*)(best + nA);
+  int* merged = bcol + nA;
+  int* cnt = merged + nA;
+  int* keep_pos = cnt + nB;      // [n] exclusive scan of "row survives"
+  int* ent_pos = keep_pos + n;   // [n] exclusive scan of list lengths
+  int* wave_tot = ent_pos + n;   // [2][16]
+  if constexpr (FROM_GLOBAL) {
+    for (int a = tid; a < nA; a += NT) {
+      best[a] = g_best[i0 + a];
+      bcol[a] = g_bcol[i0 + a];
+    }
+    __syncthreads();
+  }
 
   // Phase 3: keep the r_eff best edges.  rank = number of A tokens that come before this one in
   // (similarity descending, position ascending) order; 8 consecutive lanes share an A token and
   // split the tokens it is compared with.  slot = number of kept edges with the same destination
   // and a lower source position (the order of a destination's source list).
-  for (int b = tid; b < nB; b += kPlanThreads) cnt[b] = 0;
-  for (int a0 = 0; a0 < nA; a0 += kPlanThreads / 8) {
+  for (int b = tid; b < nB; b += NT) cnt[b] = 0;
+  for (int a0 = 0; a0 < nA; a0 += NT / 8) {
     const int a = min(a0 + (tid >> 3), nA - 1), part = tid & 7;
     const float v = best[a];
     int rank = 0;
@@ -242,7 +287,7 @@ __device__ __forceinline__ void merge_plan_body(
     }
   }
   __syncthreads();
-  for (int a0 = 0; a0 < nA; a0 += kPlanThreads / 8) {
+  for (int a0 = 0; a0 < nA; a0 += NT / 8) {
     const int a = min(a0 + (tid >> 3), nA - 1), part = tid & 7;
     const int dst = bcol[a];
     int slot = 0;
@@ -258,16 +303,24 @@ __device__ __forceinline__ void merge_plan_body(
   __syncthreads();
 
   // Phase 4: positions.  keep(i) = 1 unless i is a merged A token; entries(i) = keep(i) * (1 +
-  // number of sources merged into i).  Exclusive scans of both over i = 0..n-1, one position per
-  // thread (n <= 1024): wave scan by shuffles, then the wave totals.
+  // number of sources merged into i).  Exclusive scans of both over i = 0..n-1: every thread takes
+  // ceil(n / NT) consecutive positions (one when n <= NT), wave scan of the thread sums by shuffles,
+  // then the wave totals.
   {
-    const int i = tid, lane = tid & 63, w = tid >> 6;
-    int k = 0, e = 0;
-    if (i < n) {
-      k = (i & 1) ? 1 : (merged[i >> 1] ? 0 : 1);
-      e = k ? 1 + ((i & 1) ? cnt[i >> 1] : 0) : 0;
+    const int C = (n + NT - 1) / NT;
+    const int lane = tid & 63, w = tid >> 6;
+    auto keep_of = [&](int i) { return (i & 1) ? 1 : (merged[i >> 1] ? 0 : 1); };
+    auto ent_of = [&](int i, int k) { return k ? 1 + ((i & 1) ? cnt[i >> 1] : 0) : 0; };
+    int k_sum = 0, e_sum = 0;
+    for (int c = 0; c < C; ++c) {
+      const int i = tid * C + c;
+      if (i < n) {
+        const int k = keep_of(i);
+        k_sum += k;
+        e_sum += ent_of(i, k);
+      }
     }
-    int sk = k, se = e;
+    int sk = k_sum, se = e_sum;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
       const int tk = __shfl_up(sk, o, kWave), te = __shfl_up(se, o, kWave);
@@ -275,18 +328,24 @@ __device__ __forceinline__ void merge_plan_body(
     }
     if (lane == 63) { wave_tot[w] = sk; wave_tot[16 + w] = se; }
     __syncthreads();
-    int ok = 0, oe = 0;
-    for (int j = 0; j < w; ++j) { ok += wave_tot[j]; oe += wave_tot[16 + j]; }
-    if (i < n) {
-      keep_pos[i] = ok + sk - k;
-      ent_pos[i] = oe + se - e;
+    int pk = sk - k_sum, pe = se - e_sum;
+    for (int j = 0; j < w; ++j) { pk += wave_tot[j]; pe += wave_tot[16 + j]; }
+    for (int c = 0; c < C; ++c) {
+      const int i = tid * C + c;
+      if (i < n) {
+        const int k = keep_of(i), e = ent_of(i, k);
+        keep_pos[i] = pk;
+        ent_pos[i] = pe;
+        pk += k;
+        pe += e;
+      }
     }
   }
   __syncthreads();
 
   // Phase 5: write the lists: every surviving row opens its list with itself, every merged A token
   // enters its destination's list at its slot.
-  for (int i = tid; i < n; i += kPlanThreads) {
+  for (int i = tid; i < n; i += NT) {
     const bool odd = i & 1;
     if (!odd && merged[i >> 1]) {
       const int a = i >> 1, d = 2 * bcol[a] + 1;
@@ -297,6 +356,21 @@ __device__ __forceinline__ void merge_plan_body(
       src_list[e] = i0 + i;
     }
   }
+}
+
+// The whole plan of query q by one workgroup of kPlanThreads threads (tid = thread index; lds: its dynamic LDS).
+template <typename T, bool ROWS_IN_LDS>
+__device__ __forceinline__ void merge_plan_body(
+    const T* __restrict__ src, int64_t row_stride, int col_off, int H, int dm, const int32_t* __restrict__ in_off,
+    const int32_t* __restrict__ out_off, const int32_t* __restrict__ reff_arr, const int32_t* __restrict__ troff,
+    int n_lead, int32_t* __restrict__ src_list, int32_t* __restrict__ row_ptr, int32_t* __restrict__ trace_src,
+    int32_t* __restrict__ trace_dst, float* rows, float* lds, const int q, const int tid) {
+  merge_plan_select<T, ROWS_IN_LDS, false>(src, row_stride, col_off, H, dm, in_off, reff_arr, n_lead, rows, lds, nullptr,
+                                           nullptr, q, tid);
+  const int n = in_off[q + 1] - in_off[q];
+  float* small = ROWS_IN_LDS ? lds + (size_t)max(n, 0) * plan_row_floats(dm) : lds;
+  merge_plan_lists<kPlanThreads, false>(small, nullptr, nullptr, in_off, out_off, reff_arr, troff, src_list, row_ptr,
+                                        trace_src, trace_dst, q, tid);
 }
 
 }  // namespace otas

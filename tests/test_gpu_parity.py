@@ -711,6 +711,30 @@ def test_longest_sequences_f32(torch_cuda, lib):
     ctx.close()
 
 
+def test_long_ragged_sequences_bf16_plan_split_over_two_launches(torch_cuda, lib):
+    """bf16, head width 64, H = 4: the encoder runs the merge plan's selection beside attention and writes its lists
+    beside the output projection (256 threads there: a 554-token query gives every thread three positions of the
+    scans; 554 is the longest query this path takes).  Ragged lengths 554 / 300 / 130 / 9, r up to 100, one query that
+    merges nothing.  Lock-step against the oracle: sizes identical, every differing edge a near-tie."""
+    torch = torch_cuda
+    cfg = synth.config("tiny")
+    cfg.D, cfg.H, cfg.F, cfg.dtype, cfg.n0, cfg.L, cfg.B = 256, 4, 512, "bf16", 554, 3, 5
+    cfg.strategies = [(0, 100), (4, 37), (0, 16), (0, 3), (2, 0)]
+    ctx, layers = hz.make_context(cfg)
+    lens = [554, 296, 130, 9, 75]
+    toks = [synth.query_tokens(cfg, q)[:n] for q, n in enumerate(lens)]
+    prm = [synth.query_prompts(cfg, q) for q in range(cfg.B)]
+    R = [r for _, r in cfg.strategies]
+    x0, off = hz.gpu_prepend(ctx, toks, prm)
+    assert np.diff(off).tolist() == [554, 300, 130, 9, 77]
+    gpu = hz.gpu_forward(ctx, x0, off, R)
+    rep = hz.compare_lockstep(cfg, layers, toks, prm, R, gpu)
+    print(rep)
+    assert rep["sizes_equal"] and rep["max_err"] <= BF16_TOL and rep["max_deficit"] <= NEAR_TIE
+    assert np.diff(gpu["offsets"]).tolist() == [254, 189, 82, 3, 77]   # 9 -> 6 -> 4 -> 3: r clamps to half the unprotected tokens
+    ctx.close()
+
+
 def test_per_launch_timing_api(torch_cuda, lib):
     """otas_timing_*: one record per launch in launch order, kinds named, the event-pair overhead is
     calibrated and non-negative, records stop when timing is off, and timing changes no result."""
