@@ -74,7 +74,7 @@ def algorithmic_work(cfg, lengths0, r, otas, ctx):
         else:
             w["layer_norm_bytes"] += Tm[l] * D * (4.0 + e)           # LN2 on its own
             w["layer_norm_method_bytes"] += Tm[l] * D * 2.0 * e
-        S = ctx.otas_splitk_factor(int(Tm[l]), D, F, min(8, int(2 * T[0] // max(Tm[l], 1)))) if e == 2 and not cfg.deep else 1
+        S = ctx.otas_splitk_factor(int(Tm[l]), D, F, ctx.otas_splitk_room(int(T[0]), int(Tm[l]))) if e == 2 and not cfg.deep else 1
         w["splits"].append(S)
         ln1_fused = S > 1 and l + 1 < L
         if S > 1:   # S float partial rows + residual row in, residual row out, next block's operand row out

@@ -106,10 +106,12 @@ otas_status otas_schedule(int32_t n0, int32_t P, int32_t r, int32_t n_lead, int3
  * bf16 model: 1 = one kernel with the residual epilogue; S > 1 = S partial products over K / S
  * each, added in split order by a second kernel that also applies the next block's first
  * LayerNorm (so that block launches no LayerNorm kernel of its own).  S is one of 1, 2, 3, 4, 6, 8
- * and never above max_split; the encoder passes max_split = min(8, floor(2 T0 / M)) for a batch (or
- * lane) that entered with T0 token rows, the room its workspace has for partial products.  Pure
- * host function; lets a caller account for which kernels a forward pass launches. */
+ * and never above max_split; the encoder passes max_split = otas_splitk_room(ctx, T0, M), the room
+ * the workspace of a single-lane call that entered with T0 token rows has for partial products of M
+ * rows (two float rows per token row, up to eight for batches of at most 1024 token rows).  Pure
+ * host functions; they let a caller account for which kernels a forward pass launches. */
 int32_t otas_splitk_factor(const otas_ctx *ctx, int64_t M, int32_t N, int32_t K, int32_t max_split);
+int32_t otas_splitk_room(const otas_ctx *ctx, int64_t T0, int64_t M);
 
 /* Lanes.  otas_encoder_forward and otas_encoder_layers may cut the batch into up to 8 lanes,
  * contiguous query ranges with about equal token counts, and run them side by side: lane 0 on
@@ -119,8 +121,10 @@ int32_t otas_splitk_factor(const otas_ctx *ctx, int64_t M, int32_t N, int32_t K,
  * running token count reaches floor(T0 (g + 1) / G) (every lane keeps at least one query).
  * Queries are independent (Sec. III-B: a batch is a set of queries, each with its own strategy) and
  * a lane's kernels are chosen from the lane's own row counts, so a lane's rows are, bit for bit,
- * what a call on that lane's queries alone returns; against another lane count they agree bit for
- * bit where no launch is split over K (otas_splitk_factor) and to rounding otherwise.  lanes = 0
+ * what a call on that lane's queries alone returns (given the same room for split-K partial
+ * products per token row, which the whole batch's size sets: always so for lanes of more than 4096
+ * token rows); against another lane count they agree bit for bit where no launch is split over K
+ * (otas_splitk_factor) and to rounding otherwise.  lanes = 0
  * (the default) lets the library choose from the batch size (today: 1); 1 runs the whole batch as
  * one sequence of launches.
  * Environment: the library reads one variable, OTAS_DEBUG (any value: name failing HIP calls on

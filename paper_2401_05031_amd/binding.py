@@ -103,6 +103,7 @@ def load_library():
         "otas_clock_probe_start": (i32, [vp, i32]),
         "otas_clock_probe_read": (i32, [vp, C.POINTER(C.c_float), i32, _I32P]),
         "otas_splitk_factor": (i32, [vp, C.c_int64, i32, i32, i32]),
+        "otas_splitk_room": (i32, [vp, C.c_int64, C.c_int64]),
         "otas_sched_create": (i32, [C.POINTER(_SchedParams), i32, _I32P, i32, _F64P, _F64P, i32, _F64P, _I32P,
                                     C.POINTER(vp)]),
         "otas_sched_destroy": (None, [vp]),
@@ -126,7 +127,7 @@ EXPORTED = ("otas_create", "otas_destroy", "otas_schedule", "otas_workspace_byte
             "otas_merge_workspace_bytes", "otas_prompt_prepend", "otas_prompt_prepend_pool", "otas_token_merge", "otas_token_merge_static",
             "otas_encoder_forward", "otas_encoder_layers", "otas_encoder_forward_deep", "otas_patch_embed_workspace_bytes", "otas_patch_embed", "otas_task_heads", "otas_layer_norm", "otas_linear", "otas_attention", "otas_linear_kernel", "otas_linear_choice", "otas_strerror",
             "otas_timing_enable", "otas_timing_kinds", "otas_timing_kind_name", "otas_timing_read",
-            "otas_timing_read_launches", "otas_timing_overhead_ms", "otas_set_lanes", "otas_splitk_factor",
+            "otas_timing_read_launches", "otas_timing_overhead_ms", "otas_set_lanes", "otas_splitk_factor", "otas_splitk_room",
             "otas_clock_probe_start", "otas_clock_probe_read",
             "otas_sched_create", "otas_sched_destroy", "otas_sched_rate_table", "otas_sched_add_query", "otas_sched_allocate",
             "otas_sched_num_batches", "otas_sched_batch_info", "otas_sched_batch_queries", "otas_sched_estimate",
@@ -346,6 +347,9 @@ class Context:
 
     def otas_timing_kind_names(self) -> List[str]:
         return [self._lib.otas_timing_kind_name(i).decode() for i in range(self._lib.otas_timing_kinds())]
+
+    def otas_splitk_room(self, T0: int, M: int) -> int:
+        return int(self._lib.otas_splitk_room(self._h, int(T0), int(M)))
 
     def otas_splitk_factor(self, M: int, N: int, K: int, max_split: int = 8) -> int:
         return int(self._lib.otas_splitk_factor(self._h, int(M), int(N), int(K), int(max_split)))

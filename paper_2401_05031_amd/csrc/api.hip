@@ -26,7 +26,9 @@ constexpr int64_t kPlanSideMinRows = 32768;  // batches below this many rows pla
 constexpr int kStageSlots = 32;
 constexpr size_t kSlotInts = kPlanInts / kStageSlots;
 constexpr int kMaxLanes = 8;
-constexpr int kPartRows = 2;   // split-K workspace: this many float rows of width D per token row
+// Split-K workspace: float rows of width D per (padded) token row of the batch.  Two for large batches; small
+// batches, whose products leave most CUs idle and split up to eight ways, get up to eight (8192 rows in all).
+inline int part_rows_factor(size_t rows) { return (int)std::min<size_t>(8, std::max<size_t>(2, 8192 / std::max<size_t>(rows, 1))); }
 
 // Scratch of otas_token_merge_static: the merge lists of one call (src_list [rows] | row_ptr [rows + 64]).
 // One copy per GPU, held until the process ends; every call on a GPU shares it.
@@ -151,6 +153,7 @@ otas_status upload_plan(otas_ctx* c, const std::vector<int32_t>& host) {
 
 struct WorkspaceLayout {
   size_t xa, xb, h, qkv, hid, part, sizes_a, sizes_b, src_list, row_ptr, total;
+  int part_factor;   // float rows of the split-K buffer per token row
 };
 
 WorkspaceLayout forward_layout(const otas_model_desc& d, int64_t T0) {
@@ -164,7 +167,8 @@ WorkspaceLayout forward_layout(const otas_model_desc& d, int64_t T0) {
   w.h = take(rows * d.D * es);
   w.qkv = take(rows * 3 * d.D * es);
   w.hid = take(rows * d.F * es);
-  w.part = take(d.dtype == OTAS_BF16 ? kPartRows * rows * d.D * sizeof(float) : 0);   // split-K partial products
+  w.part_factor = part_rows_factor(rows);
+  w.part = take(d.dtype == OTAS_BF16 ? w.part_factor * rows * d.D * sizeof(float) : 0);   // split-K partial products
   w.sizes_a = take(rows * sizeof(int32_t));
   w.sizes_b = take(rows * sizeof(int32_t));
   w.src_list = take(rows * sizeof(int32_t));
@@ -756,7 +760,7 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
       // selection (the long part: keys, similarities, best matches) and the lists, which need nothing else, are
       // written by extra workgroups of the projection's launch: the plan's serial chain beside attention gets
       // shorter by a quarter.  The selection's result waits in the split-K partial buffer, idle between two MLPs.
-      float* sel_best = (float*)(ws + w.part) + (size_t)kPartRows * ln.row0 * D;
+      float* sel_best = (float*)(ws + w.part) + (size_t)w.part_factor * ln.row0 * D;
       int32_t* sel_bcol = (int32_t*)(sel_best + T);
       const bool tail = fuse && linear_plan_tail_fits(T, D, D, Bg);
       if (fuse) {
@@ -814,11 +818,11 @@ otas_status run_layers(otas_ctx* c, int32_t layer_begin, int32_t layer_end, cons
       // MLP + residual
       OTAS_LAUNCH_ON(K_FC1, s, launch_linear(dt, hbuf, wl.w_fc1, wl.b_fc1, nullptr, hid, Tn, F, D, EPI_GELU, s));
       void* x_next = (l == L - 1) ? (void*)((float*)x_out + (size_t)ln.rowL * D) : x_mlp;
-      const int S = splitk_factor(dt, Tn, D, F, (int)std::min<int64_t>(8, kPartRows * ln.T[0] / std::max<int64_t>(Tn, 1)));
+      const int S = splitk_factor(dt, Tn, D, F, (int)std::min<int64_t>(8, w.part_factor * ln.T[0] / std::max<int64_t>(Tn, 1)));
       if (S > 1) {
         // few tiles, long K: S partial products, then one pass that adds them, the bias and the
         // residual and already applies the next block's first LayerNorm to the row in registers
-        float* part = (float*)(ws + w.part) + (size_t)kPartRows * ln.row0 * D;
+        float* part = (float*)(ws + w.part) + (size_t)w.part_factor * ln.row0 * D;
         OTAS_LAUNCH_ON(K_FC2, s, launch_linear_splitk(hid, wl.w_fc2, part, Tn, D, F, S, s));
         const bool more = l + 1 < L;
         const otas_layer_weights* wn = more ? &c->layers[layer_begin + l + 1] : nullptr;
@@ -1119,6 +1123,12 @@ otas_status otas_set_lanes(otas_ctx* c, int32_t lanes) {
   if (!c || lanes < 0 || lanes > kMaxLanes) return OTAS_EINVAL;
   c->lanes = lanes;
   return OTAS_OK;
+}
+
+int32_t otas_splitk_room(const otas_ctx* c, int64_t T0, int64_t M) {
+  if (!c || T0 <= 0 || M <= 0) return 1;
+  const size_t rows = (size_t)((T0 + kRowPad - 1) / kRowPad * kRowPad);
+  return (int32_t)std::max<int64_t>(1, std::min<int64_t>(8, part_rows_factor(rows) * T0 / M));
 }
 
 int32_t otas_splitk_factor(const otas_ctx* c, int64_t M, int32_t N, int32_t K, int32_t max_split) {

@@ -5,6 +5,7 @@
 //   * attention_rows_kernel -- one wave per query row, fp32 arithmetic throughout (f32 models,
 //                              and the fallback for head widths the MFMA kernel does not take).
 //   * attention_mfma_kernel -- bf16 MFMA with one head's K and V staged in LDS (bf16 models).
+#include <algorithm>
 #include <cstdlib>
 
 #include "common.h"
@@ -293,28 +294,29 @@ __global__ __launch_bounds__(64 * NW, DH <= 64 ? 4 : 2) void attention_mfma_kern
 // written beside the next launch), the others run attention, each on 16 / NW heads of one (query, row block) side by side.
 // The plan workgroups come first in dispatch order, so their long serial chains start at once and the attention
 // workgroups fill the other CUs.  Head width 64 only (a 1024-thread workgroup leaves 128 registers per lane).
-// grid.x = B + xblks * (H / G) * B with G = 16 / NW.
+// grid.x = B * parts + xblks * (H / G) * B with G = 16 / NW (parts = plan workgroups per query, 1 for the whole plan).
 template <bool BIAS, int KC, int NW>
 __global__ __launch_bounds__(1024) void attention_plan_kernel(
     const bf16_t* __restrict__ qkv, const int32_t* __restrict__ sizes, const int32_t* __restrict__ off, int D, int H,
     float scale, bf16_t* __restrict__ o, int B, int xblks, const int32_t* __restrict__ out_off,
     const int32_t* __restrict__ reff_arr, const int32_t* __restrict__ troff, int n_lead,
     int32_t* __restrict__ src_list, int32_t* __restrict__ row_ptr, int32_t* __restrict__ trace_src,
-    int32_t* __restrict__ trace_dst, float* __restrict__ sel_best, int32_t* __restrict__ sel_bcol, int unit_lds) {
+    int32_t* __restrict__ trace_dst, float* __restrict__ sel_best, int32_t* __restrict__ sel_bcol, int parts,
+    int unit_lds) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int DH = 64, G = 16 / NW;
-  if ((int)blockIdx.x < B) {   // workgroup-uniform
-    if (sel_best)   // the selection only: the lists are written beside the output projection
+  if ((int)blockIdx.x < B * parts) {   // workgroup-uniform
+    if (sel_best)   // the selection only, `parts` workgroups per query: the lists are written beside the output projection
       merge_plan_select<bf16_t, true, true>(qkv, 3 * (int64_t)D, D, H, DH, off, reff_arr, n_lead, nullptr,
-                                            reinterpret_cast<float*>(smem), sel_best, sel_bcol, (int)blockIdx.x,
-                                            (int)threadIdx.x);
+                                            reinterpret_cast<float*>(smem), sel_best, sel_bcol,
+                                            (int)blockIdx.x / parts, (int)threadIdx.x, (int)blockIdx.x % parts, parts);
     else
       merge_plan_body<bf16_t, true>(qkv, 3 * (int64_t)D, D, H, DH, off, out_off, reff_arr, troff, n_lead, src_list,
                                     row_ptr, trace_src, trace_dst, nullptr, reinterpret_cast<float*>(smem),
                                     (int)blockIdx.x, (int)threadIdx.x);
     return;
   }
-  int id = (int)blockIdx.x - B;
+  int id = (int)blockIdx.x - B * parts;
   const int hg = H / G;
   const int xblk = id % xblks;
   id /= xblks;
@@ -381,6 +383,11 @@ hipError_t launch_attention_plan(const void* qkv, const int32_t* sizes, const in
   const float scale = 1.0f / sqrtf(64.0f);
   const int32_t* sz = size_bias ? sizes : nullptr;
   constexpr int LD = 64 + 8;
+  // Workgroups per query for the selection: a small batch leaves most CUs idle, and the selection's chain (load the
+  // keys, unit length, similarities: each proportional to the A tokens a workgroup owns, plus all B tokens) is what
+  // the launch then waits for.  Up to 64 plan workgroups in all, and no more per query than it has blocks of 32 A tokens.
+  int parts = 1;
+  if (sel_best) parts = std::max(1, std::min(std::min(4, 64 / B), (max_n / 2 + 31) / 32));
 #define OTAS_FUSED(BIASV, KC, NWV)                                                                                \
   do {                                                                                                            \
     constexpr int G = 16 / NWV;                                                                                   \
@@ -392,10 +399,10 @@ hipError_t launch_attention_plan(const void* qkv, const int32_t* sizes, const in
     hipError_t e = set_max_dynamic_lds((const void*)kern, 160 * 1024);                                            \
     if (e != hipSuccess) return e;                                                                                \
     const int xblks = (max_n + 32 * NWV - 1) / (32 * NWV);                                                        \
-    dim3 grid((unsigned)(B + xblks * (H / G) * B)), block(1024);                                                  \
+    dim3 grid((unsigned)(B * parts + xblks * (H / G) * B)), block(1024);                                          \
     kern<<<grid, block, lds, s>>>((const bf16_t*)qkv, sz, d_off, D, H, scale, (bf16_t*)o, B, xblks, d_out_off,    \
                                   d_reff, d_troff, n_lead, src_list, row_ptr, trace_src, trace_dst, sel_best,     \
-                                  sel_bcol, (int)unit);                                                           \
+                                  sel_bcol, parts, (int)unit);                                                    \
   } while (0)
   if (max_n > 128 && max_n <= 256) {
     if (sz) OTAS_FUSED(true, 256, 8); else OTAS_FUSED(false, 256, 8);

@@ -453,16 +453,30 @@ __global__ __launch_bounds__(256) void splitk_reduce_ln_kernel(const float* __re
     const int c = lane + 64 * i;
     if (c < chunks) {
       Vec<float> lo = load_vec<float>(pr + c * V), hi = load_vec<float>(pr + c * V + 4);
-#pragma unroll
-      for (int k = 0; k < 4; ++k) { v[i][k] = lo.get(k); v[i][4 + k] = hi.get(k); }
-      for (int sp = 1; sp < S; ++sp) {
-        lo = load_vec<float>(pr + sp * split_stride + c * V);
-        hi = load_vec<float>(pr + sp * split_stride + c * V + 4);
-#pragma unroll
-        for (int k = 0; k < 4; ++k) { v[i][k] += lo.get(k); v[i][4 + k] += hi.get(k); }
-      }
+      // bias and residual are requested here, with the partial results, and used after them
       const Vec<bf16_t> bv = load_vec<bf16_t>(bias + c * V);
       const Vec<float> rlo = load_vec<float>(rr + c * V), rhi = load_vec<float>(rr + c * V + 4);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) { v[i][k] = lo.get(k); v[i][4 + k] = hi.get(k); }
+      // the other partial results seven at a time (all of them for S <= 8): their loads are in flight together,
+      // the additions keep the order sp = 1, 2, ... (S is the same for the whole launch: the tests on it are scalar branches)
+      constexpr int UB = 7;
+      for (int sp = 1; sp < S; sp += UB) {
+        Vec<float> plo[UB], phi[UB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u)
+          if (sp + u < S) {
+            const float* p = pr + (size_t)(sp + u) * split_stride + c * V;
+            plo[u] = load_vec<float>(p);
+            phi[u] = load_vec<float>(p + 4);
+          }
+#pragma unroll
+        for (int u = 0; u < UB; ++u)
+          if (sp + u < S) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { v[i][k] += plo[u].get(k); v[i][4 + k] += phi[u].get(k); }
+          }
+      }
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         v[i][k] = (v[i][k] + bv.get(k)) + rlo.get(k);

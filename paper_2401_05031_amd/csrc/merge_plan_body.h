@@ -41,15 +41,30 @@ constexpr size_t kPlanListsLdsMax = 4 * (3 * 512 + 512 + 2 * 1024 + 32);
 // token; bcol[a] = that B token) stays in LDS behind the metric rows, valid for every thread on return.
 // TO_GLOBAL = true: it goes to g_best[i0 + a], g_bcol[i0 + a] (a < nA) for merge_plan_lists in a later launch.
 // Queries with nothing to merge return at once.
+// part / parts: the A tokens are dealt to `parts` workgroups in blocks of 32 (block k goes to workgroup k % parts);
+// this one is number `part` and computes the rows it needs -- all B tokens and its own A tokens -- and the result
+// of its A tokens only (parts > 1 needs TO_GLOBAL).  Every row and every similarity is computed by the same
+// arithmetic in the same order whatever `parts` is.
 template <typename T, bool ROWS_IN_LDS, bool TO_GLOBAL>
 __device__ __forceinline__ void merge_plan_select(
     const T* __restrict__ src, int64_t row_stride, int col_off, int H, int dm, const int32_t* __restrict__ in_off,
     const int32_t* __restrict__ reff_arr, int n_lead, float* rows, float* lds, float* __restrict__ g_best,
-    int32_t* __restrict__ g_bcol, const int q, const int tid) {
+    int32_t* __restrict__ g_bcol, const int q, const int tid, const int part = 0, const int parts = 1) {
   const int i0 = in_off[q], n = in_off[q + 1] - i0;
   if (n <= 0 || reff_arr[q] <= 0) return;
   const int half = dm >> 1, hp = (half + 3) & ~3;   // columns per parity, and their padded count
   const int nA = (n + 1) >> 1, nB = n >> 1, ldm = 2 * hp + 4;
+  const int nAb = (nA + 31) >> 5, nBb = (nB + 31) >> 5;
+  const int nAl = (nAb - part + parts - 1) / parts;   // A blocks of this workgroup: part, part + parts, ...
+  if (nAl <= 0) return;
+  // The rows this workgroup needs, numbered u = 0 .. n_need - 1: the nB B tokens, then its A blocks (the last
+  // block may run past nA: -1).
+  const int n_need = nB + nAl * 32;
+  auto token_of = [&](int u) {
+    if (u < nB) return 2 * u + 1;
+    const int v = u - nB, a = (part + parts * (v >> 5)) * 32 + (v & 31);
+    return a < nA ? 2 * a : -1;
+  };
   // Metric rows in LDS: the A tokens (even positions) first, then the B tokens, one row of ldm
   // floats per token, so that consecutive tokens of one set are ldm = dm + 4 floats apart (16 lanes
   // reading 16 bytes each from 16 consecutive rows then fall on all 64 banks once).  Inside a row the
@@ -77,8 +92,9 @@ __device__ __forceinline__ void merge_plan_select(
   if (sizeof(T) == 2 && (dm & 7) == 0 && (row_stride & 7) == 0 && (col_off & 7) == 0 &&
       (reinterpret_cast<uintptr_t>(src) & 15) == 0) {
     const int c8n = dm >> 3;
-    for (int t = tid; t < n * c8n; t += kPlanThreads) {
-      const int i = t / c8n, c = (t - i * c8n) * 8;
+    for (int t = tid; t < n_need * c8n; t += kPlanThreads) {
+      const int u = t / c8n, c = (t - u * c8n) * 8, i = token_of(u);
+      if (i < 0) continue;
       const T* p = src + (size_t)(i0 + i) * row_stride + col_off + c;
       float m[8];
 #pragma unroll
@@ -97,8 +113,9 @@ __device__ __forceinline__ void merge_plan_select(
     }
   } else {
     const int c4n = dm >> 2;
-    for (int t = tid; t < n * c4n; t += kPlanThreads) {
-      const int i = t / c4n, c = (t - i * c4n) * 4;
+    for (int t = tid; t < n_need * c4n; t += kPlanThreads) {
+      const int u = t / c4n, c = (t - u * c4n) * 4, i = token_of(u);
+      if (i < 0) continue;
       const T* p = src + (size_t)(i0 + i) * row_stride + col_off + c;
       float m0 = 0.f, m1 = 0.f, m2 = 0.f, m3 = 0.f;
 #pragma unroll 4
@@ -116,9 +133,9 @@ __device__ __forceinline__ void merge_plan_select(
     }
   }
   if (hp != half)   // the padding columns take part in the contraction: zero
-    for (int t = tid; t < n * 2 * (hp - half); t += kPlanThreads) {
-      const int i = t / (2 * (hp - half)), c = t - i * (2 * (hp - half));
-      row_of(i)[(c & 1) * hp + half + (c >> 1)] = 0.f;
+    for (int t = tid; t < n_need * 2 * (hp - half); t += kPlanThreads) {
+      const int u = t / (2 * (hp - half)), c = t - u * (2 * (hp - half)), i = token_of(u);
+      if (i >= 0) row_of(i)[(c & 1) * hp + half + (c >> 1)] = 0.f;
     }
   __syncthreads();
   // Phase 1: unit length.  16 consecutive lanes share a row of 2 hp floats (the zero padding adds nothing): lane j
@@ -126,9 +143,10 @@ __device__ __forceinline__ void merge_plan_select(
   // a fixed butterfly, and every lane scales its own pieces.
   {
     const int q4 = (2 * hp) >> 2;   // 16-byte pieces per row
-    for (int i0r = 0; i0r < n; i0r += kPlanThreads / 16) {
-      const int i = i0r + (tid >> 4), j = tid & 15;
-      float* r = row_of(min(i, n - 1));
+    for (int u0 = 0; u0 < n_need; u0 += kPlanThreads / 16) {
+      const int u = u0 + (tid >> 4), j = tid & 15;
+      const int i = u < n_need ? token_of(u) : -1;
+      float* r = row_of(i >= 0 ? i : 1);   // n >= 2 here: token 1 exists
       float ss = 0.f;
       for (int m = j; m < q4; m += 16) {
         const floatx4 v = *reinterpret_cast<const floatx4*>(r + 4 * m);
@@ -139,7 +157,7 @@ __device__ __forceinline__ void merge_plan_select(
       ss += __shfl_xor(ss, 4, kWave);
       ss += __shfl_xor(ss, 8, kWave);
       const float rn = 1.0f / fmaxf(sqrtf(ss), 1e-12f);
-      if (i < n)
+      if (i >= 0)
         for (int m = j; m < q4; m += 16) {
           floatx4 v = *reinterpret_cast<const floatx4*>(r + 4 * m);
           v[0] *= rn; v[1] *= rn; v[2] *= rn; v[3] *= rn;
@@ -154,18 +172,17 @@ __device__ __forceinline__ void merge_plan_select(
   // (v_mfma_f32_32x32x2_f32), transposed: B tokens are the first operand (rows), A tokens the second
   // (columns), so a lane owns ONE A token and holds 16 of a 32-token B block's similarities in its
   // accumulator (rows 8 (e / 4) + 4 (lane >> 5) + (e & 3)): its arg-max is a scan of its own registers
-  // in ascending B order plus one exchange with lane ^ 32.  Wave w owns A block w % nAb and every
+  // in ascending B order plus one exchange with lane ^ 32.  Wave w owns the workgroup's A block w % nAl and every
   // G-th B block; the G partial results per A token are combined through LDS.  Ties go to the
   // lowest B position at every step.
-  const int nAb = (nA + 31) >> 5, nBb = (nB + 31) >> 5;
-  const int G = max(1, 16 / nAb);
+  const int G = max(1, 16 / nAl);
   int* part_c = wave_tot + 32;
   float* part_v = reinterpret_cast<float*>(part_c + 512);
   {
     const int lane = tid & 63, w = tid >> 6;
     const int fr = lane & 31, fk = lane >> 5;
-    for (int ab = w % nAb, grp = w / nAb; grp < G; grp = G) {   // one (A block, B group) per wave
-      const int a = ab * 32 + fr;
+    for (int al = w % nAl, grp = w / nAl; grp < G; grp = G) {   // one (A block, B group) per wave
+      const int a = (part + parts * al) * 32 + fr;
       const float* pa = mh + (size_t)min(a, nA - 1) * ldm + fk * hp;
       float bv = -INFINITY;
       int bc = 0x7fffffff;
@@ -201,18 +218,20 @@ __device__ __forceinline__ void merge_plan_select(
       const int oc = __shfl_xor(bc, 32, kWave);
       if (ov > bv || (ov == bv && oc < bc)) { bv = ov; bc = oc; }
       if (fk == 0) {
-        part_v[grp * (nAb * 32) + a] = bv;
-        part_c[grp * (nAb * 32) + a] = bc;
+        part_v[grp * (nAl * 32) + al * 32 + fr] = bv;
+        part_c[grp * (nAl * 32) + al * 32 + fr] = bc;
       }
     }
   }
   __syncthreads();
-  for (int a = tid; a < nA; a += kPlanThreads) {
-    float bv = part_v[a];
-    int bc = part_c[a];
+  for (int t = tid; t < nAl * 32; t += kPlanThreads) {
+    const int a = (part + parts * (t >> 5)) * 32 + (t & 31);
+    if (a >= nA) continue;
+    float bv = part_v[t];
+    int bc = part_c[t];
     for (int g = 1; g < G; ++g) {
-      const float v = part_v[g * (nAb * 32) + a];
-      const int c = part_c[g * (nAb * 32) + a];
+      const float v = part_v[g * (nAl * 32) + t];
+      const int c = part_c[g * (nAl * 32) + t];
       if (v > bv || (v == bv && c < bc)) { bv = v; bc = c; }
     }
     const float v = (2 * a < n_lead) ? -INFINITY : bv;   // protected leading token: never a merge source

@@ -596,7 +596,7 @@ def test_lanes_bit_identical_full_batch_bf16(torch_cuda, lib):
         ranges = lane_ranges(G)
         for q0, q1 in ranges:
             assert torch.equal(got[int(off[q0]):int(off[q1])], run(q0, q1, 1)), (G, q0, q1)
-        if all(ctx.otas_splitk_factor(int(off[q1] - off[q0]), cfg.D, cfg.F, 2) == 1 for q0, q1 in ranges):
+        if all(ctx.otas_splitk_factor(int(off[q1] - off[q0]), cfg.D, cfg.F, ctx.otas_splitk_room(int(off[q1] - off[q0]), int(off[q1] - off[q0]))) == 1 for q0, q1 in ranges):
             assert torch.equal(got, whole), G
     assert ctx.otas_splitk_factor(T0, cfg.D, cfg.F, 2) == 1 and ctx.otas_splitk_factor(T0 // 2, cfg.D, cfg.F, 2) == 1
     ctx.close()
