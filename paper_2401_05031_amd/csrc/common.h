@@ -56,22 +56,25 @@ __device__ inline float wave_max(float v) {
 // Exact GELU: 0.5 x (1 + erf(x / sqrt 2)).
 __device__ inline float gelu_exact(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f)); }
 
-// The same GELU for results that are rounded to bf16 afterwards: erf by the rational-exponential
-// formula 7.1.26 of Abramowitz & Stegun (|error| < 1.5e-7, three orders below half a bf16 unit),
-// which costs one exp, one reciprocal and a short polynomial instead of the library erff.
-// With z = |x| / sqrt 2, t = 1 / (1 + p z) and erf z = 1 - poly(t) t exp(-z^2):
-//   0.5 x (1 + erf(x / sqrt 2)) = max(x, 0) - |x| * (0.5 poly(t)) * t * exp(-x^2 / 2),
-// which needs neither the sign transfer nor z itself (the halves are folded into the coefficients).
+// The same GELU for results that are rounded to bf16 afterwards, written as
+//   0.5 x (1 + erf(x / sqrt 2)) = max(x, 0) - |x| Phi(-|x|),   Phi = the standard normal distribution function.
+// log2 Phi(-u) is smooth and close to a parabola: a polynomial of degree 6 in u on [0, 6] (least squares on a
+// fine grid, re-weighted until the error of u Phi(-u) is flat) reproduces u Phi(-u) to 5e-8; beyond u = 6 the
+// term is below 6e-9 |x| and u is clamped.  Evaluated in fp32 the whole function is within 3e-7 of the exact one
+// over [-8, 8], four orders below half a bf16 unit of a result of size 1, for six multiply-adds and one exp2 --
+// against a reciprocal, an exp2 and eleven other instructions for erf by formula 7.1.26 of Abramowitz & Stegun
+// (same accuracy), which this replaces: transcendentals run at quarter rate, and in the GEMM epilogue of the
+// MLP's first linear this function is all the ALU work there is.
 __device__ inline float gelu_bf16(float x) {
-  const float ax = fabsf(x);
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752440f, ax, 1.0f));   // 1 ulp reciprocal
-  const float e = __builtin_amdgcn_exp2f(x * x * (-0.5f * 1.44269504088896340736f));
-  float p = fmaf(0.5f * 1.061405429f, t, 0.5f * -1.453152027f);
-  p = fmaf(p, t, 0.5f * 1.421413741f);
-  p = fmaf(p, t, 0.5f * -0.284496736f);
-  p = fmaf(p, t, 0.5f * 0.254829592f);
+  const float u = fminf(fabsf(x), 6.0f);
+  float p = fmaf(3.30306029e-05f, u, -7.68667320e-04f);
+  p = fmaf(p, u, 8.07889923e-03f);
+  p = fmaf(p, u, -5.34093268e-02f);
+  p = fmaf(p, u, -4.58772987e-01f);
+  p = fmaf(p, u, -1.15120113e+00f);
+  p = fmaf(p, u, -9.99993145e-01f);
   const float relu = __builtin_amdgcn_fmed3f(x, 0.0f, 3.0e38f);   // max(x, 0) in one instruction
-  return fmaf(-ax, p * t * e, relu);
+  return fmaf(-fabsf(x), __builtin_amdgcn_exp2f(p), relu);
 }
 
 }  // namespace otas
