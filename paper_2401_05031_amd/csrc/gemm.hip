@@ -157,10 +157,19 @@ __device__ inline void mfma_epilogue(const floatx16 (&acc)[TM][TN], float* stage
         const floatx4 v = {acc[i][j][g * 4 + 0], acc[i][j][g * 4 + 1], acc[i][j][g * 4 + 2], acc[i][j][g * 4 + 3]};
         *reinterpret_cast<floatx4*>(stage + fr * LDR + j * 32 + g * 8 + fk * 4) = v;
       }
+    // the slab is read back four rows per lane at a time before anything is stored: one LDS wait per group
+    // instead of one per store
+    constexpr int GRP = NIT < 4 ? NIT : 4;
+    floatx4 ag[GRP];
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
       const int row = it * RPI + rrow;
-      const floatx4 a = *reinterpret_cast<const floatx4*>(stage + row * LDR + rcol);
+      if (it % GRP == 0) {
+#pragma unroll
+        for (int u = 0; u < GRP; ++u)
+          ag[u] = *reinterpret_cast<const floatx4*>(stage + ((it + u) * RPI + rrow) * LDR + rcol);
+      }
+      const floatx4 a = ag[it % GRP];
       float v[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] = EPI == EPI_PARTIAL ? a[e] : a[e] + (float)bb[e];
@@ -226,13 +235,15 @@ __device__ inline void mfma_epilogue_bf16(const floatx16 (&acc)[TM][TN], bf16_t*
         const bf16x4 o = {(bf16_t)v[0], (bf16_t)v[1], (bf16_t)v[2], (bf16_t)v[3]};
         *reinterpret_cast<bf16x4*>(stage + fr * LDR + j * 32 + g * 8 + fk * 4) = o;
       }
+    // all of the slab's rows are read back before the first is stored: one LDS wait per slab instead of one per
+    // store, and one address computation (the rows of a lane are RPI * N elements apart)
+    bf16x8 a[NIT];
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-      const int row = it * RPI + rrow;
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(stage + row * LDR + rcol);
-      const int64_t m = m_slab + row;
-      if (m < M && n_ok) *reinterpret_cast<bf16x8*>(Y + (size_t)m * N + n_out) = a;
-    }
+    for (int it = 0; it < NIT; ++it) a[it] = *reinterpret_cast<const bf16x8*>(stage + (it * RPI + rrow) * LDR + rcol);
+    bf16_t* yp = Y + (size_t)(m_slab + rrow) * N + n_out;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it)
+      if (m_slab + it * RPI + rrow < M && n_ok) *reinterpret_cast<bf16x8*>(yp + (size_t)it * RPI * N) = a[it];
   }
 }
 
