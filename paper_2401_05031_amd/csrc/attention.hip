@@ -289,14 +289,19 @@ __global__ __launch_bounds__(64 * NW, DH <= 64 ? 4 : 2) void attention_mfma_kern
 }
 
 // Attention and the merge plan of a layer in ONE launch (both only read the layer's QKV projection, and
-// kernels of one stream do not overlap): workgroups 0 .. B-1 of 1024 threads run the plan of query 0 .. B-1
-// (merge_plan_body; or only its selection, merge_plan_select, when sel_best is given: the lists are then
-// written beside the next launch), the others run attention, each on 16 / NW heads of one (query, row block) side by side.
-// The plan workgroups come first in dispatch order, so their long serial chains start at once and the attention
-// workgroups fill the other CUs.  Head width 64 only (a 1024-thread workgroup leaves 128 registers per lane).
-// grid.x = B * parts + xblks * (H / G) * B with G = 16 / NW (parts = plan workgroups per query, 1 for the whole plan).
+// kernels of one stream do not overlap): the first workgroups run the plan -- workgroup q the whole plan of query q
+// (merge_plan_body), or, when sel_best is given, `parts` workgroups per query only its selection
+// (merge_plan_select: the lists are then written beside the next launch) -- the others run attention, each on
+// 8 / NW heads of one (query, row block) side by side.  The plan workgroups come first in dispatch order, so their
+// long serial chains start at once and the attention workgroups fill the other CUs.  Workgroups of 512 threads:
+// attention then has the shape of the stand-alone kernel (one head of eight waves, or two of four: heads in one
+// workgroup share its barriers, and four heads in lock-step in 1024-thread workgroups cost attention a fifth of its
+// speed), and a plan workgroup shares its CU with an attention workgroup instead of taking the CU.  Head width 64
+// only (four waves per SIMD leave 128 registers per lane).
+// grid.x = B * parts + xblks * (H / G) * B with G = 8 / NW (parts = plan workgroups per query, 1 for the whole plan).
+constexpr int kFusedThreads = 512;
 template <bool BIAS, int KC, int NW>
-__global__ __launch_bounds__(1024) void attention_plan_kernel(
+__global__ __launch_bounds__(kFusedThreads, 4) void attention_plan_kernel(
     const bf16_t* __restrict__ qkv, const int32_t* __restrict__ sizes, const int32_t* __restrict__ off, int D, int H,
     float scale, bf16_t* __restrict__ o, int B, int xblks, const int32_t* __restrict__ out_off,
     const int32_t* __restrict__ reff_arr, const int32_t* __restrict__ troff, int n_lead,
@@ -304,16 +309,17 @@ __global__ __launch_bounds__(1024) void attention_plan_kernel(
     int32_t* __restrict__ trace_dst, float* __restrict__ sel_best, int32_t* __restrict__ sel_bcol, int parts,
     int unit_lds) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  constexpr int DH = 64, G = 16 / NW;
+  constexpr int DH = 64, WT = kFusedThreads, G = WT / 64 / NW;
   if ((int)blockIdx.x < B * parts) {   // workgroup-uniform
     if (sel_best)   // the selection only, `parts` workgroups per query: the lists are written beside the output projection
-      merge_plan_select<bf16_t, true, true>(qkv, 3 * (int64_t)D, D, H, DH, off, reff_arr, n_lead, nullptr,
-                                            reinterpret_cast<float*>(smem), sel_best, sel_bcol,
-                                            (int)blockIdx.x / parts, (int)threadIdx.x, (int)blockIdx.x % parts, parts);
+      merge_plan_select<bf16_t, true, true, WT>(qkv, 3 * (int64_t)D, D, H, DH, off, reff_arr, n_lead, nullptr,
+                                                reinterpret_cast<float*>(smem), sel_best, sel_bcol,
+                                                (int)blockIdx.x / parts, (int)threadIdx.x, (int)blockIdx.x % parts,
+                                                parts);
     else
-      merge_plan_body<bf16_t, true>(qkv, 3 * (int64_t)D, D, H, DH, off, out_off, reff_arr, troff, n_lead, src_list,
-                                    row_ptr, trace_src, trace_dst, nullptr, reinterpret_cast<float*>(smem),
-                                    (int)blockIdx.x, (int)threadIdx.x);
+      merge_plan_body<bf16_t, true, WT>(qkv, 3 * (int64_t)D, D, H, DH, off, out_off, reff_arr, troff, n_lead, src_list,
+                                        row_ptr, trace_src, trace_dst, nullptr, reinterpret_cast<float*>(smem),
+                                        (int)blockIdx.x, (int)threadIdx.x);
     return;
   }
   int id = (int)blockIdx.x - B * parts;
@@ -363,7 +369,7 @@ static hipError_t attention_mfma(const void* qkv, const int32_t* sz, const int32
 bool attention_plan_takes(int dtype, int max_n, int D, int H) {
   if (dtype == 0 || H <= 0 || D != 64 * H || max_n <= 0 || max_n > kPlanThreads) return false;
   if (merge_plan_lds_bytes(max_n, 64) > 160 * 1024) return false;
-  const int G = (max_n > 128 && max_n <= 256) ? 2 : 4;   // heads per workgroup: 16 waves / (8 or 4 waves per head)
+  const int G = (max_n > 128 && max_n <= 256) ? 1 : 2;   // heads per workgroup: 8 waves / (8 or 4 waves per head)
   return H % G == 0;
 }
 
@@ -390,7 +396,7 @@ hipError_t launch_attention_plan(const void* qkv, const int32_t* sizes, const in
   if (sel_best) parts = std::max(1, std::min(std::min(4, 64 / B), (max_n / 2 + 31) / 32));
 #define OTAS_FUSED(BIASV, KC, NWV)                                                                                \
   do {                                                                                                            \
-    constexpr int G = 16 / NWV;                                                                                   \
+    constexpr int G = kFusedThreads / 64 / NWV;                                                                   \
     if (H % G != 0) return hipErrorInvalidValue;                                                                  \
     const size_t unit = ((size_t)(KC + KC + 4) * LD * sizeof(bf16_t) + KC * sizeof(float) + 15) & ~(size_t)15;    \
     const size_t lds = unit * G > plan_lds ? unit * G : plan_lds;                                                 \
@@ -399,7 +405,7 @@ hipError_t launch_attention_plan(const void* qkv, const int32_t* sizes, const in
     hipError_t e = set_max_dynamic_lds((const void*)kern, 160 * 1024);                                            \
     if (e != hipSuccess) return e;                                                                                \
     const int xblks = (max_n + 32 * NWV - 1) / (32 * NWV);                                                        \
-    dim3 grid((unsigned)(B * parts + xblks * (H / G) * B)), block(1024);                                          \
+    dim3 grid((unsigned)(B * parts + xblks * (H / G) * B)), block(kFusedThreads);                                 \
     kern<<<grid, block, lds, s>>>((const bf16_t*)qkv, sz, d_off, D, H, scale, (bf16_t*)o, B, xblks, d_out_off,    \
                                   d_reff, d_troff, n_lead, src_list, row_ptr, trace_src, trace_dst, sel_best,     \
                                   sel_bcol, parts, (int)unit);                                                    \

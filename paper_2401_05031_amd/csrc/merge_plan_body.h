@@ -1,8 +1,8 @@
 // The plan of the merging module (Sec. II-C) for one query, as device functions that a workgroup executes:
 //   merge_plan_select  phases 0-2: head-mean metric, unit length, every A token's most similar B token
-//                      (kPlanThreads threads)
+//                      (NT threads, a multiple of 64: kPlanThreads on its own, fewer beside attention)
 //   merge_plan_lists   phases 3-5: the r best edges, list slots, scans, the lists (any multiple of 64 threads)
-//   merge_plan_body    both, one after the other (kPlanThreads threads)
+//   merge_plan_body    both, one after the other
 // Used by merge_plan_kernel (one workgroup per query runs the whole plan), by the kernel that runs the selection
 // beside attention in one launch, and by the GEMM kernels that run the list phases beside the projection.
 #ifndef OTAS_MERGE_PLAN_BODY_H_
@@ -30,7 +30,7 @@ static inline size_t plan_lists_lds_bytes(int max_n) {
 }
 constexpr size_t kPlanListsLdsMax = 4 * (3 * 512 + 512 + 2 * 1024 + 32);
 
-// One workgroup of 1024 threads per query (q; tid = thread index in the workgroup; lds: its dynamic LDS).
+// One workgroup of NT threads per query (q; tid = thread index in the workgroup; lds: its dynamic LDS).
 // src: the vectors the similarity is taken on; the metric of token i is the mean over H heads of src[(i0 + i) * row_stride + col_off + h * dm + c] (H = 1 for
 // a caller-supplied metric, H heads of the attention keys inside the encoder), normalised to unit
 // length with fp32 arithmetic.
@@ -45,7 +45,7 @@ constexpr size_t kPlanListsLdsMax = 4 * (3 * 512 + 512 + 2 * 1024 + 32);
 // this one is number `part` and computes the rows it needs -- all B tokens and its own A tokens -- and the result
 // of its A tokens only (parts > 1 needs TO_GLOBAL).  Every row and every similarity is computed by the same
 // arithmetic in the same order whatever `parts` is.
-template <typename T, bool ROWS_IN_LDS, bool TO_GLOBAL>
+template <typename T, bool ROWS_IN_LDS, bool TO_GLOBAL, int NT = kPlanThreads>
 __device__ __forceinline__ void merge_plan_select(
     const T* __restrict__ src, int64_t row_stride, int col_off, int H, int dm, const int32_t* __restrict__ in_off,
     const int32_t* __restrict__ reff_arr, int n_lead, float* rows, float* lds, float* __restrict__ g_best,
@@ -92,7 +92,7 @@ __device__ __forceinline__ void merge_plan_select(
   if (sizeof(T) == 2 && (dm & 7) == 0 && (row_stride & 7) == 0 && (col_off & 7) == 0 &&
       (reinterpret_cast<uintptr_t>(src) & 15) == 0) {
     const int c8n = dm >> 3;
-    for (int t = tid; t < n_need * c8n; t += kPlanThreads) {
+    for (int t = tid; t < n_need * c8n; t += NT) {
       const int u = t / c8n, c = (t - u * c8n) * 8, i = token_of(u);
       if (i < 0) continue;
       const T* p = src + (size_t)(i0 + i) * row_stride + col_off + c;
@@ -113,7 +113,7 @@ __device__ __forceinline__ void merge_plan_select(
     }
   } else {
     const int c4n = dm >> 2;
-    for (int t = tid; t < n_need * c4n; t += kPlanThreads) {
+    for (int t = tid; t < n_need * c4n; t += NT) {
       const int u = t / c4n, c = (t - u * c4n) * 4, i = token_of(u);
       if (i < 0) continue;
       const T* p = src + (size_t)(i0 + i) * row_stride + col_off + c;
@@ -133,7 +133,7 @@ __device__ __forceinline__ void merge_plan_select(
     }
   }
   if (hp != half)   // the padding columns take part in the contraction: zero
-    for (int t = tid; t < n_need * 2 * (hp - half); t += kPlanThreads) {
+    for (int t = tid; t < n_need * 2 * (hp - half); t += NT) {
       const int u = t / (2 * (hp - half)), c = t - u * (2 * (hp - half)), i = token_of(u);
       if (i >= 0) row_of(i)[(c & 1) * hp + half + (c >> 1)] = 0.f;
     }
@@ -143,7 +143,7 @@ __device__ __forceinline__ void merge_plan_select(
   // a fixed butterfly, and every lane scales its own pieces.
   {
     const int q4 = (2 * hp) >> 2;   // 16-byte pieces per row
-    for (int u0 = 0; u0 < n_need; u0 += kPlanThreads / 16) {
+    for (int u0 = 0; u0 < n_need; u0 += NT / 16) {
       const int u = u0 + (tid >> 4), j = tid & 15;
       const int i = u < n_need ? token_of(u) : -1;
       float* r = row_of(i >= 0 ? i : 1);   // n >= 2 here: token 1 exists
@@ -175,13 +175,18 @@ __device__ __forceinline__ void merge_plan_select(
   // in ascending B order plus one exchange with lane ^ 32.  Wave w owns the workgroup's A block w % nAl and every
   // G-th B block; the G partial results per A token are combined through LDS.  Ties go to the
   // lowest B position at every step.
-  const int G = max(1, 16 / nAl);
+  constexpr int NWV = NT / 64;
+  const int G = max(1, NWV / nAl);
   int* part_c = wave_tot + 32;
   float* part_v = reinterpret_cast<float*>(part_c + 512);
   {
     const int lane = tid & 63, w = tid >> 6;
     const int fr = lane & 31, fk = lane >> 5;
-    for (int al = w % nAl, grp = w / nAl; grp < G; grp = G) {   // one (A block, B group) per wave
+    // nAl <= NWV: one (A block, B group) per wave, groups beyond G idle; more A blocks than waves: one group, the
+    // waves take the blocks in turn
+    const bool wide = nAl > NWV;
+    const int grp = wide ? 0 : w / nAl;
+    for (int al = wide ? w : w % nAl; al < nAl && grp < G; al += wide ? NWV : nAl) {
       const int a = (part + parts * al) * 32 + fr;
       const float* pa = mh + (size_t)min(a, nA - 1) * ldm + fk * hp;
       float bv = -INFINITY;
@@ -224,7 +229,7 @@ __device__ __forceinline__ void merge_plan_select(
     }
   }
   __syncthreads();
-  for (int t = tid; t < nAl * 32; t += kPlanThreads) {
+  for (int t = tid; t < nAl * 32; t += NT) {
     const int a = (part + parts * (t >> 5)) * 32 + (t & 31);
     if (a >= nA) continue;
     float bv = part_v[t];
@@ -377,19 +382,19 @@ __device__ __forceinline__ void merge_plan_lists(
   }
 }
 
-// The whole plan of query q by one workgroup of kPlanThreads threads (tid = thread index; lds: its dynamic LDS).
-template <typename T, bool ROWS_IN_LDS>
+// The whole plan of query q by one workgroup of NT threads (a multiple of 64; tid = thread index; lds: its dynamic LDS).
+template <typename T, bool ROWS_IN_LDS, int NT = kPlanThreads>
 __device__ __forceinline__ void merge_plan_body(
     const T* __restrict__ src, int64_t row_stride, int col_off, int H, int dm, const int32_t* __restrict__ in_off,
     const int32_t* __restrict__ out_off, const int32_t* __restrict__ reff_arr, const int32_t* __restrict__ troff,
     int n_lead, int32_t* __restrict__ src_list, int32_t* __restrict__ row_ptr, int32_t* __restrict__ trace_src,
     int32_t* __restrict__ trace_dst, float* rows, float* lds, const int q, const int tid) {
-  merge_plan_select<T, ROWS_IN_LDS, false>(src, row_stride, col_off, H, dm, in_off, reff_arr, n_lead, rows, lds, nullptr,
-                                           nullptr, q, tid);
+  merge_plan_select<T, ROWS_IN_LDS, false, NT>(src, row_stride, col_off, H, dm, in_off, reff_arr, n_lead, rows, lds,
+                                               nullptr, nullptr, q, tid);
   const int n = in_off[q + 1] - in_off[q];
   float* small = ROWS_IN_LDS ? lds + (size_t)max(n, 0) * plan_row_floats(dm) : lds;
-  merge_plan_lists<kPlanThreads, false>(small, nullptr, nullptr, in_off, out_off, reff_arr, troff, src_list, row_ptr,
-                                        trace_src, trace_dst, q, tid);
+  merge_plan_lists<NT, false>(small, nullptr, nullptr, in_off, out_off, reff_arr, troff, src_list, row_ptr, trace_src,
+                              trace_dst, q, tid);
 }
 
 }  // namespace otas
