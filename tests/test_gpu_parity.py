@@ -735,6 +735,30 @@ def test_long_ragged_sequences_bf16_plan_split_over_two_launches(torch_cuda, lib
     ctx.close()
 
 
+def test_splitk_factor_and_room_are_consistent(torch_cuda, lib):
+    """The split factor of the MLP's second linear is one of 1, 2, 3, 4, 6, 8, never above the room the caller
+    names, 1 for f32 models and for full ViT-B batches; the room is two partial rows per token row, up to eight for
+    batches of at most 1024 rows, never below 1 or above 8."""
+    cfg = synth.config("vitb_plain")
+    cfg.L = 1
+    ctx, _ = hz.make_context(cfg)
+    for M in (1, 64, 197, 704, 1344, 2368, 3392, 4416, 5440, 8512, 12608, 67072):
+        for room in (1, 2, 3, 5, 8):
+            S = ctx.otas_splitk_factor(M, cfg.D, cfg.F, room)
+            assert S in (1, 2, 3, 4, 6, 8) and S <= room, (M, room, S)
+    assert ctx.otas_splitk_factor(12608, cfg.D, cfg.F, 8) == 1
+    assert ctx.otas_splitk_factor(197, cfg.D, cfg.F, 8) > 1
+    assert ctx.otas_splitk_factor(197, cfg.D, cfg.D, 8) == 1          # K = 768: never split
+    assert [ctx.otas_splitk_room(T0, T0) for T0 in (197, 1024, 1025, 2048, 2049, 4096, 12608)] == [8, 8, 6, 4, 3, 2, 2]
+    assert ctx.otas_splitk_room(12608, 704) == 8 and ctx.otas_splitk_room(12608, 5440) == 4
+    assert ctx.otas_splitk_room(12608, 10 ** 9) == 1
+    ctx.close()
+    cfg32 = synth.config("tiny")
+    ctx32, _ = hz.make_context(cfg32)
+    assert ctx32.otas_splitk_factor(197, cfg32.D, 4096, 8) == 1
+    ctx32.close()
+
+
 def test_per_launch_timing_api(torch_cuda, lib):
     """otas_timing_*: one record per launch in launch order, kinds named, the event-pair overhead is
     calibrated and non-negative, records stop when timing is off, and timing changes no result."""
