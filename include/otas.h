@@ -319,6 +319,10 @@ otas_status otas_linear_kernel(otas_ctx *ctx, int32_t kernel, const void *x, con
  * pairs around a one-wave kernel that spins for 10 us / 30 us of the device's wall clock, less the
  * spin and less 1 us for the dispatch's own ramp (otas_timing_overhead_ms; 0 when the calibration
  * is not self-consistent) -- and every record is reported net of it.
+ * A launch has one kind, named for its main work: where the encoder runs the merge plan (or its
+ * selection phases) inside the attention launch and the plan's list-writing phases inside the
+ * output projection's launch (bf16 models of head width 64), those records are "attention" and
+ * "gemm_proj", and "merge_plan" counts only the plans that had a launch of their own.
  * total_ms / launches: host arrays of otas_timing_kinds() entries.  Off by default. */
 otas_status otas_timing_enable(otas_ctx *ctx, int32_t on);
 int32_t otas_timing_kinds(void);
