@@ -959,7 +959,17 @@ otas_status otas_encoder_forward_deep(otas_ctx* c, const void* x0, const int32_t
     OTAS_LAUNCH(K_LN, launch_layer_norm(dt, true, x_cur, wl.ln2_g, wl.ln2_b, hbuf, T, D, d.ln_eps, s));
     OTAS_LAUNCH(K_FC1, launch_linear(dt, hbuf, wl.w_fc1, wl.b_fc1, nullptr, hid, T, F, D, EPI_GELU, s));
     void* x_next = (l == L - 1) ? x_out : (void*)x_buf[cur];
-    OTAS_LAUNCH(K_FC2, launch_linear(dt, hid, wl.w_fc2, wl.b_fc2, x_cur, x_next, T, D, F, EPI_RESIDUAL, s));
+    // few rows, long K: split over K as in run_layers; the next block's LayerNorm is not folded into the reduce,
+    // because that block first replaces or inserts prompt rows
+    const int S = splitk_factor(dt, T, D, F, (int)std::min<int64_t>(8, w.part_factor * T_max / std::max<int64_t>(T, 1)));
+    if (S > 1) {
+      float* part = (float*)(ws + w.part);
+      OTAS_LAUNCH(K_FC2, launch_linear_splitk(hid, wl.w_fc2, part, T, D, F, S, s));
+      OTAS_LAUNCH(K_REDUCE, launch_splitk_reduce_ln(part, S, wl.b_fc2, x_cur, (float*)x_next, T, D, nullptr, nullptr,
+                                                    nullptr, d.ln_eps, s));
+    } else {
+      OTAS_LAUNCH(K_FC2, launch_linear(dt, hid, wl.w_fc2, wl.b_fc2, x_cur, x_next, T, D, F, EPI_RESIDUAL, s));
+    }
   }
   OTAS_LAUNCH(K_MISC, launch_fill_i32(sizes_out, 1, T_max, s));
   return OTAS_OK;
