@@ -7,10 +7,13 @@
 //   * bf16 MFMA (v_mfma_f32_32x32x16_bf16), fp32 accumulate, operand tiles loaded straight into
 //     swizzled LDS stages, fused bias / GELU / residual epilogue (bf16 models):
 //       gemm_mfma_k32_kernel     128 x 128, K step 32, three workgroups per CU (also split-K)
-//       gemm_mfma128k64_kernel   128 x 128, K step 64, two per CU
+//       gemm_mfma128k64_kernel   128 x 128, K step 64, two per CU (also split-K: the form split launches run)
 //       gemm_mfma256w8_kernel    192 / 256 / 320 x 256, eight waves, one per CU
 //       gemm_mfma64_kernel       64 x 64, K step 32, for products of very few rows
-//     pick_mfma_kernel chooses among them with a cost model fitted to measured launch times.
+//     pick_mfma_kernel chooses among them with a cost model fitted to measured launch times; splitk_factor
+//     decides with the same model whether the MLP's second linear is split over K.
+//     Each kernel has a PLAN form for the attention output projection, whose first workgroups write the lists
+//     of the layer's merge plan (merge_plan_lists) instead of computing a tile.
 #include <algorithm>
 #include <cmath>
 #include <cstdlib>
@@ -1061,3 +1064,4 @@ hipError_t launch_linear_kernel(int kernel, int dtype, const void* x, const void
 }
 
 }  // namespace otas
+#undef OTAS_PLAN_TAIL_OR_TILE
