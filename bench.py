@@ -88,11 +88,14 @@ def algorithmic_work(cfg, lengths0, r, otas, ctx):
 class Strategy:
     """One workload resident on the GPU: context, inputs, workspace, outputs."""
 
-    def __init__(self, name):
+    def __init__(self, name, batch=0):
         import torch
         import paper_2401_05031_amd as otas
         self.name = name
         self.cfg = cfg = synth.config(name)
+        if batch and batch < cfg.B:      # the first `batch` queries of the workload: what a serving loop sends at low rates
+            cfg.B = batch
+            cfg.strategies = cfg.strategies[:batch]
         self.ctx = otas.Context.from_host_weights(cfg.L, cfg.D, cfg.H, cfg.F,
                                                   otas.OTAS_F32 if cfg.dtype == "f32" else otas.OTAS_BF16,
                                                   cfg.ln_eps, cfg.n_lead, synth.all_weights(cfg))
@@ -220,7 +223,8 @@ def measured_traffic(workload):
 
 def rooflines(res):
     k, w = res["kernels"], res["work"]
-    traffic = measured_traffic(res["name"])
+    full = res["cfg"].B == synth.config(res["name"]).B      # the stored traffic is the full batch's
+    traffic = measured_traffic(res["name"]) if full else {}
     gemm_ms = sum(k[n][0] for n in ("gemm_qkv", "gemm_proj", "gemm_fc1", "gemm_fc2"))
     gemm_launches = sum(k[n][1] for n in ("gemm_qkv", "gemm_proj", "gemm_fc1", "gemm_fc2"))
     gemm_flops = sum(w[n] for n in ("gemm_qkv", "gemm_proj", "gemm_fc1", "gemm_fc2"))
@@ -351,6 +355,11 @@ def main():
     ap.add_argument("--workload", default="vitb_r16", choices=list(synth.CONFIG_NAMES))
     ap.add_argument("--others", default="vitb_plain,vitb_p10_r8,vitb_deep10_replace,vitb_deep2_grow,vitl_ragged,vith_mixed",
                     help="further workloads reported per strategy (the two large ragged ones run few steps)")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="run the headline workload on its first BATCH queries only (latency studies and profiler runs of "
+                         "small batches; the stored HBM traffic figures do not apply then and are left out)")
+    ap.add_argument("--small-batches", default="1,4,8,16,32",
+                    help="batch sizes whose single-forward latency is reported beside the full batch's ('' = none)")
     ap.add_argument("--cpu-queries", type=int, default=32)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-clock", action="store_true",
@@ -380,7 +389,7 @@ def main():
     # merge plan's fork/join adds ~170 us per layer), which must not leak into a later strategy's
     # throughput.
     names = [args.workload] + [n for n in args.others.split(",") if n and n != args.workload]
-    strategies = [Strategy(n) for n in names]
+    strategies = [Strategy(n, args.batch if i == 0 else 0) for i, n in enumerate(names)]
     # Everything is set up: move what exists out of the garbage collector's sight.  With torch imported a
     # full collection takes ~38 ms on the host, and one of them landing inside a 50-step timed region
     # (the host runs at most a few steps ahead of the GPU) reads as +0.7 ms per step for that strategy.
@@ -392,6 +401,18 @@ def main():
                       args.warmup if not big else min(args.warmup, 3))
     for st in strategies:
         st.time_single_forwards(21)
+    # Small batches of the headline workload: median of 21 single forward passes each (prepend included), one
+    # context per batch size, closed again at once.
+    small = {}
+    for b in [int(v) for v in args.small_batches.split(",") if v]:
+        if b >= strategies[0].cfg.B:
+            continue
+        sb = Strategy(args.workload, b)
+        sb.time_steps(5, 3)
+        sb.time_single_forwards(21)
+        small[str(b)] = round(sb.latency_ms, 4)
+        sb.ctx.close()
+        del sb
     # The clock figures are an extra: if the probe fails, the line is still printed without them.
     idle_mhz = None
     for i, st in enumerate(strategies):
@@ -428,7 +449,9 @@ def main():
     rf = rooflines(head)
     cfg = head["cfg"]
     out = {
-        "metric": BASELINE_METRIC, "value": round(head["img_s"], 1), "unit": "images/s",
+        "metric": BASELINE_METRIC if cfg.B == synth.config(cfg.name).B
+        else BASELINE_METRIC + f" [this run: the first {cfg.B} queries of the batch only]",
+        "value": round(head["img_s"], 1), "unit": "images/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(head["ms"], 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
@@ -436,6 +459,7 @@ def main():
                                f"strategy (P, r) = {'mixed' if len(set(cfg.strategies)) > 1 else cfg.strategies[0]}",
                    "global_batch": cfg.B, "seq_len": cfg.n0, "parallelism": "single GPU"},
         "single_forward_ms_median": round(head["latency_ms"], 4),
+        "small_batch_single_forward_ms_median": small,
         "roofline": dict({k: rf["gemm"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic")},
                          traffic_source="rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, stored in "
                                         "paper_2401_05031_amd/hbm_traffic.json (profiles/hbm_traffic_vitb_r16_pmc.md); "

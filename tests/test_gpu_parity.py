@@ -1112,7 +1112,8 @@ def test_bench_prints_one_json_line_with_the_contract_keys(torch_cuda, lib):
     import sys
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "3", "--warmup", "1", "--others", "",
-                        "--cpu-queries", "2"], capture_output=True, text=True, timeout=110, cwd=root)
+                        "--cpu-queries", "2", "--small-batches", "1,8"], capture_output=True, text=True, timeout=110,
+                       cwd=root)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [l for l in r.stdout.splitlines() if l.strip()]
     assert len(lines) == 1
@@ -1130,6 +1131,8 @@ def test_bench_prints_one_json_line_with_the_contract_keys(torch_cuda, lib):
     assert rf["traffic"] is None or rf["traffic"] > 0
     # head width 64, bf16: attention and the merge plan of a layer go out as one launch, recorded as attention
     assert b["rooflines"]["attention"].get("includes_merge_plan") is True and "merge_plan" not in b["rooflines"]
+    sm = b["small_batch_single_forward_ms_median"]
+    assert set(sm) == {"1", "8"} and 0.0 < sm["1"] <= sm["8"] * 1.2 and sm["8"] < b["single_forward_ms_median"]
     sc = b["shader_clock"]
     assert 300 < sc["under_load_mhz"]["median"] <= sc["idle_mhz"] * 1.05 and sc["rated_mhz"] == 2400.0
     assert sc["peak_at_measured_clock"] == pytest.approx(2500.0 * sc["under_load_mhz"]["median"] / 2400.0, rel=1e-3)
