@@ -279,19 +279,22 @@ def test_attention_bf16_head_widths_and_long_sequences(torch_cuda, lib, D, H):
     cfg = synth.Config("attn", L=1, D=D, H=H, F=2 * D, dtype="bf16", B=1, n0=8, strategies=[(0, 0)], seed=11)
     ctx, _ = hz.make_context(cfg)
     rng = np.random.default_rng(D + H)
-    ns = [1, 33, 197, 256, 257, 300, 700, 129]
-    off = np.concatenate([[0], np.cumsum(ns)]).astype(np.int32)
-    qkv = synth.round_to_bf16(rng.standard_normal((int(off[-1]), 3 * D)).astype(np.float32))
-    sizes = rng.integers(1, 6, int(off[-1])).astype(np.int32)
-    for flags in (0, lib.OTAS_FLAG_SIZE_BIAS):
-        o = torch.full((int(off[-1]), D), float("nan"), dtype=torch.bfloat16, device="cuda")
-        ctx.otas_attention(_t(torch, qkv, torch.bfloat16), torch.from_numpy(sizes).to("cuda"), off, flags, o)
-        got = o.to(torch.float32).cpu().numpy()
-        assert np.isfinite(got).all()
-        for q, n in enumerate(ns):
-            sl = slice(off[q], off[q + 1])
-            ref = orc.attention_heads(qkv[sl].astype(np.float64), H, sizes[sl], bool(flags))
-            assert hz.rel_err(got[sl], ref) <= 1e-2, (q, n, flags)
+    # the longest query picks the kernel's shape for the whole batch: beyond 256 rows (also just beyond: 257 tokens
+    # are a 224-pixel image at patch 14), 129 .. 256, up to 128
+    for ns in ([1, 33, 197, 256, 257, 300, 700, 129], [257, 267, 320, 300, 161, 160, 31, 289], [197, 256, 130, 7],
+               [128, 64, 97, 2]):
+        off = np.concatenate([[0], np.cumsum(ns)]).astype(np.int32)
+        qkv = synth.round_to_bf16(rng.standard_normal((int(off[-1]), 3 * D)).astype(np.float32))
+        sizes = rng.integers(1, 6, int(off[-1])).astype(np.int32)
+        for flags in (0, lib.OTAS_FLAG_SIZE_BIAS):
+            o = torch.full((int(off[-1]), D), float("nan"), dtype=torch.bfloat16, device="cuda")
+            ctx.otas_attention(_t(torch, qkv, torch.bfloat16), torch.from_numpy(sizes).to("cuda"), off, flags, o)
+            got = o.to(torch.float32).cpu().numpy()
+            assert np.isfinite(got).all()
+            for q, n in enumerate(ns):
+                sl = slice(off[q], off[q + 1])
+                ref = orc.attention_heads(qkv[sl].astype(np.float64), H, sizes[sl], bool(flags))
+                assert hz.rel_err(got[sl], ref) <= 1e-2, (q, n, flags)
     ctx.close()
 
 
