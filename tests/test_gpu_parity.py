@@ -637,6 +637,41 @@ def test_linear_bf16_every_kernel_ragged_rows(torch_cuda, lib, M, N, K, epi):
     ctx.close()
 
 
+def test_gelu_epilogue_over_every_bf16_input_in_range(torch_cuda, lib):
+    """The GELU of the MFMA kernels' epilogue (a polynomial for log2 Phi(-|x|) and one exp2, not erf) on EVERY
+    bf16 value in [-9, 9]: an identity weight and a zero bias make the pre-activation the input itself.  Against
+    the exact erf form in float64: the absolute error before the result is rounded to bf16 is within 4e-7, so
+    the rounded result is within half a bf16 unit + 4e-7 of the exact value everywhere, and equals the correctly
+    rounded value for all but a small share of the inputs."""
+    torch = torch_cuda
+    cfg = synth.config("vitb_plain")
+    cfg.L = 1
+    ctx, _ = hz.make_context(cfg)
+    bits = np.arange(0, 1 << 16, dtype=np.uint32)
+    vals = (bits << 16).view(np.float32)
+    vals = vals[np.isfinite(vals) & (np.abs(vals) <= 9.0)]
+    K = 256
+    M = -(-vals.size // K)
+    x = np.zeros(M * K, dtype=np.float32)
+    x[:vals.size] = vals
+    x = x.reshape(M, K)
+    w = np.eye(K, dtype=np.float32)
+    out = torch.full((M, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ctx.otas_linear(_t(torch, x, torch.bfloat16), _t(torch, w, torch.bfloat16),
+                    torch.zeros(K, dtype=torch.bfloat16, device="cuda"), None, M, K, K, 1, out)
+    got = out.to(torch.float32).cpu().numpy().astype(np.float64)
+    ref = orc.gelu(x.astype(np.float64))
+    half_unit = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 1e-30))) - 8)     # half a bf16 unit at the exact value
+    assert np.all(np.abs(got - ref) <= half_unit + 4e-7)
+    exact_rounded = synth.round_to_bf16(ref.astype(np.float32)).astype(np.float64)
+    big = np.abs(ref) > 1e-4                                                       # below that 4e-7 is whole bf16 units
+    share = float(np.mean(got[big] != exact_rounded[big]))
+    print("share of inputs whose GELU is not the correctly rounded bf16 value: %.4f %%" % (100 * share))
+    assert share <= 1e-3          # measured 2.6e-4
+    assert np.all(got[x >= 8.0] == x[x >= 8.0].astype(np.float64)) and np.all(np.abs(got[x <= -8.0]) <= 1e-6)
+    ctx.close()
+
+
 @pytest.mark.parametrize("kernel", range(1, 8))
 def test_linear_every_named_kernel_whole_output(torch_cuda, lib, kernel):
     """Every GEMM kernel of the library forced by name (otas_linear_kernel) on shapes with ragged row
