@@ -60,7 +60,7 @@ __device__ inline float gelu_exact(float x) { return 0.5f * x * (1.0f + erff(x *
 //   0.5 x (1 + erf(x / sqrt 2)) = max(x, 0) - |x| Phi(-|x|),   Phi = the standard normal distribution function.
 // log2 Phi(-u) is smooth and close to a parabola: a polynomial of degree 6 in u on [0, 6] (least squares on a
 // fine grid, re-weighted until the error of u Phi(-u) is flat) reproduces u Phi(-u) to 5e-8; beyond u = 6 the
-// term is below 6e-9 |x| and u is clamped.  Evaluated in fp32 the whole function is within 3e-7 of the exact one
+// term is below 6e-9 and u is clamped (in the polynomial and in the product).  Evaluated in fp32 the whole function is within 3e-7 of the exact one
 // over [-8, 8], four orders below half a bf16 unit of a result of size 1, for six multiply-adds and one exp2 --
 // against a reciprocal, an exp2 and eleven other instructions for erf by formula 7.1.26 of Abramowitz & Stegun
 // (same accuracy), which this replaces: transcendentals run at quarter rate, and in the GEMM epilogue of the
@@ -74,7 +74,7 @@ __device__ inline float gelu_bf16(float x) {
   p = fmaf(p, u, -1.15120113e+00f);
   p = fmaf(p, u, -9.99993145e-01f);
   const float relu = __builtin_amdgcn_fmed3f(x, 0.0f, 3.0e38f);   // max(x, 0) in one instruction
-  return fmaf(-fabsf(x), __builtin_amdgcn_exp2f(p), relu);
+  return fmaf(-u, __builtin_amdgcn_exp2f(p), relu);   // u, not |x|: beyond 6 the term stays 6e-9 (also for infinities)
 }
 
 }  // namespace otas
